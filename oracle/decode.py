@@ -1,0 +1,29 @@
+"""One decode step of Algorithm 1 for the fixed static pattern, and the index build
+it depends on (test oracle; see package header)."""
+import numpy as np
+
+from . import attention, mips, projection, search
+
+
+def build_index(K, Q_prefill, deg, knn):
+    """Sec. 3.2: exact KNN from each prefill query to the keys, projected into a
+    key-key graph. Returns (adj [N][deg], entry, L [M][knn])."""
+    L, _ = mips.knn_lists(Q_prefill, K, knn)
+    adj, entry = projection.project(L, np.asarray(K).shape[0], deg)
+    return adj, entry, L
+
+
+def decode_step(q, K, V, adj, entry, sink, window, topk, ef, expand=1):
+    """Algorithm 1 with PredictActiveTokens fixed to sink + window (Sec. 3.3):
+    Omega = VectorSearch(q) minus the static set; o_Omega by Eq. 2 over Omega;
+    o_W by Eq. 2 over W; combined by Eq. 4-5.
+    Returns (out[d], lse, ids[topk], stats)."""
+    N = np.asarray(K).shape[0]
+    W = attention.static_ids(N, sink, window)
+    ids, stats = search.greedy_search(q, K, adj, entry, ef, topk, expand, exclude=W)
+    omega = ids[ids >= 0]
+    o_o, l_o = attention.partial_attention(q, K, V, omega)
+    o_w, l_w = attention.partial_attention(q, K, V, W)
+    out, lse = attention.merge(o_w, l_w, o_o, l_o)
+    stats = dict(stats, o_omega=o_o, lse_omega=l_o, o_w=o_w, lse_w=l_w)
+    return out, lse, ids, stats
