@@ -1,0 +1,148 @@
+/*
+ * libra — RetrievalAttention decode hot path and index build for AMD MI355X (gfx950).
+ *
+ * C ABI. Every tensor argument is a DEVICE pointer to contiguous row-major memory
+ * owned by the caller unless the comment says "host". The library never frees or
+ * retains caller tensors; an ra_index owns only its graph and its private workspace.
+ * All device work is enqueued on `stream` (a hipStream_t passed as void*; NULL is the
+ * default stream). Decode-path calls return without synchronising. Argument checks
+ * run before any HIP call and return a status; nothing aborts or throws across the ABI.
+ *
+ * Notation (paper, arXiv 2409.10516): N keys per KV head, M prefill queries per query
+ * head, d head dimension, W the static token set of Sec. 3.3 (first `sink` and last
+ * `window` tokens), Omega the retrieved set, topk = |Omega| requested, ef the search
+ * beam width, deg the graph degree bound, knn the length of the exact KNN lists.
+ *
+ * Shapes: K, V        [n_seq][n_kv_heads][N][d]
+ *         Q_prefill   [n_seq][n_q_heads][M][d]
+ *         q           [n_seq][n_q_heads][d]
+ *         out         [n_seq][n_q_heads][d]   float32
+ *         lse         [n_seq][n_q_heads]      float32 (natural log, logits scaled by 1/sqrt(d))
+ *         ids         [n_seq][n_q_heads][topk] int32, best first, padded with -1
+ * Query head h reads KV head h / (n_q_heads / n_kv_heads): one index per query head,
+ * one KV copy per group (Appendix C, "Implementation").
+ * Supported: d = 128; dtype float32 or bfloat16 (q, K, V, Q_prefill share the dtype).
+ */
+#ifndef RA_H
+#define RA_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct ra_index ra_index;   /* opaque; create with ra_build_index / ra_index_import */
+
+typedef enum {
+    RA_OK = 0,
+    RA_EINVAL = 1,   /* null pointer, non-positive size, ef < topk, knn > N, ...          */
+    RA_ESHAPE = 2,   /* sizes inconsistent with each other or with the index             */
+    RA_EDTYPE = 3,   /* unknown dtype                                                    */
+    RA_ENOMEM = 4,   /* device allocation failed                                         */
+    RA_EHIP = 5,     /* a HIP call failed; see ra_last_error()                           */
+    RA_EUNSUP = 6    /* valid but not supported by this build (d != 128, deg > 64, ...)  */
+} ra_status;
+
+typedef enum { RA_F32 = 0, RA_BF16 = 1 } ra_dtype;
+
+/* Per (sequence, query head) search counters, written by the device. */
+typedef struct {
+    int32_t n_visited;    /* keys scored (entry included)                                */
+    int32_t n_expanded;   /* adjacency rows read                                         */
+    int32_t n_iters;      /* dependent search steps                                      */
+    int32_t n_returned;   /* valid ids written (<= topk)                                 */
+} ra_stats;
+
+/* Limits of this build (checked, RA_EUNSUP beyond them). */
+#define RA_MAX_DEG 64
+#define RA_MAX_KNN 64
+#define RA_MAX_EF 1024
+#define RA_MAX_EXPAND 32
+#define RA_MAX_TOPK 1024
+
+/* ---- index build (Sec. 3.2) -------------------------------------------------------- */
+
+/* Exact KNN of Sec. 3.2 / Fig. 2b: for every prefill query the ids of its `knn` keys of
+ * largest inner product over ALL N keys of its KV head (non-causal, unscaled), ordered
+ * best first; ties go to the lower id.  L_out: device int32 [n_seq][n_q_heads][M][knn]. */
+ra_status ra_knn(const void* K, const void* Q_prefill, ra_dtype dt,
+                 int n_seq, int n_q_heads, int n_kv_heads, int64_t N, int64_t M, int d,
+                 int knn, void* stream, int32_t* L_out);
+
+/* Projection of Sec. 3.2 (keys that share query vectors are linked; queries are dropped).
+ * L: device int32 [n_graphs][M][knn] with distinct ids per row. Writes, per graph, the
+ * adjacency adj [n_graphs][N][deg] (padded with -1) and the entry point entry [n_graphs]
+ * (both device). Integer arithmetic only: identical lists give identical graphs.
+ * Reading: candidates of key a are the keys sharing a list with it, ranked by the Jaccard
+ * overlap of their list memberships (ties: larger co-occurrence count, then lower id); two
+ * slots per row hold the children of a in a binary heap laid over the keys sorted by
+ * (membership count descending, id ascending), whose root is the entry point. */
+ra_status ra_project(const int32_t* L, int n_graphs, int64_t N, int64_t M, int knn, int deg,
+                     void* stream, int32_t* adj, int32_t* entry);
+
+/* ra_knn followed by ra_project for every (sequence, query head); returns a handle that
+ * owns the graphs. Synchronises `stream` before returning. */
+ra_status ra_build_index(const void* K, const void* Q_prefill, ra_dtype dt,
+                         int n_seq, int n_q_heads, int n_kv_heads, int64_t N, int64_t M, int d,
+                         int deg, int knn, void* stream, ra_index** out);
+
+/* ---- decode step (Algorithm 1 with the fixed static pattern of Sec. 3.3) ----------- */
+
+/* VectorSearch(q): bounded best-first walk over each head's graph from its entry point.
+ * Each step expands the `expand` best unexpanded beam entries (1 = textbook greedy),
+ * scores their unvisited neighbours and keeps the best `ef`. Scores are float32 inner
+ * products summed in a fixed order; order is (score descending, id ascending). ids
+ * receives the best `topk` beam entries outside W. stats may be NULL.
+ * Requires 1 <= topk <= ef <= RA_MAX_EF, 1 <= expand <= RA_MAX_EXPAND. */
+ra_status ra_search(const void* q, const ra_index* idx, const void* K, ra_dtype dt,
+                    int64_t N, int sink, int window, int topk, int ef, int expand,
+                    void* stream, int32_t* ids, ra_stats* stats);
+
+/* Eq. 2 over Omega = valid entries of ids (each head its own row of ids) and over W,
+ * each as (o, lse), and their combination by Eq. 4-5 into out/lse. The four partial
+ * outputs (o_omega [n_seq][n_q][d], lse_omega [n_seq][n_q], o_w, lse_w) may each be NULL.
+ * ids must not contain members of W (ra_search guarantees it). A head with an empty
+ * Omega gets out = o_W; with W empty too, out = 0 and lse = -inf. */
+ra_status ra_attend(const void* q, const ra_index* idx, const void* K, const void* V,
+                    ra_dtype dt, int64_t N, int sink, int window, int topk,
+                    const int32_t* ids, void* stream, float* out, float* lse,
+                    float* o_omega, float* lse_omega, float* o_w, float* lse_w);
+
+/* ra_search then ra_attend: one layer's decode-step attention for all sequences and
+ * query heads. ids and stats may be NULL (ids then live in the index workspace). */
+ra_status ra_decode_step(const void* q, const ra_index* idx, const void* K, const void* V,
+                         ra_dtype dt, int64_t N, int sink, int window, int topk, int ef,
+                         int expand, void* stream, float* out, float* lse, int32_t* ids,
+                         ra_stats* stats);
+
+/* ---- handle management ------------------------------------------------------------- */
+
+/* Build a handle from HOST arrays adj [n_seq*n_q_heads][N][deg], entries [n_seq*n_q_heads]
+ * (copied to the device). Used for persistence and to run device stages on a given graph. */
+ra_status ra_index_import(const int32_t* adj_host, const int32_t* entries_host, int n_seq,
+                          int n_q_heads, int n_kv_heads, int64_t N, int deg, ra_index** out);
+
+/* Copy one graph back to HOST arrays adj_host [N][deg] and *entry_host. Synchronises. */
+ra_status ra_index_export(const ra_index* idx, int seq, int q_head, int32_t* adj_host,
+                          int32_t* entry_host);
+
+/* what: 0 n_seq, 1 n_q_heads, 2 n_kv_heads, 3 N, 4 deg, 5 bytes of device memory owned. */
+int64_t ra_index_info(const ra_index* idx, int what);
+
+/* Device pointers to the handle's graphs (adj [n_graphs][N][deg], entry [n_graphs]). */
+const int32_t* ra_index_adj(const ra_index* idx);
+const int32_t* ra_index_entry(const ra_index* idx);
+
+void ra_index_free(ra_index* idx);
+
+/* Message for the calling thread's most recent non-OK status ("" if none). */
+const char* ra_last_error(void);
+
+/* Library version string. */
+const char* ra_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* RA_H */

@@ -1,0 +1,7 @@
+"""RetrievalAttention decode hot path and index build for AMD MI355X.
+
+`binding` wraps the C ABI of libra.so (include/ra.h); `synth` holds the seeded input
+generators. The library is loaded on first use, not at import.
+"""
+from .binding import (Index, RaError, lib, ra_attend, ra_build_index, ra_decode_step,  # noqa: F401
+                      ra_index_export, ra_index_import, ra_knn, ra_project, ra_search)

@@ -1,0 +1,297 @@
+// C ABI of libra (declared in include/ra.h): argument checks, handle management and the
+// sequencing of the device stages. No arithmetic of the method lives here.
+#include <stdarg.h>
+#include <stdio.h>
+#include <string.h>
+
+#include <new>
+
+#include "common.h"
+
+static thread_local char g_err[512] = "";
+
+void ra_set_error(const char* fmt, ...) {
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof(g_err), fmt, ap);
+    va_end(ap);
+}
+
+extern "C" const char* ra_last_error(void) { return g_err; }
+extern "C" const char* ra_version(void) { return "libra 0.1 (gfx950)"; }
+
+// ---- shared argument checks (run before any HIP call) ----------------------------------
+static ra_status check_dtype(ra_dtype dt) {
+    if (dt != RA_F32 && dt != RA_BF16) RA_FAIL(RA_EDTYPE, "unknown dtype %d", (int)dt);
+    return RA_OK;
+}
+
+static ra_status check_heads(int n_seq, int n_q, int n_kv) {
+    if (n_seq < 1 || n_q < 1 || n_kv < 1)
+        RA_FAIL(RA_EINVAL, "n_seq, n_q_heads, n_kv_heads must be positive (%d, %d, %d)", n_seq, n_q,
+                n_kv);
+    if (n_q % n_kv) RA_FAIL(RA_EINVAL, "n_q_heads %d is not a multiple of n_kv_heads %d", n_q, n_kv);
+    const int G = n_q / n_kv;
+    if (G != 1 && G != 2 && G != 4 && G != 8)
+        RA_FAIL(RA_EUNSUP, "query heads per KV head must be 1, 2, 4 or 8 (got %d)", G);
+    return RA_OK;
+}
+
+static ra_status check_dim(int d) {
+    if (d < 1) RA_FAIL(RA_EINVAL, "d must be positive");
+    if (d != RA_D) RA_FAIL(RA_EUNSUP, "this build supports d = %d only (got %d)", RA_D, d);
+    return RA_OK;
+}
+
+static ra_status check_decode_args(const ra_index* idx, int64_t N, int sink, int window, int topk) {
+    if (!idx) RA_FAIL(RA_EINVAL, "index handle is NULL");
+    if (N != idx->N) RA_FAIL(RA_ESHAPE, "N = %lld but the index was built over %lld keys",
+                             (long long)N, (long long)idx->N);
+    if (sink < 0 || window < 0) RA_FAIL(RA_EINVAL, "sink and window must be non-negative");
+    if (topk < 1) RA_FAIL(RA_EINVAL, "topk must be positive");
+    if (topk > RA_MAX_TOPK) RA_FAIL(RA_EUNSUP, "topk %d exceeds RA_MAX_TOPK %d", topk, RA_MAX_TOPK);
+    return RA_OK;
+}
+
+static ra_status check_search_args(int topk, int ef, int expand) {
+    if (ef < 1 || expand < 1) RA_FAIL(RA_EINVAL, "ef and expand must be positive");
+    if (ef < topk) RA_FAIL(RA_EINVAL, "ef (%d) must be at least topk (%d)", ef, topk);
+    if (ef > RA_MAX_EF) RA_FAIL(RA_EUNSUP, "ef %d exceeds RA_MAX_EF %d", ef, RA_MAX_EF);
+    if (expand > RA_MAX_EXPAND)
+        RA_FAIL(RA_EUNSUP, "expand %d exceeds RA_MAX_EXPAND %d", expand, RA_MAX_EXPAND);
+    return RA_OK;
+}
+
+static ra_status check_build_args(int64_t N, int64_t M, int deg, int knn, bool need_deg) {
+    if (N < 1 || M < 1) RA_FAIL(RA_EINVAL, "N and M must be positive");
+    if (N > 0x7fffffff / 2) RA_FAIL(RA_EUNSUP, "N too large for 31-bit ids");
+    if (knn < 1) RA_FAIL(RA_EINVAL, "knn must be positive");
+    if (knn > N) RA_FAIL(RA_EINVAL, "knn (%d) exceeds N (%lld)", knn, (long long)N);
+    if (knn > RA_MAX_KNN) RA_FAIL(RA_EUNSUP, "knn %d exceeds RA_MAX_KNN %d", knn, RA_MAX_KNN);
+    if (need_deg) {
+        if (deg < 2) RA_FAIL(RA_EINVAL, "deg must be at least 2 (two backbone slots)");
+        if (deg > RA_MAX_DEG) RA_FAIL(RA_EUNSUP, "deg %d exceeds RA_MAX_DEG %d", deg, RA_MAX_DEG);
+    }
+    return RA_OK;
+}
+
+#define RA_TRY(expr)                  \
+    do {                              \
+        ra_status rc_ = (expr);       \
+        if (rc_ != RA_OK) return rc_; \
+    } while (0)
+
+// ---- workspace -----------------------------------------------------------------------
+static ra_status grow(void** p, size_t* have, size_t need) {
+    if (need <= *have) return RA_OK;
+    if (*p) RA_HIP(hipFree(*p));
+    *p = nullptr;
+    *have = 0;
+    RA_HIP(hipMalloc(p, need));
+    *have = need;
+    return RA_OK;
+}
+
+static ra_status new_handle(int n_seq, int n_q, int n_kv, int64_t N, int deg, ra_index** out) {
+    ra_index* ix = new (std::nothrow) ra_index();
+    if (!ix) RA_FAIL(RA_ENOMEM, "host allocation failed");
+    memset(ix, 0, sizeof(*ix));
+    ix->n_seq = n_seq; ix->n_q = n_q; ix->n_kv = n_kv; ix->N = N; ix->deg = deg;
+    const size_t graphs = (size_t)n_seq * n_q;
+    ix->graph_bytes = graphs * N * deg * sizeof(int32_t);
+    hipError_t e = hipGetDevice(&ix->device);
+    if (e == hipSuccess) e = hipMalloc((void**)&ix->adj, ix->graph_bytes);
+    if (e == hipSuccess) e = hipMalloc((void**)&ix->entry, graphs * sizeof(int32_t));
+    if (e != hipSuccess) {
+        ra_set_error("allocating the graph (%zu B) failed: %s", ix->graph_bytes, hipGetErrorString(e));
+        if (ix->adj) (void)hipFree(ix->adj);
+        delete ix;
+        return e == hipErrorOutOfMemory ? RA_ENOMEM : RA_EHIP;
+    }
+    *out = ix;
+    return RA_OK;
+}
+
+extern "C" void ra_index_free(ra_index* ix) {
+    if (!ix) return;
+    if (ix->adj) (void)hipFree(ix->adj);
+    if (ix->entry) (void)hipFree(ix->entry);
+    if (ix->partials) (void)hipFree(ix->partials);
+    if (ix->ids_ws) (void)hipFree(ix->ids_ws);
+    if (ix->bitset) (void)hipFree(ix->bitset);
+    delete ix;
+}
+
+extern "C" int64_t ra_index_info(const ra_index* ix, int what) {
+    if (!ix) return -1;
+    switch (what) {
+        case 0: return ix->n_seq;
+        case 1: return ix->n_q;
+        case 2: return ix->n_kv;
+        case 3: return ix->N;
+        case 4: return ix->deg;
+        case 5: return (int64_t)(ix->graph_bytes + (size_t)ix->n_seq * ix->n_q * 4 +
+                                 ix->partials_bytes + ix->ids_bytes + ix->bitset_bytes);
+        default: return -1;
+    }
+}
+
+extern "C" const int32_t* ra_index_adj(const ra_index* ix) { return ix ? ix->adj : nullptr; }
+extern "C" const int32_t* ra_index_entry(const ra_index* ix) { return ix ? ix->entry : nullptr; }
+
+extern "C" ra_status ra_index_import(const int32_t* adj_host, const int32_t* entries_host, int n_seq,
+                                     int n_q, int n_kv, int64_t N, int deg, ra_index** out) {
+    if (!adj_host || !entries_host || !out) RA_FAIL(RA_EINVAL, "NULL argument");
+    RA_TRY(check_heads(n_seq, n_q, n_kv));
+    if (N < 1) RA_FAIL(RA_EINVAL, "N must be positive");
+    if (N > 0x7fffffff / 2) RA_FAIL(RA_EUNSUP, "N too large for 31-bit ids");
+    if (deg < 1) RA_FAIL(RA_EINVAL, "deg must be positive");
+    if (deg > RA_MAX_DEG) RA_FAIL(RA_EUNSUP, "deg %d exceeds RA_MAX_DEG %d", deg, RA_MAX_DEG);
+    const size_t graphs = (size_t)n_seq * n_q;
+    for (size_t g = 0; g < graphs; ++g)
+        if (entries_host[g] < 0 || entries_host[g] >= N)
+            RA_FAIL(RA_EINVAL, "entry point %d of graph %zu is outside [0, N)", entries_host[g], g);
+    const size_t cells = graphs * (size_t)N * deg;
+    for (size_t i = 0; i < cells; ++i)
+        if (adj_host[i] < -1 || adj_host[i] >= N)
+            RA_FAIL(RA_EINVAL, "adjacency cell %zu holds %d, outside [-1, N)", i, adj_host[i]);
+    ra_index* ix = nullptr;
+    RA_TRY(new_handle(n_seq, n_q, n_kv, N, deg, &ix));
+    hipError_t e = hipMemcpy(ix->adj, adj_host, ix->graph_bytes, hipMemcpyHostToDevice);
+    if (e == hipSuccess)
+        e = hipMemcpy(ix->entry, entries_host, graphs * sizeof(int32_t), hipMemcpyHostToDevice);
+    if (e != hipSuccess) {
+        ra_set_error("copying the graph to the device failed: %s", hipGetErrorString(e));
+        ra_index_free(ix);
+        return RA_EHIP;
+    }
+    *out = ix;
+    return RA_OK;
+}
+
+extern "C" ra_status ra_index_export(const ra_index* ix, int seq, int q_head, int32_t* adj_host,
+                                     int32_t* entry_host) {
+    if (!ix || !adj_host || !entry_host) RA_FAIL(RA_EINVAL, "NULL argument");
+    if (seq < 0 || seq >= ix->n_seq || q_head < 0 || q_head >= ix->n_q)
+        RA_FAIL(RA_EINVAL, "(seq %d, q_head %d) outside the index (%d x %d)", seq, q_head, ix->n_seq,
+                ix->n_q);
+    const size_t g = (size_t)seq * ix->n_q + q_head;
+    const size_t row_bytes = (size_t)ix->N * ix->deg * sizeof(int32_t);
+    RA_HIP(hipDeviceSynchronize());
+    RA_HIP(hipMemcpy(adj_host, ix->adj + g * (size_t)ix->N * ix->deg, row_bytes, hipMemcpyDeviceToHost));
+    RA_HIP(hipMemcpy(entry_host, ix->entry + g, sizeof(int32_t), hipMemcpyDeviceToHost));
+    return RA_OK;
+}
+
+// ---- index build -----------------------------------------------------------------------
+extern "C" ra_status ra_knn(const void* K, const void* Q, ra_dtype dt, int n_seq, int n_q, int n_kv,
+                            int64_t N, int64_t M, int d, int knn, void* stream, int32_t* L_out) {
+    if (!K || !Q || !L_out) RA_FAIL(RA_EINVAL, "NULL argument");
+    RA_TRY(check_dtype(dt));
+    RA_TRY(check_heads(n_seq, n_q, n_kv));
+    RA_TRY(check_dim(d));
+    RA_TRY(check_build_args(N, M, 2, knn, false));
+    return ra_launch_knn(K, Q, dt, n_seq, n_q, n_kv, N, M, knn, (hipStream_t)stream, L_out);
+}
+
+extern "C" ra_status ra_project(const int32_t* L, int n_graphs, int64_t N, int64_t M, int knn,
+                                int deg, void* stream, int32_t* adj, int32_t* entry) {
+    if (!L || !adj || !entry) RA_FAIL(RA_EINVAL, "NULL argument");
+    if (n_graphs < 1) RA_FAIL(RA_EINVAL, "n_graphs must be positive");
+    RA_TRY(check_build_args(N, M, deg, knn, true));
+    const size_t ws_bytes = ra_project_workspace_bytes(n_graphs, N, M, knn);
+    void* ws = nullptr;
+    RA_HIP(hipMalloc(&ws, ws_bytes));
+    ra_status rc = ra_launch_project(L, n_graphs, N, M, knn, deg, ws, (hipStream_t)stream, adj, entry);
+    hipError_t e = hipStreamSynchronize((hipStream_t)stream);
+    (void)hipFree(ws);
+    if (rc != RA_OK) return rc;
+    RA_HIP(e);
+    return RA_OK;
+}
+
+extern "C" ra_status ra_build_index(const void* K, const void* Q, ra_dtype dt, int n_seq, int n_q,
+                                    int n_kv, int64_t N, int64_t M, int d, int deg, int knn,
+                                    void* stream, ra_index** out) {
+    if (!K || !Q || !out) RA_FAIL(RA_EINVAL, "NULL argument");
+    RA_TRY(check_dtype(dt));
+    RA_TRY(check_heads(n_seq, n_q, n_kv));
+    RA_TRY(check_dim(d));
+    RA_TRY(check_build_args(N, M, deg, knn, true));
+    const int graphs = n_seq * n_q;
+    ra_index* ix = nullptr;
+    RA_TRY(new_handle(n_seq, n_q, n_kv, N, deg, &ix));
+    int32_t* L = nullptr;
+    hipError_t e = hipMalloc((void**)&L, (size_t)graphs * M * knn * sizeof(int32_t));
+    if (e != hipSuccess) {
+        ra_set_error("allocating the KNN lists failed: %s", hipGetErrorString(e));
+        ra_index_free(ix);
+        return e == hipErrorOutOfMemory ? RA_ENOMEM : RA_EHIP;
+    }
+    ra_status rc = ra_launch_knn(K, Q, dt, n_seq, n_q, n_kv, N, M, knn, (hipStream_t)stream, L);
+    if (rc == RA_OK) rc = ra_project(L, graphs, N, M, knn, deg, stream, ix->adj, ix->entry);
+    if (rc == RA_OK && hipStreamSynchronize((hipStream_t)stream) != hipSuccess) {
+        ra_set_error("index build failed on the device: %s", hipGetErrorString(hipGetLastError()));
+        rc = RA_EHIP;
+    }
+    (void)hipFree(L);
+    if (rc != RA_OK) {
+        ra_index_free(ix);
+        return rc;
+    }
+    *out = ix;
+    return RA_OK;
+}
+
+// ---- decode step -----------------------------------------------------------------------
+extern "C" ra_status ra_search(const void* q, const ra_index* idx, const void* K, ra_dtype dt,
+                               int64_t N, int sink, int window, int topk, int ef, int expand,
+                               void* stream, int32_t* ids, ra_stats* stats) {
+    if (!q || !K || !ids) RA_FAIL(RA_EINVAL, "NULL argument");
+    RA_TRY(check_dtype(dt));
+    RA_TRY(check_decode_args(idx, N, sink, window, topk));
+    RA_TRY(check_search_args(topk, ef, expand));
+    ra_index* ix = const_cast<ra_index*>(idx);
+    if (ra_search_needs_global_bitset(N, ix->deg, ef, expand)) {
+        const size_t need = (size_t)ix->n_seq * ix->n_q * ((N + 31) >> 5) * 4;
+        RA_TRY(grow((void**)&ix->bitset, &ix->bitset_bytes, need));
+    }
+    return ra_launch_search(q, ix->adj, ix->entry, K, dt, ix->n_seq, ix->n_q, ix->n_kv, N, ix->deg,
+                            sink, window, topk, ef, expand, ix->bitset, (hipStream_t)stream, ids,
+                            stats);
+}
+
+extern "C" ra_status ra_attend(const void* q, const ra_index* idx, const void* K, const void* V,
+                               ra_dtype dt, int64_t N, int sink, int window, int topk,
+                               const int32_t* ids, void* stream, float* out, float* lse,
+                               float* o_omega, float* lse_omega, float* o_w, float* lse_w) {
+    if (!q || !K || !V || !ids || !out || !lse) RA_FAIL(RA_EINVAL, "NULL argument");
+    RA_TRY(check_dtype(dt));
+    RA_TRY(check_decode_args(idx, N, sink, window, topk));
+    ra_index* ix = const_cast<ra_index*>(idx);
+    const size_t need =
+        ra_attend_partial_floats(ix->n_seq, ix->n_q, ix->n_kv, N, sink, window, topk) * sizeof(float);
+    RA_TRY(grow((void**)&ix->partials, &ix->partials_bytes, need));
+    return ra_launch_attend(q, K, V, dt, ix->n_seq, ix->n_q, ix->n_kv, N, sink, window, topk, ids,
+                            ix->partials, (hipStream_t)stream, out, lse, o_omega, lse_omega, o_w,
+                            lse_w);
+}
+
+extern "C" ra_status ra_decode_step(const void* q, const ra_index* idx, const void* K, const void* V,
+                                    ra_dtype dt, int64_t N, int sink, int window, int topk, int ef,
+                                    int expand, void* stream, float* out, float* lse, int32_t* ids,
+                                    ra_stats* stats) {
+    if (!q || !K || !V || !out || !lse) RA_FAIL(RA_EINVAL, "NULL argument");
+    RA_TRY(check_dtype(dt));
+    RA_TRY(check_decode_args(idx, N, sink, window, topk));
+    RA_TRY(check_search_args(topk, ef, expand));
+    ra_index* ix = const_cast<ra_index*>(idx);
+    if (!ids) {
+        RA_TRY(grow((void**)&ix->ids_ws, &ix->ids_bytes,
+                    (size_t)ix->n_seq * ix->n_q * topk * sizeof(int32_t)));
+        ids = ix->ids_ws;
+    }
+    RA_TRY(ra_search(q, idx, K, dt, N, sink, window, topk, ef, expand, stream, ids, stats));
+    return ra_attend(q, idx, K, V, dt, N, sink, window, topk, ids, stream, out, lse, nullptr,
+                     nullptr, nullptr, nullptr);
+}

@@ -1,0 +1,87 @@
+// Shared host/device declarations of libra (internal; the public ABI is include/ra.h).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "ra.h"
+
+#define RA_D 128            // head dimension this build supports
+#define RA_WAVE 64
+
+// ---- error plumbing (host) ---------------------------------------------------------
+void ra_set_error(const char* fmt, ...);
+
+#define RA_FAIL(code, ...)            \
+    do {                              \
+        ra_set_error(__VA_ARGS__);    \
+        return (code);                \
+    } while (0)
+
+#define RA_HIP(call)                                                              \
+    do {                                                                          \
+        hipError_t e_ = (call);                                                   \
+        if (e_ != hipSuccess) {                                                   \
+            ra_set_error("%s failed: %s (%s:%d)", #call, hipGetErrorString(e_),   \
+                         __FILE__, __LINE__);                                     \
+            return e_ == hipErrorOutOfMemory ? RA_ENOMEM : RA_EHIP;               \
+        }                                                                         \
+    } while (0)
+
+// ---- handle --------------------------------------------------------------------------
+struct ra_index {
+    int n_seq, n_q, n_kv, deg;
+    int64_t N;
+    int device;
+    int32_t* adj;       // [n_seq*n_q][N][deg]
+    int32_t* entry;     // [n_seq*n_q]
+    // decode workspace, grown on demand (never shrinks)
+    float* partials;    // attention partial records
+    size_t partials_bytes;
+    int32_t* ids_ws;    // [n_seq*n_q][topk] when the caller passes ids == NULL
+    size_t ids_bytes;
+    uint32_t* bitset;   // global visited bitsets for contexts too long for LDS
+    size_t bitset_bytes;
+    size_t graph_bytes;
+};
+
+// ---- launchers implemented in the .hip files (all enqueue on `st`, no sync) ----------
+ra_status ra_launch_search(const void* q, const int32_t* adj, const int32_t* entry, const void* K,
+                           ra_dtype dt, int n_seq, int n_q, int n_kv, int64_t N, int deg,
+                           int sink, int window, int topk, int ef, int expand, uint32_t* bitset,
+                           hipStream_t st, int32_t* ids, ra_stats* stats);
+size_t ra_search_lds_bytes(int64_t N, int deg, int ef, int expand, bool global_bitset);
+bool ra_search_needs_global_bitset(int64_t N, int deg, int ef, int expand);
+
+size_t ra_attend_partial_floats(int n_seq, int n_q, int n_kv, int64_t N, int sink, int window,
+                                int topk);
+ra_status ra_launch_attend(const void* q, const void* K, const void* V, ra_dtype dt, int n_seq,
+                           int n_q, int n_kv, int64_t N, int sink, int window, int topk,
+                           const int32_t* ids, float* partials, hipStream_t st, float* out,
+                           float* lse, float* o_omega, float* lse_omega, float* o_w,
+                           float* lse_w);
+
+ra_status ra_launch_knn(const void* K, const void* Q, ra_dtype dt, int n_seq, int n_q, int n_kv,
+                        int64_t N, int64_t M, int knn, hipStream_t st, int32_t* L);
+
+size_t ra_project_workspace_bytes(int n_graphs, int64_t N, int64_t M, int knn);
+ra_status ra_launch_project(const int32_t* L, int n_graphs, int64_t N, int64_t M, int knn, int deg,
+                            void* workspace, hipStream_t st, int32_t* adj, int32_t* entry);
+
+// ---- device helpers ------------------------------------------------------------------
+#ifdef __HIPCC__
+__device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
+__device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
+
+// Monotone map float -> uint32 (larger float -> larger uint). -0 is folded into +0 first
+// so that equal floats map to equal integers.
+__device__ __forceinline__ uint32_t f32_ordered(float f) {
+    f = f + 0.0f;
+    uint32_t u = __float_as_uint(f);
+    return (u & 0x80000000u) ? ~u : (u | 0x80000000u);
+}
+__device__ __forceinline__ float f32_from_ordered(uint32_t o) {
+    uint32_t u = (o & 0x80000000u) ? (o & 0x7fffffffu) : ~o;
+    return __uint_as_float(u);
+}
+#endif

@@ -1,0 +1,168 @@
+"""Parity of the HIP decode path (search, attention, merge) with the CPU oracle, through
+the C ABI, on graphs built by the oracle (stage isolation). GPU only."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2409_10516_amd as ra
+from oracle import attention as OA, decode as OD, mips as OM, search as OS
+from paper_2409_10516_amd import synth
+from tests.util import lse_close, oracle_graphs, out_close, to_np, tol_for
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def _cases():
+    return {
+        "config0_small": lambda: synth.make_config0(N=1024, M=256, T=6, window=32),
+        "llama_bf16": lambda: synth.make_llama_layer(11, N=1536, M=768, T=3, n_q=8, n_kv=2,
+                                                     ef=64, topk=20, window=100),
+        "llama_f32_2seq": lambda: synth.make_llama_layer(12, N=700, M=300, T=2, n_seq=2, n_q=4,
+                                                         n_kv=4, dtype=torch.float32, ef=48,
+                                                         topk=16, window=37, deg=12, knn=9),
+        "integer_ties": lambda: synth.make_integer_case(5, N=200, M=64, T=5, d=128, n_q=2,
+                                                        n_kv=1, deg=8, knn=6, topk=9, ef=20,
+                                                        sink=3, window=10),
+    }
+
+
+_cache = {}
+
+
+def _prepared(name):
+    if name not in _cache:
+        w = _cases()[name]()
+        adj, ent, L = oracle_graphs(w)
+        n_seq, n_kv = w.K.shape[:2]
+        n_q = w.Q_prefill.shape[1]
+        idx = ra.ra_index_import(torch.from_numpy(adj), torch.from_numpy(ent), n_seq, n_q, n_kv)
+        _cache[name] = (w, adj, ent, idx, w.K.to(DEV), w.V.to(DEV))
+    return _cache[name]
+
+
+@pytest.mark.parametrize("name", list(_cases()))
+@pytest.mark.parametrize("expand", [1, 4, 32])
+def test_search_ids_and_counters_bit_exact(name, expand):
+    w, adj, ent, idx, Kd, Vd = _prepared(name)
+    n_seq, n_kv, N, d = w.K.shape
+    n_q = w.Q_prefill.shape[1]
+    W = OA.static_ids(N, w.sink, w.window)
+    for t in range(w.q_decode.shape[0]):
+        ids, st = ra.ra_search(w.q_decode[t].to(DEV), idx, Kd, w.sink, w.window, w.topk, w.ef,
+                               expand)
+        ids, st = ids.cpu().numpy(), st.cpu().numpy()
+        for s in range(n_seq):
+            for h in range(n_q):
+                g = s * n_q + h
+                K = to_np(w.K[s, h // (n_q // n_kv)])
+                ref, rst = OS.greedy_search(to_np(w.q_decode[t, s, h]), K, adj[g], ent[g], w.ef,
+                                            w.topk, expand, exclude=W)
+                assert ids[s, h].tolist() == ref.tolist(), (name, expand, t, s, h)
+                assert st[s, h].tolist() == [rst["n_visited"], rst["n_expanded"], rst["n_iters"],
+                                             rst["n_returned"]], (name, expand, t, s, h)
+
+
+@pytest.mark.parametrize("name", list(_cases()))
+def test_attend_matches_eq2_and_eq4(name):
+    w, adj, ent, idx, Kd, Vd = _prepared(name)
+    n_seq, n_kv, N, d = w.K.shape
+    n_q = w.Q_prefill.shape[1]
+    tol = tol_for(w.K.dtype)
+    W = OA.static_ids(N, w.sink, w.window)
+    rng = np.random.default_rng(3)
+    rest = np.setdiff1d(np.arange(N), W)
+    topk = w.topk
+    ids = -np.ones((n_seq, n_q, topk), np.int32)
+    for s in range(n_seq):
+        for h in range(n_q):
+            n_valid = topk if (s + h) % 3 else topk - 3           # some rows are padded
+            ids[s, h, :n_valid] = rng.choice(rest, size=n_valid, replace=False)
+    q = w.q_decode[0]
+    out, lse, oo, lo, ow, lw = [x.cpu().numpy() for x in ra.ra_attend(
+        q.to(DEV), idx, Kd, Vd, w.sink, w.window, torch.from_numpy(ids).to(DEV), partials=True)]
+    for s in range(n_seq):
+        for h in range(n_q):
+            K = to_np(w.K[s, h // (n_q // n_kv)]); V = to_np(w.V[s, h // (n_q // n_kv)])
+            qq = to_np(q[s, h])
+            om = ids[s, h][ids[s, h] >= 0]
+            r_oo, r_lo = OA.partial_attention(qq, K, V, om)
+            r_ow, r_lw = OA.partial_attention(qq, K, V, W)
+            r_o, r_l = OA.merge(r_ow, r_lw, r_oo, r_lo)
+            assert out_close(oo[s, h], r_oo, tol) and lse_close(lo[s, h], r_lo, tol)
+            assert out_close(ow[s, h], r_ow, tol) and lse_close(lw[s, h], r_lw, tol)
+            assert out_close(out[s, h], r_o, tol) and lse_close(lse[s, h], r_l, tol)
+
+
+@pytest.mark.parametrize("name", list(_cases()))
+@pytest.mark.parametrize("expand", [1, 8])
+def test_decode_step_end_to_end(name, expand):
+    w, adj, ent, idx, Kd, Vd = _prepared(name)
+    n_seq, n_kv, N, d = w.K.shape
+    n_q = w.Q_prefill.shape[1]
+    tol = tol_for(w.K.dtype)
+    for t in range(w.q_decode.shape[0]):
+        out, lse, ids, st = ra.ra_decode_step(w.q_decode[t].to(DEV), idx, Kd, Vd, w.sink, w.window,
+                                              w.topk, w.ef, expand)
+        out, lse, ids = out.cpu().numpy(), lse.cpu().numpy(), ids.cpu().numpy()
+        for s in range(n_seq):
+            for h in range(n_q):
+                g = s * n_q + h
+                K = to_np(w.K[s, h // (n_q // n_kv)]); V = to_np(w.V[s, h // (n_q // n_kv)])
+                r_out, r_lse, r_ids, _ = OD.decode_step(to_np(w.q_decode[t, s, h]), K, V, adj[g],
+                                                        ent[g], w.sink, w.window, w.topk, w.ef,
+                                                        expand)
+                assert ids[s, h].tolist() == r_ids.tolist()
+                assert out_close(out[s, h], r_out, tol) and lse_close(lse[s, h], r_lse, tol)
+
+
+def test_exhaustive_beam_equals_bruteforce_and_full_attention():
+    """ef >= N: the search returns the exact top-k; with topk covering every non-static key
+    the decode output is Eq. 1 over the whole context."""
+    w = synth.make_integer_case(9, N=300, M=80, T=3, d=128, deg=8, knn=6, topk=5, ef=300,
+                                sink=4, window=20)
+    adj, ent, _ = oracle_graphs(w)
+    idx = ra.ra_index_import(torch.from_numpy(adj), torch.from_numpy(ent), 1, 1, 1)
+    Kd, Vd = w.K.to(DEV), w.V.to(DEV)
+    K, V = to_np(w.K[0, 0]), to_np(w.V[0, 0])
+    W = OA.static_ids(300, 4, 20)
+    for t in range(3):
+        q = w.q_decode[t].to(DEV)
+        ids, st = ra.ra_search(q, idx, Kd, 4, 20, 7, 300, 5)
+        assert ids[0, 0].tolist() == OM.topk_bruteforce(to_np(q[0, 0]), K, 7, exclude=W).tolist()
+        assert int(st[0, 0, 0]) == 300
+        out, lse, ids, _ = ra.ra_decode_step(q, idx, Kd, Vd, 4, 20, 276, 300, 3)
+        ref_o, ref_l = OA.full_attention(to_np(q[0, 0]), K, V)
+        assert sorted(ids[0, 0].tolist()) == list(range(4, 280))
+        assert out_close(out[0, 0].cpu().numpy(), ref_o, 1e-5)
+        assert lse_close(float(lse[0, 0]), ref_l, 1e-5)
+
+
+@pytest.mark.parametrize("sink,window,topk", [(0, 0, 8), (500, 0, 8), (0, 500, 8), (7, 1, 60),
+                                              (2, 3, 40)])
+def test_edge_static_sets_and_padding(sink, window, topk):
+    w = synth.make_integer_case(2, N=70, M=30, T=2, d=128, deg=6, knn=5)
+    adj, ent, _ = oracle_graphs(w)
+    idx = ra.ra_index_import(torch.from_numpy(adj), torch.from_numpy(ent), 1, 1, 1)
+    Kd, Vd = w.K.to(DEV), w.V.to(DEV)
+    K, V = to_np(w.K[0, 0]), to_np(w.V[0, 0])
+    for t in range(2):
+        q = w.q_decode[t].to(DEV)
+        out, lse, ids, st = ra.ra_decode_step(q, idx, Kd, Vd, sink, window, topk, 64, 2)
+        r_out, r_lse, r_ids, rst = OD.decode_step(to_np(q[0, 0]), K, V, adj[0], ent[0], sink, window,
+                                                  topk, 64, 2)
+        assert ids[0, 0].tolist() == r_ids.tolist()
+        assert int(st[0, 0, 3]) == rst["n_returned"]
+        assert out_close(out[0, 0].cpu().numpy(), r_out, 1e-5)
+        assert lse_close(float(lse[0, 0]), r_lse, 1e-5)
+
+
+def test_argument_errors_reach_python():
+    w, adj, ent, idx, Kd, Vd = _prepared("integer_ties")
+    q = w.q_decode[0].to(DEV)
+    with pytest.raises(ra.RaError) as e:
+        ra.ra_search(q, idx, Kd, 0, 0, 10, 5, 1)          # ef < topk
+    assert e.value.status == 1
+    with pytest.raises(ra.RaError) as e:
+        ra.ra_search(q, idx, Kd[:, :, :100].contiguous(), 0, 0, 5, 10, 1)    # N mismatch
+    assert e.value.status == 2
