@@ -1,6 +1,414 @@
+// Projection of the query->key KNN lists into a key-key graph (Sec. 3.2: keys connected to
+// the same query vectors are linked and the query vectors are dropped). Integer arithmetic
+// only, so identical lists give bit-identical graphs.
+//
+// Reading implemented (the paper states the step in one sentence):
+//   pop(i)  = number of lists holding key i;   c(a,b) = number of lists holding both;
+//   pi      = keys by (pop descending, id ascending); entry = pi[0];
+//   row(a)  = [pi[2t+1], pi[2t+2]] for a = pi[t] (a binary heap over popularity: every key is
+//             reachable from the entry) followed by a's co-listed keys ranked by the Jaccard
+//             overlap c / (pop(a) + pop(b) - c), ties by larger c, then lower id, until deg.
+//
+// Device plan, all stream-ordered, no host round trip:
+//   1. pop by atomic histogram over the list cells.
+//   2. one workgroup per graph: prefix sums over the keys (CSR offsets of the inverted lists,
+//      compaction of the keys with pop > 0), a stable 4-bit LSD radix sort of those keys by
+//      descending pop, and from it pi, its inverse pos, and the entry point.
+//   3. inverted lists (key -> the lists that hold it) filled through per-key cursors.
+//   4. backbone children and -1 padding for every row (fully coalesced).
+//   5. persistent workgroups walk the populated keys in pi order (largest first): for key a
+//      they stream the lists that hold a, bump a counter per co-listed key (table indexed by
+//      pos, so it is as small as the populated set), collect first-touched keys as the
+//      candidate list, then extract the best `deg` candidates by repeated exact arg-max
+//      (fractions compared by 64-bit cross-multiplication), reset the touched counters and
+//      write the row.
+// No global sort of the M*knn*(knn-1) co-occurrence pairs is needed: the skewed keys that sit
+// in nearly every list are simply the longest-running work items and are scheduled first.
 #include "common.h"
-size_t ra_project_workspace_bytes(int, int64_t, int64_t, int) { return 256; }
-ra_status ra_launch_project(const int32_t*, int, int64_t, int64_t, int, int, void*, hipStream_t,
-                            int32_t*, int32_t*) {
-    RA_FAIL(RA_EUNSUP, "ra_project not built yet");
+
+#define PJ_T 1024                 // threads of the ordering kernel
+#define PJ_ROW_T 256              // threads of the row kernel
+#define PJ_MAX_WG 2048
+
+typedef unsigned long long u64;
+
+struct ProjWs {                   // per-graph device arrays, carved from one workspace
+    int32_t* pop;                 // [N]
+    int32_t* pos;                 // [N]   position of key in pi
+    int32_t* pi;                  // [N]
+    int32_t* off;                 // [N+1] CSR offsets of inverted lists
+    int32_t* cur;                 // [N]   fill cursors
+    int32_t* inv;                 // [M*knn]
+    int32_t* hk[2];               // [cap] radix ping-pong: keys
+    int32_t* hi[2];               // [cap] radix ping-pong: ids
+    int32_t* H;                   // [1]   number of populated keys
+};
+
+static size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
+
+struct ProjLayout {
+    size_t per_graph, o_pop, o_pos, o_pi, o_off, o_cur, o_inv, o_hk0, o_hk1, o_hi0, o_hi1, o_H;
+    size_t scratch_per_wg, o_scratch;
+    int n_wg;
+    int64_t cap;
+};
+
+static ProjLayout proj_layout(int n_graphs, int64_t N, int64_t M, int knn) {
+    ProjLayout l;
+    const int64_t cells = M * knn;
+    l.cap = N < cells ? N : cells;
+    size_t o = 0;
+    l.o_pop = o; o += align256((size_t)N * 4);
+    l.o_pos = o; o += align256((size_t)N * 4);
+    l.o_pi = o; o += align256((size_t)N * 4);
+    l.o_off = o; o += align256((size_t)(N + 1) * 4);
+    l.o_cur = o; o += align256((size_t)N * 4);
+    l.o_inv = o; o += align256((size_t)cells * 4);
+    l.o_hk0 = o; o += align256((size_t)l.cap * 4);
+    l.o_hk1 = o; o += align256((size_t)l.cap * 4);
+    l.o_hi0 = o; o += align256((size_t)l.cap * 4);
+    l.o_hi1 = o; o += align256((size_t)l.cap * 4);
+    l.o_H = o; o += 256;
+    l.per_graph = o;
+    // row kernel scratch: per workgroup a counter table and a candidate list of `cap` entries
+    l.scratch_per_wg = align256((size_t)l.cap * 4) * 2;
+    int per_graph_wg = 64;
+    while (per_graph_wg > 1 &&
+           ((size_t)per_graph_wg * n_graphs > PJ_MAX_WG ||
+            (size_t)per_graph_wg * n_graphs * l.scratch_per_wg > ((size_t)3 << 30)))
+        per_graph_wg >>= 1;
+    l.n_wg = per_graph_wg;
+    l.o_scratch = l.per_graph * n_graphs;
+    return l;
+}
+
+size_t ra_project_workspace_bytes(int n_graphs, int64_t N, int64_t M, int knn) {
+    const ProjLayout l = proj_layout(n_graphs, N, M, knn);
+    return l.o_scratch + (size_t)l.n_wg * n_graphs * l.scratch_per_wg;
+}
+
+__device__ __forceinline__ ProjWs carve(char* ws, const ProjLayout& l, int g) {
+    char* b = ws + (size_t)g * l.per_graph;
+    ProjWs w;
+    w.pop = (int32_t*)(b + l.o_pop); w.pos = (int32_t*)(b + l.o_pos); w.pi = (int32_t*)(b + l.o_pi);
+    w.off = (int32_t*)(b + l.o_off); w.cur = (int32_t*)(b + l.o_cur); w.inv = (int32_t*)(b + l.o_inv);
+    w.hk[0] = (int32_t*)(b + l.o_hk0); w.hk[1] = (int32_t*)(b + l.o_hk1);
+    w.hi[0] = (int32_t*)(b + l.o_hi0); w.hi[1] = (int32_t*)(b + l.o_hi1);
+    w.H = (int32_t*)(b + l.o_H);
+    return w;
+}
+
+// ---- 0. clear --------------------------------------------------------------------------
+__global__ void pj_zero_kernel(char* ws, ProjLayout l, int64_t N, int n_graphs) {
+    const int g = blockIdx.y;
+    ProjWs w = carve(ws, l, g);
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < N;
+         i += (int64_t)gridDim.x * blockDim.x) {
+        w.pop[i] = 0;
+        w.cur[i] = 0;
+    }
+    // counter tables of the row kernel must start at zero
+    uint32_t* sc = (uint32_t*)(ws + l.o_scratch);
+    const size_t words = (size_t)l.n_wg * n_graphs * l.scratch_per_wg / 4;
+    const size_t stride = (size_t)gridDim.x * gridDim.y * blockDim.x;
+    for (size_t i = ((size_t)blockIdx.y * gridDim.x + blockIdx.x) * blockDim.x + threadIdx.x;
+         i < words; i += stride)
+        sc[i] = 0u;
+}
+
+// ---- 1. pop ----------------------------------------------------------------------------
+__global__ void pj_pop_kernel(const int32_t* __restrict__ L, char* ws, ProjLayout l, int64_t cells,
+                              int64_t N) {
+    const int g = blockIdx.y;
+    ProjWs w = carve(ws, l, g);
+    const int32_t* Lg = L + (size_t)g * cells;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < cells;
+         i += (int64_t)gridDim.x * blockDim.x) {
+        const int32_t k = Lg[i];
+        if (k >= 0 && k < N) atomicAdd(&w.pop[k], 1);
+    }
+}
+
+// ---- 2. ordering -----------------------------------------------------------------------
+// exclusive scan of one int per thread over the workgroup; *total receives the sum
+__device__ __forceinline__ int block_exscan(int v, int* wsum, int* total) {
+    const int lane = threadIdx.x & 63, wv = threadIdx.x >> 6, nw = blockDim.x >> 6;
+    int inc = v;
+#pragma unroll
+    for (int d = 1; d < 64; d <<= 1) {
+        const int n = __shfl_up(inc, d);
+        if (lane >= d) inc += n;
+    }
+    if (lane == 63) wsum[wv] = inc;
+    __syncthreads();
+    int base = 0, tot = 0;
+    for (int i = 0; i < nw; ++i) {
+        const int s = wsum[i];
+        if (i < wv) base += s;
+        tot += s;
+    }
+    __syncthreads();
+    *total = tot;
+    return base + inc - v;
+}
+
+__global__ __launch_bounds__(PJ_T) void pj_order_kernel(char* ws, ProjLayout l, int64_t N, int64_t M,
+                                                        int32_t* __restrict__ entry) {
+    __shared__ int wsum[PJ_T / 64];
+    __shared__ int wtot[PJ_T / 64][16];
+    __shared__ int base[16];
+    const int g = blockIdx.x, tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+    ProjWs w = carve(ws, l, g);
+
+    // A. compaction of populated keys (ascending id), CSR offsets, zero-pop ranks
+    int hot_run = 0, off_run = 0;
+    for (int64_t b0 = 0; b0 < N; b0 += PJ_T) {
+        const int64_t i = b0 + tid;
+        const int p = i < N ? w.pop[i] : 0;
+        const int hot = p > 0 ? 1 : 0;
+        int th, tp;
+        const int eh = block_exscan(hot, wsum, &th);
+        const int ep = block_exscan(p, wsum, &tp);
+        if (i < N) {
+            w.off[i] = off_run + ep;
+            const int hr = hot_run + eh;
+            if (hot) {
+                w.hi[0][hr] = (int)i;
+                w.hk[0][hr] = (int)(M - p);          // ascending key = descending pop
+            } else {
+                w.pos[i] = (int)i - hr;              // rank among zero-pop keys (H added below)
+            }
+        }
+        hot_run += th;
+        off_run += tp;
+    }
+    const int H = hot_run;
+    if (tid == 0) {
+        w.off[N] = off_run;
+        *w.H = H;
+    }
+    __syncthreads();
+
+    // B. stable LSD radix sort of (key, id) by key, 4 bits per pass
+    int bits = 1;
+    while (((int64_t)1 << bits) < M) ++bits;
+    int src = 0;
+    for (int shift = 0; shift < bits; shift += 4) {
+        if (tid < 16) base[tid] = 0;
+        __syncthreads();
+        for (int b0 = 0; b0 < H; b0 += PJ_T) {
+            const int i = b0 + tid;
+            if (i < H) atomicAdd(&base[(w.hk[src][i] >> shift) & 15], 1);
+        }
+        __syncthreads();
+        if (tid == 0) {
+            int run = 0;
+            for (int v = 0; v < 16; ++v) {
+                const int c = base[v];
+                base[v] = run;
+                run += c;
+            }
+        }
+        __syncthreads();
+        for (int b0 = 0; b0 < H; b0 += PJ_T) {
+            const int i = b0 + tid;
+            const bool valid = i < H;
+            const int key = valid ? w.hk[src][i] : 0, id = valid ? w.hi[src][i] : 0;
+            const int dg = (key >> shift) & 15;
+            int wrank = 0;
+#pragma unroll
+            for (int v = 0; v < 16; ++v) {
+                const u64 mask = __ballot(valid && dg == v);
+                if (dg == v) wrank = __popcll(mask & ((1ull << lane) - 1ull));
+                if (lane == 0) wtot[wv][v] = __popcll(mask);
+            }
+            __syncthreads();
+            if (valid) {
+                int before = 0;
+                for (int x = 0; x < wv; ++x) before += wtot[x][dg];
+                const int dst = base[dg] + before + wrank;
+                w.hk[src ^ 1][dst] = key;
+                w.hi[src ^ 1][dst] = id;
+            }
+            __syncthreads();
+            if (tid < 16) {
+                int add = 0;
+                for (int x = 0; x < PJ_T / 64; ++x) add += wtot[x][tid];
+                base[tid] += add;
+            }
+            __syncthreads();
+        }
+        src ^= 1;
+    }
+    __syncthreads();
+
+    // C. pi, pos, entry
+    for (int t = tid; t < H; t += PJ_T) {
+        const int id = w.hi[src][t];
+        w.pi[t] = id;
+        w.pos[id] = t;
+    }
+    for (int64_t i = tid; i < N; i += PJ_T) {
+        if (w.pop[i] == 0) {
+            const int p = H + w.pos[i];
+            w.pos[i] = p;
+            w.pi[p] = (int)i;
+        }
+    }
+    if (tid == 0) entry[g] = H > 0 ? w.hi[src][0] : 0;
+}
+
+// ---- 3. inverted lists -----------------------------------------------------------------
+__global__ void pj_inv_kernel(const int32_t* __restrict__ L, char* ws, ProjLayout l, int64_t cells,
+                              int knn, int64_t N) {
+    const int g = blockIdx.y;
+    ProjWs w = carve(ws, l, g);
+    const int32_t* Lg = L + (size_t)g * cells;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < cells;
+         i += (int64_t)gridDim.x * blockDim.x) {
+        const int32_t k = Lg[i];
+        if (k >= 0 && k < N) {
+            const int slot = atomicAdd(&w.cur[k], 1);
+            w.inv[w.off[k] + slot] = (int32_t)(i / knn);
+        }
+    }
+}
+
+// ---- 4. backbone + padding for every row -----------------------------------------------
+__global__ void pj_backbone_kernel(char* ws, ProjLayout l, int64_t N, int deg,
+                                   int32_t* __restrict__ adj) {
+    const int g = blockIdx.y;
+    ProjWs w = carve(ws, l, g);
+    int32_t* adj_g = adj + (size_t)g * N * deg;
+    const int64_t cells = N * deg;
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < cells;
+         i += (int64_t)gridDim.x * blockDim.x) {
+        const int64_t a = i / deg;
+        const int slot = (int)(i % deg);
+        int32_t v = -1;
+        if (slot < 2) {
+            const int64_t ch = 2 * (int64_t)w.pos[a] + 1 + slot;
+            if (ch < N) v = w.pi[ch];
+        }
+        adj_g[i] = v;
+    }
+}
+
+// ---- 5. rows of populated keys ---------------------------------------------------------
+struct Cand { uint32_t c, pb; int32_t b; };
+
+// is x ranked before y for a key of popularity pa?  (Jaccard desc, count desc, id asc)
+__device__ __forceinline__ bool cand_before(const Cand& x, const Cand& y, uint32_t pa) {
+    const u64 lhs = (u64)x.c * (u64)(pa + y.pb - y.c);
+    const u64 rhs = (u64)y.c * (u64)(pa + x.pb - x.c);
+    if (lhs != rhs) return lhs > rhs;
+    if (x.c != y.c) return x.c > y.c;
+    return x.b < y.b;
+}
+
+__global__ __launch_bounds__(PJ_ROW_T) void pj_rows_kernel(const int32_t* __restrict__ L, char* ws,
+                                                           ProjLayout l, int64_t N, int64_t M,
+                                                           int knn, int deg,
+                                                           int32_t* __restrict__ adj) {
+    __shared__ int s_ncand;
+    __shared__ Cand s_red[PJ_ROW_T / 64];
+    __shared__ Cand s_prev;
+    __shared__ int32_t s_sel[RA_MAX_DEG];
+    __shared__ int s_nsel;
+    const int g = blockIdx.y, tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+    ProjWs w = carve(ws, l, g);
+    const int32_t* Lg = L + (size_t)g * M * knn;
+    int32_t* adj_g = adj + (size_t)g * N * deg;
+    char* sc = ws + l.o_scratch + ((size_t)g * gridDim.x + blockIdx.x) * l.scratch_per_wg;
+    uint32_t* cnt = (uint32_t*)sc;                                 // [cap] indexed by pos
+    int32_t* cand = (int32_t*)(sc + l.scratch_per_wg / 2);         // [cap]
+    const int H = *w.H;
+
+    for (int t = blockIdx.x; t < H; t += gridDim.x) {
+        const int a = w.pi[t];
+        const uint32_t pa = (uint32_t)w.pop[a];
+        const int o0 = w.off[a];
+        if (tid == 0) { s_ncand = 0; s_nsel = 0; }
+        __syncthreads();
+        // count co-listed keys
+        const int64_t work = (int64_t)pa * knn;
+        for (int64_t x = tid; x < work; x += PJ_ROW_T) {
+            const int j = w.inv[o0 + (int)(x / knn)];
+            const int b = Lg[(size_t)j * knn + (int)(x % knn)];
+            if (b != a && b >= 0 && b < N) {
+                if (atomicAdd(&cnt[w.pos[b]], 1u) == 0u) cand[atomicAdd(&s_ncand, 1)] = b;
+            }
+        }
+        __syncthreads();
+        const int nc = s_ncand;
+        const int want = nc < deg ? nc : deg;
+        // extract the best `want` candidates, one exact arg-max per round
+        for (int r = 0; r < want; ++r) {
+            Cand best; best.c = 0; best.pb = 0; best.b = -1;
+            const Cand prev = s_prev;               // valid from round 1 on
+            for (int x = tid; x < nc; x += PJ_ROW_T) {
+                Cand cd;
+                cd.b = cand[x];
+                cd.c = cnt[w.pos[cd.b]];
+                cd.pb = (uint32_t)w.pop[cd.b];
+                if (r > 0 && !cand_before(prev, cd, pa)) continue;     // already taken
+                if (best.b < 0 || cand_before(cd, best, pa)) best = cd;
+            }
+#pragma unroll
+            for (int d = 32; d > 0; d >>= 1) {
+                Cand o;
+                o.c = __shfl_xor(best.c, d); o.pb = __shfl_xor(best.pb, d); o.b = __shfl_xor(best.b, d);
+                if (o.b >= 0 && (best.b < 0 || cand_before(o, best, pa))) best = o;
+            }
+            if (lane == 0) s_red[wv] = best;
+            __syncthreads();
+            if (tid == 0) {
+                Cand bb = s_red[0];
+                for (int x = 1; x < PJ_ROW_T / 64; ++x) {
+                    const Cand o = s_red[x];
+                    if (o.b >= 0 && (bb.b < 0 || cand_before(o, bb, pa))) bb = o;
+                }
+                s_prev = bb;
+                s_sel[s_nsel++] = bb.b;
+            }
+            __syncthreads();
+        }
+        // reset the touched counters for the next key
+        for (int x = tid; x < nc; x += PJ_ROW_T) cnt[w.pos[cand[x]]] = 0u;
+        // row = backbone children, then ranked candidates not already present
+        if (tid == 0) {
+            int32_t* row = adj_g + (size_t)a * deg;
+            int n = 0;
+            int32_t kids[2] = {-1, -1};
+            for (int s = 0; s < 2 && n < deg; ++s) {
+                const int64_t ch = 2 * (int64_t)t + 1 + s;
+                if (ch < N) { kids[s] = w.pi[ch]; row[n++] = kids[s]; }
+            }
+            for (int x = 0; x < s_nsel && n < deg; ++x) {
+                const int32_t b = s_sel[x];
+                if (b != kids[0] && b != kids[1]) row[n++] = b;
+            }
+            for (; n < deg; ++n) row[n] = -1;
+        }
+        __syncthreads();
+    }
+}
+
+ra_status ra_launch_project(const int32_t* L, int n_graphs, int64_t N, int64_t M, int knn, int deg,
+                            void* workspace, hipStream_t st, int32_t* adj, int32_t* entry) {
+    if (M * (int64_t)knn >= ((int64_t)1 << 31))
+        RA_FAIL(RA_EUNSUP, "M * knn must stay below 2^31 list cells");
+    const ProjLayout l = proj_layout(n_graphs, N, M, knn);
+    char* ws = (char*)workspace;
+    const int64_t cells = M * knn;
+    const unsigned gx = 256;
+    hipLaunchKernelGGL(pj_zero_kernel, dim3(gx, n_graphs), dim3(256), 0, st, ws, l, N, n_graphs);
+    hipLaunchKernelGGL(pj_pop_kernel, dim3(gx, n_graphs), dim3(256), 0, st, L, ws, l, cells, N);
+    hipLaunchKernelGGL(pj_order_kernel, dim3(n_graphs), dim3(PJ_T), 0, st, ws, l, N, M, entry);
+    hipLaunchKernelGGL(pj_inv_kernel, dim3(gx, n_graphs), dim3(256), 0, st, L, ws, l, cells, knn, N);
+    hipLaunchKernelGGL(pj_backbone_kernel, dim3(gx, n_graphs), dim3(256), 0, st, ws, l, N, deg, adj);
+    hipLaunchKernelGGL(pj_rows_kernel, dim3(l.n_wg, n_graphs), dim3(PJ_ROW_T), 0, st, L, ws, l, N, M,
+                       knn, deg, adj);
+    RA_HIP(hipGetLastError());
+    return RA_OK;
 }

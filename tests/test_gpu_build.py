@@ -1,0 +1,136 @@
+"""Parity of the HIP index build (exact KNN on the matrix cores, projection) with the CPU
+oracle, through the C ABI. GPU only."""
+import json
+import os
+
+import numpy as np
+import pytest
+import torch
+
+import paper_2409_10516_amd as ra
+from oracle import attention as OA, decode as OD, mips as OM, projection as OP
+from paper_2409_10516_amd import synth
+from tests.util import knn_equivalent, lse_close, out_close, to_np, tol_for
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+GOLD = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def _cases():
+    return {
+        "config0_small": lambda: synth.make_config0(N=1024, M=256, T=2, window=32),
+        "llama_bf16": lambda: synth.make_llama_layer(11, N=1536, M=768, T=2, n_q=8, n_kv=2,
+                                                     ef=64, topk=20, window=100),
+        "llama_f32_ragged": lambda: synth.make_llama_layer(12, N=701, M=299, T=2, n_seq=2, n_q=4,
+                                                           n_kv=4, dtype=torch.float32, ef=48,
+                                                           topk=16, window=37, deg=12, knn=9),
+        "integer_ties": lambda: synth.make_integer_case(5, N=200, M=64, T=2, d=128, n_q=2,
+                                                        n_kv=1, deg=8, knn=6, topk=9, ef=20,
+                                                        sink=3, window=10),
+        "integer_bf16_knn64": lambda: synth.make_integer_case(6, N=333, M=150, T=2, d=128, n_q=1,
+                                                              n_kv=1, dtype=torch.bfloat16, deg=64,
+                                                              knn=64, topk=9, ef=20),
+    }
+
+
+def _heads(w):
+    n_seq, n_kv, N, d = w.K.shape
+    n_q = w.Q_prefill.shape[1]
+    for s in range(n_seq):
+        for h in range(n_q):
+            yield s, h, s * n_q + h, to_np(w.K[s, h // (n_q // n_kv)]), to_np(w.Q_prefill[s, h])
+
+
+@pytest.mark.parametrize("name", list(_cases()))
+def test_knn_lists(name):
+    w = _cases()[name]()
+    L = ra.ra_knn(w.K.to(DEV), w.Q_prefill.to(DEV), w.knn).cpu().numpy()
+    for s, h, g, K, Q in _heads(w):
+        ref, _ = OM.knn_lists(Q, K, w.knn)
+        diff = knn_equivalent(L[s, h], ref, Q, K)
+        if name.startswith("integer"):
+            assert diff == 0          # integer-valued inputs: every score is exact
+
+
+def test_projection_hand_worked_example():
+    g = json.load(open(os.path.join(GOLD, "projection_hand.json")))
+    L = torch.tensor([g["L"]], dtype=torch.int32, device=DEV)
+    adj, entry = ra.ra_project(L, g["N"], g["deg"])
+    assert entry.cpu().tolist() == [g["entry"]]
+    assert adj[0].cpu().tolist() == g["adj"]
+
+
+@pytest.mark.parametrize("name", list(_cases()))
+@pytest.mark.parametrize("deg", [None, 2, 5])
+def test_projection_bit_exact_on_oracle_lists(name, deg):
+    w = _cases()[name]()
+    deg = deg or w.deg
+    N = w.K.shape[2]
+    Ls, refs = [], []
+    for s, h, g, K, Q in _heads(w):
+        L, _ = OM.knn_lists(Q, K, w.knn)
+        Ls.append(L)
+        refs.append(OP.project(L, N, deg))
+    adj, entry = ra.ra_project(torch.from_numpy(np.stack(Ls)).to(DEV), N, deg)
+    adj, entry = adj.cpu().numpy(), entry.cpu().numpy()
+    for g, (radj, rent) in enumerate(refs):
+        assert entry[g] == rent
+        assert np.array_equal(adj[g], radj), np.argwhere(adj[g] != radj)[:5]
+
+
+def test_projection_skewed_lists():
+    """Every list holds the same two hub keys plus a few others (the shape the Llama-like
+    generator produces at scale), and some keys are in no list at all."""
+    rng = np.random.default_rng(0)
+    N, M, knn, deg = 500, 400, 8, 10
+    L = np.empty((M, knn), np.int32)
+    for j in range(M):
+        rest = rng.choice(np.arange(2, 120), size=knn - 2, replace=False)
+        L[j] = np.concatenate([[0, 1], rest])[rng.permutation(knn)]
+    radj, rent = OP.project(L, N, deg)
+    adj, entry = ra.ra_project(torch.from_numpy(L[None]).to(DEV), N, deg)
+    assert int(entry[0]) == rent
+    assert np.array_equal(adj[0].cpu().numpy(), radj)
+
+
+@pytest.mark.parametrize("name", list(_cases()))
+def test_build_index_then_decode(name):
+    """ra_build_index = KNN + projection; its graph must be the oracle's projection of the
+    device's own KNN lists (which may differ from the float64 lists only in near-ties), and a
+    decode step on it must match the oracle run on the exported graph."""
+    w = _cases()[name]()
+    Kd, Vd, Qd = w.K.to(DEV), w.V.to(DEV), w.Q_prefill.to(DEV)
+    n_seq, n_kv, N, d = w.K.shape
+    n_q = w.Q_prefill.shape[1]
+    L = ra.ra_knn(Kd, Qd, w.knn).cpu().numpy()
+    idx = ra.ra_build_index(Kd, Qd, w.deg, w.knn)
+    assert (idx.n_seq, idx.n_q_heads, idx.n_kv_heads, idx.N, idx.deg) == (n_seq, n_q, n_kv, N, w.deg)
+    tol = tol_for(w.K.dtype)
+    q = w.q_decode[0]
+    out, lse, ids, st = ra.ra_decode_step(q.to(DEV), idx, Kd, Vd, w.sink, w.window, w.topk, w.ef, 4)
+    out, lse, ids = out.cpu().numpy(), lse.cpu().numpy(), ids.cpu().numpy()
+    for s, h, g, K, Q in _heads(w):
+        radj, rent = OP.project(L[s, h], N, w.deg)
+        adj, ent = ra.ra_index_export(idx, s, h)
+        assert ent == rent and np.array_equal(adj.numpy(), radj)
+        V = to_np(w.V[s, h // (n_q // n_kv)])
+        r_out, r_lse, r_ids, _ = OD.decode_step(to_np(q[s, h]), K, V, radj, rent, w.sink, w.window,
+                                                w.topk, w.ef, 4)
+        assert ids[s, h].tolist() == r_ids.tolist()
+        assert out_close(out[s, h], r_out, tol) and lse_close(lse[s, h], r_lse, tol)
+    idx.free()
+
+
+def test_build_argument_errors():
+    w = synth.make_integer_case(1, N=64, M=16, d=128)
+    Kd, Qd = w.K.to(DEV), w.Q_prefill.to(DEV)
+    with pytest.raises(ra.RaError) as e:
+        ra.ra_knn(Kd, Qd, 65)                        # knn > N
+    assert e.value.status == 1
+    with pytest.raises(ra.RaError) as e:
+        ra.ra_build_index(Kd, Qd, 1, 4)              # deg < 2
+    assert e.value.status == 1
+    with pytest.raises(ra.RaError) as e:
+        ra.ra_build_index(Kd[..., :64].contiguous(), Qd[..., :64].contiguous(), 8, 4)   # d != 128
+    assert e.value.status == 6
