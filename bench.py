@@ -21,6 +21,10 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
+# HBM bytes per search_kernel launch of the default workload, from the two rocprofv3 --pmc runs
+# summarised in profiles/search_attend_config2_hbm_counters.md (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0,
+# KiB per dispatch, scale factors from a 1 GiB device copy in the same runs).
+SEARCH_TRAFFIC_BYTES_CONFIG2 = (8577 + 14) * 1024
 MFMA_BF16_PEAK_TFLOPS = 2500.0
 
 
@@ -39,6 +43,8 @@ def parse():
     p.add_argument("--cpu-heads", type=int, default=16, help="heads the CPU oracle is timed on")
     p.add_argument("--no-cpu-baseline", action="store_true")
     p.add_argument("--graph", type=int, default=1, help="replay the step from a captured HIP graph")
+    p.add_argument("--copy-calibration", action="store_true",
+                   help="also run three plain 1 GiB device copies (reference for HBM counters)")
     return p.parse_args()
 
 
@@ -192,6 +198,14 @@ def main():
     attend_bytes = returned * 2 * d * esz + n_seq * n_kv * W * 2 * d * esz
     attend_gbs = attend_bytes / (attend_ms * 1e-3) / 1e9
 
+    if a.copy_calibration:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device=dev).fill_(1)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
+
     # ---- recall@100 against brute force (CPU oracle) on a sample of layers ---------------
     from oracle import attention as OA, mips as OM
     rec = []
@@ -251,7 +265,9 @@ def main():
                    "sink": sink, "window": window, "hip_graph": bool(a.graph)},
         "roofline": {"bound": "hbm", "kernel": "search_kernel", "achieved": search_gbs,
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": search_gbs / HBM_PEAK_GBS,
-                     "traffic": None, "avg_launch_ms": search_ms,
+                     "traffic": (SEARCH_TRAFFIC_BYTES_CONFIG2 if (a.workload == "config2" and a.expand == 32
+                                 and not a.context) else None),
+                     "avg_launch_ms": search_ms,
                      "algorithmic_bytes_per_launch": search_bytes,
                      "visited_per_search": visited / heads, "expanded_per_search": expanded / heads,
                      "iters_per_search": iters / heads},
