@@ -21,10 +21,10 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
-# HBM bytes per search_kernel launch of the default workload, from the two rocprofv3 --pmc runs
-# summarised in profiles/search_attend_config2_hbm_counters.md (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0,
-# KiB per dispatch, scale factors from a 1 GiB device copy in the same runs).
-SEARCH_TRAFFIC_BYTES_CONFIG2 = (8577 + 14) * 1024
+# HBM bytes per decode_kernel launch of the default workload, from the two rocprofv3 --pmc runs
+# summarised under profiles/ (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0, KiB per dispatch, scale factors
+# from a 1 GiB device copy in the same runs).
+DECODE_TRAFFIC_BYTES_CONFIG2 = None
 MFMA_BF16_PEAK_TFLOPS = 2500.0
 
 
@@ -168,34 +168,46 @@ def main():
     wall = time.perf_counter() - t0
     ms_per_step = 1e3 * wall / a.steps
 
-    # ---- dominant kernel (graph search): live HIP-event timing on the launch stream -------
-    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
-          for _ in range(a.steps * len(layers))]
-    ev_at = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
-             for _ in range(a.steps * len(layers))]
+    # ---- dominant kernel: live HIP-event timing on the launch stream ----------------------
+    # The timed region launches one fused kernel per layer (decode_kernel: search, sparse and
+    # static attention, combination). It is timed here launch by launch; the stand-alone stage
+    # kernels (ra_search, ra_attend) are timed the same way for the breakdown.
+    def timed_pass(fn):
+        evs = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
+               for _ in range(a.steps * len(layers))]
+        i = 0
+        for t in range(a.steps):
+            for L in layers:
+                evs[i][0].record()
+                fn(L, t)
+                evs[i][1].record()
+                i += 1
+        torch.cuda.synchronize()
+        return sum(s_.elapsed_time(e_) for s_, e_ in evs) / len(evs)
+
+    def fused_only(L, t):
+        ra.ra_decode_step(L["q"][t % T], L["idx"], L["K"], L["V"], sink, window, topk, ef, a.expand,
+                          out=L["out"], lse=L["lse"], ids=L["ids"], stats=L["st"])
+
     stats_sum = np.zeros(4, np.float64)
-    i = 0
-    for t in range(a.steps):
-        for L in layers:
-            ev[i][0].record()
-            search_only(L, t)
-            ev[i][1].record()
-            ev_at[i][0].record()
-            attend_only(L, t)
-            ev_at[i][1].record()
-            i += 1
+    decode_ms = timed_pass(fused_only)
+    for t in range(T):
+        step(t)
         torch.cuda.synchronize()
         for L in layers:
             stats_sum += L["st"].double().sum(dim=(0, 1)).cpu().numpy()
-    n_launch = a.steps * len(layers)
-    search_ms = sum(s.elapsed_time(e) for s, e in ev) / n_launch
-    attend_ms = sum(s.elapsed_time(e) for s, e in ev_at) / n_launch
+    search_ms = timed_pass(search_only)
+    attend_ms = timed_pass(attend_only)
+    n_launch = T * len(layers)
     visited, expanded, iters, returned = stats_sum / n_launch      # per launch (all heads)
-    # algorithmic bytes of one search launch: key rows scored + adjacency rows read + q + ids
+    # algorithmic bytes of one launch: key rows scored + adjacency rows read + q + ids (search),
+    # retrieved K/V rows per query head + static K/V rows per KV head (attention)
     search_bytes = visited * d * esz + expanded * deg * 4 + heads * (d * esz + topk * 4)
-    search_gbs = search_bytes / (search_ms * 1e-3) / 1e9
     W = min(N, sink + window)
     attend_bytes = returned * 2 * d * esz + n_seq * n_kv * W * 2 * d * esz
+    decode_bytes = search_bytes + attend_bytes
+    decode_gbs = decode_bytes / (decode_ms * 1e-3) / 1e9
+    search_gbs = search_bytes / (search_ms * 1e-3) / 1e9
     attend_gbs = attend_bytes / (attend_ms * 1e-3) / 1e9
 
     if a.copy_calibration:
@@ -263,16 +275,17 @@ def main():
                                f"{n_kv} kv heads, d={d}, N={N}, M={N} prefill queries/head",
                    "topk": topk, "ef": ef, "expand": a.expand, "deg": deg, "knn": w0.knn,
                    "sink": sink, "window": window, "hip_graph": bool(a.graph)},
-        "roofline": {"bound": "hbm", "kernel": "search_kernel", "achieved": search_gbs,
-                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": search_gbs / HBM_PEAK_GBS,
-                     "traffic": (SEARCH_TRAFFIC_BYTES_CONFIG2 if (a.workload == "config2" and a.expand == 32
-                                 and not a.context) else None),
-                     "avg_launch_ms": search_ms,
-                     "algorithmic_bytes_per_launch": search_bytes,
+        "roofline": {"bound": "hbm", "kernel": "decode_kernel", "achieved": decode_gbs,
+                     "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": decode_gbs / HBM_PEAK_GBS,
+                     "traffic": (DECODE_TRAFFIC_BYTES_CONFIG2 if (a.workload == "config2"
+                                 and a.expand == 32 and not a.context) else None),
+                     "avg_launch_ms": decode_ms, "algorithmic_bytes_per_launch": decode_bytes,
                      "visited_per_search": visited / heads, "expanded_per_search": expanded / heads,
                      "iters_per_search": iters / heads},
-        "attend": {"avg_launch_ms": attend_ms, "achieved_GBs": attend_gbs,
-                   "frac": attend_gbs / HBM_PEAK_GBS},
+        "stages": {"ra_search": {"avg_launch_ms": search_ms, "algorithmic_GBs": search_gbs,
+                                 "algorithmic_bytes_per_launch": search_bytes},
+                   "ra_attend": {"avg_launch_ms": attend_ms, "algorithmic_GBs": attend_gbs,
+                                 "algorithmic_bytes_per_launch": attend_bytes}},
         "build": {"seconds": t_build, "generate_seconds": t_gen,
                   "knn_TFLOPs_incl_projection": build_flop / max(t_build, 1e-9) / 1e12},
         "cpu_baseline": cpu,

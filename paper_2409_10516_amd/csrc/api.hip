@@ -291,7 +291,10 @@ extern "C" ra_status ra_decode_step(const void* q, const ra_index* idx, const vo
                     (size_t)ix->n_seq * ix->n_q * topk * sizeof(int32_t)));
         ids = ix->ids_ws;
     }
-    RA_TRY(ra_search(q, idx, K, dt, N, sink, window, topk, ef, expand, stream, ids, stats));
-    return ra_attend(q, idx, K, V, dt, N, sink, window, topk, ids, stream, out, lse, nullptr,
-                     nullptr, nullptr, nullptr);
+    const size_t heads = (size_t)ix->n_seq * ix->n_q;
+    if (ra_decode_needs_global_bitset(N, ix->deg, ef, expand, topk))
+        RA_TRY(grow((void**)&ix->bitset, &ix->bitset_bytes, heads * ((N + 31) >> 5) * 4));
+    return ra_launch_decode(q, ix->adj, ix->entry, K, V, dt, ix->n_seq, ix->n_q, ix->n_kv, N, ix->deg,
+                            sink, window, topk, ef, expand, ix->bitset, (hipStream_t)stream, out, lse,
+                            ids, stats);
 }

@@ -1,0 +1,241 @@
+// Sparse attention over the retrieved set Omega (Eq. 2), dense attention over the static
+// set W (Sec. 3.3), and their exact combination (Appendix A, Eq. 4-5).
+//
+// Split-row design for a part with 256 CUs and few heads in flight: the rows of W and of
+// Omega are cut into chunks of 64; one workgroup turns one chunk into a partial record
+// (un-normalised sum of exp(z - m) v, the local maximum m, the local sum l). W chunks
+// are shared by the query heads of a GQA group (K/V rows are read once for all of them,
+// Appendix C: one KV copy per group); Omega chunks belong to one query head. A second tiny
+// kernel combines all records of a head with the re-scaling of Eq. 5 generalised from two
+// sets to P sets, and can also emit the two set-level results (o_W, lse_W), (o_Omega,
+// lse_Omega) of Eq. 4.
+//
+// Device functions shared by the stand-alone attention kernels and the fused decode kernel.
+//
+// Row access: 16 lanes read one 128-element row (16 B per lane for bf16, 2 x 16 B for
+// fp32), so a wavefront fetches 4 rows per load instruction and a workgroup 16.
+#pragma once
+#include "common.h"
+
+#define AT_CH 64            // rows per chunk
+#define AT_RS 132           // floats per partial record: 128 acc, m, l, 2 pad
+#define AT_THREADS 256
+
+struct RowSrc {             // which context rows a chunk covers
+    const int32_t* ids;     // gathered: ids of this head (nullptr for static)
+    int64_t N;
+    int s, w;               // static ranges [0,s) and [N-w,N)
+    int count;              // rows available (Wn or topk)
+    int interleave;         // 0: chunk c covers rows [64c, 64c+64). T > 0: T teams share rows
+                            // round-robin, chunk c / local row j covers row
+                            // (c / T) * 64 T + (c % T) * 16 + j % 16 + 16 T (j / 16)
+};
+
+__device__ __forceinline__ int64_t chunk_row(const RowSrc& src, int r) {
+    if (r >= src.count) return -1;
+    if (src.ids) {
+        const int64_t id = src.ids[r];
+        return id < src.N ? id : -1;          // -1 padding (or a bad id) is skipped
+    }
+    return r < src.s ? (int64_t)r : src.N - src.w + (r - src.s);
+}
+
+template <int DT>
+__device__ __forceinline__ void load_row8(const void* base, int64_t row, int lane16, float* o) {
+    if (DT == RA_BF16) {
+        const uint4 u = *reinterpret_cast<const uint4*>(
+            reinterpret_cast<const uint16_t*>(base) + row * RA_D + lane16 * 8);
+        o[0] = bf16_lo(u.x); o[1] = bf16_hi(u.x); o[2] = bf16_lo(u.y); o[3] = bf16_hi(u.y);
+        o[4] = bf16_lo(u.z); o[5] = bf16_hi(u.z); o[6] = bf16_lo(u.w); o[7] = bf16_hi(u.w);
+    } else {
+        const float4* p = reinterpret_cast<const float4*>(
+            reinterpret_cast<const float*>(base) + row * RA_D + lane16 * 8);
+        const float4 a = p[0], b = p[1];
+        o[0] = a.x; o[1] = a.y; o[2] = a.z; o[3] = a.w;
+        o[4] = b.x; o[5] = b.y; o[6] = b.z; o[7] = b.w;
+    }
+}
+
+template <int CTRL>
+__device__ __forceinline__ float at_dpp(float v) {
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xF, 0xF, true));
+}
+
+// One chunk for NH query heads that share the same K/V rows.
+// `tid` is the thread's index inside its team of AT_THREADS threads (a workgroup may hold
+// several teams, each with its own `smem`; every team must call this the same number of
+// times because it contains workgroup barriers). An inactive team computes on an empty row
+// source and writes nothing.
+template <int DT, int NH>
+__device__ void attend_chunk(int tid, bool active, const void* q0, const void* Kh, const void* Vh,
+                             const RowSrc& src, int chunk, float scale, float* rec0,
+                             int64_t rec_stride, float* smem) {
+    const int grp = tid >> 4, lane16 = tid & 15;
+    float qv[NH][8], acc[NH][8], m[NH], l[NH];
+#pragma unroll
+    for (int g = 0; g < NH; ++g) {
+        load_row8<DT>(q0, g, lane16, qv[g]);
+        m[g] = -INFINITY;
+        l[g] = 0.f;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) acc[g][e] = 0.f;
+    }
+    constexpr int RPG = AT_CH / 16;    // rows per 16-lane group
+    int64_t rid[RPG];
+    float kv[RPG][8], vv[RPG][8];
+#pragma unroll
+    for (int i = 0; i < RPG; ++i) {
+        const int r = src.interleave
+            ? (chunk / src.interleave) * AT_CH * src.interleave + (chunk % src.interleave) * 16 + grp +
+                  16 * src.interleave * i
+            : chunk * AT_CH + grp + 16 * i;
+        rid[i] = chunk_row(src, r);
+        if (rid[i] >= 0) {
+            load_row8<DT>(Kh, rid[i], lane16, kv[i]);
+            load_row8<DT>(Vh, rid[i], lane16, vv[i]);
+        }
+    }
+#pragma unroll
+    for (int i = 0; i < RPG; ++i) {
+        if (rid[i] < 0) continue;
+#pragma unroll
+        for (int g = 0; g < NH; ++g) {
+            float dot = 0.f;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) dot = fmaf(qv[g][e], kv[i][e], dot);
+            dot += at_dpp<0xB1>(dot);      // xor 1
+            dot += at_dpp<0x4E>(dot);      // xor 2
+            dot += at_dpp<0x141>(dot);     // half-mirror: the other quad pair of the row of 8
+            dot += at_dpp<0x140>(dot);     // mirror: the other half of the row of 16
+            const float z = dot * scale;
+            const float mn = fmaxf(m[g], z);
+            const float corr = expf(m[g] - mn);      // exp(-inf) = 0 on the first row
+            const float p = expf(z - mn);
+            l[g] = l[g] * corr + p;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) acc[g][e] = fmaf(p, vv[i][e], acc[g][e] * corr);
+            m[g] = mn;
+        }
+    }
+    // combine the 16 row-groups of the workgroup, one head at a time
+    float* sm = smem;                       // [16]
+    float* sl = sm + 16;                    // [16]
+    float* sa = sl + 16;                    // [16][128]
+#pragma unroll
+    for (int g = 0; g < NH; ++g) {
+        if (g) __syncthreads();
+        if (lane16 == 0) {
+            sm[grp] = m[g];
+            sl[grp] = l[g];
+        }
+#pragma unroll
+        for (int e = 0; e < 8; ++e) sa[grp * RA_D + lane16 * 8 + e] = acc[g][e];
+        __syncthreads();
+        if (tid < RA_D && active) {
+            float mx = -INFINITY;
+#pragma unroll
+            for (int j = 0; j < 16; ++j) mx = fmaxf(mx, sm[j]);
+            float a = 0.f, ll = 0.f;
+            if (mx > -INFINITY) {
+#pragma unroll
+                for (int j = 0; j < 16; ++j) {
+                    const float wgt = expf(sm[j] - mx);
+                    a = fmaf(sa[j * RA_D + tid], wgt, a);
+                    ll = fmaf(sl[j], wgt, ll);
+                }
+            }
+            float* rec = rec0 + g * rec_stride;
+            rec[tid] = a;
+            if (tid == 0) {
+                rec[RA_D] = mx;
+                rec[RA_D + 1] = ll;
+            }
+        }
+    }
+}
+
+// Combination of one head's P = nS + nG partial records: Eq. 4-5 with the re-scaling factors
+// written for P sets. Called by 128 threads (t = output dimension). COHERENT = true reads the
+// records past the L1 cache (they were written by other workgroups of the same launch).
+template <bool COHERENT>
+__device__ __forceinline__ float rec_load(const float* p) {
+    if (COHERENT)
+        return __int_as_float(__hip_atomic_load(reinterpret_cast<const int*>(p), __ATOMIC_RELAXED,
+                                                __HIP_MEMORY_SCOPE_AGENT));
+    return *p;
+}
+
+template <bool COHERENT>
+__device__ __forceinline__ void merge_head(const float* rec, int nS, int nG, int t, size_t head,
+                                           float* __restrict__ out, float* __restrict__ lse,
+                                           float* __restrict__ o_om, float* __restrict__ lse_om,
+                                           float* __restrict__ o_w, float* __restrict__ lse_w) {
+    const int P = nS + nG;
+    float M[2] = {-INFINITY, -INFINITY}, L[2] = {0.f, 0.f}, A[2] = {0.f, 0.f};
+    // records are taken sixteen at a time so that their loads are in flight together (one round
+    // trip for the usual P <= 16); each set keeps an online (max, sum, weighted sum)
+    for (int i0 = 0; i0 < P; i0 += 16) {
+        float rm[16], rl[16], ra[16];
+#pragma unroll
+        for (int u = 0; u < 16; ++u) {
+            const int i = i0 + u < P ? i0 + u : P - 1;
+            rm[u] = rec_load<COHERENT>(rec + i * AT_RS + RA_D);
+            rl[u] = rec_load<COHERENT>(rec + i * AT_RS + RA_D + 1);
+            ra[u] = rec_load<COHERENT>(rec + i * AT_RS + t);
+        }
+#pragma unroll
+        for (int set = 0; set < 2; ++set) {
+            const int lo = set == 0 ? 0 : nS, hi = set == 0 ? nS : P;
+            float cm = M[set];
+#pragma unroll
+            for (int u = 0; u < 16; ++u)
+                if (i0 + u >= lo && i0 + u < hi) cm = fmaxf(cm, rm[u]);
+            if (cm > -INFINITY) {
+                const float corr = expf(M[set] - cm);      // 0 while the set's max is still -inf
+                float a = A[set] * corr, l = L[set] * corr;
+#pragma unroll
+                for (int u = 0; u < 16; ++u) {
+                    if (i0 + u >= lo && i0 + u < hi) {
+                        const float wgt = expf(rm[u] - cm);
+                        a = fmaf(ra[u], wgt, a);
+                        l = fmaf(rl[u], wgt, l);
+                    }
+                }
+                M[set] = cm; L[set] = l; A[set] = a;
+            }
+        }
+    }
+    // set-level results of Eq. 4: o_W (set 0) and o_Omega (set 1)
+    float* o_set[2] = {o_w, o_om};
+    float* l_set[2] = {lse_w, lse_om};
+#pragma unroll
+    for (int set = 0; set < 2; ++set) {
+        const bool empty = !(L[set] > 0.f);
+        if (o_set[set]) o_set[set][head * RA_D + t] = empty ? 0.f : A[set] / L[set];
+        if (l_set[set] && t == 0) l_set[set][head] = empty ? -INFINITY : M[set] + logf(L[set]);
+    }
+    // Eq. 5: gamma_i = exp(m_i - m) l_i / sum_j exp(m_j - m) l_j with m = max(m_1, m_2)
+    const float mx = fmaxf(M[0], M[1]);
+    float o = 0.f, ls = -INFINITY;
+    if (mx > -INFINITY) {
+        const float e0 = L[0] > 0.f ? expf(M[0] - mx) : 0.f;
+        const float e1 = L[1] > 0.f ? expf(M[1] - mx) : 0.f;
+        const float l = L[0] * e0 + L[1] * e1;
+        o = (A[0] * e0 + A[1] * e1) / l;
+        ls = mx + logf(l);
+    }
+    out[head * RA_D + t] = o;
+    if (t == 0) lse[head] = ls;
+}
+
+// static set W of Sec. 3.3 as two id ranges [0, s) and [N - w, N); overlapping ranges merge
+static inline void static_ranges(int64_t N, int sink, int window, int* s, int* w) {
+    int64_t ss = sink < 0 ? 0 : sink, ww = window < 0 ? 0 : window;
+    if (ss > N) ss = N;
+    if (ww > N) ww = N;
+    if (ss + ww >= N) { ss = N; ww = 0; }
+    *s = (int)ss;
+    *w = (int)ww;
+}
+
+#define AT_TEAM_LDS_FLOATS (32 + 16 * RA_D)      // LDS floats one team of attend_chunk needs

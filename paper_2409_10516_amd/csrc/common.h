@@ -61,6 +61,12 @@ ra_status ra_launch_attend(const void* q, const void* K, const void* V, ra_dtype
                            float* lse, float* o_omega, float* lse_omega, float* o_w,
                            float* lse_w);
 
+bool ra_decode_needs_global_bitset(int64_t N, int deg, int ef, int expand, int topk);
+ra_status ra_launch_decode(const void* q, const int32_t* adj, const int32_t* entry, const void* K,
+                           const void* V, ra_dtype dt, int n_seq, int n_q, int n_kv, int64_t N, int deg,
+                           int sink, int window, int topk, int ef, int expand, uint32_t* bitset,
+                           hipStream_t st, float* out, float* lse, int32_t* ids, ra_stats* stats);
+
 ra_status ra_launch_knn(const void* K, const void* Q, ra_dtype dt, int n_seq, int n_q, int n_kv,
                         int64_t N, int64_t M, int knn, hipStream_t st, int32_t* L);
 

@@ -1,0 +1,188 @@
+// One launch per layer for the whole decode step of Algorithm 1 (fixed static pattern): one
+// workgroup per (sequence, query head) runs the graph search (search_dev.h) and then, without
+// leaving the compute unit, Eq. 2 over W u Omega for its head: the retrieved ids are still
+// in LDS, the 64 groups of 16 lanes share the rows of both sets round-robin, every group keeps
+// an online (max, sum, weighted sum) over its rows, and the groups' partial results are
+// combined with the re-scaling factors of Eq. 5 written for many sets (first across the four
+// groups of a wavefront by lane exchange, then across the 16 wavefronts through LDS). Carrying
+// the running maximum across both sets is the same arithmetic as computing o_W and o_Omega apart
+// and combining them by Eq. 4.
+//
+// Nothing crosses workgroups, on purpose. A variant that computed the static rows once per GQA
+// group in separate workgroups of the same launch, and let the last finisher combine, was
+// measured: the agent-scope release/acquire it needs (the part has one L2 per XCD, so the
+// fences write back and invalidate L2) cost about 18 us per launch, more than the whole
+// attention. Here the four query heads of a group each read the 644 static rows themselves;
+// the repeats are served by L2 and the bytes are irrelevant next to the search's latency.
+#include "attend_dev.h"
+#include "search_dev.h"
+
+#define DC_ROWS 4          // rows in flight per 16-lane group
+
+struct Softmax8 {          // a lane's share of an online-softmax state: 8 of the 128 outputs
+    float m, l, acc[8];
+};
+
+__device__ __forceinline__ void sm_merge(Softmax8& a, float mo, float lo, const float* acco) {
+    const float mn = fmaxf(a.m, mo);
+    if (mn == -INFINITY) return;                    // both empty
+    const float ca = expf(a.m - mn), co = expf(mo - mn);
+    a.l = a.l * ca + lo * co;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) a.acc[e] = a.acc[e] * ca + acco[e] * co;
+    a.m = mn;
+}
+
+template <int DT, bool GBITS>
+__global__ __launch_bounds__(SR_THREADS) void decode_kernel(
+    const void* __restrict__ q, const int32_t* __restrict__ adj, const int32_t* __restrict__ entry,
+    const void* __restrict__ K, const void* __restrict__ V, int n_q, int n_kv, int64_t N, int deg,
+    int s, int w, int topk, int ef, int expand, uint32_t* __restrict__ gbits,
+    int32_t* __restrict__ ids, ra_stats* __restrict__ stats, int ids_off, float scale,
+    float* __restrict__ out, float* __restrict__ lse) {
+    extern __shared__ __align__(16) unsigned char lds_raw[];
+    const int tid = threadIdx.x, grp = tid >> 4, lane16 = tid & 15;
+    const int lane = tid & (RA_WAVE - 1), wv = tid / RA_WAVE;
+    const int head = blockIdx.x, seq = head / n_q, h = head % n_q, kvh = h / (n_q / n_kv);
+    const size_t esz = DT == RA_BF16 ? 2 : 4;
+    int32_t* lds_ids = reinterpret_cast<int32_t*>(lds_raw + ids_off);
+    const int cnt = run_search<DT, GBITS>(lds_raw, head, q, adj, entry, K, n_q, n_kv, N, deg, s, w,
+                                          topk, ef, expand, gbits, ids, stats, lds_ids);
+    // ---- Eq. 2 over Omega (rows [0, cnt): ids in LDS) and W (rows [cnt, cnt + s + w))
+    const char* Kh = reinterpret_cast<const char*>(K) + ((size_t)seq * n_kv + kvh) * N * RA_D * esz;
+    const char* Vh = reinterpret_cast<const char*>(V) + ((size_t)seq * n_kv + kvh) * N * RA_D * esz;
+    float qv[8];
+    load_row8<DT>(reinterpret_cast<const char*>(q) + (size_t)head * RA_D * esz, 0, lane16, qv);
+    const int R = cnt + s + w;
+    Softmax8 st;
+    st.m = -INFINITY;
+    st.l = 0.f;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) st.acc[e] = 0.f;
+    for (int r0 = 0; r0 < R; r0 += SR_NG * DC_ROWS) {
+        int64_t rid[DC_ROWS];
+        float kv[DC_ROWS][8], vv[DC_ROWS][8];
+#pragma unroll
+        for (int u = 0; u < DC_ROWS; ++u) {
+            const int r = r0 + u * SR_NG + grp;
+            int64_t id = -1;
+            if (r < cnt) id = lds_ids[r];
+            else if (r < R) id = r - cnt < s ? (int64_t)(r - cnt) : N - w + (r - cnt - s);
+            rid[u] = id;
+            const int64_t safe = id >= 0 ? id : 0;      // loads stay unconditional
+            load_row8<DT>(Kh, safe, lane16, kv[u]);
+            load_row8<DT>(Vh, safe, lane16, vv[u]);
+        }
+#pragma unroll
+        for (int u = 0; u < DC_ROWS; ++u) {
+            if (rid[u] < 0) continue;
+            float dot = 0.f;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) dot = fmaf(qv[e], kv[u][e], dot);
+            dot += at_dpp<0xB1>(dot);
+            dot += at_dpp<0x4E>(dot);
+            dot += at_dpp<0x141>(dot);
+            dot += at_dpp<0x140>(dot);
+            const float z = dot * scale;
+            const float mn = fmaxf(st.m, z);
+            const float corr = expf(st.m - mn);         // exp(-inf) = 0 on the first row
+            const float p = expf(z - mn);
+            st.l = st.l * corr + p;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) st.acc[e] = fmaf(p, vv[u][e], st.acc[e] * corr);
+            st.m = mn;
+        }
+    }
+    // ---- combine the four groups of each wavefront by lane exchange
+#pragma unroll
+    for (int d = 16; d <= 32; d <<= 1) {
+        const float mo = __shfl_xor(st.m, d), lo = __shfl_xor(st.l, d);
+        float ao[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) ao[e] = __shfl_xor(st.acc[e], d);
+        sm_merge(st, mo, lo, ao);
+    }
+    // ---- then the 16 wavefronts through LDS (the search state is dead; ids sit behind it)
+    float* sm = reinterpret_cast<float*>(lds_raw);          // [16]
+    float* sl = sm + SR_THREADS / RA_WAVE;                   // [16]
+    float* sa = sl + SR_THREADS / RA_WAVE;                   // [16][128]
+    if (lane < 16) {
+        if (lane == 0) {
+            sm[wv] = st.m;
+            sl[wv] = st.l;
+        }
+#pragma unroll
+        for (int e = 0; e < 8; ++e) sa[wv * RA_D + lane * 8 + e] = st.acc[e];
+    }
+    __syncthreads();
+    if (tid < RA_D) {
+        float mx = -INFINITY;
+#pragma unroll
+        for (int j = 0; j < SR_THREADS / RA_WAVE; ++j) mx = fmaxf(mx, sm[j]);
+        float a = 0.f, l = 0.f;
+        if (mx > -INFINITY) {
+#pragma unroll
+            for (int j = 0; j < SR_THREADS / RA_WAVE; ++j) {
+                const float wgt = expf(sm[j] - mx);
+                a = fmaf(sa[j * RA_D + tid], wgt, a);
+                l = fmaf(sl[j], wgt, l);
+            }
+        }
+        const bool empty = !(l > 0.f);
+        out[(size_t)head * RA_D + tid] = empty ? 0.f : a / l;
+        if (tid == 0) lse[head] = empty ? -INFINITY : mx + logf(l);
+    }
+}
+
+static size_t decode_lds_bytes(int64_t N, int deg, int ef, int expand, int topk, bool gb, int* ids_off) {
+    size_t a = search_lds_bytes(N, deg, ef, expand, gb);
+    const size_t b = (size_t)(SR_THREADS / RA_WAVE) * (RA_D + 2) * sizeof(float);
+    if (b > a) a = b;
+    a = (a + 15) & ~(size_t)15;
+    *ids_off = (int)a;
+    return a + (size_t)topk * sizeof(int32_t);
+}
+
+bool ra_decode_needs_global_bitset(int64_t N, int deg, int ef, int expand, int topk) {
+    int off;
+    return decode_lds_bytes(N, deg, ef, expand, topk, false, &off) > SR_LDS_LIMIT;
+}
+
+__global__ void dc_fill_u32_kernel(uint32_t* p, size_t n, uint32_t v) {
+    for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n;
+         i += (size_t)gridDim.x * blockDim.x)
+        p[i] = v;
+}
+
+ra_status ra_launch_decode(const void* q, const int32_t* adj, const int32_t* entry, const void* K,
+                           const void* V, ra_dtype dt, int n_seq, int n_q, int n_kv, int64_t N, int deg,
+                           int sink, int window, int topk, int ef, int expand, uint32_t* bitset,
+                           hipStream_t st, float* out, float* lse, int32_t* ids, ra_stats* stats) {
+    int s, w;
+    static_ranges(N, sink, window, &s, &w);
+    const int heads = n_seq * n_q;
+    const bool gb = ra_decode_needs_global_bitset(N, deg, ef, expand, topk);
+    int ids_off;
+    const size_t lds = decode_lds_bytes(N, deg, ef, expand, topk, gb, &ids_off);
+    if (lds > SR_LDS_LIMIT)
+        RA_FAIL(RA_EUNSUP, "decode state needs %zu B of LDS (limit %d): lower ef or expand", lds,
+                SR_LDS_LIMIT);
+    if (gb) {
+        if (!bitset) RA_FAIL(RA_EINVAL, "global visited bitset missing");
+        const size_t words = (size_t)heads * ((N + 31) >> 5);
+        hipLaunchKernelGGL(dc_fill_u32_kernel, dim3(1024), dim3(256), 0, st, bitset, words, 0u);
+    }
+    const float scale = 1.0f / sqrtf((float)RA_D);
+#define RA_DC_GO(DTV, GB)                                                                          \
+    hipLaunchKernelGGL((decode_kernel<DTV, GB>), dim3(heads), dim3(SR_THREADS), lds, st, q, adj,   \
+                       entry, K, V, n_q, n_kv, N, deg, s, w, topk, ef, expand, bitset, ids, stats, \
+                       ids_off, scale, out, lse)
+    if (dt == RA_BF16) {
+        if (gb) RA_DC_GO(RA_BF16, true); else RA_DC_GO(RA_BF16, false);
+    } else {
+        if (gb) RA_DC_GO(RA_F32, true); else RA_DC_GO(RA_F32, false);
+    }
+#undef RA_DC_GO
+    RA_HIP(hipGetLastError());
+    return RA_OK;
+}

@@ -1,138 +1,5 @@
-// VectorSearch(q) of Algorithm 1: bounded best-first walk over one head's key graph
-// (Sec. 2.4 describes proximity-graph search as a greedy walk towards the most similar
-// vectors). One workgroup of 1024 threads per (sequence, query head); the whole search state
-// lives in LDS:
-//   * visited: an exact bitset over the N keys (N/8 bytes; a global-memory bitset is used
-//     instead when the context is too long for LDS),
-//   * beam: at most ef entries, always sorted, as 64-bit keys
-//         [ordered(score) : 32][0x7fffffff - id : 31][not-yet-expanded : 1]
-//     so that "larger key" is exactly "(score descending, id ascending)" and one integer
-//     compare decides; ids are unique in the beam, so the flag bit never decides.
-// Each step expands the `expand` best unexpanded entries at once: their adjacency rows
-// are read with one coalesced load per row, unvisited neighbours are claimed with an LDS
-// atomic-or (which also removes duplicates), their key rows are gathered by 16-lane
-// groups (16 B per lane; four rows per wavefront load), scored, filtered against the
-// beam's worst entry, and merged into the beam by rank (counting, no serial insertion). The beam after a step is the top-ef of a set union, so
-// it does not depend on the order in which candidates were claimed.
-//
-// Scores decide integer results, so they are computed in one fixed float32 order: each
-// of 16 lanes sums its 8 contiguous products left to right, then the 16 partial sums are
-// added pairwise over adjacent lanes (xor 1, 2, 4, 8). Identical key rows therefore score
-// identically, and a CPU reference can reproduce every bit.
-#include "common.h"
-
-#define SR_THREADS 1024
-#define SR_LDS_LIMIT (64 * 1024)
-#define SR_UNROLL 2               // key rows in flight per 16-lane group
-
-#define SR_NG (SR_THREADS / 16)     // 16-lane groups per workgroup
-
-enum { C_NCAND = 1, C_NKEEP = 2, C_WTOT = 8, C_COUNT = 8 + SR_THREADS / RA_WAVE };
-
-typedef unsigned long long u64;
-
-__device__ __forceinline__ u64 make_key(float score, int id) {
-    return ((u64)f32_ordered(score) << 32) | ((u64)(uint32_t)(0x7fffffff - id) << 1) | 1ull;
-}
-__device__ __forceinline__ int key_id(u64 k) { return 0x7fffffff - (int)((uint32_t)k >> 1); }
-
-template <int DT>
-__device__ __forceinline__ void load_q8(const void* q, int lane16, float* qv) {
-    if (DT == RA_BF16) {
-        const uint4 u = reinterpret_cast<const uint4*>(q)[lane16];
-        qv[0] = bf16_lo(u.x); qv[1] = bf16_hi(u.x); qv[2] = bf16_lo(u.y); qv[3] = bf16_hi(u.y);
-        qv[4] = bf16_lo(u.z); qv[5] = bf16_hi(u.z); qv[6] = bf16_lo(u.w); qv[7] = bf16_hi(u.w);
-    } else {
-        const float4 a = reinterpret_cast<const float4*>(q)[lane16 * 2];
-        const float4 b = reinterpret_cast<const float4*>(q)[lane16 * 2 + 1];
-        qv[0] = a.x; qv[1] = a.y; qv[2] = a.z; qv[3] = a.w;
-        qv[4] = b.x; qv[5] = b.y; qv[6] = b.z; qv[7] = b.w;
-    }
-}
-
-// Raw 32 B (fp32) / 16 B (bf16) of a key row owned by this lane.
-template <int DT> struct RowBits { uint4 a; uint4 b; };
-
-template <int DT>
-__device__ __forceinline__ RowBits<DT> load_key(const void* Kh, int64_t row, int lane16) {
-    RowBits<DT> r;
-    if (DT == RA_BF16) {
-        r.a = reinterpret_cast<const uint4*>(reinterpret_cast<const uint16_t*>(Kh) + row * RA_D)[lane16];
-        r.b = r.a;
-    } else {
-        const uint4* p = reinterpret_cast<const uint4*>(reinterpret_cast<const float*>(Kh) + row * RA_D);
-        r.a = p[lane16 * 2];
-        r.b = p[lane16 * 2 + 1];
-    }
-    return r;
-}
-
-template <int CTRL>
-__device__ __forceinline__ float dpp_f32(float v) {
-    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xF, 0xF, true));
-}
-
-// The fixed-order inner product described in the file header. All 16 lanes of the group
-// return the same value.
-template <int DT>
-__device__ __forceinline__ float score_fixed(const RowBits<DT>& r, const float* qv) {
-    float acc;
-    if (DT == RA_BF16) {
-        // bf16 x bf16 products are exact in float32, so fma == multiply-then-add here
-        acc = qv[0] * bf16_lo(r.a.x);
-        acc = fmaf(qv[1], bf16_hi(r.a.x), acc);
-        acc = fmaf(qv[2], bf16_lo(r.a.y), acc);
-        acc = fmaf(qv[3], bf16_hi(r.a.y), acc);
-        acc = fmaf(qv[4], bf16_lo(r.a.z), acc);
-        acc = fmaf(qv[5], bf16_hi(r.a.z), acc);
-        acc = fmaf(qv[6], bf16_lo(r.a.w), acc);
-        acc = fmaf(qv[7], bf16_hi(r.a.w), acc);
-    } else {
-        // product rounded, then added (this file is compiled with contraction off)
-        acc = __fmul_rn(qv[0], __uint_as_float(r.a.x));
-        acc = __fadd_rn(acc, __fmul_rn(qv[1], __uint_as_float(r.a.y)));
-        acc = __fadd_rn(acc, __fmul_rn(qv[2], __uint_as_float(r.a.z)));
-        acc = __fadd_rn(acc, __fmul_rn(qv[3], __uint_as_float(r.a.w)));
-        acc = __fadd_rn(acc, __fmul_rn(qv[4], __uint_as_float(r.b.x)));
-        acc = __fadd_rn(acc, __fmul_rn(qv[5], __uint_as_float(r.b.y)));
-        acc = __fadd_rn(acc, __fmul_rn(qv[6], __uint_as_float(r.b.z)));
-        acc = __fadd_rn(acc, __fmul_rn(qv[7], __uint_as_float(r.b.w)));
-    }
-    // pairwise tree over adjacent lanes with DPP lane permutations inside a row of 16:
-    // quad_perm [1,0,3,2] and [2,3,0,1] are xor 1 and xor 2; after them the four lanes of a
-    // quad hold the same sum, so half-mirror (i -> 7-i) and mirror (i -> 15-i) deliver exactly
-    // what xor 4 and xor 8 would, and float addition commutes.
-    acc = __fadd_rn(acc, dpp_f32<0xB1>(acc));
-    acc = __fadd_rn(acc, dpp_f32<0x4E>(acc));
-    acc = __fadd_rn(acc, dpp_f32<0x141>(acc));
-    acc = __fadd_rn(acc, dpp_f32<0x140>(acc));
-    return acc;
-}
-
-// number of entries of the descending array arr[0..n) that beat k (flag bit ignored)
-__device__ __forceinline__ int count_better(const u64* arr, int n, u64 k) {
-    int lo = 0, hi = n;
-    const u64 kk = k | 1ull;
-    while (lo < hi) {
-        const int mid = (lo + hi) >> 1;
-        if ((arr[mid] | 1ull) > kk) lo = mid + 1; else hi = mid;
-    }
-    return lo;
-}
-
-static_assert(RA_MAX_EF <= SR_THREADS, "one beam entry per thread");
-
-// number of the first min(n, 16) entries of arr that are larger than k; all 16 are read (the
-// caller's buffer has 16 entries of slack) so that the loads go out together.
-__device__ __forceinline__ int count_above16(const u64* arr, int n, u64 k) {
-    u64 v[16];
-#pragma unroll
-    for (int u = 0; u < 16; ++u) v[u] = arr[u];
-    int cnt = 0;
-#pragma unroll
-    for (int u = 0; u < 16; ++u) cnt += (u < n && v[u] > k) ? 1 : 0;
-    return cnt;
-}
+// Stand-alone launch of the graph search (ra_search); the search itself is in search_dev.h.
+#include "search_dev.h"
 
 template <int DT, bool GBITS>
 __global__ __launch_bounds__(SR_THREADS) void search_kernel(
@@ -141,195 +8,8 @@ __global__ __launch_bounds__(SR_THREADS) void search_kernel(
     int ef, int expand, uint32_t* __restrict__ gbits, int32_t* __restrict__ ids,
     ra_stats* __restrict__ stats) {
     extern __shared__ __align__(16) unsigned char lds_raw[];
-    const int tid = threadIdx.x, grp = tid >> 4, lane16 = tid & 15;
-    const int lane = tid & (RA_WAVE - 1), wv = tid / RA_WAVE;
-    const int head = blockIdx.x, seq = head / n_q, h = head % n_q, kvh = h / (n_q / n_kv);
-    const size_t esz = DT == RA_BF16 ? 2 : 4;
-    const char* Kh = reinterpret_cast<const char*>(K) + ((size_t)seq * n_kv + kvh) * N * RA_D * esz;
-    const int32_t* adj_h = adj + (size_t)head * N * deg;
-    const int maxc = expand * deg;
-    const int nwords = (int)((N + 31) >> 5);
-
-    u64* cur = reinterpret_cast<u64*>(lds_raw);
-    u64* nxt = cur + ef;
-    u64* ckey = nxt + ef;            // [maxc + 16] candidates that passed the beam threshold
-    int* cid = reinterpret_cast<int*>(ckey + maxc + 16);  // [maxc] claimed neighbour ids
-    int* cnt = cid + maxc;           // [ef + maxc] merge counters, zero between steps
-    int* picks = cnt + ef + maxc;    // [RA_MAX_EXPAND]
-    int* ctr = picks + RA_MAX_EXPAND;
-    int* wtot = ctr + C_WTOT;
-    uint32_t* bits = GBITS ? gbits + (size_t)head * nwords
-                           : reinterpret_cast<uint32_t*>(ctr + C_COUNT);
-
-    if (!GBITS)
-        for (int i = tid; i < nwords; i += SR_THREADS) bits[i] = 0u;
-    for (int i = tid; i < ef + maxc; i += SR_THREADS) cnt[i] = 0;
-    float qv[8];
-    load_q8<DT>(reinterpret_cast<const char*>(q) + (size_t)head * RA_D * esz, lane16, qv);
-    const int e0 = entry[head];
-    __syncthreads();
-    if (grp == 0) {
-        const RowBits<DT> r = load_key<DT>(Kh, e0, lane16);
-        const float sc = score_fixed<DT>(r, qv);
-        if (tid == 0) {
-            cur[0] = make_key(sc, e0);
-            atomicOr(&bits[e0 >> 5], 1u << (e0 & 31));
-        }
-    }
-    int bn = 1, n_visited = 1, n_expanded = 0, n_iters = 0;
-    __syncthreads();
-
-    for (;;) {
-        // ---- pick the `expand` best unexpanded entries: the beam is sorted and has at most
-        //      one entry per thread, so the picks are the first `expand` set flags in thread
-        //      order (ballot prefix inside a wavefront, wavefront totals through LDS)
-        const u64 mykey = tid < bn ? cur[tid] : 0ull;
-        const bool un = (mykey & 1ull) != 0;
-        const u64 unmask = __ballot(un);
-        if (lane == 0) wtot[wv] = __popcll(unmask);
-        if (tid == 0) {
-            ctr[C_NCAND] = 0;
-            ctr[C_NKEEP] = 0;
-        }
-        __syncthreads();
-        int before = 0, total = 0;
-        for (int x = 0; x < SR_THREADS / RA_WAVE; ++x) {
-            const int c = wtot[x];
-            if (x < wv) before += c;
-            total += c;
-        }
-        const int np = total < expand ? total : expand;
-        if (np == 0) break;
-        {
-            const int rank = before + __popcll(unmask & ((1ull << lane) - 1ull));
-            if (un && rank < expand) {
-                picks[rank] = key_id(mykey);
-                cur[tid] = mykey & ~1ull;
-            }
-        }
-        __syncthreads();
-        ++n_iters;
-        n_expanded += np;
-
-        // ---- read the picked adjacency rows (all loads issued before any is consumed),
-        //      claim unvisited neighbours
-        {
-            const int cells = np * deg;
-            for (int x0 = 0; x0 < cells; x0 += SR_THREADS * 2) {
-                int nbv[2];
-#pragma unroll
-                for (int u = 0; u < 2; ++u) {
-                    // out-of-range slots re-read the last cell: loads without a branch around
-                    // them can all be issued before the first one is consumed
-                    const int x = x0 + u * SR_THREADS + tid;
-                    const int xc = x < cells ? x : cells - 1;
-                    const int v = adj_h[(size_t)picks[xc / deg] * deg + (xc % deg)];
-                    nbv[u] = x < cells ? v : -1;
-                }
-#pragma unroll
-                for (int u = 0; u < 2; ++u) {
-                    const int nb = nbv[u];
-                    if (nb >= 0 && nb < N) {
-                        const uint32_t bit = 1u << (nb & 31);
-                        const uint32_t old = atomicOr(&bits[nb >> 5], bit);
-                        if (!(old & bit)) cid[atomicAdd(&ctr[C_NCAND], 1)] = nb;
-                    }
-                }
-            }
-        }
-        __syncthreads();
-        const int nc = ctr[C_NCAND];
-        n_visited += nc;
-
-        // ---- gather and score the new candidates; keep those that can enter the beam
-        const u64 worst = bn == ef ? (cur[bn - 1] >> 1) : 0ull;
-        for (int c0 = 0; c0 < nc; c0 += SR_NG * SR_UNROLL) {
-            RowBits<DT> rows[SR_UNROLL];
-            int cidv[SR_UNROLL];
-#pragma unroll
-            for (int u = 0; u < SR_UNROLL; ++u) {
-                if (c0 + u * SR_NG >= nc) break;          // uniform over the workgroup
-                const int c = c0 + u * SR_NG + grp;
-                cidv[u] = c < nc ? cid[c] : -1;
-                // groups without a candidate re-read the entry row instead of branching
-                rows[u] = load_key<DT>(Kh, cidv[u] >= 0 ? cidv[u] : e0, lane16);
-            }
-#pragma unroll
-            for (int u = 0; u < SR_UNROLL; ++u) {
-                if (c0 + u * SR_NG >= nc) break;
-                const float sc = score_fixed<DT>(rows[u], qv);
-                if (lane16 == 0 && cidv[u] >= 0) {
-                    const u64 key = make_key(sc, cidv[u]);
-                    if ((key >> 1) > worst) ckey[atomicAdd(&ctr[C_NKEEP], 1)] = key;
-                }
-            }
-        }
-        __syncthreads();
-        const int nk = ctr[C_NKEEP];
-        if (nk == 0) continue;       // uniform: nothing enters the beam
-
-        // ---- merge by counting into the other beam buffer, truncating at ef. The final position
-        //      of an element of (beam u kept candidates) is the number of elements that beat it:
-        //      a beam entry's index plus the candidates above it; a candidate's rank among the
-        //      candidates plus the beam entries above it. The (element, 16 candidates) count
-        //      tasks are spread over all wavefronts but the last, which meanwhile ranks the
-        //      candidates against the sorted beam by binary search; partial counts meet in LDS.
-        {
-            const int E = bn + nk;
-            const int nch = (nk + 15) >> 4;
-            const int items = E * nch;
-            constexpr int A_T = SR_THREADS - RA_WAVE;
-            if (tid < A_T) {
-                for (int a = tid; a < items; a += A_T) {
-                    const int ch = a / E, e = a - ch * E;
-                    const u64 ke = (e < bn ? cur[e] : ckey[e - bn]) | 1ull;   // candidates carry flag 1
-                    const int c = count_above16(ckey + ch * 16, nk - ch * 16, ke);
-                    if (c) atomicAdd(&cnt[e], c);
-                }
-            } else {
-                for (int c = tid - A_T; c < nk; c += RA_WAVE) {
-                    const int b = count_better(cur, bn, ckey[c]);
-                    if (b) atomicAdd(&cnt[bn + c], b);
-                }
-            }
-            __syncthreads();
-            for (int e = tid; e < E; e += SR_THREADS) {
-                const int c = cnt[e];
-                cnt[e] = 0;
-                const u64 k = e < bn ? cur[e] : ckey[e - bn];
-                const int pos = (e < bn ? e : 0) + c;
-                if (pos < ef) nxt[pos] = k;
-            }
-        }
-        __syncthreads();
-        bn = bn + nk < ef ? bn + nk : ef;
-        u64* t = cur; cur = nxt; nxt = t;
-    }
-
-    // ---- result: best-first beam entries outside the static set W = [0,s) u [N-w,N)
-    if (tid < RA_WAVE) {
-        int32_t* out = ids + (size_t)head * topk;
-        int cnt = 0;
-        for (int base = 0; base < bn && cnt < topk; base += RA_WAVE) {
-            const int i = base + tid;
-            const int id = i < bn ? key_id(cur[i]) : -1;
-            const bool ok = i < bn && id >= s && id < N - w;
-            const u64 mask = __ballot(ok);
-            const int pos = cnt + __popcll(mask & ((1ull << tid) - 1ull));
-            if (ok && pos < topk) out[pos] = id;
-            cnt += __popcll(mask);
-        }
-        if (cnt > topk) cnt = topk;
-        for (int i = cnt + tid; i < topk; i += RA_WAVE) out[i] = -1;
-        if (stats && tid == 0) {
-            ra_stats st;
-            st.n_visited = n_visited;
-            st.n_expanded = n_expanded;
-            st.n_iters = n_iters;
-            st.n_returned = cnt;
-            stats[head] = st;
-        }
-    }
+    run_search<DT, GBITS>(lds_raw, blockIdx.x, q, adj, entry, K, n_q, n_kv, N, deg, s, w, topk, ef,
+                          expand, gbits, ids, stats, nullptr);
 }
 
 __global__ void fill_u32_kernel(uint32_t* p, size_t n, uint32_t v) {
@@ -339,11 +19,7 @@ __global__ void fill_u32_kernel(uint32_t* p, size_t n, uint32_t v) {
 }
 
 size_t ra_search_lds_bytes(int64_t N, int deg, int ef, int expand, bool global_bitset) {
-    const int maxc = expand * deg;
-    size_t b = (size_t)2 * ef * 8 + (size_t)(maxc + 16) * 8 + (size_t)maxc * 4 + (size_t)(ef + maxc) * 4 +
-               (RA_MAX_EXPAND + C_COUNT) * 4;
-    if (!global_bitset) b += (size_t)((N + 31) >> 5) * 4;
-    return b;
+    return search_lds_bytes(N, deg, ef, expand, global_bitset);
 }
 
 bool ra_search_needs_global_bitset(int64_t N, int deg, int ef, int expand) {
