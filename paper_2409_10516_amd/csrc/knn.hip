@@ -11,16 +11,14 @@
 // (about knn * ln(N / knn) per query over the whole stream) take the insertion path, where the
 // wavefront inserts them one at a time into the query's sorted list in LDS.
 //
-// A wavefront owns 32 queries for the whole key stream (their B operands stay in registers);
-// a workgroup is 4 wavefronts = 128 queries. Lists hold 64-bit keys
+// A wavefront owns NQ x 32 queries for the whole key stream (their B operands stay in registers,
+// and every key operand fetched feeds NQ MFMA chains); a workgroup is 4 wavefronts. Lists hold 64-bit keys
 // [ordered(score):32][~id:32], so "larger key" is "(score descending, id ascending)".
 // The inner-product summation order is the hardware's; identical key rows still score
 // identically for a given query because they go through the same instruction sequence.
 #include "common.h"
 
 #define KN_THREADS 256
-#define KN_QPW 32                        // queries per wavefront
-#define KN_QPB (KN_QPW * KN_THREADS / RA_WAVE)   // queries per workgroup
 
 typedef unsigned long long u64;
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
@@ -88,75 +86,94 @@ __device__ __forceinline__ f32x16 block_scores(const Operand<DT>& a, const Opera
     return c;
 }
 
-// grid: x = block of KN_QPB queries, y = graph (seq * n_q + h)
-template <int DT>
+// grid: x = block of NQ * 128 queries, y = graph (seq * n_q + h). A wavefront owns NQ sets of 32
+// queries, so every key operand it loads feeds NQ MFMA chains.
+template <int DT, int NQ>
 __global__ __launch_bounds__(KN_THREADS) void knn_kernel(
     const void* __restrict__ K, const void* __restrict__ Q, int n_q, int n_kv, int64_t N, int64_t M,
     int knn, int32_t* __restrict__ L_out) {
     extern __shared__ __align__(16) unsigned char lds_raw[];
-    u64* lists = reinterpret_cast<u64*>(lds_raw);           // [KN_QPB][knn]
+    constexpr int QPW = 32 * NQ, QPB = QPW * (KN_THREADS / RA_WAVE);
+    u64* lists = reinterpret_cast<u64*>(lds_raw);           // [QPB][knn]
     const int tid = threadIdx.x, wv = tid / RA_WAVE, lane = tid % RA_WAVE;
     const int col = lane & 31, half = lane >> 5;
     const int graph = blockIdx.y, seq = graph / n_q, h = graph % n_q, kvh = h / (n_q / n_kv);
     const size_t esz = DT == RA_BF16 ? 2 : 4;
     const char* Kh = reinterpret_cast<const char*>(K) + ((size_t)seq * n_kv + kvh) * N * RA_D * esz;
     const char* Qh = reinterpret_cast<const char*>(Q) + (size_t)graph * M * RA_D * esz;
-    const int64_t q0 = (int64_t)blockIdx.x * KN_QPB + wv * KN_QPW;   // first query of this wave
+    const int64_t q0 = (int64_t)blockIdx.x * QPB + wv * QPW;   // first query of this wave
 
-    for (int i = tid; i < KN_QPB * knn; i += KN_THREADS) lists[i] = 0ull;
-    u64* my_lists = lists + (size_t)wv * KN_QPW * knn;
+    for (int i = tid; i < QPB * knn; i += KN_THREADS) lists[i] = 0ull;
+    u64* my_lists = lists + (size_t)wv * QPW * knn;
 
-    Operand<DT> b;
-    {
-        int64_t qr = q0 + col;
+    Operand<DT> b[NQ];
+#pragma unroll
+    for (int sidx = 0; sidx < NQ; ++sidx) {
+        int64_t qr = q0 + sidx * 32 + col;
         if (qr >= M) qr = M - 1;                   // clamp loads; such columns are never written
-        load_operand<DT>(Qh, qr, half, b);
+        load_operand<DT>(Qh, qr, half, b[sidx]);
     }
     __syncthreads();
 
-    float tau = -INFINITY;
+    float tau[NQ];
+#pragma unroll
+    for (int sidx = 0; sidx < NQ; ++sidx) tau[sidx] = -INFINITY;
     const int64_t nblk = (N + 31) / 32;
-    Operand<DT> a;
-    {
-        int64_t kr = col;
+
+    auto load_keys = [&](int64_t kb, Operand<DT>& dst) {
+        int64_t kr = kb * 32 + col;
         if (kr >= N) kr = N - 1;
-        load_operand<DT>(Kh, kr, half, a);
-    }
-    for (int64_t kb = 0; kb < nblk; ++kb) {
-        f32x16 c = block_scores<DT>(a, b);
-        if (kb + 1 < nblk) {                       // next block's key rows
-            int64_t kr = (kb + 1) * 32 + col;
-            if (kr >= N) kr = N - 1;
-            load_operand<DT>(Kh, kr, half, a);
-        }
+        load_operand<DT>(Kh, kr, half, dst);
+    };
+    // scores of one 32-key block against the wave's NQ query sets, then the selection
+    auto process = [&](const Operand<DT>& a, int64_t kb) {
+        f32x16 c[NQ];
+#pragma unroll
+        for (int sidx = 0; sidx < NQ; ++sidx) c[sidx] = block_scores<DT>(a, b[sidx]);
         const int64_t kbase = kb * 32;
-        if (kbase + 32 > N) {                      // ragged tail: rows beyond N never qualify
 #pragma unroll
-            for (int r = 0; r < 16; ++r)
-                if (kbase + (r / 4) * 8 + half * 4 + (r % 4) >= N) c[r] = -INFINITY;
-        }
-        float mx = fmaxf(c[0], c[1]);
+        for (int sidx = 0; sidx < NQ; ++sidx) {
+            f32x16& cs = c[sidx];
+            if (kbase + 32 > N) {                  // ragged tail: rows beyond N never qualify
 #pragma unroll
-        for (int r = 2; r < 16; ++r) mx = fmaxf(mx, c[r]);
-        if (__ballot(mx >= tau) == 0ull) continue;
-        // insertion path (rare after the first few blocks)
+                for (int r = 0; r < 16; ++r)
+                    if (kbase + (r / 4) * 8 + half * 4 + (r % 4) >= N) cs[r] = -INFINITY;
+            }
+            float mx = fmaxf(cs[0], cs[1]);
 #pragma unroll
-        for (int r = 0; r < 16; ++r) {
-            u64 mask = __ballot(c[r] >= tau && c[r] > -INFINITY);
-            while (mask) {
-                const int src = __ffsll((long long)mask) - 1;
-                const float sc = __shfl(c[r], src);
-                const int id = (int)(kbase + (r / 4) * 8 + (src >> 5) * 4 + (r % 4));
-                const int jq = src & 31;
-                const float nt = knn_insert(my_lists + (size_t)jq * knn, knn, sc, id, lane);
-                if (col == jq) tau = nt;
-                mask &= mask - 1;
-                mask &= __ballot(c[r] >= tau && c[r] > -INFINITY);
+            for (int r = 2; r < 16; ++r) mx = fmaxf(mx, cs[r]);
+            if (__ballot(mx >= tau[sidx]) == 0ull) continue;
+            // insertion path (rare after the first few blocks)
+            u64* set_lists = my_lists + (size_t)sidx * 32 * knn;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                u64 mask = __ballot(cs[r] >= tau[sidx] && cs[r] > -INFINITY);
+                while (mask) {
+                    const int src = __ffsll((long long)mask) - 1;
+                    const float sc = __shfl(cs[r], src);
+                    const int id = (int)(kbase + (r / 4) * 8 + (src >> 5) * 4 + (r % 4));
+                    const int jq = src & 31;
+                    const float nt = knn_insert(set_lists + (size_t)jq * knn, knn, sc, id, lane);
+                    if (col == jq) tau[sidx] = nt;
+                    mask &= mask - 1;
+                    mask &= __ballot(cs[r] >= tau[sidx] && cs[r] > -INFINITY);
+                }
             }
         }
+    };
+    // two key-operand register sets: the next block's rows are requested before the current
+    // block's MFMAs are issued, so their latency hides behind a whole block of matrix work
+    Operand<DT> a0, a1;
+    load_keys(0, a0);
+    for (int64_t kb = 0; kb < nblk; kb += 2) {
+        if (kb + 1 < nblk) load_keys(kb + 1, a1);
+        process(a0, kb);
+        if (kb + 1 >= nblk) break;
+        if (kb + 2 < nblk) load_keys(kb + 2, a0);
+        process(a1, kb + 1);
     }
     // write the ids, best first
-    for (int jq = 0; jq < KN_QPW; ++jq) {
+    for (int jq = 0; jq < QPW; ++jq) {
         const int64_t qr = q0 + jq;
         if (qr >= M) break;
         if (lane < knn)
@@ -166,14 +183,20 @@ __global__ __launch_bounds__(KN_THREADS) void knn_kernel(
 
 ra_status ra_launch_knn(const void* K, const void* Q, ra_dtype dt, int n_seq, int n_q, int n_kv,
                         int64_t N, int64_t M, int knn, hipStream_t st, int32_t* L) {
-    const dim3 grid((unsigned)((M + KN_QPB - 1) / KN_QPB), (unsigned)(n_seq * n_q));
-    const size_t lds = (size_t)KN_QPB * knn * sizeof(u64);
-    if (dt == RA_BF16)
-        hipLaunchKernelGGL((knn_kernel<RA_BF16>), grid, dim3(KN_THREADS), lds, st, K, Q, n_q, n_kv,
+    if (dt == RA_BF16) {
+        constexpr int NQ = 2;
+        constexpr int QPB = 32 * NQ * (KN_THREADS / RA_WAVE);
+        const dim3 grid((unsigned)((M + QPB - 1) / QPB), (unsigned)(n_seq * n_q));
+        const size_t lds = (size_t)QPB * knn * sizeof(u64);
+        hipLaunchKernelGGL((knn_kernel<RA_BF16, NQ>), grid, dim3(KN_THREADS), lds, st, K, Q, n_q, n_kv,
                            N, M, knn, L);
-    else
-        hipLaunchKernelGGL((knn_kernel<RA_F32>), grid, dim3(KN_THREADS), lds, st, K, Q, n_q, n_kv,
+    } else {
+        constexpr int QPB = 32 * (KN_THREADS / RA_WAVE);
+        const dim3 grid((unsigned)((M + QPB - 1) / QPB), (unsigned)(n_seq * n_q));
+        const size_t lds = (size_t)QPB * knn * sizeof(u64);
+        hipLaunchKernelGGL((knn_kernel<RA_F32, 1>), grid, dim3(KN_THREADS), lds, st, K, Q, n_q, n_kv,
                            N, M, knn, L);
+    }
     RA_HIP(hipGetLastError());
     return RA_OK;
 }
