@@ -18,10 +18,11 @@
 //   4. backbone children and -1 padding for every row (fully coalesced).
 //   5. persistent workgroups walk the populated keys in pi order (largest first): for key a
 //      they stream the lists that hold a, bump a counter per co-listed key (table indexed by
-//      pos, so it is as small as the populated set), collect first-touched keys as the
-//      candidate list, then extract the best `deg` candidates by repeated exact arg-max
-//      (fractions compared by 64-bit cross-multiplication), reset the touched counters and
-//      write the row.
+//      pos, so it is as small as the populated set: in LDS when it fits, else in global
+//      scratch), collect first-touched keys as the candidate list, gather each candidate's
+//      (count, popularity, id) once while resetting its counter, then extract the best `deg`
+//      candidates by repeated exact arg-max (fractions compared by 64-bit cross-multiplication)
+//      and write the row.
 // No global sort of the M*knn*(knn-1) co-occurrence pairs is needed: the skewed keys that sit
 // in nearly every list are simply the longest-running work items and are scheduled first.
 #include "common.h"
@@ -70,8 +71,8 @@ static ProjLayout proj_layout(int n_graphs, int64_t N, int64_t M, int knn) {
     l.o_hi1 = o; o += align256((size_t)l.cap * 4);
     l.o_H = o; o += 256;
     l.per_graph = o;
-    // row kernel scratch: per workgroup a counter table and a candidate list of `cap` entries
-    l.scratch_per_wg = align256((size_t)l.cap * 4) * 2;
+    // row kernel scratch: per workgroup four int arrays of `cap` entries
+    l.scratch_per_wg = align256((size_t)l.cap * 4) * 4;     // counters, candidates, two tuple columns
     int per_graph_wg = 64;
     while (per_graph_wg > 1 &&
            ((size_t)per_graph_wg * n_graphs > PJ_MAX_WG ||
@@ -306,51 +307,61 @@ __device__ __forceinline__ bool cand_before(const Cand& x, const Cand& y, uint32
     return x.b < y.b;
 }
 
-__global__ __launch_bounds__(PJ_ROW_T) void pj_rows_kernel(const int32_t* __restrict__ L, char* ws,
-                                                           ProjLayout l, int64_t N, int64_t M,
-                                                           int knn, int deg,
-                                                           int32_t* __restrict__ adj) {
-    __shared__ int s_ncand;
-    __shared__ Cand s_red[PJ_ROW_T / 64];
-    __shared__ Cand s_prev;
-    __shared__ int32_t s_sel[RA_MAX_DEG];
-    __shared__ int s_nsel;
-    const int g = blockIdx.y, tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
-    ProjWs w = carve(ws, l, g);
-    const int32_t* Lg = L + (size_t)g * M * knn;
-    int32_t* adj_g = adj + (size_t)g * N * deg;
-    char* sc = ws + l.o_scratch + ((size_t)g * gridDim.x + blockIdx.x) * l.scratch_per_wg;
-    uint32_t* cnt = (uint32_t*)sc;                                 // [cap] indexed by pos
-    int32_t* cand = (int32_t*)(sc + l.scratch_per_wg / 2);         // [cap]
-    const int H = *w.H;
+#define PJ_LDS_CNT 8192           // co-occurrence counters kept in LDS when the populated set fits
+#define PJ_LDS_TUP 2048           // candidate tuples kept in LDS when the candidate list fits
 
+// Rows of the populated keys of one graph. LDSCNT: the counter table (indexed by pi-position,
+// < H) lives in LDS instead of the workgroup's global scratch; LDS atomics are an order of
+// magnitude cheaper than L2 atomics and the table is small whenever the queries share their
+// favourite keys (H is a few thousand at 128K context).
+template <bool LDSCNT>
+__device__ __forceinline__ void rows_for_graph(const int32_t* __restrict__ Lg, const ProjWs& w,
+                                               uint32_t* cnt, int32_t* cand, uint32_t* tc_g,
+                                               uint32_t* tp_g, uint32_t* tc_l, uint32_t* tp_l,
+                                               int32_t* tb_l, int64_t N, int knn, int deg, int H,
+                                               int32_t* __restrict__ adj_g, int* s_ncand,
+                                               Cand* s_red, Cand* s_prev, int32_t* s_sel,
+                                               int* s_nsel) {
+    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
     for (int t = blockIdx.x; t < H; t += gridDim.x) {
         const int a = w.pi[t];
         const uint32_t pa = (uint32_t)w.pop[a];
         const int o0 = w.off[a];
-        if (tid == 0) { s_ncand = 0; s_nsel = 0; }
+        if (tid == 0) { *s_ncand = 0; *s_nsel = 0; }
         __syncthreads();
-        // count co-listed keys
+        // count co-listed keys; the first touch of a counter appends the key to the candidates
         const int64_t work = (int64_t)pa * knn;
         for (int64_t x = tid; x < work; x += PJ_ROW_T) {
             const int j = w.inv[o0 + (int)(x / knn)];
             const int b = Lg[(size_t)j * knn + (int)(x % knn)];
             if (b != a && b >= 0 && b < N) {
-                if (atomicAdd(&cnt[w.pos[b]], 1u) == 0u) cand[atomicAdd(&s_ncand, 1)] = b;
+                if (atomicAdd(&cnt[w.pos[b]], 1u) == 0u) cand[atomicAdd(s_ncand, 1)] = b;
             }
         }
         __syncthreads();
-        const int nc = s_ncand;
+        const int nc = *s_ncand;
         const int want = nc < deg ? nc : deg;
+        // gather (count, popularity, id) of every candidate once; reset its counter on the way
+        const bool tl = nc <= PJ_LDS_TUP;
+        uint32_t* tc = tl ? tc_l : tc_g;
+        uint32_t* tp = tl ? tp_l : tp_g;
+        int32_t* tb = tl ? tb_l : cand;
+        for (int x = tid; x < nc; x += PJ_ROW_T) {
+            const int b = cand[x];
+            const int pb = w.pos[b];
+            tc[x] = cnt[pb];
+            cnt[pb] = 0u;
+            tp[x] = (uint32_t)w.pop[b];
+            if (tl) tb[x] = b;
+        }
+        __syncthreads();
         // extract the best `want` candidates, one exact arg-max per round
         for (int r = 0; r < want; ++r) {
             Cand best; best.c = 0; best.pb = 0; best.b = -1;
-            const Cand prev = s_prev;               // valid from round 1 on
+            const Cand prev = *s_prev;              // valid from round 1 on
             for (int x = tid; x < nc; x += PJ_ROW_T) {
                 Cand cd;
-                cd.b = cand[x];
-                cd.c = cnt[w.pos[cd.b]];
-                cd.pb = (uint32_t)w.pop[cd.b];
+                cd.b = tb[x]; cd.c = tc[x]; cd.pb = tp[x];
                 if (r > 0 && !cand_before(prev, cd, pa)) continue;     // already taken
                 if (best.b < 0 || cand_before(cd, best, pa)) best = cd;
             }
@@ -368,13 +379,11 @@ __global__ __launch_bounds__(PJ_ROW_T) void pj_rows_kernel(const int32_t* __rest
                     const Cand o = s_red[x];
                     if (o.b >= 0 && (bb.b < 0 || cand_before(o, bb, pa))) bb = o;
                 }
-                s_prev = bb;
-                s_sel[s_nsel++] = bb.b;
+                *s_prev = bb;
+                s_sel[(*s_nsel)++] = bb.b;
             }
             __syncthreads();
         }
-        // reset the touched counters for the next key
-        for (int x = tid; x < nc; x += PJ_ROW_T) cnt[w.pos[cand[x]]] = 0u;
         // row = backbone children, then ranked candidates not already present
         if (tid == 0) {
             int32_t* row = adj_g + (size_t)a * deg;
@@ -384,13 +393,47 @@ __global__ __launch_bounds__(PJ_ROW_T) void pj_rows_kernel(const int32_t* __rest
                 const int64_t ch = 2 * (int64_t)t + 1 + s;
                 if (ch < N) { kids[s] = w.pi[ch]; row[n++] = kids[s]; }
             }
-            for (int x = 0; x < s_nsel && n < deg; ++x) {
+            for (int x = 0; x < *s_nsel && n < deg; ++x) {
                 const int32_t b = s_sel[x];
                 if (b != kids[0] && b != kids[1]) row[n++] = b;
             }
             for (; n < deg; ++n) row[n] = -1;
         }
         __syncthreads();
+    }
+}
+
+__global__ __launch_bounds__(PJ_ROW_T) void pj_rows_kernel(const int32_t* __restrict__ L, char* ws,
+                                                           ProjLayout l, int64_t N, int64_t M,
+                                                           int knn, int deg,
+                                                           int32_t* __restrict__ adj) {
+    __shared__ int s_ncand;
+    __shared__ Cand s_red[PJ_ROW_T / 64];
+    __shared__ Cand s_prev;
+    __shared__ int32_t s_sel[RA_MAX_DEG];
+    __shared__ int s_nsel;
+    __shared__ uint32_t s_cnt[PJ_LDS_CNT];
+    __shared__ uint32_t s_tc[PJ_LDS_TUP], s_tp[PJ_LDS_TUP];
+    __shared__ int32_t s_tb[PJ_LDS_TUP];
+    const int g = blockIdx.y;
+    ProjWs w = carve(ws, l, g);
+    const int32_t* Lg = L + (size_t)g * M * knn;
+    int32_t* adj_g = adj + (size_t)g * N * deg;
+    char* sc = ws + l.o_scratch + ((size_t)g * gridDim.x + blockIdx.x) * l.scratch_per_wg;
+    const size_t quarter = l.scratch_per_wg / 4;
+    uint32_t* cnt_g = (uint32_t*)sc;                               // [cap] indexed by pos, zero at rest
+    int32_t* cand = (int32_t*)(sc + quarter);                      // [cap]
+    uint32_t* tc_g = (uint32_t*)(sc + 2 * quarter);                // [cap]
+    uint32_t* tp_g = (uint32_t*)(sc + 3 * quarter);                // [cap]
+    const int H = *w.H;
+    if (H <= PJ_LDS_CNT) {
+        for (int i = threadIdx.x; i < H; i += PJ_ROW_T) s_cnt[i] = 0u;
+        __syncthreads();
+        rows_for_graph<true>(Lg, w, s_cnt, cand, tc_g, tp_g, s_tc, s_tp, s_tb, N, knn, deg, H, adj_g,
+                             &s_ncand, s_red, &s_prev, s_sel, &s_nsel);
+    } else {
+        rows_for_graph<false>(Lg, w, cnt_g, cand, tc_g, tp_g, s_tc, s_tp, s_tb, N, knn, deg, H, adj_g,
+                              &s_ncand, s_red, &s_prev, s_sel, &s_nsel);
     }
 }
 
