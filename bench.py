@@ -210,6 +210,45 @@ def main():
     search_gbs = search_bytes / (search_ms * 1e-3) / 1e9
     attend_gbs = attend_bytes / (attend_ms * 1e-3) / 1e9
 
+    # ---- exact baselines on the same data (the paper's "Flat" retrieval and full attention) ---
+    flat_ws = torch.empty(ra.lib().ra_flat_workspace_bytes(n_seq, n_q, N), dtype=torch.uint8, device=dev)
+    full_ws = torch.empty(ra.lib().ra_full_attention_workspace_bytes(n_seq, n_q, n_kv, N),
+                          dtype=torch.uint8, device=dev)
+    flat_ids = torch.empty((n_seq, n_q, topk), dtype=torch.int32, device=dev)
+    f_out, f_lse = torch.empty((n_seq, n_q, d), **f32), torch.empty((n_seq, n_q), **f32)
+    base_layers = layers[:min(len(layers), 4)]
+
+    def timed_layers(fn, reps=5):
+        fn(base_layers[0])
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            for L in base_layers:
+                fn(L)
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / (reps * len(base_layers))
+
+    t_last = (a.steps - 1) % T
+    flat_ms = timed_layers(lambda L: ra.ra_flat_topk(L["q"][t_last], L["K"], sink, window, topk,
+                                                     workspace=flat_ws, ids=flat_ids))
+    full_ms = timed_layers(lambda L: ra.ra_full_attention(L["q"][t_last], L["K"], L["V"],
+                                                          workspace=full_ws, out=f_out, lse=f_lse))
+    key_bytes = n_seq * n_kv * N * d * esz
+    # recall of the graph search against the exact scan, every head of every layer, on the device
+    hits = total = 0
+    for L in layers:
+        ra.ra_decode_step(L["q"][t_last], L["idx"], L["K"], L["V"], sink, window, topk, ef, a.expand,
+                          out=L["out"], lse=L["lse"], ids=L["ids"], stats=L["st"])
+        ra.ra_flat_topk(L["q"][t_last], L["K"], sink, window, topk, workspace=flat_ws, ids=flat_ids)
+        got, ref = L["ids"].long(), flat_ids.long()
+        match = (got.unsqueeze(-1) == ref.unsqueeze(-2)) & (ref.unsqueeze(-2) >= 0)
+        hits += int(match.any(-2).sum())
+        total += int((ref >= 0).sum())
+    recall_device = hits / max(total, 1)
+    del flat_ws, full_ws
+
     if a.copy_calibration:
         src = torch.empty(1 << 30, dtype=torch.uint8, device=dev).fill_(1)
         dst = torch.empty_like(src)
@@ -270,7 +309,7 @@ def main():
         "value": ms_per_step, "unit": "ms", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
         "ms_per_step": ms_per_step, "higher_is_better": False, "scaling": "weak",
         "vs_baseline": None, "dtype": "bf16" if esz == 2 else "f32", "data": "synthetic",
-        "recall_at_100": recall,
+        "recall_at_100": recall_device, "recall_at_100_cpu_oracle_sample": recall,
         "config": {"workload": f"{a.workload}: {len(layers)} layers x {n_seq} seq x {n_q} q heads / "
                                f"{n_kv} kv heads, d={d}, N={N}, M={N} prefill queries/head",
                    "topk": topk, "ef": ef, "expand": a.expand, "deg": deg, "knn": w0.knn,
@@ -286,6 +325,13 @@ def main():
                                  "algorithmic_bytes_per_launch": search_bytes},
                    "ra_attend": {"avg_launch_ms": attend_ms, "algorithmic_GBs": attend_gbs,
                                  "algorithmic_bytes_per_launch": attend_bytes}},
+        "exact_baselines": {
+            "flat_topk": {"ms_per_layer": flat_ms, "key_scan_GBs": key_bytes / (flat_ms * 1e-3) / 1e9,
+                          "frac_of_hbm_peak": key_bytes / (flat_ms * 1e-3) / 1e9 / HBM_PEAK_GBS},
+            "full_attention": {"ms_per_layer": full_ms,
+                               "kv_scan_GBs": 2 * key_bytes / (full_ms * 1e-3) / 1e9,
+                               "frac_of_hbm_peak": 2 * key_bytes / (full_ms * 1e-3) / 1e9 / HBM_PEAK_GBS},
+            "graph_decode_ms_per_layer": decode_ms},
         "build": {"seconds": t_build, "generate_seconds": t_gen,
                   "knn_TFLOPs_incl_projection": build_flop / max(t_build, 1e-9) / 1e12},
         "cpu_baseline": cpu,

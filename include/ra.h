@@ -26,6 +26,7 @@
 #ifndef RA_H
 #define RA_H
 
+#include <stddef.h>
 #include <stdint.h>
 
 #ifdef __cplusplus
@@ -109,12 +110,33 @@ ra_status ra_attend(const void* q, const ra_index* idx, const void* K, const voi
                     const int32_t* ids, void* stream, float* out, float* lse,
                     float* o_omega, float* lse_omega, float* o_w, float* lse_w);
 
-/* ra_search then ra_attend: one layer's decode-step attention for all sequences and
- * query heads. ids and stats may be NULL (ids then live in the index workspace). */
+/* One layer's decode-step attention for all sequences and query heads: the results of
+ * ra_search followed by ra_attend, computed by a single fused launch (search, Eq. 2 over
+ * Omega and W, Eq. 4-5). ids and stats may be NULL (ids then live in the index workspace).
+ * Calls on one handle share its workspace: calls that overlap in time on one handle race. */
 ra_status ra_decode_step(const void* q, const ra_index* idx, const void* K, const void* V,
                          ra_dtype dt, int64_t N, int sink, int window, int topk, int ef,
                          int expand, void* stream, float* out, float* lse, int32_t* ids,
                          ra_stats* stats);
+
+/* ---- exact baselines on the same harness ------------------------------------------- */
+
+/* The paper's "Flat" retrieval (exact KNN by linear scan, Sec. 4.1 and Table 5): the topk keys of
+ * largest inner product outside W for every (sequence, query head), best first, ties to the lower
+ * id, padded with -1. Scores are the same fixed-order float32 inner products ra_search uses, so
+ * the two rank keys identically and recall of the graph search can be measured on the device.
+ * workspace: device memory of at least ra_flat_workspace_bytes(n_seq, n_q_heads, N) bytes. */
+size_t ra_flat_workspace_bytes(int n_seq, int n_q_heads, int64_t N);
+ra_status ra_flat_topk(const void* q, const void* K, ra_dtype dt, int n_seq, int n_q_heads,
+                       int n_kv_heads, int64_t N, int d, int sink, int window, int topk,
+                       void* workspace, size_t workspace_bytes, void* stream, int32_t* ids);
+
+/* Eq. 1: softmax attention over all N tokens (what the method approximates), as (out, lse).
+ * workspace: device memory of at least ra_full_attention_workspace_bytes(...) bytes. */
+size_t ra_full_attention_workspace_bytes(int n_seq, int n_q_heads, int n_kv_heads, int64_t N);
+ra_status ra_full_attention(const void* q, const void* K, const void* V, ra_dtype dt, int n_seq,
+                            int n_q_heads, int n_kv_heads, int64_t N, int d, void* workspace,
+                            size_t workspace_bytes, void* stream, float* out, float* lse);
 
 /* ---- handle management ------------------------------------------------------------- */
 

@@ -20,10 +20,12 @@ def scores_f64(q, K):
     return np.asarray(K, np.float64) @ np.asarray(q, np.float64)
 
 
-def topk_bruteforce(q, K, k, exclude=None):
+def topk_bruteforce(q, K, k, exclude=None, score_fn=None):
     """Exact top-k by linear scan (the paper's "Flat" baseline, Sec. 4.1), skipping
-    the ids in `exclude`. Returns ids best-first (fewer than k if fewer eligible)."""
-    s = scores_f64(q, K)
+    the ids in `exclude`. Returns ids best-first (fewer than k if fewer eligible).
+    Scores are float64 inner products unless `score_fn(q, K)` is given (used to take the
+    decision in the float32 order of oracle/search.py when a device scan is checked)."""
+    s = scores_f64(q, K) if score_fn is None else np.asarray(score_fn(q, K))
     ids = np.arange(s.shape[0], dtype=np.int64)
     if exclude is not None and len(exclude):
         keep = np.ones(s.shape[0], bool)

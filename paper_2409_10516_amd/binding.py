@@ -60,6 +60,14 @@ def lib() -> C.CDLL:
     L.ra_index_entry.restype = vp
     L.ra_index_free.argtypes = [vp]
     L.ra_index_free.restype = None
+    L.ra_flat_workspace_bytes.argtypes = [i32, i32, i64]
+    L.ra_flat_workspace_bytes.restype = C.c_size_t
+    L.ra_flat_topk.argtypes = [vp, vp, i32, i32, i32, i32, i64, i32, i32, i32, i32, vp, C.c_size_t, vp, vp]
+    L.ra_flat_topk.restype = i32
+    L.ra_full_attention_workspace_bytes.argtypes = [i32, i32, i32, i64]
+    L.ra_full_attention_workspace_bytes.restype = C.c_size_t
+    L.ra_full_attention.argtypes = [vp, vp, vp, i32, i32, i32, i32, i64, i32, vp, C.c_size_t, vp, vp, vp]
+    L.ra_full_attention.restype = i32
     for name in ("ra_knn", "ra_project", "ra_build_index", "ra_search", "ra_attend",
                  "ra_decode_step", "ra_index_import", "ra_index_export"):
         getattr(L, name).restype = i32
@@ -242,3 +250,37 @@ def ra_decode_step(q, idx: Index, K, V, sink: int, window: int, topk: int, ef: i
                                 window, topk, ef, expand, _stream(stream), _ptr(out), _ptr(lse),
                                 _ptr(ids), _ptr(stats)))
     return out, lse, ids, stats
+
+
+def ra_flat_topk(q, K, sink: int, window: int, topk: int, stream=None, workspace=None, ids=None):
+    """Exact top-k by linear scan for every (sequence, query head) -> ids int32 [n_seq][n_q][topk]."""
+    _dev(q, K, workspace, ids)
+    n_seq, n_q, d = q.shape
+    n_kv, N = K.shape[1], K.shape[2]
+    need = lib().ra_flat_workspace_bytes(n_seq, n_q, N)
+    if workspace is None:
+        workspace = torch.empty(need, dtype=torch.uint8, device=q.device)
+    if ids is None:
+        ids = torch.empty((n_seq, n_q, topk), dtype=torch.int32, device=q.device)
+    _check(lib().ra_flat_topk(_ptr(q), _ptr(K), _dt(K), n_seq, n_q, n_kv, N, d, sink, window, topk,
+                              _ptr(workspace), workspace.numel(), _stream(stream), _ptr(ids)))
+    return ids
+
+
+def ra_full_attention(q, K, V, stream=None, workspace=None, out=None, lse=None):
+    """Eq. 1 over the whole context -> (out float32 [n_seq][n_q][d], lse float32 [n_seq][n_q])."""
+    _dev(q, K, V, workspace, out, lse)
+    n_seq, n_q, d = q.shape
+    n_kv, N = K.shape[1], K.shape[2]
+    need = lib().ra_full_attention_workspace_bytes(n_seq, n_q, n_kv, N)
+    if workspace is None:
+        workspace = torch.empty(need, dtype=torch.uint8, device=q.device)
+    f = dict(dtype=torch.float32, device=q.device)
+    if out is None:
+        out = torch.empty((n_seq, n_q, d), **f)
+    if lse is None:
+        lse = torch.empty((n_seq, n_q), **f)
+    _check(lib().ra_full_attention(_ptr(q), _ptr(K), _ptr(V), _dt(K), n_seq, n_q, n_kv, N, d,
+                                   _ptr(workspace), workspace.numel(), _stream(stream), _ptr(out),
+                                   _ptr(lse)))
+    return out, lse

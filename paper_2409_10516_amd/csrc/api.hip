@@ -298,3 +298,64 @@ extern "C" ra_status ra_decode_step(const void* q, const ra_index* idx, const vo
                             sink, window, topk, ef, expand, ix->bitset, (hipStream_t)stream, out, lse,
                             ids, stats);
 }
+
+// ---- exact baselines (the paper's "Flat" retrieval and full attention) ---------------------
+extern "C" size_t ra_flat_workspace_bytes(int n_seq, int n_q_heads, int64_t N) {
+    if (n_seq < 1 || n_q_heads < 1 || N < 1) return 0;
+    return (size_t)n_seq * n_q_heads * N * sizeof(uint32_t);
+}
+
+extern "C" ra_status ra_flat_topk(const void* q, const void* K, ra_dtype dt, int n_seq, int n_q,
+                                  int n_kv, int64_t N, int d, int sink, int window, int topk,
+                                  void* workspace, size_t workspace_bytes, void* stream,
+                                  int32_t* ids) {
+    if (!q || !K || !ids || !workspace) RA_FAIL(RA_EINVAL, "NULL argument");
+    RA_TRY(check_dtype(dt));
+    RA_TRY(check_heads(n_seq, n_q, n_kv));
+    RA_TRY(check_dim(d));
+    if (N < 1) RA_FAIL(RA_EINVAL, "N must be positive");
+    if (sink < 0 || window < 0) RA_FAIL(RA_EINVAL, "sink and window must be non-negative");
+    if (topk < 1) RA_FAIL(RA_EINVAL, "topk must be positive");
+    if (topk > RA_MAX_TOPK) RA_FAIL(RA_EUNSUP, "topk %d exceeds RA_MAX_TOPK %d", topk, RA_MAX_TOPK);
+    if (workspace_bytes < ra_flat_workspace_bytes(n_seq, n_q, N))
+        RA_FAIL(RA_ESHAPE, "workspace of %zu B is smaller than ra_flat_workspace_bytes", workspace_bytes);
+    return ra_launch_flat_topk(q, K, dt, n_seq, n_q, n_kv, N, sink, window, topk,
+                               (uint32_t*)workspace, (hipStream_t)stream, ids);
+}
+
+extern "C" size_t ra_full_attention_workspace_bytes(int n_seq, int n_q_heads, int n_kv_heads,
+                                                     int64_t N) {
+    if (n_seq < 1 || n_q_heads < 1 || n_kv_heads < 1 || N < 1) return 0;
+    // partial records of a fully static context, preceded by one padded id per head
+    return 256 + (size_t)n_seq * n_q_heads * sizeof(int32_t) +
+           ra_attend_partial_floats(n_seq, n_q_heads, n_kv_heads, N, (int)(N > 0x7fffffff ? 0x7fffffff : N),
+                                    0, 1) * sizeof(float);
+}
+
+__global__ void api_fill_i32_kernel(int32_t* p, int n, int32_t v) {
+    const int i = blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) p[i] = v;
+}
+
+extern "C" ra_status ra_full_attention(const void* q, const void* K, const void* V, ra_dtype dt,
+                                       int n_seq, int n_q, int n_kv, int64_t N, int d,
+                                       void* workspace, size_t workspace_bytes, void* stream,
+                                       float* out, float* lse) {
+    if (!q || !K || !V || !out || !lse || !workspace) RA_FAIL(RA_EINVAL, "NULL argument");
+    RA_TRY(check_dtype(dt));
+    RA_TRY(check_heads(n_seq, n_q, n_kv));
+    RA_TRY(check_dim(d));
+    if (N < 1) RA_FAIL(RA_EINVAL, "N must be positive");
+    if (N > 0x7fffffff / 2) RA_FAIL(RA_EUNSUP, "N too large");
+    if (workspace_bytes < ra_full_attention_workspace_bytes(n_seq, n_q, n_kv, N))
+        RA_FAIL(RA_ESHAPE, "workspace of %zu B is smaller than ra_full_attention_workspace_bytes",
+                workspace_bytes);
+    const int heads = n_seq * n_q;
+    int32_t* ids = (int32_t*)workspace;                       // one id per head, all -1: Omega is empty
+    float* partials = (float*)((char*)workspace + ((heads * sizeof(int32_t) + 255) & ~(size_t)255));
+    hipLaunchKernelGGL(api_fill_i32_kernel, dim3((heads + 255) / 256), dim3(256), 0,
+                       (hipStream_t)stream, ids, heads, -1);
+    // the whole context as the "static" set of Eq. 2: W = [0, N), Omega empty
+    return ra_launch_attend(q, K, V, dt, n_seq, n_q, n_kv, N, (int)N, 0, 1, ids, partials,
+                            (hipStream_t)stream, out, lse, nullptr, nullptr, nullptr, nullptr);
+}

@@ -6,7 +6,7 @@ template <int DT, int G>
 __global__ __launch_bounds__(AT_THREADS) void attend_partial_kernel(
     const void* __restrict__ q, const void* __restrict__ K, const void* __restrict__ V,
     const int32_t* __restrict__ ids, float* __restrict__ partials, int n_q, int n_kv, int64_t N,
-    int s, int w, int topk, int nS, int nG, float scale) {
+    int s, int w, int topk, int nS, int nG, int sub, float scale) {
     extern __shared__ float smem[];
     const int kvh = blockIdx.y, seq = blockIdx.z, x = blockIdx.x;
     const int P = nS + nG;
@@ -18,12 +18,12 @@ __global__ __launch_bounds__(AT_THREADS) void attend_partial_kernel(
     float* rec_g = partials + ((size_t)seq * n_q + h0) * P * AT_RS;
     if (x < nS) {
         RowSrc src{nullptr, N, s, w, s + w, 0};
-        attend_chunk<DT, G>(threadIdx.x, true, qg, Kh, Vh, src, x, scale, rec_g + (size_t)x * AT_RS,
+        attend_chunk<DT, G>(threadIdx.x, true, qg, Kh, Vh, src, x, sub, scale, rec_g + (size_t)x * AT_RS,
                             (int64_t)P * AT_RS, smem);
     } else {
         const int t = x - nS, g = t / nG, c = t % nG;
         RowSrc src{ids + ((size_t)seq * n_q + h0 + g) * topk, N, 0, 0, topk, 0};
-        attend_chunk<DT, 1>(threadIdx.x, true, qg + (size_t)g * RA_D * esz, Kh, Vh, src, c, scale,
+        attend_chunk<DT, 1>(threadIdx.x, true, qg + (size_t)g * RA_D * esz, Kh, Vh, src, c, 1, scale,
                             rec_g + ((size_t)g * P + nS + c) * AT_RS, 0, smem);
     }
 }
@@ -38,11 +38,21 @@ __global__ __launch_bounds__(RA_D) void attend_merge_kernel(
                       lse_om, o_w, lse_w);
 }
 
+// 64-row sub-chunks per static workgroup: 1 for the decode step's few hundred static rows, more
+// when the static range is long (full attention), so that a head never has more than about 128
+// static records to combine
+static int static_sub(int rows) {
+    int sub = 1;
+    while (sub < 64 && (rows + AT_CH * sub - 1) / (AT_CH * sub) > 128) sub <<= 1;
+    return sub;
+}
+
 size_t ra_attend_partial_floats(int n_seq, int n_q, int n_kv, int64_t N, int sink, int window,
                                 int topk) {
     int s, w;
     static_ranges(N, sink, window, &s, &w);
-    const int nS = (s + w + AT_CH - 1) / AT_CH, nG = (topk + AT_CH - 1) / AT_CH;
+    const int sub = static_sub(s + w);
+    const int nS = (s + w + AT_CH * sub - 1) / (AT_CH * sub), nG = (topk + AT_CH - 1) / AT_CH;
     return (size_t)n_seq * n_q * (nS + nG) * AT_RS;
 }
 
@@ -50,11 +60,11 @@ template <int DT>
 static ra_status launch_partial(int G, dim3 grid, size_t lds, hipStream_t st, const void* q,
                                 const void* K, const void* V, const int32_t* ids, float* partials,
                                 int n_q, int n_kv, int64_t N, int s, int w, int topk, int nS, int nG,
-                                float scale) {
+                                int sub, float scale) {
 #define RA_AT_CASE(GG)                                                                          \
     case GG:                                                                                    \
         hipLaunchKernelGGL((attend_partial_kernel<DT, GG>), grid, dim3(AT_THREADS), lds, st, q, K, \
-                           V, ids, partials, n_q, n_kv, N, s, w, topk, nS, nG, scale);          \
+                           V, ids, partials, n_q, n_kv, N, s, w, topk, nS, nG, sub, scale);     \
         break;
     switch (G) {
         RA_AT_CASE(1)
@@ -76,15 +86,16 @@ ra_status ra_launch_attend(const void* q, const void* K, const void* V, ra_dtype
     int s, w;
     static_ranges(N, sink, window, &s, &w);
     const int G = n_q / n_kv;
-    const int nS = (s + w + AT_CH - 1) / AT_CH, nG = (topk + AT_CH - 1) / AT_CH;
+    const int sub = static_sub(s + w);
+    const int nS = (s + w + AT_CH * sub - 1) / (AT_CH * sub), nG = (topk + AT_CH - 1) / AT_CH;
     const float scale = 1.0f / sqrtf((float)RA_D);
     dim3 grid(nS + G * nG, n_kv, n_seq);
     const size_t lds = (size_t)AT_TEAM_LDS_FLOATS * sizeof(float);
     ra_status rc = dt == RA_BF16
         ? launch_partial<RA_BF16>(G, grid, lds, st, q, K, V, ids, partials, n_q, n_kv, N, s, w,
-                                  topk, nS, nG, scale)
+                                  topk, nS, nG, sub, scale)
         : launch_partial<RA_F32>(G, grid, lds, st, q, K, V, ids, partials, n_q, n_kv, N, s, w,
-                                 topk, nS, nG, scale);
+                                 topk, nS, nG, sub, scale);
     if (rc != RA_OK) return rc;
     RA_HIP(hipGetLastError());
     hipLaunchKernelGGL(attend_merge_kernel, dim3(n_q, n_seq), dim3(RA_D), 0, st, partials, n_q, nS,

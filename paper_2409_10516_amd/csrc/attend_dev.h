@@ -62,13 +62,15 @@ __device__ __forceinline__ float at_dpp(float v) {
 }
 
 // One chunk for NH query heads that share the same K/V rows.
+// A call covers `n_sub` consecutive sub-chunks of 64 rows (1 for the decode step; more when a
+// long dense range is streamed, so that the number of partial records stays small).
 // `tid` is the thread's index inside its team of AT_THREADS threads (a workgroup may hold
 // several teams, each with its own `smem`; every team must call this the same number of
 // times because it contains workgroup barriers). An inactive team computes on an empty row
 // source and writes nothing.
 template <int DT, int NH>
 __device__ void attend_chunk(int tid, bool active, const void* q0, const void* Kh, const void* Vh,
-                             const RowSrc& src, int chunk, float scale, float* rec0,
+                             const RowSrc& src, int chunk, int n_sub, float scale, float* rec0,
                              int64_t rec_stride, float* smem) {
     const int grp = tid >> 4, lane16 = tid & 15;
     float qv[NH][8], acc[NH][8], m[NH], l[NH];
@@ -80,15 +82,17 @@ __device__ void attend_chunk(int tid, bool active, const void* q0, const void* K
 #pragma unroll
         for (int e = 0; e < 8; ++e) acc[g][e] = 0.f;
     }
-    constexpr int RPG = AT_CH / 16;    // rows per 16-lane group
+    constexpr int RPG = AT_CH / 16;    // rows per 16-lane group and sub-chunk
+    // the call covers sub-chunks [chunk * n_sub, (chunk + 1) * n_sub) of 64 rows each
+    for (int sub = chunk * n_sub; sub < (chunk + 1) * n_sub; ++sub) {
     int64_t rid[RPG];
     float kv[RPG][8], vv[RPG][8];
 #pragma unroll
     for (int i = 0; i < RPG; ++i) {
         const int r = src.interleave
-            ? (chunk / src.interleave) * AT_CH * src.interleave + (chunk % src.interleave) * 16 + grp +
+            ? (sub / src.interleave) * AT_CH * src.interleave + (sub % src.interleave) * 16 + grp +
                   16 * src.interleave * i
-            : chunk * AT_CH + grp + 16 * i;
+            : sub * AT_CH + grp + 16 * i;
         rid[i] = chunk_row(src, r);
         if (rid[i] >= 0) {
             load_row8<DT>(Kh, rid[i], lane16, kv[i]);
@@ -116,6 +120,7 @@ __device__ void attend_chunk(int tid, bool active, const void* q0, const void* K
             for (int e = 0; e < 8; ++e) acc[g][e] = fmaf(p, vv[i][e], acc[g][e] * corr);
             m[g] = mn;
         }
+    }
     }
     // combine the 16 row-groups of the workgroup, one head at a time
     float* sm = smem;                       // [16]

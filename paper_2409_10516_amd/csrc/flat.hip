@@ -1,0 +1,179 @@
+// The paper's exact baselines on the same harness: "Flat" retrieval (exact top-k by scanning
+// every key, Sec. 4.1 and Table 5) and full attention over the whole context (Eq. 1). On a part
+// with 8 TB/s of HBM these set the honest reference for the graph search: one layer's keys at
+// 128K context are 268 MB, i.e. tens of microseconds of streaming.
+//
+// Flat top-k, two kernels:
+//   1. flat_scores_kernel: streams K once per KV head and scores every key against the query
+//      heads of its GQA group (16 lanes per key row, the same fixed-order float32 inner product
+//      as the graph search, so both rank keys identically); writes one order-preserving uint32
+//      per (head, key), 0 for keys of the static set W, which retrieval must not return.
+//   2. flat_select_kernel: one workgroup per head. Radix select over the 32-bit keys (four
+//      8-bit histogram passes, most significant first) finds the k-th largest key exactly; the
+//      keys above it plus the lowest ids among its ties are collected and sorted by (score
+//      descending, id ascending) with a bitonic network in LDS.
+#include "search_dev.h"
+
+#define FL_THREADS 256
+#define FL_CHUNK 2048              // keys per workgroup of the scoring kernel
+#define FL_SEL_T 1024
+
+// grid: x = chunk of FL_CHUNK keys, y = KV head, z = seq
+template <int DT, int G>
+__global__ __launch_bounds__(FL_THREADS) void flat_scores_kernel(
+    const void* __restrict__ q, const void* __restrict__ K, int n_q, int n_kv, int64_t N, int s, int w,
+    uint32_t* __restrict__ keys) {
+    const int tid = threadIdx.x, grp = tid >> 4, lane16 = tid & 15;
+    const int kvh = blockIdx.y, seq = blockIdx.z, h0 = seq * n_q + kvh * G;
+    const size_t esz = DT == RA_BF16 ? 2 : 4;
+    const char* Kh = reinterpret_cast<const char*>(K) + ((size_t)seq * n_kv + kvh) * N * RA_D * esz;
+    float qv[G][8];
+#pragma unroll
+    for (int g = 0; g < G; ++g)
+        load_q8<DT>(reinterpret_cast<const char*>(q) + (size_t)(h0 + g) * RA_D * esz, lane16, qv[g]);
+    const int64_t base = (int64_t)blockIdx.x * FL_CHUNK;
+    for (int r0 = 0; r0 < FL_CHUNK; r0 += 16 * 4) {
+        RowBits<DT> rows[4];
+        int64_t id[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            id[u] = base + r0 + u * 16 + grp;
+            rows[u] = load_key<DT>(Kh, id[u] < N ? id[u] : N - 1, lane16);   // loads stay unconditional
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+#pragma unroll
+            for (int g = 0; g < G; ++g) {
+                const float sc = score_fixed<DT>(rows[u], qv[g]);
+                if (lane16 == 0 && id[u] < N) {
+                    const bool is_static = id[u] < s || id[u] >= N - w;
+                    keys[(size_t)(h0 + g) * N + id[u]] = is_static ? 0u : f32_ordered(sc);
+                }
+            }
+        }
+    }
+}
+
+// grid: x = head; block = FL_SEL_T threads. ids_out [heads][topk], padded with -1.
+__global__ __launch_bounds__(FL_SEL_T) void flat_select_kernel(const uint32_t* __restrict__ keys,
+                                                               int64_t N, int topk,
+                                                               int32_t* __restrict__ ids_out) {
+    __shared__ unsigned hist[256];
+    __shared__ unsigned s_prefix, s_need, s_cnt, s_eq_total, s_run;
+    __shared__ unsigned long long sel[RA_MAX_TOPK];
+    __shared__ int wtot[FL_SEL_T / RA_WAVE];
+    const int tid = threadIdx.x, lane = tid & (RA_WAVE - 1), wv = tid / RA_WAVE;
+    const uint32_t* kh = keys + (size_t)blockIdx.x * N;
+    int32_t* out = ids_out + (size_t)blockIdx.x * topk;
+    // ---- radix select: the topk-th largest key (keys of W are 0 and sort last)
+    if (tid == 0) { s_prefix = 0u; s_need = (unsigned)topk; }
+    __syncthreads();
+    for (int shift = 24; shift >= 0; shift -= 8) {
+        if (tid < 256) hist[tid] = 0u;
+        __syncthreads();
+        const unsigned prefix = s_prefix;
+        const unsigned himask = shift == 24 ? 0u : (0xffffffffu << (shift + 8));
+        for (int64_t i = tid; i < N; i += FL_SEL_T) {
+            const uint32_t k = kh[i];
+            if ((k & himask) == prefix) atomicAdd(&hist[(k >> shift) & 255u], 1u);
+        }
+        __syncthreads();
+        if (tid == 0) {
+            unsigned need = s_need, bin = 255u;
+            for (;; --bin) {                     // walk from the largest digit down
+                const unsigned c = hist[bin];
+                if (c >= need || bin == 0u) break;
+                need -= c;
+            }
+            s_prefix = prefix | (bin << shift);
+            s_need = need;                       // how many are wanted from this digit's keys
+            if (shift == 0) s_eq_total = hist[bin];
+        }
+        __syncthreads();
+    }
+    const uint32_t T = s_prefix;                 // the topk-th largest key
+    const unsigned need_eq = s_need;             // entries wanted among the keys equal to T
+    const unsigned eq_total = s_eq_total;
+    if (tid == 0) { s_cnt = 0u; s_run = 0u; }
+    __syncthreads();
+    // ---- collect: every key above T; among the ties, the lowest ids
+    const bool ordered = eq_total > need_eq;     // more ties than wanted: take them in id order
+    for (int64_t i0 = 0; i0 < N; i0 += FL_SEL_T) {
+        const int64_t i = i0 + tid;
+        const uint32_t k = i < N ? kh[i] : 0u;
+        if (i < N && k > T)
+            sel[atomicAdd(&s_cnt, 1u)] = ((unsigned long long)k << 32) | (0xffffffffu - (uint32_t)i);
+        const bool tie = i < N && k == T && T != 0u;
+        if (!ordered) {
+            if (tie) sel[atomicAdd(&s_cnt, 1u)] = ((unsigned long long)k << 32) | (0xffffffffu - (uint32_t)i);
+        } else {
+            // stable: a tie is taken iff fewer than need_eq ties precede it
+            const unsigned long long m = __ballot(tie);
+            if (lane == 0) wtot[wv] = __popcll(m);
+            __syncthreads();
+            unsigned before = s_run;
+            for (int x = 0; x < wv; ++x) before += wtot[x];
+            const unsigned rank = before + __popcll(m & ((1ull << lane) - 1ull));
+            if (tie && rank < need_eq)
+                sel[atomicAdd(&s_cnt, 1u)] = ((unsigned long long)k << 32) | (0xffffffffu - (uint32_t)i);
+            __syncthreads();
+            if (tid == 0) {
+                unsigned tot = 0;
+                for (int x = 0; x < FL_SEL_T / RA_WAVE; ++x) tot += wtot[x];
+                s_run += tot;
+            }
+            __syncthreads();
+        }
+    }
+    __syncthreads();
+    const int n = (int)s_cnt;                    // <= topk (fewer when W leaves fewer eligible keys)
+    // ---- sort (score descending, id ascending) = 64-bit key descending
+    int n2 = 1;
+    while (n2 < n) n2 <<= 1;
+    for (int i = n + tid; i < n2; i += FL_SEL_T) sel[i] = 0ull;
+    __syncthreads();
+    for (int k = 2; k <= n2; k <<= 1) {
+        for (int j = k >> 1; j > 0; j >>= 1) {
+            for (int i = tid; i < n2; i += FL_SEL_T) {
+                const int ixj = i ^ j;
+                if (ixj > i) {
+                    const unsigned long long a = sel[i], b = sel[ixj];
+                    const bool desc = (i & k) == 0;
+                    if (desc ? (a < b) : (a > b)) { sel[i] = b; sel[ixj] = a; }
+                }
+            }
+            __syncthreads();
+        }
+    }
+    for (int i = tid; i < topk; i += FL_SEL_T)
+        out[i] = i < n ? (int32_t)(0xffffffffu - (uint32_t)sel[i]) : -1;
+}
+
+ra_status ra_launch_flat_topk(const void* q, const void* K, ra_dtype dt, int n_seq, int n_q, int n_kv,
+                              int64_t N, int sink, int window, int topk, uint32_t* keys_ws,
+                              hipStream_t st, int32_t* ids) {
+    int64_t ss = sink < 0 ? 0 : sink, ww = window < 0 ? 0 : window;
+    if (ss > N) ss = N;
+    if (ww > N) ww = N;
+    if (ss + ww >= N) { ss = N; ww = 0; }
+    const int G = n_q / n_kv;
+    const dim3 grid((unsigned)((N + FL_CHUNK - 1) / FL_CHUNK), n_kv, n_seq);
+#define RA_FL_CASE(DTV, GG)                                                                     \
+    case GG:                                                                                    \
+        hipLaunchKernelGGL((flat_scores_kernel<DTV, GG>), grid, dim3(FL_THREADS), 0, st, q, K, n_q, \
+                           n_kv, N, (int)ss, (int)ww, keys_ws);                                 \
+        break;
+    if (dt == RA_BF16) {
+        switch (G) { RA_FL_CASE(RA_BF16, 1) RA_FL_CASE(RA_BF16, 2) RA_FL_CASE(RA_BF16, 4) RA_FL_CASE(RA_BF16, 8)
+            default: RA_FAIL(RA_EUNSUP, "query heads per KV head must be 1, 2, 4 or 8 (got %d)", G); }
+    } else {
+        switch (G) { RA_FL_CASE(RA_F32, 1) RA_FL_CASE(RA_F32, 2) RA_FL_CASE(RA_F32, 4) RA_FL_CASE(RA_F32, 8)
+            default: RA_FAIL(RA_EUNSUP, "query heads per KV head must be 1, 2, 4 or 8 (got %d)", G); }
+    }
+#undef RA_FL_CASE
+    RA_HIP(hipGetLastError());
+    hipLaunchKernelGGL(flat_select_kernel, dim3(n_seq * n_q), dim3(FL_SEL_T), 0, st, keys_ws, N, topk,
+                       ids);
+    RA_HIP(hipGetLastError());
+    return RA_OK;
+}

@@ -1,0 +1,104 @@
+"""Parity of the exact baselines (flat-scan top-k, full attention) with the CPU oracle. GPU only."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2409_10516_amd as ra
+from oracle import attention as OA, mips as OM, search as OS
+from paper_2409_10516_amd import synth
+from tests.util import lse_close, out_close, to_np, tol_for
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def _cases():
+    return {
+        "config0_small": (lambda: synth.make_config0(N=3000, M=8, T=3, window=32), 100),
+        "llama_bf16": (lambda: synth.make_llama_layer(11, N=5000, M=8, T=2, n_q=8, n_kv=2,
+                                                      window=100), 64),
+        "llama_f32_2seq": (lambda: synth.make_llama_layer(12, N=701, M=8, T=2, n_seq=2, n_q=4, n_kv=4,
+                                                          dtype=torch.float32, window=37), 16),
+        "integer_ties": (lambda: synth.make_integer_case(5, N=2500, M=8, T=3, d=128, n_q=2, n_kv=1,
+                                                         sink=3, window=10), 200),
+        "integer_bf16_g8": (lambda: synth.make_integer_case(6, N=300, M=8, T=2, d=128, n_q=8, n_kv=1,
+                                                            dtype=torch.bfloat16, lo=-1, hi=1,
+                                                            sink=0, window=0), 33),
+    }
+
+
+@pytest.mark.parametrize("name", list(_cases()))
+def test_flat_topk_is_exact(name):
+    mk, topk = _cases()[name]
+    w = mk()
+    n_seq, n_kv, N, d = w.K.shape
+    n_q = w.q_decode.shape[2]
+    Kd = w.K.to(DEV)
+    W = OA.static_ids(N, w.sink, w.window)
+    for t in range(w.q_decode.shape[0]):
+        ids = ra.ra_flat_topk(w.q_decode[t].to(DEV), Kd, w.sink, w.window, topk).cpu().numpy()
+        for s in range(n_seq):
+            for h in range(n_q):
+                K = to_np(w.K[s, h // (n_q // n_kv)])
+                ref = OM.topk_bruteforce(to_np(w.q_decode[t, s, h]), K, topk, exclude=W,
+                                         score_fn=OS.score32)
+                assert ids[s, h].tolist() == ref.tolist(), (name, t, s, h)
+
+
+def test_flat_topk_pads_when_few_keys_are_eligible():
+    w = synth.make_integer_case(3, N=90, M=4, T=1, d=128)
+    ids = ra.ra_flat_topk(w.q_decode[0].to(DEV), w.K.to(DEV), 40, 45, 12).cpu().numpy()[0, 0]
+    ref = OM.topk_bruteforce(to_np(w.q_decode[0, 0, 0]), to_np(w.K[0, 0]), 12,
+                             exclude=OA.static_ids(90, 40, 45), score_fn=OS.score32)
+    assert len(ref) == 5 and ids[:5].tolist() == ref.tolist() and (ids[5:] == -1).all()
+    ids = ra.ra_flat_topk(w.q_decode[0].to(DEV), w.K.to(DEV), 60, 60, 4).cpu().numpy()[0, 0]
+    assert (ids == -1).all()                     # everything is static
+
+
+def test_flat_topk_all_scores_equal_takes_lowest_ids():
+    K = torch.ones((1, 1, 5000, 128), dtype=torch.bfloat16)
+    q = torch.ones((1, 1, 128), dtype=torch.bfloat16)
+    ids = ra.ra_flat_topk(q.to(DEV), K.to(DEV), 2, 0, 50).cpu().numpy()[0, 0]
+    assert ids.tolist() == list(range(2, 52))
+
+
+@pytest.mark.parametrize("name", list(_cases()))
+def test_full_attention_matches_eq1(name):
+    mk, _ = _cases()[name]
+    w = mk()
+    n_seq, n_kv, N, d = w.K.shape
+    n_q = w.q_decode.shape[2]
+    tol = tol_for(w.K.dtype)
+    out, lse = ra.ra_full_attention(w.q_decode[0].to(DEV), w.K.to(DEV), w.V.to(DEV))
+    out, lse = out.cpu().numpy(), lse.cpu().numpy()
+    for s in range(n_seq):
+        for h in range(n_q):
+            g = h // (n_q // n_kv)
+            ro, rl = OA.full_attention(to_np(w.q_decode[0, s, h]), to_np(w.K[s, g]), to_np(w.V[s, g]))
+            assert out_close(out[s, h], ro, tol) and lse_close(lse[s, h], rl, tol)
+
+
+def test_full_attention_long_context_uses_few_records():
+    """A 40000-token context takes the multi-sub-chunk path of the attention kernel."""
+    w = synth.make_llama_layer(21, N=40000, M=8, T=1, n_q=4, n_kv=2)
+    out, lse = ra.ra_full_attention(w.q_decode[0].to(DEV), w.K.to(DEV), w.V.to(DEV))
+    out, lse = out.cpu().numpy(), lse.cpu().numpy()
+    for h in (0, 3):
+        ro, rl = OA.full_attention(to_np(w.q_decode[0, 0, h]), to_np(w.K[0, h // 2]), to_np(w.V[0, h // 2]))
+        assert out_close(out[0, h], ro, 2e-3) and lse_close(lse[0, h], rl, 2e-3)
+
+
+def test_graph_recall_can_be_measured_on_device():
+    """recall@k of ra_search against ra_flat_topk equals the recall against the CPU brute force."""
+    w = synth.make_llama_layer(31, N=4096, M=2048, T=1, n_q=4, n_kv=2, ef=64, topk=32, window=64,
+                               device=DEV)
+    idx = ra.ra_build_index(w.K, w.Q_prefill, w.deg, w.knn)
+    ids, _ = ra.ra_search(w.q_decode[0], idx, w.K, w.sink, w.window, w.topk, w.ef, 8)
+    flat = ra.ra_flat_topk(w.q_decode[0], w.K, w.sink, w.window, w.topk)
+    W = OA.static_ids(4096, w.sink, w.window)
+    for h in range(4):
+        truth = OM.topk_bruteforce(to_np(w.q_decode[0, 0, h]), to_np(w.K[0, h // 2]), w.topk,
+                                   exclude=W, score_fn=OS.score32)
+        assert flat[0, h].cpu().tolist() == truth.tolist()
+        assert OM.recall(ids[0, h].cpu().numpy(), flat[0, h].cpu().numpy()) == \
+            OM.recall(ids[0, h].cpu().numpy(), truth)
