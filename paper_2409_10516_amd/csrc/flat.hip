@@ -8,15 +8,18 @@
 //      heads of its GQA group (16 lanes per key row, the same fixed-order float32 inner product
 //      as the graph search, so both rank keys identically); writes one order-preserving uint32
 //      per (head, key), 0 for keys of the static set W, which retrieval must not return.
-//   2. flat_select_kernel: one workgroup per head. Radix select over the 32-bit keys (four
-//      8-bit histogram passes, most significant first) finds the k-th largest key exactly; the
-//      keys above it plus the lowest ids among its ties are collected and sorted by (score
-//      descending, id ascending) with a bitonic network in LDS.
+//   2. flat_select_kernel: one workgroup per head. A threshold placed from a strided sample
+//      lets one pass collect a few hundred candidates that provably contain the top-k; they are
+//      sorted by (score descending, id ascending) with a bitonic network in LDS. When the
+//      sample cannot place a safe threshold, an exact radix select over all keys (four 8-bit
+//      histogram passes) finds the k-th largest key, and the keys above it plus the lowest ids
+//      among its ties are taken.
 #include "search_dev.h"
 
 #define FL_THREADS 256
-#define FL_CHUNK 2048              // keys per workgroup of the scoring kernel
+#define FL_CHUNK 512               // keys per workgroup of the scoring kernel
 #define FL_SEL_T 1024
+#define FL_ROWS 8                  // key rows in flight per 16-lane group
 
 // grid: x = chunk of FL_CHUNK keys, y = KV head, z = seq
 template <int DT, int G>
@@ -32,16 +35,16 @@ __global__ __launch_bounds__(FL_THREADS) void flat_scores_kernel(
     for (int g = 0; g < G; ++g)
         load_q8<DT>(reinterpret_cast<const char*>(q) + (size_t)(h0 + g) * RA_D * esz, lane16, qv[g]);
     const int64_t base = (int64_t)blockIdx.x * FL_CHUNK;
-    for (int r0 = 0; r0 < FL_CHUNK; r0 += 16 * 4) {
-        RowBits<DT> rows[4];
-        int64_t id[4];
+    for (int r0 = 0; r0 < FL_CHUNK; r0 += 16 * FL_ROWS) {
+        RowBits<DT> rows[FL_ROWS];
+        int64_t id[FL_ROWS];
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
+        for (int u = 0; u < FL_ROWS; ++u) {
             id[u] = base + r0 + u * 16 + grp;
             rows[u] = load_key<DT>(Kh, id[u] < N ? id[u] : N - 1, lane16);   // loads stay unconditional
         }
 #pragma unroll
-        for (int u = 0; u < 4; ++u) {
+        for (int u = 0; u < FL_ROWS; ++u) {
 #pragma unroll
             for (int g = 0; g < G; ++g) {
                 const float sc = score_fixed<DT>(rows[u], qv[g]);
@@ -54,79 +57,153 @@ __global__ __launch_bounds__(FL_THREADS) void flat_scores_kernel(
     }
 }
 
-// grid: x = head; block = FL_SEL_T threads. ids_out [heads][topk], padded with -1.
-__global__ __launch_bounds__(FL_SEL_T) void flat_select_kernel(const uint32_t* __restrict__ keys,
-                                                               int64_t N, int topk,
-                                                               int32_t* __restrict__ ids_out) {
-    __shared__ unsigned hist[256];
-    __shared__ unsigned s_prefix, s_need, s_cnt, s_eq_total, s_run;
-    __shared__ unsigned long long sel[RA_MAX_TOPK];
-    __shared__ int wtot[FL_SEL_T / RA_WAVE];
-    const int tid = threadIdx.x, lane = tid & (RA_WAVE - 1), wv = tid / RA_WAVE;
-    const uint32_t* kh = keys + (size_t)blockIdx.x * N;
-    int32_t* out = ids_out + (size_t)blockIdx.x * topk;
-    // ---- radix select: the topk-th largest key (keys of W are 0 and sort last)
-    if (tid == 0) { s_prefix = 0u; s_need = (unsigned)topk; }
+// Radix select over keys kh[0], kh[stride], ... (n of them): the `want`-th largest key, found
+// exactly by four 8-bit histogram passes, most significant digit first. Returns it in *T, the
+// number of entries wanted among the keys equal to it in *need_eq and their total in *eq_total.
+__device__ __forceinline__ void radix_select(const uint32_t* __restrict__ kh, int64_t n, int64_t stride,
+                                             unsigned want, unsigned* hist, unsigned* wsum,
+                                             unsigned* s_prefix, unsigned* s_need,
+                                             unsigned* s_eq_total) {
+    const int tid = threadIdx.x;
+    if (tid == 0) { *s_prefix = 0u; *s_need = want; }
     __syncthreads();
     for (int shift = 24; shift >= 0; shift -= 8) {
         if (tid < 256) hist[tid] = 0u;
         __syncthreads();
-        const unsigned prefix = s_prefix;
+        const unsigned prefix = *s_prefix, need = *s_need;     // both stable until the barrier below
         const unsigned himask = shift == 24 ? 0u : (0xffffffffu << (shift + 8));
-        for (int64_t i = tid; i < N; i += FL_SEL_T) {
-            const uint32_t k = kh[i];
-            if ((k & himask) == prefix) atomicAdd(&hist[(k >> shift) & 255u], 1u);
+        for (int64_t i0 = tid; i0 < n; i0 += FL_SEL_T * 4) {
+            uint32_t kv[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int64_t i = i0 + (int64_t)u * FL_SEL_T;
+                kv[u] = kh[(i < n ? i : n - 1) * stride];
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+                if (i0 + (int64_t)u * FL_SEL_T < n && (kv[u] & himask) == prefix)
+                    atomicAdd(&hist[(kv[u] >> shift) & 255u], 1u);
         }
         __syncthreads();
-        if (tid == 0) {
-            unsigned need = s_need, bin = 255u;
-            for (;; --bin) {                     // walk from the largest digit down
-                const unsigned c = hist[bin];
-                if (c >= need || bin == 0u) break;
-                need -= c;
+        // the digit where the count, accumulated from the largest digit down, reaches `need`:
+        // thread t < 256 owns digit 255 - t; inclusive scan over t, one thread matches
+        unsigned v = 0u, inc = 0u;
+        if (tid < 256) {
+            v = hist[255 - tid];
+            inc = v;
+#pragma unroll
+            for (int d = 1; d < RA_WAVE; d <<= 1) {
+                const unsigned o = __shfl_up(inc, d);
+                if ((tid & (RA_WAVE - 1)) >= d) inc += o;
             }
-            s_prefix = prefix | (bin << shift);
-            s_need = need;                       // how many are wanted from this digit's keys
-            if (shift == 0) s_eq_total = hist[bin];
+            if ((tid & (RA_WAVE - 1)) == RA_WAVE - 1) wsum[tid / RA_WAVE] = inc;
+        }
+        __syncthreads();
+        if (tid < 256) {
+            for (int x = 0; x < tid / RA_WAVE; ++x) inc += wsum[x];
+            const unsigned excl = inc - v;
+            if (excl < need && (inc >= need || tid == 255)) {
+                const unsigned bin = 255u - (unsigned)tid;
+                *s_prefix = prefix | (bin << shift);
+                *s_need = need - excl;           // how many are wanted from this digit's keys
+                if (shift == 0) *s_eq_total = v;
+            }
         }
         __syncthreads();
     }
-    const uint32_t T = s_prefix;                 // the topk-th largest key
-    const unsigned need_eq = s_need;             // entries wanted among the keys equal to T
-    const unsigned eq_total = s_eq_total;
-    if (tid == 0) { s_cnt = 0u; s_run = 0u; }
-    __syncthreads();
-    // ---- collect: every key above T; among the ties, the lowest ids
-    const bool ordered = eq_total > need_eq;     // more ties than wanted: take them in id order
-    for (int64_t i0 = 0; i0 < N; i0 += FL_SEL_T) {
-        const int64_t i = i0 + tid;
-        const uint32_t k = i < N ? kh[i] : 0u;
-        if (i < N && k > T)
-            sel[atomicAdd(&s_cnt, 1u)] = ((unsigned long long)k << 32) | (0xffffffffu - (uint32_t)i);
-        const bool tie = i < N && k == T && T != 0u;
-        if (!ordered) {
-            if (tie) sel[atomicAdd(&s_cnt, 1u)] = ((unsigned long long)k << 32) | (0xffffffffu - (uint32_t)i);
-        } else {
-            // stable: a tie is taken iff fewer than need_eq ties precede it
-            const unsigned long long m = __ballot(tie);
-            if (lane == 0) wtot[wv] = __popcll(m);
-            __syncthreads();
-            unsigned before = s_run;
-            for (int x = 0; x < wv; ++x) before += wtot[x];
-            const unsigned rank = before + __popcll(m & ((1ull << lane) - 1ull));
-            if (tie && rank < need_eq)
+}
+
+#define FL_CAND 4096               // candidate capacity of the fast path
+#define FL_SAMPLE 4096             // keys sampled to place the threshold
+
+// grid: x = head; block = FL_SEL_T threads. ids_out [heads][topk], padded with -1.
+// Fast path: a threshold is placed from a strided sample so that about four times topk keys
+// lie above it (the rank-r key of a 1-in-`stride` sample sits near rank r * stride of the
+// whole); one pass collects every key at or above it; if at least topk and at most FL_CAND were
+// collected, sorting them gives the exact answer (all ties of the k-th key are in the set).
+// Otherwise (tiny or adversarial inputs) the exact radix select over all keys decides.
+__global__ __launch_bounds__(FL_SEL_T) void flat_select_kernel(const uint32_t* __restrict__ keys,
+                                                               int64_t N, int topk,
+                                                               int32_t* __restrict__ ids_out) {
+    __shared__ unsigned hist[256], wsum4[4];
+    __shared__ unsigned s_prefix, s_need, s_cnt, s_eq_total, s_run;
+    __shared__ unsigned long long sel[FL_CAND];
+    __shared__ int wtot[FL_SEL_T / RA_WAVE];
+    const int tid = threadIdx.x, lane = tid & (RA_WAVE - 1), wv = tid / RA_WAVE;
+    const uint32_t* kh = keys + (size_t)blockIdx.x * N;
+    int32_t* out = ids_out + (size_t)blockIdx.x * topk;
+    int n = -1;                                  // number of selected entries once known
+    const int64_t stride = N / FL_SAMPLE;
+    if (stride >= 8 && (int64_t)topk * 4 <= N / 4) {
+        const unsigned want = (unsigned)((4 * (int64_t)topk + stride - 1) / stride) + 2u;
+        radix_select(kh, N / stride, stride, want, hist, wsum4, &s_prefix, &s_need, &s_eq_total);
+        const uint32_t T0 = s_prefix;
+        if (tid == 0) s_cnt = 0u;
+        __syncthreads();
+        if (T0 != 0u) {
+            for (int64_t i0 = tid; i0 < N; i0 += FL_SEL_T * 8) {
+                uint32_t kv[8];
+#pragma unroll
+                for (int u = 0; u < 8; ++u) {                 // loads first, all in flight
+                    const int64_t i = i0 + (int64_t)u * FL_SEL_T;
+                    kv[u] = kh[i < N ? i : N - 1];
+                }
+#pragma unroll
+                for (int u = 0; u < 8; ++u) {
+                    const int64_t i = i0 + (int64_t)u * FL_SEL_T;
+                    if (i < N && kv[u] >= T0) {
+                        const unsigned at = atomicAdd(&s_cnt, 1u);
+                        if (at < FL_CAND)
+                            sel[at] = ((unsigned long long)kv[u] << 32) | (0xffffffffu - (uint32_t)i);
+                    }
+                }
+            }
+        }
+        __syncthreads();
+        const unsigned c = s_cnt;
+        if (T0 != 0u && c >= (unsigned)topk && c <= FL_CAND) n = (int)c;
+        __syncthreads();
+    }
+    if (n < 0) {
+        // ---- exact radix select over all keys (keys of W are 0 and sort last)
+        radix_select(kh, N, 1, (unsigned)topk, hist, wsum4, &s_prefix, &s_need, &s_eq_total);
+        const uint32_t T = s_prefix;             // the topk-th largest key
+        const unsigned need_eq = s_need;         // entries wanted among the keys equal to T
+        const unsigned eq_total = s_eq_total;
+        if (tid == 0) { s_cnt = 0u; s_run = 0u; }
+        __syncthreads();
+        // collect every key above T; among the ties, the lowest ids
+        const bool ordered = eq_total > need_eq; // more ties than wanted: take them in id order
+        for (int64_t i0 = 0; i0 < N; i0 += FL_SEL_T) {
+            const int64_t i = i0 + tid;
+            const uint32_t k = i < N ? kh[i] : 0u;
+            if (i < N && k > T)
                 sel[atomicAdd(&s_cnt, 1u)] = ((unsigned long long)k << 32) | (0xffffffffu - (uint32_t)i);
-            __syncthreads();
-            if (tid == 0) {
-                unsigned tot = 0;
-                for (int x = 0; x < FL_SEL_T / RA_WAVE; ++x) tot += wtot[x];
-                s_run += tot;
+            const bool tie = i < N && k == T && T != 0u;
+            if (!ordered) {
+                if (tie) sel[atomicAdd(&s_cnt, 1u)] = ((unsigned long long)k << 32) | (0xffffffffu - (uint32_t)i);
+            } else {
+                // stable: a tie is taken iff fewer than need_eq ties precede it
+                const unsigned long long m = __ballot(tie);
+                if (lane == 0) wtot[wv] = __popcll(m);
+                __syncthreads();
+                unsigned before = s_run;
+                for (int x = 0; x < wv; ++x) before += wtot[x];
+                const unsigned rank = before + __popcll(m & ((1ull << lane) - 1ull));
+                if (tie && rank < need_eq)
+                    sel[atomicAdd(&s_cnt, 1u)] = ((unsigned long long)k << 32) | (0xffffffffu - (uint32_t)i);
+                __syncthreads();
+                if (tid == 0) {
+                    unsigned tot = 0;
+                    for (int x = 0; x < FL_SEL_T / RA_WAVE; ++x) tot += wtot[x];
+                    s_run += tot;
+                }
+                __syncthreads();
             }
-            __syncthreads();
         }
+        __syncthreads();
+        n = (int)s_cnt;                          // <= topk (fewer when W leaves fewer eligible keys)
     }
-    __syncthreads();
-    const int n = (int)s_cnt;                    // <= topk (fewer when W leaves fewer eligible keys)
     // ---- sort (score descending, id ascending) = 64-bit key descending
     int n2 = 1;
     while (n2 < n) n2 <<= 1;

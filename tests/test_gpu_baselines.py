@@ -55,11 +55,29 @@ def test_flat_topk_pads_when_few_keys_are_eligible():
     assert (ids == -1).all()                     # everything is static
 
 
-def test_flat_topk_all_scores_equal_takes_lowest_ids():
-    K = torch.ones((1, 1, 5000, 128), dtype=torch.bfloat16)
+@pytest.mark.parametrize("N", [5000, 40000])
+def test_flat_topk_all_scores_equal_takes_lowest_ids(N):
+    K = torch.ones((1, 1, N, 128), dtype=torch.bfloat16)
     q = torch.ones((1, 1, 128), dtype=torch.bfloat16)
     ids = ra.ra_flat_topk(q.to(DEV), K.to(DEV), 2, 0, 50).cpu().numpy()[0, 0]
     assert ids.tolist() == list(range(2, 52))
+
+
+@pytest.mark.parametrize("topk", [1, 100, 1024])
+def test_flat_topk_sampled_threshold_path(topk):
+    """Contexts of 32K keys and more place the selection threshold from a sample."""
+    w = synth.make_llama_layer(41, N=40000, M=8, T=1, n_q=4, n_kv=2, window=640)
+    ids = ra.ra_flat_topk(w.q_decode[0].to(DEV), w.K.to(DEV), 4, 640, topk).cpu().numpy()
+    W = OA.static_ids(40000, 4, 640)
+    for h in range(4):
+        ref = OM.topk_bruteforce(to_np(w.q_decode[0, 0, h]), to_np(w.K[0, h // 2]), topk, exclude=W,
+                                 score_fn=OS.score32)
+        assert ids[0, h].tolist() == ref.tolist()
+    # integer-valued keys: thousands of exact ties around the k-th score
+    wi = synth.make_integer_case(8, N=40000, M=4, T=1, d=128, lo=-1, hi=1)
+    ids = ra.ra_flat_topk(wi.q_decode[0].to(DEV), wi.K.to(DEV), 0, 0, topk).cpu().numpy()[0, 0]
+    ref = OM.topk_bruteforce(to_np(wi.q_decode[0, 0, 0]), to_np(wi.K[0, 0]), topk, score_fn=OS.score32)
+    assert ids.tolist() == ref.tolist()
 
 
 @pytest.mark.parametrize("name", list(_cases()))
