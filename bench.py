@@ -37,7 +37,7 @@ def parse():
                    choices=["config2", "config1", "config3", "config0"])
     p.add_argument("--layers", type=int, default=None, help="override the layer count (debug)")
     p.add_argument("--context", type=int, default=None, help="override N (debug)")
-    p.add_argument("--expand", type=int, default=32, help="search expansion width")
+    p.add_argument("--expand", type=int, default=64, help="search expansion width")
     p.add_argument("--tokens", type=int, default=8, help="distinct decode queries per head")
     p.add_argument("--recall-layers", type=int, default=2)
     p.add_argument("--cpu-heads", type=int, default=16, help="heads the CPU oracle is timed on")
@@ -317,7 +317,7 @@ def main():
         "roofline": {"bound": "hbm", "kernel": "decode_kernel", "achieved": decode_gbs,
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": decode_gbs / HBM_PEAK_GBS,
                      "traffic": (DECODE_TRAFFIC_BYTES_CONFIG2 if (a.workload == "config2"
-                                 and a.expand == 32 and not a.context) else None),
+                                 and a.expand == 64 and not a.context) else None),
                      "avg_launch_ms": decode_ms, "algorithmic_bytes_per_launch": decode_bytes,
                      "visited_per_search": visited / heads, "expanded_per_search": expanded / heads,
                      "iters_per_search": iters / heads},

@@ -59,7 +59,7 @@ typedef struct {
 #define RA_MAX_DEG 64
 #define RA_MAX_KNN 64
 #define RA_MAX_EF 1024
-#define RA_MAX_EXPAND 32
+#define RA_MAX_EXPAND 64
 #define RA_MAX_TOPK 1024
 
 /* ---- index build (Sec. 3.2) -------------------------------------------------------- */

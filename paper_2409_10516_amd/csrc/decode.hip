@@ -17,7 +17,6 @@
 #include "attend_dev.h"
 #include "search_dev.h"
 
-#define DC_ROWS 4          // rows in flight per 16-lane group
 
 struct Softmax8 {          // a lane's share of an online-softmax state: 8 of the 128 outputs
     float m, l, acc[8];
@@ -53,6 +52,7 @@ __global__ __launch_bounds__(SR_THREADS) void decode_kernel(
     const char* Vh = reinterpret_cast<const char*>(V) + ((size_t)seq * n_kv + kvh) * N * RA_D * esz;
     float qv[8];
     load_row8<DT>(reinterpret_cast<const char*>(q) + (size_t)head * RA_D * esz, 0, lane16, qv);
+    constexpr int DC_ROWS = DT == RA_BF16 ? 6 : 3;       // rows in flight per 16-lane group
     const int R = cnt + s + w;
     Softmax8 st;
     st.m = -INFINITY;

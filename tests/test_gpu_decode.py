@@ -42,7 +42,7 @@ def _prepared(name):
 
 
 @pytest.mark.parametrize("name", list(_cases()))
-@pytest.mark.parametrize("expand", [1, 4, 32])
+@pytest.mark.parametrize("expand", [1, 4, 32, 64])
 def test_search_ids_and_counters_bit_exact(name, expand):
     w, adj, ent, idx, Kd, Vd = _prepared(name)
     n_seq, n_kv, N, d = w.K.shape
