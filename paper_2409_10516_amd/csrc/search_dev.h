@@ -135,6 +135,16 @@ __device__ __forceinline__ int count_above16(const u64* arr, int n, u64 k) {
     return cnt;
 }
 
+// Workgroup -> (sequence, query head). Consecutive workgroup ids are dealt round-robin to the 8
+// XCDs, each with its own L2. The query heads of a GQA group read the same key and value rows, so
+// they are given workgroup ids that are congruent modulo 8 (group + n_groups * member) and share
+// one L2, whenever the number of groups is a multiple of 8; otherwise the identity map is used.
+__device__ __forceinline__ int xcd_aware_head(int block, int heads, int G) {
+    const int n_groups = heads / G;
+    if (G == 1 || (n_groups & 7)) return block;
+    return (block % n_groups) * G + block / n_groups;
+}
+
 // The whole search of one (sequence, query head) by one workgroup of SR_THREADS threads.
 // `lds_raw` is the workgroup's dynamic LDS (ra_search_lds_bytes of it). Writes ids/stats of
 // `head`; when `lds_ids` is not null the ids are also left there (LDS) for a fused consumer.
