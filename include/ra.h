@@ -119,6 +119,18 @@ ra_status ra_decode_step(const void* q, const ra_index* idx, const void* K, cons
                          int expand, void* stream, float* out, float* lse, int32_t* ids,
                          ra_stats* stats);
 
+/* The decode step after generation has appended tokens to the KV cache: the index still covers
+ * the first N_index keys (the N it was built with), the cache now holds N >= N_index tokens per
+ * (sequence, KV head), and consecutive heads start every kv_stride >= N rows
+ * (K, V: [n_seq][n_kv_heads][kv_stride][d], rows [0, N) valid). The paper does not say how new
+ * tokens enter the index; here they join the static set until the index is rebuilt:
+ * W = [0, sink) u [min(N - window, N_index), N), Omega comes from the graph over [0, N_index).
+ * With N = N_index and kv_stride = N this is ra_decode_step. */
+ra_status ra_decode_step_grown(const void* q, const ra_index* idx, const void* K, const void* V,
+                               ra_dtype dt, int64_t N, int64_t kv_stride, int sink, int window,
+                               int topk, int ef, int expand, void* stream, float* out, float* lse,
+                               int32_t* ids, ra_stats* stats);
+
 /* ---- exact baselines on the same harness ------------------------------------------- */
 
 /* The paper's "Flat" retrieval (exact KNN by linear scan, Sec. 4.1 and Table 5): the topk keys of

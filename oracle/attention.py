@@ -7,10 +7,14 @@ and the exact combination of two disjoint subsets' partial results    (Eq. 4-5).
 import numpy as np
 
 
-def static_ids(N, sink, window):
+def static_ids(N, sink, window, n_index=None):
     """Static pattern W of Sec. 3.3: the first `sink` tokens and the last `window`
-    tokens of the N-token context (clipped to [0, N); overlapping ranges merge)."""
+    tokens of the N-token context (clipped to [0, N); overlapping ranges merge).
+    The paper does not say how tokens generated after the index was built are handled;
+    this build attends them densely: with `n_index` given, tokens [n_index, N) join W."""
     s = set(range(0, min(max(sink, 0), N))) | set(range(max(N - max(window, 0), 0), N))
+    if n_index is not None:
+        s |= set(range(n_index, N))
     return np.array(sorted(s), dtype=np.int64)
 
 

@@ -13,13 +13,14 @@ def build_index(K, Q_prefill, deg, knn):
     return adj, entry, L
 
 
-def decode_step(q, K, V, adj, entry, sink, window, topk, ef, expand=1):
+def decode_step(q, K, V, adj, entry, sink, window, topk, ef, expand=1, n_index=None):
     """Algorithm 1 with PredictActiveTokens fixed to sink + window (Sec. 3.3):
     Omega = VectorSearch(q) minus the static set; o_Omega by Eq. 2 over Omega;
     o_W by Eq. 2 over W; combined by Eq. 4-5.
-    Returns (out[d], lse, ids[topk], stats)."""
+    Returns (out[d], lse, ids[topk], stats). `n_index` (default: all N keys) is the
+    number of keys the graph was built over; later tokens are part of W."""
     N = np.asarray(K).shape[0]
-    W = attention.static_ids(N, sink, window)
+    W = attention.static_ids(N, sink, window, n_index)
     ids, stats = search.greedy_search(q, K, adj, entry, ef, topk, expand, exclude=W)
     omega = ids[ids >= 0]
     o_o, l_o = attention.partial_attention(q, K, V, omega)

@@ -50,6 +50,9 @@ def lib() -> C.CDLL:
     L.ra_attend.argtypes = [vp, vp, vp, vp, i32, i64, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp]
     L.ra_decode_step.argtypes = [vp, vp, vp, vp, i32, i64, i32, i32, i32, i32, i32, vp, vp, vp,
                                  vp, vp]
+    L.ra_decode_step_grown.argtypes = [vp, vp, vp, vp, i32, i64, i64, i32, i32, i32, i32, i32, vp, vp,
+                                       vp, vp, vp]
+    L.ra_decode_step_grown.restype = i32
     L.ra_index_import.argtypes = [vp, vp, i32, i32, i32, i64, i32, C.POINTER(vp)]
     L.ra_index_export.argtypes = [vp, i32, i32, vp, vp]
     L.ra_index_info.argtypes = [vp, i32]
@@ -232,9 +235,11 @@ def ra_attend(q, idx: Index, K, V, sink: int, window: int, ids: torch.Tensor, st
 
 
 def ra_decode_step(q, idx: Index, K, V, sink: int, window: int, topk: int, ef: int,
-                   expand: int = 1, stream=None, out=None, lse=None, ids=None, stats=None):
+                   expand: int = 1, stream=None, out=None, lse=None, ids=None, stats=None,
+                   n_tokens: Optional[int] = None):
     """One layer's decode-step attention. Output tensors may be passed in to avoid
-    allocation; -> (out, lse, ids, stats)."""
+    allocation; -> (out, lse, ids, stats). With n_tokens given, K/V are caches of capacity
+    K.shape[2] rows per head holding n_tokens >= idx.N valid tokens (ra_decode_step_grown)."""
     _dev(q, K, V, out, lse, ids, stats)
     n_seq, n_q, d = q.shape
     f = dict(dtype=torch.float32, device=q.device)
@@ -246,9 +251,14 @@ def ra_decode_step(q, idx: Index, K, V, sink: int, window: int, topk: int, ef: i
         ids = torch.empty((n_seq, n_q, topk), dtype=torch.int32, device=q.device)
     if stats is None:
         stats = _stats_tensor(n_seq * n_q, q.device).view(n_seq, n_q, 4)
-    _check(lib().ra_decode_step(_ptr(q), idx.handle, _ptr(K), _ptr(V), _dt(K), K.shape[2], sink,
-                                window, topk, ef, expand, _stream(stream), _ptr(out), _ptr(lse),
-                                _ptr(ids), _ptr(stats)))
+    if n_tokens is None:
+        _check(lib().ra_decode_step(_ptr(q), idx.handle, _ptr(K), _ptr(V), _dt(K), K.shape[2], sink,
+                                    window, topk, ef, expand, _stream(stream), _ptr(out), _ptr(lse),
+                                    _ptr(ids), _ptr(stats)))
+    else:
+        _check(lib().ra_decode_step_grown(_ptr(q), idx.handle, _ptr(K), _ptr(V), _dt(K), n_tokens,
+                                          K.shape[2], sink, window, topk, ef, expand, _stream(stream),
+                                          _ptr(out), _ptr(lse), _ptr(ids), _ptr(stats)))
     return out, lse, ids, stats
 
 

@@ -277,13 +277,20 @@ extern "C" ra_status ra_attend(const void* q, const ra_index* idx, const void* K
                             lse_w);
 }
 
-extern "C" ra_status ra_decode_step(const void* q, const ra_index* idx, const void* K, const void* V,
-                                    ra_dtype dt, int64_t N, int sink, int window, int topk, int ef,
-                                    int expand, void* stream, float* out, float* lse, int32_t* ids,
-                                    ra_stats* stats) {
+extern "C" ra_status ra_decode_step_grown(const void* q, const ra_index* idx, const void* K,
+                                          const void* V, ra_dtype dt, int64_t N, int64_t kv_stride,
+                                          int sink, int window, int topk, int ef, int expand,
+                                          void* stream, float* out, float* lse, int32_t* ids,
+                                          ra_stats* stats) {
     if (!q || !K || !V || !out || !lse) RA_FAIL(RA_EINVAL, "NULL argument");
     RA_TRY(check_dtype(dt));
-    RA_TRY(check_decode_args(idx, N, sink, window, topk));
+    if (!idx) RA_FAIL(RA_EINVAL, "index handle is NULL");
+    if (N < idx->N)
+        RA_FAIL(RA_ESHAPE, "N = %lld is below the %lld keys the index was built over", (long long)N,
+                (long long)idx->N);
+    if (kv_stride < N)
+        RA_FAIL(RA_ESHAPE, "kv_stride %lld is below N = %lld", (long long)kv_stride, (long long)N);
+    RA_TRY(check_decode_args(idx, idx->N, sink, window, topk));
     RA_TRY(check_search_args(topk, ef, expand));
     ra_index* ix = const_cast<ra_index*>(idx);
     if (!ids) {
@@ -292,11 +299,22 @@ extern "C" ra_status ra_decode_step(const void* q, const ra_index* idx, const vo
         ids = ix->ids_ws;
     }
     const size_t heads = (size_t)ix->n_seq * ix->n_q;
-    if (ra_decode_needs_global_bitset(N, ix->deg, ef, expand, topk))
-        RA_TRY(grow((void**)&ix->bitset, &ix->bitset_bytes, heads * ((N + 31) >> 5) * 4));
-    return ra_launch_decode(q, ix->adj, ix->entry, K, V, dt, ix->n_seq, ix->n_q, ix->n_kv, N, ix->deg,
-                            sink, window, topk, ef, expand, ix->bitset, (hipStream_t)stream, out, lse,
-                            ids, stats);
+    if (ra_decode_needs_global_bitset(ix->N, ix->deg, ef, expand, topk))
+        RA_TRY(grow((void**)&ix->bitset, &ix->bitset_bytes, heads * ((ix->N + 31) >> 5) * 4));
+    return ra_launch_decode(q, ix->adj, ix->entry, K, V, dt, ix->n_seq, ix->n_q, ix->n_kv, ix->N, N,
+                            kv_stride, ix->deg, sink, window, topk, ef, expand, ix->bitset,
+                            (hipStream_t)stream, out, lse, ids, stats);
+}
+
+extern "C" ra_status ra_decode_step(const void* q, const ra_index* idx, const void* K, const void* V,
+                                    ra_dtype dt, int64_t N, int sink, int window, int topk, int ef,
+                                    int expand, void* stream, float* out, float* lse, int32_t* ids,
+                                    ra_stats* stats) {
+    if (idx && N != idx->N)
+        RA_FAIL(RA_ESHAPE, "N = %lld but the index was built over %lld keys (ra_decode_step_grown "
+                "accepts a longer cache)", (long long)N, (long long)idx->N);
+    return ra_decode_step_grown(q, idx, K, V, dt, N, N, sink, window, topk, ef, expand, stream, out, lse,
+                                ids, stats);
 }
 
 // ---- exact baselines (the paper's "Flat" retrieval and full attention) ---------------------

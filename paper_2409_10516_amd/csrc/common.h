@@ -63,9 +63,10 @@ ra_status ra_launch_attend(const void* q, const void* K, const void* V, ra_dtype
 
 bool ra_decode_needs_global_bitset(int64_t N, int deg, int ef, int expand, int topk);
 ra_status ra_launch_decode(const void* q, const int32_t* adj, const int32_t* entry, const void* K,
-                           const void* V, ra_dtype dt, int n_seq, int n_q, int n_kv, int64_t N, int deg,
-                           int sink, int window, int topk, int ef, int expand, uint32_t* bitset,
-                           hipStream_t st, float* out, float* lse, int32_t* ids, ra_stats* stats);
+                           const void* V, ra_dtype dt, int n_seq, int n_q, int n_kv, int64_t Ng, int64_t N,
+                           int64_t kv_stride, int deg, int sink, int window, int topk, int ef, int expand,
+                           uint32_t* bitset, hipStream_t st, float* out, float* lse, int32_t* ids,
+                           ra_stats* stats);
 
 ra_status ra_launch_flat_topk(const void* q, const void* K, ra_dtype dt, int n_seq, int n_q, int n_kv,
                               int64_t N, int sink, int window, int topk, uint32_t* keys_ws,

@@ -37,8 +37,9 @@ __device__ __forceinline__ void sm_merge(Softmax8& a, float mo, float lo, const 
 template <int DT, bool GBITS>
 __global__ __launch_bounds__(SR_THREADS) void decode_kernel(
     const void* __restrict__ q, const int32_t* __restrict__ adj, const int32_t* __restrict__ entry,
-    const void* __restrict__ K, const void* __restrict__ V, int n_q, int n_kv, int64_t N, int deg,
-    int s, int w, int topk, int ef, int expand, uint32_t* __restrict__ gbits,
+    const void* __restrict__ K, const void* __restrict__ V, int n_q, int n_kv, int64_t Ng, int64_t N,
+    int64_t kv_stride, int64_t wstart, int deg, int s, int topk, int ef, int expand,
+    uint32_t* __restrict__ gbits,
     int32_t* __restrict__ ids, ra_stats* __restrict__ stats, int ids_off, float scale,
     float* __restrict__ out, float* __restrict__ lse) {
     extern __shared__ __align__(16) unsigned char lds_raw[];
@@ -48,15 +49,18 @@ __global__ __launch_bounds__(SR_THREADS) void decode_kernel(
     const int seq = head / n_q, h = head % n_q, kvh = h / (n_q / n_kv);
     const size_t esz = DT == RA_BF16 ? 2 : 4;
     int32_t* lds_ids = reinterpret_cast<int32_t*>(lds_raw + ids_off);
-    const int cnt = run_search<DT, GBITS>(lds_raw, head, q, adj, entry, K, n_q, n_kv, N, deg, s, w,
-                                          topk, ef, expand, gbits, ids, stats, lds_ids);
-    // ---- Eq. 2 over Omega (rows [0, cnt): ids in LDS) and W (rows [cnt, cnt + s + w))
-    const char* Kh = reinterpret_cast<const char*>(K) + ((size_t)seq * n_kv + kvh) * N * RA_D * esz;
-    const char* Vh = reinterpret_cast<const char*>(V) + ((size_t)seq * n_kv + kvh) * N * RA_D * esz;
+    // The graph covers the first Ng of the N tokens now in the cache; W = [0, s) u [wstart, N) with
+    // wstart <= Ng, so every token appended after the build is attended densely.
+    const int cnt = run_search<DT, GBITS>(lds_raw, head, q, adj, entry, K, n_q, n_kv, Ng, kv_stride, deg,
+                                          s, (int)(Ng - wstart), topk, ef, expand, gbits, ids, stats,
+                                          lds_ids);
+    // ---- Eq. 2 over Omega (rows [0, cnt): ids in LDS) and W (rows [cnt, cnt + s + N - wstart))
+    const char* Kh = reinterpret_cast<const char*>(K) + ((size_t)seq * n_kv + kvh) * kv_stride * RA_D * esz;
+    const char* Vh = reinterpret_cast<const char*>(V) + ((size_t)seq * n_kv + kvh) * kv_stride * RA_D * esz;
     float qv[8];
     load_row8<DT>(reinterpret_cast<const char*>(q) + (size_t)head * RA_D * esz, 0, lane16, qv);
     constexpr int DC_ROWS = DT == RA_BF16 ? 6 : 3;       // rows in flight per 16-lane group
-    const int R = cnt + s + w;
+    const int R = cnt + s + (int)(N - wstart);
     Softmax8 st;
     st.m = -INFINITY;
     st.l = 0.f;
@@ -70,7 +74,7 @@ __global__ __launch_bounds__(SR_THREADS) void decode_kernel(
             const int r = r0 + u * SR_NG + grp;
             int64_t id = -1;
             if (r < cnt) id = lds_ids[r];
-            else if (r < R) id = r - cnt < s ? (int64_t)(r - cnt) : N - w + (r - cnt - s);
+            else if (r < R) id = r - cnt < s ? (int64_t)(r - cnt) : wstart + (r - cnt - s);
             rid[u] = id;
             const int64_t safe = id >= 0 ? id : 0;      // loads stay unconditional
             load_row8<DT>(Kh, safe, lane16, kv[u]);
@@ -158,28 +162,35 @@ __global__ void dc_fill_u32_kernel(uint32_t* p, size_t n, uint32_t v) {
 }
 
 ra_status ra_launch_decode(const void* q, const int32_t* adj, const int32_t* entry, const void* K,
-                           const void* V, ra_dtype dt, int n_seq, int n_q, int n_kv, int64_t N, int deg,
-                           int sink, int window, int topk, int ef, int expand, uint32_t* bitset,
-                           hipStream_t st, float* out, float* lse, int32_t* ids, ra_stats* stats) {
-    int s, w;
-    static_ranges(N, sink, window, &s, &w);
+                           const void* V, ra_dtype dt, int n_seq, int n_q, int n_kv, int64_t Ng, int64_t N,
+                           int64_t kv_stride, int deg, int sink, int window, int topk, int ef, int expand,
+                           uint32_t* bitset, hipStream_t st, float* out, float* lse, int32_t* ids,
+                           ra_stats* stats) {
+    // W = [0, s) u [wstart, N): the sink, the sliding window, and every token appended after the
+    // index was built (wstart <= Ng); overlapping ranges make everything static
+    int64_t s = sink < 0 ? 0 : sink, ww = window < 0 ? 0 : window;
+    if (s > N) s = N;
+    if (ww > N) ww = N;
+    int64_t wstart = N - ww < Ng ? N - ww : Ng;
+    if (s >= wstart) { s = 0; wstart = 0; }
+    if (N - wstart + s > 0x3fffffff) RA_FAIL(RA_EUNSUP, "static set too large");
     const int heads = n_seq * n_q;
-    const bool gb = ra_decode_needs_global_bitset(N, deg, ef, expand, topk);
+    const bool gb = ra_decode_needs_global_bitset(Ng, deg, ef, expand, topk);
     int ids_off;
-    const size_t lds = decode_lds_bytes(N, deg, ef, expand, topk, gb, &ids_off);
+    const size_t lds = decode_lds_bytes(Ng, deg, ef, expand, topk, gb, &ids_off);
     if (lds > SR_LDS_LIMIT)
         RA_FAIL(RA_EUNSUP, "decode state needs %zu B of LDS (limit %d): lower ef or expand", lds,
                 SR_LDS_LIMIT);
     if (gb) {
         if (!bitset) RA_FAIL(RA_EINVAL, "global visited bitset missing");
-        const size_t words = (size_t)heads * ((N + 31) >> 5);
+        const size_t words = (size_t)heads * ((Ng + 31) >> 5);
         hipLaunchKernelGGL(dc_fill_u32_kernel, dim3(1024), dim3(256), 0, st, bitset, words, 0u);
     }
     const float scale = 1.0f / sqrtf((float)RA_D);
 #define RA_DC_GO(DTV, GB)                                                                          \
     hipLaunchKernelGGL((decode_kernel<DTV, GB>), dim3(heads), dim3(SR_THREADS), lds, st, q, adj,   \
-                       entry, K, V, n_q, n_kv, N, deg, s, w, topk, ef, expand, bitset, ids, stats, \
-                       ids_off, scale, out, lse)
+                       entry, K, V, n_q, n_kv, Ng, N, kv_stride, wstart, deg, (int)s, topk, ef,    \
+                       expand, bitset, ids, stats, ids_off, scale, out, lse)
     if (dt == RA_BF16) {
         if (gb) RA_DC_GO(RA_BF16, true); else RA_DC_GO(RA_BF16, false);
     } else {

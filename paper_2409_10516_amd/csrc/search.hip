@@ -8,7 +8,7 @@ __global__ __launch_bounds__(SR_THREADS) void search_kernel(
     int ef, int expand, uint32_t* __restrict__ gbits, int32_t* __restrict__ ids,
     ra_stats* __restrict__ stats) {
     extern __shared__ __align__(16) unsigned char lds_raw[];
-    run_search<DT, GBITS>(lds_raw, xcd_aware_head(blockIdx.x, gridDim.x, n_q / n_kv), q, adj, entry, K, n_q, n_kv, N, deg, s, w, topk, ef,
+    run_search<DT, GBITS>(lds_raw, xcd_aware_head(blockIdx.x, gridDim.x, n_q / n_kv), q, adj, entry, K, n_q, n_kv, N, N, deg, s, w, topk, ef,
                           expand, gbits, ids, stats, nullptr);
 }
 

@@ -146,6 +146,8 @@ __device__ __forceinline__ int xcd_aware_head(int block, int heads, int G) {
 }
 
 // The whole search of one (sequence, query head) by one workgroup of SR_THREADS threads.
+// N is the number of keys the graph covers; the key rows of a (sequence, KV head) start every
+// kv_stride rows (kv_stride >= N: the cache may hold tokens appended after the index was built).
 // `lds_raw` is the workgroup's dynamic LDS (ra_search_lds_bytes of it). Writes ids/stats of
 // `head`; when `lds_ids` is not null the ids are also left there (LDS) for a fused consumer.
 // Returns the number of valid ids. Ends with the whole workgroup past a barrier.
@@ -153,13 +155,13 @@ template <int DT, bool GBITS>
 __device__ __forceinline__ int run_search(
     unsigned char* lds_raw, int head, const void* __restrict__ q, const int32_t* __restrict__ adj,
     const int32_t* __restrict__ entry, const void* __restrict__ K, int n_q, int n_kv, int64_t N,
-    int deg, int s, int w, int topk, int ef, int expand, uint32_t* __restrict__ gbits,
+    int64_t kv_stride, int deg, int s, int w, int topk, int ef, int expand, uint32_t* __restrict__ gbits,
     int32_t* __restrict__ ids, ra_stats* __restrict__ stats, int32_t* lds_ids) {
     const int tid = threadIdx.x, grp = tid >> 4, lane16 = tid & 15;
     const int lane = tid & (RA_WAVE - 1), wv = tid / RA_WAVE;
     const int seq = head / n_q, h = head % n_q, kvh = h / (n_q / n_kv);
     const size_t esz = DT == RA_BF16 ? 2 : 4;
-    const char* Kh = reinterpret_cast<const char*>(K) + ((size_t)seq * n_kv + kvh) * N * RA_D * esz;
+    const char* Kh = reinterpret_cast<const char*>(K) + ((size_t)seq * n_kv + kvh) * kv_stride * RA_D * esz;
     const int32_t* adj_h = adj + (size_t)head * N * deg;
     const int maxc = expand * deg;
     const int nwords = (int)((N + 31) >> 5);

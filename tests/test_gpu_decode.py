@@ -166,3 +166,54 @@ def test_argument_errors_reach_python():
     with pytest.raises(ra.RaError) as e:
         ra.ra_search(q, idx, Kd[:, :, :100].contiguous(), 0, 0, 5, 10, 1)    # N mismatch
     assert e.value.status == 2
+
+
+@pytest.mark.parametrize("grown,capacity_pad,window", [(1, 0, 64), (37, 19, 64), (200, 5, 16), (90, 0, 0)])
+@pytest.mark.parametrize("dtype", [torch.bfloat16, torch.float32])
+def test_decode_after_generation_appended_tokens(grown, capacity_pad, window, dtype):
+    """The index covers the first N_index tokens; the cache has grown by `grown` tokens and has
+    spare capacity. Appended tokens are attended densely; ids come from the graph."""
+    n_index, n_q, n_kv = 900, 4, 2
+    N = n_index + grown
+    w = synth.make_llama_layer(51, N=N, M=400, T=2, n_q=n_q, n_kv=n_kv, dtype=dtype, ef=48, topk=16,
+                               window=window, deg=12, knn=9)
+    from types import SimpleNamespace
+    wi = SimpleNamespace(K=w.K[:, :, :n_index].contiguous(), Q_prefill=w.Q_prefill, knn=w.knn, deg=w.deg)
+    adj, ent, _ = oracle_graphs(wi)
+    idx = ra.ra_index_import(torch.from_numpy(adj), torch.from_numpy(ent), 1, n_q, n_kv)
+    cap = N + capacity_pad
+    Kc = torch.zeros((1, n_kv, cap, 128), dtype=dtype); Kc[:, :, :N] = w.K
+    Vc = torch.full((1, n_kv, cap, 128), 7.0, dtype=dtype); Vc[:, :, :N] = w.V
+    Kd, Vd = Kc.to(DEV), Vc.to(DEV)
+    tol = tol_for(dtype)
+    for t in range(2):
+        out, lse, ids, st = ra.ra_decode_step(w.q_decode[t].to(DEV), idx, Kd, Vd, w.sink, window, w.topk,
+                                              w.ef, 4, n_tokens=N)
+        out, lse, ids = out.cpu().numpy(), lse.cpu().numpy(), ids.cpu().numpy()
+        for h in range(n_q):
+            K = to_np(w.K[0, h // 2]); V = to_np(w.V[0, h // 2])
+            r_out, r_lse, r_ids, _ = OD.decode_step(to_np(w.q_decode[t, 0, h]), K, V, adj[h], ent[h],
+                                                    w.sink, window, w.topk, w.ef, 4, n_index=n_index)
+            assert ids[0, h].tolist() == r_ids.tolist()
+            assert (ids[0, h] < n_index).all()
+            assert out_close(out[0, h], r_out, tol) and lse_close(lse[0, h], r_lse, tol)
+    with pytest.raises(ra.RaError) as e:
+        ra.ra_decode_step(w.q_decode[0].to(DEV), idx, Kd, Vd, w.sink, window, w.topk, w.ef, 4,
+                          n_tokens=n_index - 1)
+    assert e.value.status == 2
+
+
+def test_grown_cache_with_everything_retrieved_is_full_attention():
+    n_index, grown = 300, 25
+    w = synth.make_integer_case(19, N=n_index + grown, M=80, T=2, d=128, deg=8, knn=6)
+    from types import SimpleNamespace
+    wi = SimpleNamespace(K=w.K[:, :, :n_index].contiguous(), Q_prefill=w.Q_prefill, knn=6, deg=8)
+    adj, ent, _ = oracle_graphs(wi)
+    idx = ra.ra_index_import(torch.from_numpy(adj), torch.from_numpy(ent), 1, 1, 1)
+    Kd, Vd = w.K.to(DEV), w.V.to(DEV)
+    for t in range(2):
+        q = w.q_decode[t].to(DEV)
+        out, lse, ids, _ = ra.ra_decode_step(q, idx, Kd, Vd, 4, 20, 296, 300, 3, n_tokens=n_index + grown)
+        ref_o, ref_l = OA.full_attention(to_np(q[0, 0]), to_np(w.K[0, 0]), to_np(w.V[0, 0]))
+        assert sorted(ids[0, 0].tolist()) == list(range(4, 300))
+        assert out_close(out[0, 0].cpu().numpy(), ref_o, 1e-5) and lse_close(float(lse[0, 0]), ref_l, 1e-5)

@@ -128,3 +128,11 @@ def test_static_ids():
     assert A.static_ids(10, 6, 6).tolist() == list(range(10))      # overlap merges
     assert A.static_ids(5, 8, 1).tolist() == list(range(5))        # clipped
     assert A.static_ids(10, 0, 4).tolist() == [6, 7, 8, 9]
+
+
+def test_static_ids_after_generation():
+    # tokens appended after the index was built (n_index) are attended densely
+    assert A.static_ids(12, 2, 3, n_index=10).tolist() == [0, 1, 9, 10, 11]
+    assert A.static_ids(12, 2, 1, n_index=8).tolist() == [0, 1, 8, 9, 10, 11]
+    assert A.static_ids(12, 2, 3, n_index=12).tolist() == A.static_ids(12, 2, 3).tolist()
+    assert A.static_ids(6, 0, 0, n_index=2).tolist() == [2, 3, 4, 5]
