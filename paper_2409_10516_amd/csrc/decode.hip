@@ -54,6 +54,9 @@ __global__ __launch_bounds__(SR_THREADS) void decode_kernel(
     const int cnt = run_search<DT, GBITS>(lds_raw, head, q, adj, entry, K, n_q, n_kv, Ng, kv_stride, deg,
                                           s, (int)(Ng - wstart), topk, ef, expand, gbits, ids, stats,
                                           lds_ids);
+#ifdef SR_PHASE_CLOCKS
+    const long long t_attn = clock64();
+#endif
     // ---- Eq. 2 over Omega (rows [0, cnt): ids in LDS) and W (rows [cnt, cnt + s + N - wstart))
     const char* Kh = reinterpret_cast<const char*>(K) + ((size_t)seq * n_kv + kvh) * kv_stride * RA_D * esz;
     const char* Vh = reinterpret_cast<const char*>(V) + ((size_t)seq * n_kv + kvh) * kv_stride * RA_D * esz;
@@ -139,7 +142,20 @@ __global__ __launch_bounds__(SR_THREADS) void decode_kernel(
         out[(size_t)head * RA_D + tid] = empty ? 0.f : a / l;
         if (tid == 0) lse[head] = empty ? -INFINITY : mx + logf(l);
     }
+#ifdef SR_PHASE_CLOCKS
+    if (tid == 0 && blockIdx.x < 64) sr_phase_ticks[blockIdx.x * SR_NPHASE + 7] += clock64() - t_attn;
+#endif
 }
+
+#ifdef SR_PHASE_CLOCKS
+// Tuning builds only: copy the phase clocks of the fused kernel to `host` (64 x 8 values) and clear them.
+extern "C" int ra_dbg_phase_ticks(long long* host) {
+    if (hipMemcpyFromSymbol(host, HIP_SYMBOL(sr_phase_ticks), sizeof(long long) * 64 * SR_NPHASE) != hipSuccess)
+        return 1;
+    static long long zeros[64 * SR_NPHASE];
+    return hipMemcpyToSymbol(HIP_SYMBOL(sr_phase_ticks), zeros, sizeof(zeros)) != hipSuccess;
+}
+#endif
 
 static size_t decode_lds_bytes(int64_t N, int deg, int ef, int expand, int topk, bool gb, int* ids_off) {
     size_t a = search_lds_bytes(N, deg, ef, expand, gb);

@@ -28,9 +28,28 @@
 
 #define SR_NG (SR_THREADS / 16)     // 16-lane groups per workgroup
 
-enum { C_NCAND = 1, C_NKEEP = 2, C_WTOT = 8, C_COUNT = 8 + SR_THREADS / RA_WAVE };
+enum { C_NCAND = 1, C_NKEEP = 2, C_NUNEXP = 3, C_WTOT = 8, C_COUNT = 8 + SR_THREADS / RA_WAVE };
 
 typedef unsigned long long u64;
+
+// Phase clocks for tuning builds (-DSR_PHASE_CLOCKS): thread 0 of the first 64 workgroups adds the
+// ticks spent in each phase to a device array that ra_dbg_phase_ticks copies out. Off otherwise.
+#ifdef SR_PHASE_CLOCKS
+#define SR_NPHASE 8
+static __device__ long long sr_phase_ticks[64 * SR_NPHASE];
+#define SR_TICK_INIT long long tick_ = clock64()
+#define SR_TICK(p)                                                         \
+    do {                                                                   \
+        if (threadIdx.x == 0 && blockIdx.x < 64) {                         \
+            const long long now_ = clock64();                              \
+            sr_phase_ticks[blockIdx.x * SR_NPHASE + (p)] += now_ - tick_;  \
+            tick_ = now_;                                                  \
+        }                                                                  \
+    } while (0)
+#else
+#define SR_TICK_INIT
+#define SR_TICK(p)
+#endif
 
 __device__ __forceinline__ u64 make_key(float score, int id) {
     return ((u64)f32_ordered(score) << 32) | ((u64)(uint32_t)(0x7fffffff - id) << 1) | 1ull;
@@ -166,6 +185,7 @@ __device__ __forceinline__ int run_search(
     const int maxc = expand * deg;
     const int nwords = (int)((N + 31) >> 5);
 
+    SR_TICK_INIT;
     u64* cur = reinterpret_cast<u64*>(lds_raw);
     u64* nxt = cur + ef;
     u64* ckey = nxt + ef;            // [maxc + 16] candidates that passed the beam threshold
@@ -174,8 +194,13 @@ __device__ __forceinline__ int run_search(
     int* picks = cnt + ef + maxc;    // [RA_MAX_EXPAND]
     int* ctr = picks + RA_MAX_EXPAND;
     int* wtot = ctr + C_WTOT;
+    // urank[i], i in [0, bn]: unexpanded entries among the first i of the beam, as of the last pick
+    // but before its picks were marked expanded (two buffers, swapped with the beam's)
+    uint16_t* urank = reinterpret_cast<uint16_t*>(ctr + C_COUNT);    // [ef + 1]
+    uint16_t* urank_nxt = urank + ef + 1;                            // [ef + 1]
+    int* ushift = cid;               // [maxc] per kept candidate, during the merge (cid is dead then)
     uint32_t* bits = GBITS ? gbits + (size_t)head * nwords
-                           : reinterpret_cast<uint32_t*>(ctr + C_COUNT);
+                           : reinterpret_cast<uint32_t*>(urank_nxt + ef + 1);
 
     if (!GBITS)
         for (int i = tid; i < nwords; i += SR_THREADS) bits[i] = 0u;
@@ -193,37 +218,49 @@ __device__ __forceinline__ int run_search(
         }
     }
     int bn = 1, n_visited = 1, n_expanded = 0, n_iters = 0;
+    bool picked = false;             // the merge of the last step already chose this step's picks
     __syncthreads();
+    SR_TICK(5);
 
     for (;;) {
-        // ---- pick the `expand` best unexpanded entries: the beam is sorted and has at most
-        //      one entry per thread, so the picks are the first `expand` set flags in thread
-        //      order (ballot prefix inside a wavefront, wavefront totals through LDS)
-        const u64 mykey = tid < bn ? cur[tid] : 0ull;
-        const bool un = (mykey & 1ull) != 0;
-        const u64 unmask = __ballot(un);
-        if (lane == 0) wtot[wv] = __popcll(unmask);
-        if (tid == 0) {
-            ctr[C_NCAND] = 0;
-            ctr[C_NKEEP] = 0;
-        }
-        __syncthreads();
-        int before = 0, total = 0;
-        for (int x = 0; x < SR_THREADS / RA_WAVE; ++x) {
-            const int c = wtot[x];
-            if (x < wv) before += c;
-            total += c;
-        }
-        const int np = total < expand ? total : expand;
-        if (np == 0) break;
-        {
+        int np;
+        if (!picked) {
+            // ---- pick the `expand` best unexpanded entries: the beam is sorted and has at most
+            //      one entry per thread, so the picks are the first `expand` set flags in thread
+            //      order (ballot prefix inside a wavefront, wavefront totals through LDS)
+            const u64 mykey = tid < bn ? cur[tid] : 0ull;
+            const bool un = (mykey & 1ull) != 0;
+            const u64 unmask = __ballot(un);
+            if (lane == 0) wtot[wv] = __popcll(unmask);
+            if (tid == 0) {
+                ctr[C_NCAND] = 0;
+                ctr[C_NKEEP] = 0;
+                ctr[C_NUNEXP] = 0;
+            }
+            __syncthreads();
+            int before = 0, total = 0;
+            for (int x = 0; x < SR_THREADS / RA_WAVE; ++x) {
+                const int c = wtot[x];
+                if (x < wv) before += c;
+                total += c;
+            }
+            np = total < expand ? total : expand;
+            if (np == 0) break;
             const int rank = before + __popcll(unmask & ((1ull << lane) - 1ull));
+            if (tid <= bn) urank[tid] = (uint16_t)rank;
             if (un && rank < expand) {
                 picks[rank] = key_id(mykey);
                 cur[tid] = mykey & ~1ull;
             }
+            __syncthreads();
+        } else {
+            // the merge left the picks in place and counted the unexpanded entries
+            const int total = ctr[C_NUNEXP];
+            np = total < expand ? total : expand;
+            if (np == 0) break;
+            if (tid == 0) urank[bn] = (uint16_t)total;
         }
-        __syncthreads();
+        SR_TICK(0);
         ++n_iters;
         n_expanded += np;
 
@@ -256,6 +293,8 @@ __device__ __forceinline__ int run_search(
         __syncthreads();
         const int nc = ctr[C_NCAND];
         n_visited += nc;
+        SR_TICK(1);
+        if (tid == 0) ctr[C_NUNEXP] = 0;     // everyone read it before the barrier above
 
         // ---- gather and score the new candidates; keep those that can enter the beam
         const u64 worst = bn == ef ? (cur[bn - 1] >> 1) : 0ull;
@@ -282,44 +321,73 @@ __device__ __forceinline__ int run_search(
         }
         __syncthreads();
         const int nk = ctr[C_NKEEP];
-        if (nk == 0) continue;       // uniform: nothing enters the beam
+        SR_TICK(2);
+        if (nk == 0) {               // uniform: nothing enters the beam
+            picked = false;
+            continue;
+        }
 
         // ---- merge by counting into the other beam buffer, truncating at ef. The final position
         //      of an element of (beam u kept candidates) is the number of elements that beat it:
         //      a beam entry's index plus the candidates above it; a candidate's rank among the
-        //      candidates plus the beam entries above it. The (element, 16 candidates) count
-        //      tasks are spread over all wavefronts but the last, which meanwhile ranks the
-        //      candidates against the sorted beam by binary search; partial counts meet in LDS.
+        //      candidates plus the beam entries above it (binary search in the sorted beam). The
+        //      same counts give the number of *unexpanded* elements above each element (every
+        //      candidate is unexpanded; for the beam's part urank has it), so the next step's picks,
+        //      the elements with fewer than `expand` unexpanded ones above them, fall out of the merge.
         {
             const int E = bn + nk;
             const int nch = (nk + 15) >> 4;
             const int items = E * nch;
-            constexpr int A_T = SR_THREADS - RA_WAVE;
-            if (tid < A_T) {
-                for (int a = tid; a < items; a += A_T) {
-                    const int ch = a / E, e = a - ch * E;
-                    const u64 ke = (e < bn ? cur[e] : ckey[e - bn]) | 1ull;   // candidates carry flag 1
-                    const int c = count_above16(ckey + ch * 16, nk - ch * 16, ke);
-                    if (c) atomicAdd(&cnt[e], c);
-                }
-            } else {
-                for (int c = tid - A_T; c < nk; c += RA_WAVE) {
-                    const int b = count_better(cur, bn, ckey[c]);
-                    if (b) atomicAdd(&cnt[bn + c], b);
-                }
+            for (int c = tid; c < nk; c += SR_THREADS) {
+                const int b = count_better(cur, bn, ckey[c]);
+                if (b) atomicAdd(&cnt[bn + c], b);
+                const int ub = (int)urank[b] - np;            // this step's picks are expanded now
+                ushift[c] = (ub > 0 ? ub : 0) - b;
+            }
+            for (int a = tid; a < items; a += SR_THREADS) {
+                const int ch = a / E, e = a - ch * E;
+                const u64 ke = (e < bn ? cur[e] : ckey[e - bn]) | 1ull;   // candidates carry flag 1
+                const int c = count_above16(ckey + ch * 16, nk - ch * 16, ke);
+                if (c) atomicAdd(&cnt[e], c);
             }
             __syncthreads();
+            SR_TICK(3);
+            if (tid == 0) {
+                ctr[C_NCAND] = 0;
+                ctr[C_NKEEP] = 0;
+            }
             for (int e = tid; e < E; e += SR_THREADS) {
                 const int c = cnt[e];
                 cnt[e] = 0;
-                const u64 k = e < bn ? cur[e] : ckey[e - bn];
-                const int pos = (e < bn ? e : 0) + c;
-                if (pos < ef) nxt[pos] = k;
+                const bool beam = e < bn;
+                u64 k = beam ? cur[e] : ckey[e - bn];
+                const int pos = (beam ? e : 0) + c;
+                int ur;                                           // unexpanded elements above this one
+                if (beam) {
+                    const int ub = (int)urank[e] - np;
+                    ur = c + (ub > 0 ? ub : 0);
+                } else {
+                    ur = c + ushift[e - bn];
+                }
+                const bool un = pos < ef && (k & 1ull);
+                if (un && ur < expand) {
+                    picks[ur] = key_id(k);
+                    k &= ~1ull;
+                }
+                if (pos < ef) {
+                    nxt[pos] = k;
+                    urank_nxt[pos] = (uint16_t)ur;
+                }
+                const u64 um = __ballot(un);
+                if (lane == 0 && um) atomicAdd(&ctr[C_NUNEXP], __popcll(um));
             }
         }
         __syncthreads();
+        SR_TICK(4);
         bn = bn + nk < ef ? bn + nk : ef;
         u64* t = cur; cur = nxt; nxt = t;
+        uint16_t* tu = urank; urank = urank_nxt; urank_nxt = tu;
+        picked = true;
     }
 
     // ---- result: best-first beam entries outside the static set W = [0,s) u [N-w,N)
@@ -354,6 +422,7 @@ __device__ __forceinline__ int run_search(
         }
     }
     __syncthreads();
+    SR_TICK(6);
     return ctr[C_NKEEP];
 }
 
@@ -361,7 +430,7 @@ __device__ __forceinline__ int run_search(
 static inline size_t search_lds_bytes(int64_t N, int deg, int ef, int expand, bool global_bitset) {
     const int maxc = expand * deg;
     size_t b = (size_t)2 * ef * 8 + (size_t)(maxc + 16) * 8 + (size_t)maxc * 4 + (size_t)(ef + maxc) * 4 +
-               (RA_MAX_EXPAND + C_COUNT) * 4;
+               (RA_MAX_EXPAND + C_COUNT) * 4 + (size_t)(ef + 1) * 4;
     if (!global_bitset) b += (size_t)((N + 31) >> 5) * 4;
     return b;
 }
