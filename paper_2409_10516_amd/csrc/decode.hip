@@ -143,16 +143,17 @@ __global__ __launch_bounds__(SR_THREADS) void decode_kernel(
         if (tid == 0) lse[head] = empty ? -INFINITY : mx + logf(l);
     }
 #ifdef SR_PHASE_CLOCKS
-    if (tid == 0 && blockIdx.x < 64) sr_phase_ticks[blockIdx.x * SR_NPHASE + 7] += clock64() - t_attn;
+    if (tid == 0 && blockIdx.x < 64) sr_phase_ticks[blockIdx.x * SR_NITER * SR_NPHASE + 7] += clock64() - t_attn;
 #endif
 }
 
 #ifdef SR_PHASE_CLOCKS
-// Tuning builds only: copy the phase clocks of the fused kernel to `host` (64 x 8 values) and clear them.
+// Tuning builds only: copy the phase clocks of the fused kernel to `host` (64 x 16 x 8 values: workgroup,
+// search step, phase) and clear them.
 extern "C" int ra_dbg_phase_ticks(long long* host) {
-    if (hipMemcpyFromSymbol(host, HIP_SYMBOL(sr_phase_ticks), sizeof(long long) * 64 * SR_NPHASE) != hipSuccess)
+    if (hipMemcpyFromSymbol(host, HIP_SYMBOL(sr_phase_ticks), sizeof(long long) * 64 * SR_NITER * SR_NPHASE) != hipSuccess)
         return 1;
-    static long long zeros[64 * SR_NPHASE];
+    static long long zeros[64 * SR_NITER * SR_NPHASE];
     return hipMemcpyToSymbol(HIP_SYMBOL(sr_phase_ticks), zeros, sizeof(zeros)) != hipSuccess;
 }
 #endif
@@ -168,7 +169,8 @@ static size_t decode_lds_bytes(int64_t N, int deg, int ef, int expand, int topk,
 
 bool ra_decode_needs_global_bitset(int64_t N, int deg, int ef, int expand, int topk) {
     int off;
-    return decode_lds_bytes(N, deg, ef, expand, topk, false, &off) > SR_LDS_LIMIT;
+    return (size_t)((N + 31) >> 5) * 4 > SR_BITSET_LDS_MAX ||
+           decode_lds_bytes(N, deg, ef, expand, topk, false, &off) > SR_LDS_LIMIT;
 }
 
 __global__ void dc_fill_u32_kernel(uint32_t* p, size_t n, uint32_t v) {
@@ -204,9 +206,12 @@ ra_status ra_launch_decode(const void* q, const int32_t* adj, const int32_t* ent
     }
     const float scale = 1.0f / sqrtf((float)RA_D);
 #define RA_DC_GO(DTV, GB)                                                                          \
-    hipLaunchKernelGGL((decode_kernel<DTV, GB>), dim3(heads), dim3(SR_THREADS), lds, st, q, adj,   \
-                       entry, K, V, n_q, n_kv, Ng, N, kv_stride, wstart, deg, (int)s, topk, ef,    \
-                       expand, bitset, ids, stats, ids_off, scale, out, lse)
+    do {                                                                                           \
+        RA_LDS_OPT_IN((decode_kernel<DTV, GB>), lds);                                              \
+        hipLaunchKernelGGL((decode_kernel<DTV, GB>), dim3(heads), dim3(SR_THREADS), lds, st, q,    \
+                           adj, entry, K, V, n_q, n_kv, Ng, N, kv_stride, wstart, deg, (int)s,     \
+                           topk, ef, expand, bitset, ids, stats, ids_off, scale, out, lse);        \
+    } while (0)
     if (dt == RA_BF16) {
         if (gb) RA_DC_GO(RA_BF16, true); else RA_DC_GO(RA_BF16, false);
     } else {

@@ -23,7 +23,8 @@ size_t ra_search_lds_bytes(int64_t N, int deg, int ef, int expand, bool global_b
 }
 
 bool ra_search_needs_global_bitset(int64_t N, int deg, int ef, int expand) {
-    return ra_search_lds_bytes(N, deg, ef, expand, false) > SR_LDS_LIMIT;
+    return (size_t)((N + 31) >> 5) * 4 > SR_BITSET_LDS_MAX ||
+           ra_search_lds_bytes(N, deg, ef, expand, false) > SR_LDS_LIMIT;
 }
 
 ra_status ra_launch_search(const void* q, const int32_t* adj, const int32_t* entry, const void* K,
@@ -46,9 +47,12 @@ ra_status ra_launch_search(const void* q, const int32_t* adj, const int32_t* ent
         hipLaunchKernelGGL(fill_u32_kernel, dim3(1024), dim3(256), 0, st, bitset, words, 0u);
     }
 #define RA_SR_LAUNCH(DTV, GB)                                                                     \
-    hipLaunchKernelGGL((search_kernel<DTV, GB>), dim3(heads), dim3(SR_THREADS), lds, st, q, adj,  \
-                       entry, K, n_q, n_kv, N, deg, (int)ss, (int)ww, topk, ef, expand, bitset,   \
-                       ids, stats)
+    do {                                                                                          \
+        RA_LDS_OPT_IN((search_kernel<DTV, GB>), lds);                                             \
+        hipLaunchKernelGGL((search_kernel<DTV, GB>), dim3(heads), dim3(SR_THREADS), lds, st, q,   \
+                           adj, entry, K, n_q, n_kv, N, deg, (int)ss, (int)ww, topk, ef, expand,  \
+                           bitset, ids, stats);                                                   \
+    } while (0)
     if (dt == RA_BF16) {
         if (gb) RA_SR_LAUNCH(RA_BF16, true); else RA_SR_LAUNCH(RA_BF16, false);
     } else {

@@ -23,7 +23,9 @@
 #include "common.h"
 
 #define SR_THREADS 1024
-#define SR_LDS_LIMIT (64 * 1024)
+#define SR_LDS_LIMIT (160 * 1024)     // LDS a workgroup can have on this part (above 64 KB: opt-in)
+#define SR_BITSET_LDS_MAX (64 * 1024) // a longer visited bitset lives in global memory
+#define RA_MAX_DEVICES 64
 #define SR_UNROLL 2               // key rows in flight per 16-lane group
 
 #define SR_NG (SR_THREADS / 16)     // 16-lane groups per workgroup
@@ -36,18 +38,21 @@ typedef unsigned long long u64;
 // ticks spent in each phase to a device array that ra_dbg_phase_ticks copies out. Off otherwise.
 #ifdef SR_PHASE_CLOCKS
 #define SR_NPHASE 8
-static __device__ long long sr_phase_ticks[64 * SR_NPHASE];
-#define SR_TICK_INIT long long tick_ = clock64()
-#define SR_TICK(p)                                                         \
-    do {                                                                   \
-        if (threadIdx.x == 0 && blockIdx.x < 64) {                         \
-            const long long now_ = clock64();                              \
-            sr_phase_ticks[blockIdx.x * SR_NPHASE + (p)] += now_ - tick_;  \
-            tick_ = now_;                                                  \
-        }                                                                  \
+#define SR_NITER 16
+static __device__ long long sr_phase_ticks[64 * SR_NITER * SR_NPHASE];
+#define SR_TICK_INIT long long tick_ = clock64(); int tick_it_ = 0
+#define SR_TICK_ITER(i) tick_it_ = (i) < SR_NITER ? (i) : SR_NITER - 1
+#define SR_TICK(p)                                                                             \
+    do {                                                                                       \
+        if (threadIdx.x == 0 && blockIdx.x < 64) {                                             \
+            const long long now_ = clock64();                                                  \
+            sr_phase_ticks[(blockIdx.x * SR_NITER + tick_it_) * SR_NPHASE + (p)] += now_ - tick_; \
+            tick_ = now_;                                                                      \
+        }                                                                                      \
     } while (0)
 #else
 #define SR_TICK_INIT
+#define SR_TICK_ITER(i)
 #define SR_TICK(p)
 #endif
 
@@ -198,7 +203,6 @@ __device__ __forceinline__ int run_search(
     // but before its picks were marked expanded (two buffers, swapped with the beam's)
     uint16_t* urank = reinterpret_cast<uint16_t*>(ctr + C_COUNT);    // [ef + 1]
     uint16_t* urank_nxt = urank + ef + 1;                            // [ef + 1]
-    int* ushift = cid;               // [maxc] per kept candidate, during the merge (cid is dead then)
     uint32_t* bits = GBITS ? gbits + (size_t)head * nwords
                            : reinterpret_cast<uint32_t*>(urank_nxt + ef + 1);
 
@@ -223,6 +227,7 @@ __device__ __forceinline__ int run_search(
     SR_TICK(5);
 
     for (;;) {
+        SR_TICK_ITER(n_iters);
         int np;
         if (!picked) {
             // ---- pick the `expand` best unexpanded entries: the beam is sorted and has at most
@@ -340,9 +345,7 @@ __device__ __forceinline__ int run_search(
             const int items = E * nch;
             for (int c = tid; c < nk; c += SR_THREADS) {
                 const int b = count_better(cur, bn, ckey[c]);
-                if (b) atomicAdd(&cnt[bn + c], b);
-                const int ub = (int)urank[b] - np;            // this step's picks are expanded now
-                ushift[c] = (ub > 0 ? ub : 0) - b;
+                if (b) atomicAdd(&cnt[bn + c], b << 16);      // high half: beam entries above it
             }
             for (int a = tid; a < items; a += SR_THREADS) {
                 const int ch = a / E, e = a - ch * E;
@@ -357,18 +360,15 @@ __device__ __forceinline__ int run_search(
                 ctr[C_NKEEP] = 0;
             }
             for (int e = tid; e < E; e += SR_THREADS) {
-                const int c = cnt[e];
+                const int both = cnt[e];
                 cnt[e] = 0;
                 const bool beam = e < bn;
                 u64 k = beam ? cur[e] : ckey[e - bn];
-                const int pos = (beam ? e : 0) + c;
-                int ur;                                           // unexpanded elements above this one
-                if (beam) {
-                    const int ub = (int)urank[e] - np;
-                    ur = c + (ub > 0 ? ub : 0);
-                } else {
-                    ur = c + ushift[e - bn];
-                }
+                const int c = both & 0xffff;                      // candidates above this one
+                const int b = beam ? e : both >> 16;              // beam entries above this one
+                const int pos = b + c;
+                const int ub = (int)urank[b] - np;                // this step's picks are expanded now
+                const int ur = c + (ub > 0 ? ub : 0);             // unexpanded elements above this one
                 const bool un = pos < ef && (k & 1ull);
                 if (un && ur < expand) {
                     picks[ur] = key_id(k);
@@ -425,6 +425,20 @@ __device__ __forceinline__ int run_search(
     SR_TICK(6);
     return ctr[C_NKEEP];
 }
+
+// A kernel that wants more than 64 KB of dynamic LDS has to say so once per device (host side).
+#define RA_LDS_OPT_IN(KERNEL, BYTES)                                                               \
+    do {                                                                                           \
+        static size_t granted_[RA_MAX_DEVICES];                                                    \
+        int dev_ = 0;                                                                              \
+        RA_HIP(hipGetDevice(&dev_));                                                               \
+        if (dev_ < 0 || dev_ >= RA_MAX_DEVICES) RA_FAIL(RA_EUNSUP, "device %d out of range", dev_); \
+        if ((size_t)(BYTES) > 64 * 1024 && granted_[dev_] < (size_t)(BYTES)) {                      \
+            RA_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&KERNEL),                     \
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, SR_LDS_LIMIT)); \
+            granted_[dev_] = SR_LDS_LIMIT;                                                         \
+        }                                                                                          \
+    } while (0)
 
 // LDS bytes run_search needs.
 static inline size_t search_lds_bytes(int64_t N, int deg, int ef, int expand, bool global_bitset) {
