@@ -14,7 +14,8 @@ from typing import Optional
 import torch
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libra.so")
+# RA_LIBRARY names another build of the same library (a tuning build, say); default: the in-tree one
+LIB_PATH = os.environ.get("RA_LIBRARY") or os.path.join(_HERE, "libra.so")
 
 RA_F32, RA_BF16 = 0, 1
 STATUS = {0: "RA_OK", 1: "RA_EINVAL", 2: "RA_ESHAPE", 3: "RA_EDTYPE", 4: "RA_ENOMEM",

@@ -34,6 +34,74 @@ __device__ __forceinline__ void sm_merge(Softmax8& a, float mo, float lo, const 
     a.m = mn;
 }
 
+// exp for the softmax weights: the hardware exponential for bf16 data (its error, about 1e-6
+// relative for the exponents that matter, is far below the bf16 inputs'), the library one for fp32.
+template <int DT>
+__device__ __forceinline__ float sm_exp(float x) { return DT == RA_BF16 ? __expf(x) : expf(x); }
+
+// One more row for a lane's online-softmax state: logit z, the lane's 8 values of the value row.
+// The running maximum settles after a few rows, so the rescaling of the sums is skipped unless
+// some lane of the wavefront sees a larger logit.
+template <int DT>
+__device__ __forceinline__ void sm_row(Softmax8& st, float z, const float* v) {
+    if (__builtin_amdgcn_ballot_w64(z > st.m) != 0ull) {
+        const float mn = fmaxf(st.m, z);
+        const float corr = sm_exp<DT>(st.m - mn);       // exp(-inf) = 0 on the first row
+        st.l *= corr;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) st.acc[e] *= corr;
+        st.m = mn;
+    }
+    const float p = sm_exp<DT>(z - st.m);
+    st.l += p;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) st.acc[e] = fmaf(p, v[e], st.acc[e]);
+}
+
+// The 8 values of a key or value row that a lane owns, as float32.
+template <int DT>
+__device__ __forceinline__ void row_floats(const RowBits<DT>& r, float* f) {
+    if (DT == RA_BF16) {
+        f[0] = bf16_lo(r.a.x); f[1] = bf16_hi(r.a.x); f[2] = bf16_lo(r.a.y); f[3] = bf16_hi(r.a.y);
+        f[4] = bf16_lo(r.a.z); f[5] = bf16_hi(r.a.z); f[6] = bf16_lo(r.a.w); f[7] = bf16_hi(r.a.w);
+    } else {
+        f[0] = __uint_as_float(r.a.x); f[1] = __uint_as_float(r.a.y);
+        f[2] = __uint_as_float(r.a.z); f[3] = __uint_as_float(r.a.w);
+        f[4] = __uint_as_float(r.b.x); f[5] = __uint_as_float(r.b.y);
+        f[6] = __uint_as_float(r.b.z); f[7] = __uint_as_float(r.b.w);
+    }
+}
+
+// A lane's 8 query values in the form the attention logits want them: bf16 pairs stay packed and
+// go through the two-element dot instruction (exact products, float32 sums), fp32 uses fma.
+// (The search scores are not computed here: they decide ids and keep their own fixed order.)
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+template <int DT> struct LaneQuery;
+template <> struct LaneQuery<RA_BF16> {
+    uint4 q;
+    __device__ __forceinline__ LaneQuery(const void* qrow, int lane16)
+        : q(reinterpret_cast<const uint4*>(qrow)[lane16]) {}
+    __device__ __forceinline__ float dot(const RowBits<RA_BF16>& k) const {
+        float d = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, q.x), __builtin_bit_cast(bf16x2, k.a.x), 0.f, false);
+        d = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, q.y), __builtin_bit_cast(bf16x2, k.a.y), d, false);
+        d = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, q.z), __builtin_bit_cast(bf16x2, k.a.z), d, false);
+        d = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, q.w), __builtin_bit_cast(bf16x2, k.a.w), d, false);
+        return d;
+    }
+};
+template <> struct LaneQuery<RA_F32> {
+    float q[8];
+    __device__ __forceinline__ LaneQuery(const void* qrow, int lane16) { load_q8<RA_F32>(qrow, lane16, q); }
+    __device__ __forceinline__ float dot(const RowBits<RA_F32>& k) const {
+        float f[8];
+        row_floats<RA_F32>(k, f);
+        float d = 0.f;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) d = fmaf(q[e], f[e], d);
+        return d;
+    }
+};
+
 template <int DT, bool GBITS>
 __global__ __launch_bounds__(SR_THREADS) void decode_kernel(
     const void* __restrict__ q, const int32_t* __restrict__ adj, const int32_t* __restrict__ entry,
@@ -49,6 +117,8 @@ __global__ __launch_bounds__(SR_THREADS) void decode_kernel(
     const int seq = head / n_q, h = head % n_q, kvh = h / (n_q / n_kv);
     const size_t esz = DT == RA_BF16 ? 2 : 4;
     int32_t* lds_ids = reinterpret_cast<int32_t*>(lds_raw + ids_off);
+    const char* Kh = reinterpret_cast<const char*>(K) + ((size_t)seq * n_kv + kvh) * kv_stride * RA_D * esz;
+    const char* Vh = reinterpret_cast<const char*>(V) + ((size_t)seq * n_kv + kvh) * kv_stride * RA_D * esz;
     // The graph covers the first Ng of the N tokens now in the cache; W = [0, s) u [wstart, N) with
     // wstart <= Ng, so every token appended after the build is attended densely.
     const int cnt = run_search<DT, GBITS>(lds_raw, head, q, adj, entry, K, n_q, n_kv, Ng, kv_stride, deg,
@@ -58,10 +128,7 @@ __global__ __launch_bounds__(SR_THREADS) void decode_kernel(
     const long long t_attn = clock64();
 #endif
     // ---- Eq. 2 over Omega (rows [0, cnt): ids in LDS) and W (rows [cnt, cnt + s + N - wstart))
-    const char* Kh = reinterpret_cast<const char*>(K) + ((size_t)seq * n_kv + kvh) * kv_stride * RA_D * esz;
-    const char* Vh = reinterpret_cast<const char*>(V) + ((size_t)seq * n_kv + kvh) * kv_stride * RA_D * esz;
-    float qv[8];
-    load_row8<DT>(reinterpret_cast<const char*>(q) + (size_t)head * RA_D * esz, 0, lane16, qv);
+    const LaneQuery<DT> ql(reinterpret_cast<const char*>(q) + (size_t)head * RA_D * esz, lane16);
     constexpr int DC_ROWS = DT == RA_BF16 ? 6 : 3;       // rows in flight per 16-lane group
     const int R = cnt + s + (int)(N - wstart);
     Softmax8 st;
@@ -71,7 +138,7 @@ __global__ __launch_bounds__(SR_THREADS) void decode_kernel(
     for (int e = 0; e < 8; ++e) st.acc[e] = 0.f;
     for (int r0 = 0; r0 < R; r0 += SR_NG * DC_ROWS) {
         int64_t rid[DC_ROWS];
-        float kv[DC_ROWS][8], vv[DC_ROWS][8];
+        RowBits<DT> kb[DC_ROWS], vb[DC_ROWS];
 #pragma unroll
         for (int u = 0; u < DC_ROWS; ++u) {
             const int r = r0 + u * SR_NG + grp;
@@ -80,27 +147,20 @@ __global__ __launch_bounds__(SR_THREADS) void decode_kernel(
             else if (r < R) id = r - cnt < s ? (int64_t)(r - cnt) : wstart + (r - cnt - s);
             rid[u] = id;
             const int64_t safe = id >= 0 ? id : 0;      // loads stay unconditional
-            load_row8<DT>(Kh, safe, lane16, kv[u]);
-            load_row8<DT>(Vh, safe, lane16, vv[u]);
+            kb[u] = load_key<DT>(Kh, safe, lane16);
+            vb[u] = load_key<DT>(Vh, safe, lane16);
         }
 #pragma unroll
         for (int u = 0; u < DC_ROWS; ++u) {
             if (rid[u] < 0) continue;
-            float dot = 0.f;
-#pragma unroll
-            for (int e = 0; e < 8; ++e) dot = fmaf(qv[e], kv[u][e], dot);
+            float dot = ql.dot(kb[u]);
             dot += at_dpp<0xB1>(dot);
             dot += at_dpp<0x4E>(dot);
             dot += at_dpp<0x141>(dot);
             dot += at_dpp<0x140>(dot);
-            const float z = dot * scale;
-            const float mn = fmaxf(st.m, z);
-            const float corr = expf(st.m - mn);         // exp(-inf) = 0 on the first row
-            const float p = expf(z - mn);
-            st.l = st.l * corr + p;
-#pragma unroll
-            for (int e = 0; e < 8; ++e) st.acc[e] = fmaf(p, vv[u][e], st.acc[e] * corr);
-            st.m = mn;
+            float v[8];
+            row_floats<DT>(vb[u], v);
+            sm_row<DT>(st, dot * scale, v);
         }
     }
     // ---- combine the four groups of each wavefront by lane exchange
