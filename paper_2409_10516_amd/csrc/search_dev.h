@@ -37,7 +37,7 @@ typedef unsigned long long u64;
 // Phase clocks for tuning builds (-DSR_PHASE_CLOCKS): thread 0 of the first 64 workgroups adds the
 // ticks spent in each phase to a device array that ra_dbg_phase_ticks copies out. Off otherwise.
 #ifdef SR_PHASE_CLOCKS
-#define SR_NPHASE 8
+#define SR_NPHASE 12
 #define SR_NITER 16
 static __device__ long long sr_phase_ticks[64 * SR_NITER * SR_NPHASE];
 #define SR_TICK_INIT long long tick_ = clock64(); int tick_it_ = 0
@@ -145,6 +145,33 @@ __device__ __forceinline__ int count_better(const u64* arr, int n, u64 k) {
     return lo;
 }
 
+// Inclusive prefix sum over the 64 lanes of a wavefront (all lanes active): shifts inside each
+// row of 16 lanes, then lane 15 of a row added to the next row, then lane 31 to the upper half.
+template <int CTRL, int ROW_MASK>
+__device__ __forceinline__ int dpp_or_zero(int v) {
+    return __builtin_amdgcn_update_dpp(0, v, CTRL, ROW_MASK, 0xF, false);
+}
+__device__ __forceinline__ int wave_incl_scan(int v) {
+    v += dpp_or_zero<0x111, 0xF>(v);      // row_shr:1
+    v += dpp_or_zero<0x112, 0xF>(v);      // row_shr:2
+    v += dpp_or_zero<0x114, 0xF>(v);      // row_shr:4
+    v += dpp_or_zero<0x118, 0xF>(v);      // row_shr:8
+    v += dpp_or_zero<0x142, 0xA>(v);      // row_bcast:15 into rows 1 and 3
+    v += dpp_or_zero<0x143, 0xC>(v);      // row_bcast:31 into rows 2 and 3
+    return v;
+}
+
+// the same when all 16 entries count
+__device__ __forceinline__ int count_above16_full(const u64* arr, u64 k) {
+    u64 v[16];
+#pragma unroll
+    for (int u = 0; u < 16; ++u) v[u] = arr[u];
+    int cnt = 0;
+#pragma unroll
+    for (int u = 0; u < 16; ++u) cnt += v[u] > k ? 1 : 0;
+    return cnt;
+}
+
 static_assert(RA_MAX_EF <= SR_THREADS, "one beam entry per thread");
 
 // number of the first min(n, 16) entries of arr that are larger than k; all 16 are read (the
@@ -195,8 +222,10 @@ __device__ __forceinline__ int run_search(
     u64* nxt = cur + ef;
     u64* ckey = nxt + ef;            // [maxc + 16] candidates that passed the beam threshold
     int* cid = reinterpret_cast<int*>(ckey + maxc + 16);  // [maxc] claimed neighbour ids
-    int* cnt = cid + maxc;           // [ef + maxc] merge counters, zero between steps
-    int* picks = cnt + ef + maxc;    // [RA_MAX_EXPAND]
+    int* cnt = cid + maxc;           // [maxc] merge counters of the candidates, zero between steps
+    int* hist = cnt + maxc;          // [ef + 1] candidates per beam slot, zero between steps
+    int* hist_nxt = hist + ef + 1;   // [ef + 1] the one the next step fills
+    int* picks = hist_nxt + ef + 1;  // [RA_MAX_EXPAND]
     int* ctr = picks + RA_MAX_EXPAND;
     int* wtot = ctr + C_WTOT;
     // urank[i], i in [0, bn]: unexpanded entries among the first i of the beam, as of the last pick
@@ -208,7 +237,7 @@ __device__ __forceinline__ int run_search(
 
     if (!GBITS)
         for (int i = tid; i < nwords; i += SR_THREADS) bits[i] = 0u;
-    for (int i = tid; i < ef + maxc; i += SR_THREADS) cnt[i] = 0;
+    for (int i = tid; i < maxc + 2 * ef + 2; i += SR_THREADS) cnt[i] = 0;      // cnt, hist, hist_nxt
     float qv[8];
     load_q8<DT>(reinterpret_cast<const char*>(q) + (size_t)head * RA_D * esz, lane16, qv);
     const int e0 = entry[head];
@@ -332,40 +361,68 @@ __device__ __forceinline__ int run_search(
             continue;
         }
 
-        // ---- merge by counting into the other beam buffer, truncating at ef. The final position
-        //      of an element of (beam u kept candidates) is the number of elements that beat it:
-        //      a beam entry's index plus the candidates above it; a candidate's rank among the
-        //      candidates plus the beam entries above it (binary search in the sorted beam). The
-        //      same counts give the number of *unexpanded* elements above each element (every
-        //      candidate is unexpanded; for the beam's part urank has it), so the next step's picks,
-        //      the elements with fewer than `expand` unexpanded ones above them, fall out of the merge.
+        // ---- merge by rank into the other beam buffer, truncating at ef. The final position of
+        //      an element of (beam u kept candidates) is the number of elements that beat it.
+        //      A candidate: the beam entries above it (binary search in the sorted beam: its slot)
+        //      plus the candidates above it (counted, 16 comparisons per task, tasks spread over
+        //      the workgroup). A beam entry: its index plus the candidates whose slot is at or
+        //      before it, a prefix sum over the histogram of slots. The same numbers give the
+        //      count of *unexpanded* elements above each element (every candidate is unexpanded;
+        //      for the beam's part urank has it), so the next step's picks, the elements with
+        //      fewer than `expand` unexpanded ones above them, fall out of the merge.
         {
             const int E = bn + nk;
             const int nch = (nk + 15) >> 4;
-            const int items = E * nch;
+            const int items = nk * nch;
             for (int c = tid; c < nk; c += SR_THREADS) {
                 const int b = count_better(cur, bn, ckey[c]);
-                if (b) atomicAdd(&cnt[bn + c], b << 16);      // high half: beam entries above it
+                if (b) atomicAdd(&cnt[c], b << 16);           // high half: beam entries above it
+                atomicAdd(&hist[b], 1);
             }
+            SR_TICK(8);
+            const float inv_nk = 1.0f / (float)nk;
             for (int a = tid; a < items; a += SR_THREADS) {
-                const int ch = a / E, e = a - ch * E;
-                const u64 ke = (e < bn ? cur[e] : ckey[e - bn]) | 1ull;   // candidates carry flag 1
-                const int c = count_above16(ckey + ch * 16, nk - ch * 16, ke);
-                if (c) atomicAdd(&cnt[e], c);
+                // a = ch * nk + c without an integer division: the float quotient is off by at most one
+                int ch = (int)((float)a * inv_nk), c = a - ch * nk;
+                if (c < 0) { --ch; c += nk; }
+                if (c >= nk) { ++ch; c -= nk; }
+                const int above = ch + 1 < nch ? count_above16_full(ckey + ch * 16, ckey[c])
+                                               : count_above16(ckey + ch * 16, nk - ch * 16, ckey[c]);
+                if (above) atomicAdd(&cnt[c], above);
             }
+            SR_TICK(9);
             __syncthreads();
             SR_TICK(3);
             if (tid == 0) {
                 ctr[C_NCAND] = 0;
                 ctr[C_NKEEP] = 0;
             }
+            // candidates above beam entry `tid`: inclusive prefix sum of hist, by wavefront, each
+            // adding up the part of hist before its own 64 entries itself (no second barrier)
+            int cbeam = 0;
+            if (wv * RA_WAVE < bn) {
+                int before = 0;
+                for (int x = 0; x < wv; ++x) before += hist[x * RA_WAVE + lane];
+                before = __builtin_amdgcn_readlane(wave_incl_scan(before), RA_WAVE - 1);
+                cbeam = before + wave_incl_scan(tid < bn ? hist[tid] : 0);
+            }
+            for (int i = tid; i <= ef; i += SR_THREADS) hist_nxt[i] = 0;
+            SR_TICK(10);
             for (int e = tid; e < E; e += SR_THREADS) {
-                const int both = cnt[e];
-                cnt[e] = 0;
-                const bool beam = e < bn;
-                u64 k = beam ? cur[e] : ckey[e - bn];
-                const int c = both & 0xffff;                      // candidates above this one
-                const int b = beam ? e : both >> 16;              // beam entries above this one
+                const bool beam = e < bn;                         // only with e == tid
+                u64 k;
+                int c, b;                                         // candidates / beam entries above
+                if (beam) {
+                    k = cur[e];
+                    c = cbeam;
+                    b = e;
+                } else {
+                    const int both = cnt[e - bn];
+                    cnt[e - bn] = 0;
+                    k = ckey[e - bn];
+                    c = both & 0xffff;
+                    b = both >> 16;
+                }
                 const int pos = b + c;
                 const int ub = (int)urank[b] - np;                // this step's picks are expanded now
                 const int ur = c + (ub > 0 ? ub : 0);             // unexpanded elements above this one
@@ -387,6 +444,7 @@ __device__ __forceinline__ int run_search(
         bn = bn + nk < ef ? bn + nk : ef;
         u64* t = cur; cur = nxt; nxt = t;
         uint16_t* tu = urank; urank = urank_nxt; urank_nxt = tu;
+        int* th = hist; hist = hist_nxt; hist_nxt = th;
         picked = true;
     }
 
@@ -443,7 +501,7 @@ __device__ __forceinline__ int run_search(
 // LDS bytes run_search needs.
 static inline size_t search_lds_bytes(int64_t N, int deg, int ef, int expand, bool global_bitset) {
     const int maxc = expand * deg;
-    size_t b = (size_t)2 * ef * 8 + (size_t)(maxc + 16) * 8 + (size_t)maxc * 4 + (size_t)(ef + maxc) * 4 +
+    size_t b = (size_t)2 * ef * 8 + (size_t)(maxc + 16) * 8 + (size_t)maxc * 4 + (size_t)(maxc + 2 * ef + 2) * 4 +
                (RA_MAX_EXPAND + C_COUNT) * 4 + (size_t)(ef + 1) * 4;
     if (!global_bitset) b += (size_t)((N + 31) >> 5) * 4;
     return b;
