@@ -44,6 +44,8 @@ def parse():
     p.add_argument("--cpu-tokens", type=int, default=8, help="decode queries per head the CPU oracle is timed on")
     p.add_argument("--no-cpu-baseline", action="store_true")
     p.add_argument("--graph", type=int, default=1, help="replay the step from a captured HIP graph")
+    p.add_argument("--helpers", type=int, default=1,
+                   help="0: every head attends to the static set itself (no helper workgroups)")
     p.add_argument("--copy-calibration", action="store_true",
                    help="also run three plain 1 GiB device copies (reference for HBM counters)")
     return p.parse_args()
@@ -95,6 +97,8 @@ def main():
         torch.cuda.synchronize()
         t1 = time.time()
         idx = ra.ra_build_index(w.K, w.Q_prefill, w.deg, w.knn)
+        if not a.helpers:
+            idx.configure(ra.binding.RA_CFG_HELPERS, ra.binding.RA_HELPERS_OFF)
         torch.cuda.synchronize()
         t2 = time.time()
         t_gen += t1 - t0

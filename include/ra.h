@@ -161,8 +161,34 @@ ra_status ra_index_import(const int32_t* adj_host, const int32_t* entries_host, 
 ra_status ra_index_export(const ra_index* idx, int seq, int q_head, int32_t* adj_host,
                           int32_t* entry_host);
 
-/* what: 0 n_seq, 1 n_q_heads, 2 n_kv_heads, 3 N, 4 deg, 5 bytes of device memory owned. */
+/* what: 0 n_seq, 1 n_q_heads, 2 n_kv_heads, 3 N, 4 deg, 5 bytes of device memory owned,
+ * 6 whether ra_decode_step will use helper workgroups (1 / 0; synchronises the device). */
 int64_t ra_index_info(const ra_index* idx, int what);
+
+/* Settings of the handle's decode path (host side; synchronises the device).
+ *
+ * ra_decode_step computes the attention over the static set W (Sec. 3.3: o_W of Eq. 4, which
+ * does not depend on the retrieval) in extra "helper" workgroups of the same launch, one per
+ * (sequence, KV head), while the query heads' workgroups search; each head takes over its
+ * helper's result through device memory the handle owns. The wait for that result is bounded:
+ * a head that does not get it within RA_CFG_HELPER_SPIN polls computes o_W itself, and the
+ * handle stops using helpers until RA_CFG_HELPERS is set again. Results do not depend on the
+ * setting beyond the summation order of Eq. 2/4 (same tolerance).
+ *   RA_CFG_HELPERS      RA_HELPERS_ON (default), RA_HELPERS_OFF (each head attends to W itself),
+ *                       RA_HELPERS_SILENT (for tests of the bounded wait: helper workgroups are
+ *                       launched but do nothing). Setting it also clears a wait that ran out.
+ *   RA_CFG_HELPER_SPIN  polls before a head gives up, 1 .. 2^24 (default RA_HELPER_SPIN_DEFAULT,
+ *                       tens of milliseconds).
+ * Helpers are used only for GQA groups of 1, 2, 4 or 8 query heads per KV head.
+ * Two ra_decode_step calls on one handle must not overlap in time (they share this memory,
+ * like the handle's other workspaces). Returns RA_EINVAL for an unknown setting or value. */
+#define RA_CFG_HELPERS 0
+#define RA_CFG_HELPER_SPIN 1
+#define RA_HELPERS_OFF 0
+#define RA_HELPERS_ON 1
+#define RA_HELPERS_SILENT 2
+#define RA_HELPER_SPIN_DEFAULT 20000
+ra_status ra_index_configure(ra_index* idx, int what, int64_t value);
 
 /* Device pointers to the handle's graphs (adj [n_graphs][N][deg], entry [n_graphs]). */
 const int32_t* ra_index_adj(const ra_index* idx);

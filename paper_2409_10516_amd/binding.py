@@ -18,6 +18,8 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.environ.get("RA_LIBRARY") or os.path.join(_HERE, "libra.so")
 
 RA_F32, RA_BF16 = 0, 1
+RA_CFG_HELPERS, RA_CFG_HELPER_SPIN = 0, 1
+RA_HELPERS_OFF, RA_HELPERS_ON, RA_HELPERS_SILENT = 0, 1, 2
 STATUS = {0: "RA_OK", 1: "RA_EINVAL", 2: "RA_ESHAPE", 3: "RA_EDTYPE", 4: "RA_ENOMEM",
           5: "RA_EHIP", 6: "RA_EUNSUP"}
 
@@ -58,6 +60,8 @@ def lib() -> C.CDLL:
     L.ra_index_export.argtypes = [vp, i32, i32, vp, vp]
     L.ra_index_info.argtypes = [vp, i32]
     L.ra_index_info.restype = i64
+    L.ra_index_configure.argtypes = [vp, i32, i64]
+    L.ra_index_configure.restype = i32
     L.ra_index_adj.argtypes = [vp]
     L.ra_index_adj.restype = vp
     L.ra_index_entry.argtypes = [vp]
@@ -132,6 +136,11 @@ class Index:
     N = property(lambda s: s.info(3))
     deg = property(lambda s: s.info(4))
     device_bytes = property(lambda s: s.info(5))
+    helpers_active = property(lambda s: s.info(6) == 1)
+
+    def configure(self, what: int, value: int) -> None:
+        """ra_index_configure: RA_CFG_HELPERS / RA_CFG_HELPER_SPIN."""
+        _check(lib().ra_index_configure(self.handle, what, value))
 
     def free(self):
         if self._h is not None:

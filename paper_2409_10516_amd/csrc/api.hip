@@ -92,6 +92,12 @@ static ra_status grow(void** p, size_t* have, size_t need) {
     return RA_OK;
 }
 
+// records, ready words and the "helpers off" word of the fused decode kernel's hand-over area
+static size_t coop_bytes(const ra_index* ix) {
+    const size_t heads = (size_t)ix->n_seq * ix->n_q;
+    return heads * RA_COOP_REC * sizeof(float) + (heads + 1) * sizeof(uint32_t);
+}
+
 static ra_status new_handle(int n_seq, int n_q, int n_kv, int64_t N, int deg, ra_index** out) {
     ra_index* ix = new (std::nothrow) ra_index();
     if (!ix) RA_FAIL(RA_ENOMEM, "host allocation failed");
@@ -102,9 +108,15 @@ static ra_status new_handle(int n_seq, int n_q, int n_kv, int64_t N, int deg, ra
     hipError_t e = hipGetDevice(&ix->device);
     if (e == hipSuccess) e = hipMalloc((void**)&ix->adj, ix->graph_bytes);
     if (e == hipSuccess) e = hipMalloc((void**)&ix->entry, graphs * sizeof(int32_t));
+    if (e == hipSuccess) e = hipMalloc((void**)&ix->coop, coop_bytes(ix));
+    if (e == hipSuccess) e = hipMemset(ix->coop, 0, coop_bytes(ix));
+    ix->coop_mode = RA_HELPERS_ON;
+    ix->coop_spin = RA_HELPER_SPIN_DEFAULT;
     if (e != hipSuccess) {
         ra_set_error("allocating the graph (%zu B) failed: %s", ix->graph_bytes, hipGetErrorString(e));
         if (ix->adj) (void)hipFree(ix->adj);
+        if (ix->entry) (void)hipFree(ix->entry);
+        if (ix->coop) (void)hipFree(ix->coop);
         delete ix;
         return e == hipErrorOutOfMemory ? RA_ENOMEM : RA_EHIP;
     }
@@ -119,7 +131,29 @@ extern "C" void ra_index_free(ra_index* ix) {
     if (ix->partials) (void)hipFree(ix->partials);
     if (ix->ids_ws) (void)hipFree(ix->ids_ws);
     if (ix->bitset) (void)hipFree(ix->bitset);
+    if (ix->coop) (void)hipFree(ix->coop);
     delete ix;
+}
+
+extern "C" ra_status ra_index_configure(ra_index* ix, int what, int64_t value) {
+    if (!ix) RA_FAIL(RA_EINVAL, "index handle is NULL");
+    switch (what) {
+        case RA_CFG_HELPERS: {
+            if (value != RA_HELPERS_OFF && value != RA_HELPERS_ON && value != RA_HELPERS_SILENT)
+                RA_FAIL(RA_EINVAL, "helpers mode %lld", (long long)value);
+            // also forgets a wait that ran out: ready words and the off word start from zero
+            RA_HIP(hipDeviceSynchronize());
+            RA_HIP(hipMemset(ix->coop, 0, coop_bytes(ix)));
+            ix->coop_mode = (int)value;
+            return RA_OK;
+        }
+        case RA_CFG_HELPER_SPIN:
+            if (value < 1 || value > (1 << 24)) RA_FAIL(RA_EINVAL, "spin limit %lld", (long long)value);
+            ix->coop_spin = (int)value;
+            return RA_OK;
+        default:
+            RA_FAIL(RA_EINVAL, "unknown setting %d", what);
+    }
 }
 
 extern "C" int64_t ra_index_info(const ra_index* ix, int what) {
@@ -131,7 +165,18 @@ extern "C" int64_t ra_index_info(const ra_index* ix, int what) {
         case 3: return ix->N;
         case 4: return ix->deg;
         case 5: return (int64_t)(ix->graph_bytes + (size_t)ix->n_seq * ix->n_q * 4 +
-                                 ix->partials_bytes + ix->ids_bytes + ix->bitset_bytes);
+                                 ix->partials_bytes + ix->ids_bytes + ix->bitset_bytes + coop_bytes(ix));
+        case 6: {
+            if (ix->coop_mode != RA_HELPERS_ON) return 0;
+            const size_t heads = (size_t)ix->n_seq * ix->n_q;
+            uint32_t off = 1u;
+            if (hipDeviceSynchronize() != hipSuccess ||
+                hipMemcpy(&off, reinterpret_cast<const char*>(ix->coop) + heads * RA_COOP_REC * sizeof(float) +
+                                    heads * sizeof(uint32_t),
+                          sizeof(off), hipMemcpyDeviceToHost) != hipSuccess)
+                return -1;
+            return off == 0u;
+        }
         default: return -1;
     }
 }
@@ -302,8 +347,8 @@ extern "C" ra_status ra_decode_step_grown(const void* q, const ra_index* idx, co
     if (ra_decode_needs_global_bitset(ix->N, ix->deg, ef, expand, topk))
         RA_TRY(grow((void**)&ix->bitset, &ix->bitset_bytes, heads * ((ix->N + 31) >> 5) * 4));
     return ra_launch_decode(q, ix->adj, ix->entry, K, V, dt, ix->n_seq, ix->n_q, ix->n_kv, ix->N, N,
-                            kv_stride, ix->deg, sink, window, topk, ef, expand, ix->bitset,
-                            (hipStream_t)stream, out, lse, ids, stats);
+                            kv_stride, ix->deg, sink, window, topk, ef, expand, ix->bitset, ix->coop,
+                            ix->coop_mode, ix->coop_spin, (hipStream_t)stream, out, lse, ids, stats);
 }
 
 extern "C" ra_status ra_decode_step(const void* q, const ra_index* idx, const void* K, const void* V,

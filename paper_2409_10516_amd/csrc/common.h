@@ -42,8 +42,16 @@ struct ra_index {
     size_t ids_bytes;
     uint32_t* bitset;   // global visited bitsets for contexts too long for LDS
     size_t bitset_bytes;
+    // hand-over area of the fused decode kernel: per head a record (RA_COOP_REC floats: max, sum,
+    // 2 unused, 128 weighted sums) that a helper workgroup fills with the attention over the
+    // static set, then per head a ready word, then one "helpers off" word
+    float* coop;
+    int coop_mode;      // RA_HELPERS_*
+    int coop_spin;      // polls of the ready word before a head gives up on its helper
     size_t graph_bytes;
 };
+
+#define RA_COOP_REC 132
 
 // ---- launchers implemented in the .hip files (all enqueue on `st`, no sync) ----------
 ra_status ra_launch_search(const void* q, const int32_t* adj, const int32_t* entry, const void* K,
@@ -65,7 +73,7 @@ bool ra_decode_needs_global_bitset(int64_t N, int deg, int ef, int expand, int t
 ra_status ra_launch_decode(const void* q, const int32_t* adj, const int32_t* entry, const void* K,
                            const void* V, ra_dtype dt, int n_seq, int n_q, int n_kv, int64_t Ng, int64_t N,
                            int64_t kv_stride, int deg, int sink, int window, int topk, int ef, int expand,
-                           uint32_t* bitset, hipStream_t st, float* out, float* lse, int32_t* ids,
+                           uint32_t* bitset, float* coop, int coop_mode, int coop_spin, hipStream_t st, float* out, float* lse, int32_t* ids,
                            ra_stats* stats);
 
 ra_status ra_launch_flat_topk(const void* q, const void* K, ra_dtype dt, int n_seq, int n_q, int n_kv,

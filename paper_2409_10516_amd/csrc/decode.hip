@@ -8,14 +8,24 @@
 // the running maximum across both sets is the same arithmetic as computing o_W and o_Omega apart
 // and combining them by Eq. 4.
 //
-// Nothing crosses workgroups, on purpose. A variant that computed the static rows once per GQA
-// group in separate workgroups of the same launch, and let the last finisher combine, was
-// measured: the agent-scope release/acquire it needs (the part has one L2 per XCD, so the
-// fences write back and invalidate L2) cost about 18 us per launch, more than the whole
-// attention. Here the four query heads of a group each read the 644 static rows themselves; their
-// workgroups are placed on one XCD (xcd_aware_head), so the repeats, like the key rows the four
-// searches have in common, are served by that XCD's L2 (measured: 12.8 MB of HBM traffic per
-// 128K-context layer against 20.9 MB with workgroup id = head).
+// The attention over the static set W does not depend on the search, so it is taken off the
+// head's critical path: the launch has one extra "helper" workgroup per (sequence, KV head) that
+// reads the rows of W once for the whole GQA group and leaves (max, sum, weighted sums) per query
+// head in a hand-over area; the head's workgroup picks its record up after the search and only
+// attends to the retrieved rows itself. Helpers have the lowest workgroup ids, never wait for
+// anything, and are finished long before the first search is.
+//
+// The hand-over uses no fence. A variant with agent-scope release/acquire was measured: the part
+// has one L2 per XCD, so those fences write back and invalidate L2, about 18 us per launch, more
+// than the whole attention. Instead the few words that cross workgroups are written and read with
+// relaxed agent-scope atomics, which go around the non-coherent cache levels on their own: the
+// helper stores its records, waits until the stores have completed (s_waitcnt vmcnt(0), barrier),
+// then stores the ready word; the head polls the ready word, then loads the record, then clears
+// the ready word for the next launch. The wait is bounded: a head that does not see its ready word
+// within the limit attends to W itself (the same code that runs when helpers are off) and turns
+// the helpers off for later launches, so a ready word that arrives late is never taken for the
+// next launch's. Query heads of a GQA group still run on one XCD (xcd_aware_head) so that the key
+// rows their searches have in common are served by that XCD's L2.
 #include "attend_dev.h"
 #include "search_dev.h"
 
@@ -79,8 +89,9 @@ typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 template <int DT> struct LaneQuery;
 template <> struct LaneQuery<RA_BF16> {
     uint4 q;
-    __device__ __forceinline__ LaneQuery(const void* qrow, int lane16)
-        : q(reinterpret_cast<const uint4*>(qrow)[lane16]) {}
+    __device__ __forceinline__ void load(const void* qrow, int lane16) {
+        q = reinterpret_cast<const uint4*>(qrow)[lane16];
+    }
     __device__ __forceinline__ float dot(const RowBits<RA_BF16>& k) const {
         float d = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, q.x), __builtin_bit_cast(bf16x2, k.a.x), 0.f, false);
         d = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, q.y), __builtin_bit_cast(bf16x2, k.a.y), d, false);
@@ -91,7 +102,7 @@ template <> struct LaneQuery<RA_BF16> {
 };
 template <> struct LaneQuery<RA_F32> {
     float q[8];
-    __device__ __forceinline__ LaneQuery(const void* qrow, int lane16) { load_q8<RA_F32>(qrow, lane16, q); }
+    __device__ __forceinline__ void load(const void* qrow, int lane16) { load_q8<RA_F32>(qrow, lane16, q); }
     __device__ __forceinline__ float dot(const RowBits<RA_F32>& k) const {
         float f[8];
         row_floats<RA_F32>(k, f);
@@ -102,6 +113,150 @@ template <> struct LaneQuery<RA_F32> {
     }
 };
 
+// Words that cross workgroups inside one launch: relaxed agent-scope atomics (see the file header).
+__device__ __forceinline__ void xwg_store(float* p, float v) {
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void xwg_store(uint32_t* p, uint32_t v) {
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ float xwg_load(const float* p) {
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ uint32_t xwg_load(const uint32_t* p) {
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// Combine the online-softmax states of a workgroup's 64 lane groups into one (max, sum, weighted
+// sum for output `tid`), valid in threads tid < 128: first the four groups of each wavefront by
+// lane exchange, then the 16 wavefronts through LDS (16 * 130 floats at `lds`). Two barriers.
+__device__ __forceinline__ void sm_combine(Softmax8 st, float* lds, int tid, float& mx, float& l, float& a) {
+    const int lane = tid & (RA_WAVE - 1), wv = tid / RA_WAVE;
+#pragma unroll
+    for (int d = 16; d <= 32; d <<= 1) {
+        const float mo = __shfl_xor(st.m, d), lo = __shfl_xor(st.l, d);
+        float ao[8];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) ao[e] = __shfl_xor(st.acc[e], d);
+        sm_merge(st, mo, lo, ao);
+    }
+    float* sm = lds;                                         // [16]
+    float* sl = sm + SR_THREADS / RA_WAVE;                   // [16]
+    float* sa = sl + SR_THREADS / RA_WAVE;                   // [16][128]
+    __syncthreads();                                         // whatever was in `lds` is dead
+    if (lane < 16) {
+        if (lane == 0) {
+            sm[wv] = st.m;
+            sl[wv] = st.l;
+        }
+#pragma unroll
+        for (int e = 0; e < 8; ++e) sa[wv * RA_D + lane * 8 + e] = st.acc[e];
+    }
+    __syncthreads();
+    mx = -INFINITY;
+    a = 0.f;
+    l = 0.f;
+    if (tid < RA_D) {
+#pragma unroll
+        for (int j = 0; j < SR_THREADS / RA_WAVE; ++j) mx = fmaxf(mx, sm[j]);
+        if (mx > -INFINITY) {
+#pragma unroll
+            for (int j = 0; j < SR_THREADS / RA_WAVE; ++j) {
+                const float wgt = expf(sm[j] - mx);
+                a = fmaf(sa[j * RA_D + tid], wgt, a);
+                l = fmaf(sl[j], wgt, l);
+            }
+        }
+    }
+}
+
+// Helper workgroup: Eq. 2 over W for NH query heads that share one KV head (heads head0 ..
+// head0 + NH - 1), each row of W read once; leaves one record per head and then its ready word.
+template <int DT, int NH>
+__device__ __forceinline__ void static_helper(unsigned char* lds_raw, const void* q, int head0, const char* Kh,
+                                              const char* Vh, int s, int64_t wstart, int64_t N, float scale,
+                                              float* rec, uint32_t* ready) {
+    const int tid = threadIdx.x, grp = tid >> 4, lane16 = tid & 15;
+    const size_t esz = DT == RA_BF16 ? 2 : 4;
+    constexpr int ROWS = DT == RA_BF16 ? 4 : 2;              // rows in flight per 16-lane group
+    LaneQuery<DT> ql[NH];
+    Softmax8 st[NH];
+#pragma unroll
+    for (int h = 0; h < NH; ++h) {
+        ql[h].load(reinterpret_cast<const char*>(q) + (size_t)(head0 + h) * RA_D * esz, lane16);
+        st[h].m = -INFINITY;
+        st[h].l = 0.f;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) st[h].acc[e] = 0.f;
+    }
+    const int R = s + (int)(N - wstart);
+    for (int r0 = 0; r0 < R; r0 += SR_NG * ROWS) {
+        bool live[ROWS];
+        RowBits<DT> kb[ROWS], vb[ROWS];
+#pragma unroll
+        for (int u = 0; u < ROWS; ++u) {
+            const int r = r0 + u * SR_NG + grp;
+            live[u] = r < R;
+            const int64_t id = !live[u] ? 0 : r < s ? (int64_t)r : wstart + (r - s);   // loads stay unconditional
+            kb[u] = load_key<DT>(Kh, id, lane16);
+            vb[u] = load_key<DT>(Vh, id, lane16);
+        }
+#pragma unroll
+        for (int u = 0; u < ROWS; ++u) {
+            if (!live[u]) continue;
+            float v[8];
+            row_floats<DT>(vb[u], v);
+#pragma unroll
+            for (int h = 0; h < NH; ++h) {
+                float dot = ql[h].dot(kb[u]);
+                dot += at_dpp<0xB1>(dot);
+                dot += at_dpp<0x4E>(dot);
+                dot += at_dpp<0x141>(dot);
+                dot += at_dpp<0x140>(dot);
+                sm_row<DT>(st[h], dot * scale, v);
+            }
+        }
+    }
+#pragma unroll
+    for (int h = 0; h < NH; ++h) {
+        float mx, l, a;
+        sm_combine(st[h], reinterpret_cast<float*>(lds_raw), tid, mx, l, a);
+        if (tid < RA_D) {
+            float* r = rec + (size_t)(head0 + h) * RA_COOP_REC;
+            if (tid == 0) {
+                xwg_store(r, mx);
+                xwg_store(r + 1, l);
+            }
+            xwg_store(r + 4 + tid, a);
+        }
+    }
+    __builtin_amdgcn_s_waitcnt(0x0F70);      // vmcnt(0): this wavefront's record stores have completed
+    __syncthreads();                          // ... and every other wavefront's
+    if (tid < NH) xwg_store(ready + head0 + tid, 1u);
+}
+
+// The head's wait for its helper, run while the search writes its result (see NoHook): one thread
+// of the second wavefront polls the ready word, a bounded number of times, and leaves in LDS
+// whether it came; if it did not, helpers are turned off for later launches.
+struct AwaitHelper {
+    const uint32_t* ready_word;
+    uint32_t* off_word;
+    uint32_t* lds_word;
+    int spin;
+    bool on;
+    __device__ __forceinline__ void before_output() const {
+        if (!on || threadIdx.x != RA_WAVE) return;
+        uint32_t f = 0u;
+        for (int i = 0; i < spin; ++i) {
+            f = xwg_load(ready_word);
+            if (f) break;
+            __builtin_amdgcn_s_sleep(32);
+        }
+        if (!f) xwg_store(off_word, 1u);
+        *lds_word = f;
+    }
+};
+
 template <int DT, bool GBITS>
 __global__ __launch_bounds__(SR_THREADS) void decode_kernel(
     const void* __restrict__ q, const int32_t* __restrict__ adj, const int32_t* __restrict__ entry,
@@ -109,28 +264,65 @@ __global__ __launch_bounds__(SR_THREADS) void decode_kernel(
     int64_t kv_stride, int64_t wstart, int deg, int s, int topk, int ef, int expand,
     uint32_t* __restrict__ gbits,
     int32_t* __restrict__ ids, ra_stats* __restrict__ stats, int ids_off, float scale,
-    float* __restrict__ out, float* __restrict__ lse) {
+    float* __restrict__ out, float* __restrict__ lse, float* coop, int n_helpers, int coop_mode,
+    int coop_spin) {
     extern __shared__ __align__(16) unsigned char lds_raw[];
     const int tid = threadIdx.x, grp = tid >> 4, lane16 = tid & 15;
-    const int lane = tid & (RA_WAVE - 1), wv = tid / RA_WAVE;
-    const int head = xcd_aware_head(blockIdx.x, gridDim.x, n_q / n_kv);
-    const int seq = head / n_q, h = head % n_q, kvh = h / (n_q / n_kv);
     const size_t esz = DT == RA_BF16 ? 2 : 4;
+    const int G = n_q / n_kv;
+    const int n_heads = (int)gridDim.x - n_helpers;
+    // hand-over area: records, ready words, "helpers off" word (set by a head whose wait ran out)
+    uint32_t* ready = reinterpret_cast<uint32_t*>(coop + (size_t)n_heads * RA_COOP_REC);
+    const bool helpers = n_helpers > 0 && xwg_load(ready + n_heads) == 0u;
+    if ((int)blockIdx.x < n_helpers) {
+        // ---- helper workgroup of (sequence, KV head) blockIdx.x: attention over W for its G heads
+        if (!helpers || coop_mode == RA_HELPERS_SILENT) return;
+        const int g = blockIdx.x;
+        const char* Kg = reinterpret_cast<const char*>(K) + (size_t)g * kv_stride * RA_D * esz;
+        const char* Vg = reinterpret_cast<const char*>(V) + (size_t)g * kv_stride * RA_D * esz;
+        // G is 1, 2, 4 or 8 when helpers are on; 4 heads per pass over W (2 for fp32: registers)
+        constexpr int PASS = DT == RA_BF16 ? 4 : 2;
+        for (int h0 = 0; h0 < G; h0 += PASS) {
+            const int head0 = g * G + h0;
+            if (G - h0 >= PASS) static_helper<DT, PASS>(lds_raw, q, head0, Kg, Vg, s, wstart, N, scale, coop, ready);
+            else if (G - h0 == 2) static_helper<DT, 2>(lds_raw, q, head0, Kg, Vg, s, wstart, N, scale, coop, ready);
+            else static_helper<DT, 1>(lds_raw, q, head0, Kg, Vg, s, wstart, N, scale, coop, ready);
+        }
+        return;
+    }
+    const int head = xcd_aware_head((int)blockIdx.x - n_helpers, n_heads, G);
+    const int seq = head / n_q, h = head % n_q, kvh = h / G;
     int32_t* lds_ids = reinterpret_cast<int32_t*>(lds_raw + ids_off);
+    uint32_t* lds_word = reinterpret_cast<uint32_t*>(lds_ids + topk);
     const char* Kh = reinterpret_cast<const char*>(K) + ((size_t)seq * n_kv + kvh) * kv_stride * RA_D * esz;
     const char* Vh = reinterpret_cast<const char*>(V) + ((size_t)seq * n_kv + kvh) * kv_stride * RA_D * esz;
     // The graph covers the first Ng of the N tokens now in the cache; W = [0, s) u [wstart, N) with
     // wstart <= Ng, so every token appended after the build is attended densely.
     const int cnt = run_search<DT, GBITS>(lds_raw, head, q, adj, entry, K, n_q, n_kv, Ng, kv_stride, deg,
                                           s, (int)(Ng - wstart), topk, ef, expand, gbits, ids, stats,
-                                          lds_ids);
+                                          lds_ids, AwaitHelper{ready + head, ready + n_heads, lds_word,
+                                                               coop_spin, helpers});
 #ifdef SR_PHASE_CLOCKS
     const long long t_attn = clock64();
 #endif
-    // ---- Eq. 2 over Omega (rows [0, cnt): ids in LDS) and W (rows [cnt, cnt + s + N - wstart))
-    const LaneQuery<DT> ql(reinterpret_cast<const char*>(q) + (size_t)head * RA_D * esz, lane16);
+    // ---- the helper's record for this head, if its ready word came (AwaitHelper)
+    bool have_w = false;
+    float mw = -INFINITY, lw = 0.f, aw = 0.f;
+    if (helpers) {
+        have_w = *lds_word != 0u;
+        if (have_w && tid < RA_D) {
+            const float* r = coop + (size_t)head * RA_COOP_REC;
+            mw = xwg_load(r);
+            lw = xwg_load(r + 1);
+            aw = xwg_load(r + 4 + tid);
+        }
+    }
+    // ---- Eq. 2 over Omega (rows [0, cnt): ids in LDS) and, without a record, W (rows
+    //      [cnt, cnt + s + N - wstart))
+    LaneQuery<DT> ql;
+    ql.load(reinterpret_cast<const char*>(q) + (size_t)head * RA_D * esz, lane16);
     constexpr int DC_ROWS = DT == RA_BF16 ? 6 : 3;       // rows in flight per 16-lane group
-    const int R = cnt + s + (int)(N - wstart);
+    const int R = cnt + (have_w ? 0 : s + (int)(N - wstart));
     Softmax8 st;
     st.m = -INFINITY;
     st.l = 0.f;
@@ -163,44 +355,22 @@ __global__ __launch_bounds__(SR_THREADS) void decode_kernel(
             sm_row<DT>(st, dot * scale, v);
         }
     }
-    // ---- combine the four groups of each wavefront by lane exchange
-#pragma unroll
-    for (int d = 16; d <= 32; d <<= 1) {
-        const float mo = __shfl_xor(st.m, d), lo = __shfl_xor(st.l, d);
-        float ao[8];
-#pragma unroll
-        for (int e = 0; e < 8; ++e) ao[e] = __shfl_xor(st.acc[e], d);
-        sm_merge(st, mo, lo, ao);
-    }
-    // ---- then the 16 wavefronts through LDS (the search state is dead; ids sit behind it)
-    float* sm = reinterpret_cast<float*>(lds_raw);          // [16]
-    float* sl = sm + SR_THREADS / RA_WAVE;                   // [16]
-    float* sa = sl + SR_THREADS / RA_WAVE;                   // [16][128]
-    if (lane < 16) {
-        if (lane == 0) {
-            sm[wv] = st.m;
-            sl[wv] = st.l;
-        }
-#pragma unroll
-        for (int e = 0; e < 8; ++e) sa[wv * RA_D + lane * 8 + e] = st.acc[e];
-    }
-    __syncthreads();
+    // ---- Eq. 4-5: the lane groups' partial results and the helper's record, re-scaled to one maximum
+    float mx, l, a;
+    sm_combine(st, reinterpret_cast<float*>(lds_raw), tid, mx, l, a);
     if (tid < RA_D) {
-        float mx = -INFINITY;
-#pragma unroll
-        for (int j = 0; j < SR_THREADS / RA_WAVE; ++j) mx = fmaxf(mx, sm[j]);
-        float a = 0.f, l = 0.f;
-        if (mx > -INFINITY) {
-#pragma unroll
-            for (int j = 0; j < SR_THREADS / RA_WAVE; ++j) {
-                const float wgt = expf(sm[j] - mx);
-                a = fmaf(sa[j * RA_D + tid], wgt, a);
-                l = fmaf(sl[j], wgt, l);
-            }
+        const float m2 = fmaxf(mx, mw);
+        if (m2 > -INFINITY) {
+            const float c1 = expf(mx - m2), c2 = expf(mw - m2);
+            a = a * c1 + aw * c2;
+            l = l * c1 + lw * c2;
         }
         const bool empty = !(l > 0.f);
         out[(size_t)head * RA_D + tid] = empty ? 0.f : a / l;
-        if (tid == 0) lse[head] = empty ? -INFINITY : mx + logf(l);
+        if (tid == 0) {
+            lse[head] = empty ? -INFINITY : m2 + logf(l);
+            if (have_w) xwg_store(ready + head, 0u);     // taken: the next launch starts from "not ready"
+        }
     }
 #ifdef SR_PHASE_CLOCKS
     if (tid == 0 && blockIdx.x < 64) sr_phase_ticks[blockIdx.x * SR_NITER * SR_NPHASE + 7] += clock64() - t_attn;
@@ -224,7 +394,7 @@ static size_t decode_lds_bytes(int64_t N, int deg, int ef, int expand, int topk,
     if (b > a) a = b;
     a = (a + 15) & ~(size_t)15;
     *ids_off = (int)a;
-    return a + (size_t)topk * sizeof(int32_t);
+    return a + (size_t)topk * sizeof(int32_t) + 16;        // ids, then a word for the ready flag
 }
 
 bool ra_decode_needs_global_bitset(int64_t N, int deg, int ef, int expand, int topk) {
@@ -242,8 +412,8 @@ __global__ void dc_fill_u32_kernel(uint32_t* p, size_t n, uint32_t v) {
 ra_status ra_launch_decode(const void* q, const int32_t* adj, const int32_t* entry, const void* K,
                            const void* V, ra_dtype dt, int n_seq, int n_q, int n_kv, int64_t Ng, int64_t N,
                            int64_t kv_stride, int deg, int sink, int window, int topk, int ef, int expand,
-                           uint32_t* bitset, hipStream_t st, float* out, float* lse, int32_t* ids,
-                           ra_stats* stats) {
+                           uint32_t* bitset, float* coop, int coop_mode, int coop_spin, hipStream_t st,
+                           float* out, float* lse, int32_t* ids, ra_stats* stats) {
     // W = [0, s) u [wstart, N): the sink, the sliding window, and every token appended after the
     // index was built (wstart <= Ng); overlapping ranges make everything static
     int64_t s = sink < 0 ? 0 : sink, ww = window < 0 ? 0 : window;
@@ -265,12 +435,18 @@ ra_status ra_launch_decode(const void* q, const int32_t* adj, const int32_t* ent
         hipLaunchKernelGGL(dc_fill_u32_kernel, dim3(1024), dim3(256), 0, st, bitset, words, 0u);
     }
     const float scale = 1.0f / sqrtf((float)RA_D);
+    // one helper workgroup per (sequence, KV head) in front of the heads' (GQA groups of 1, 2, 4 or 8)
+    const int G = n_q / n_kv;
+    const bool coop_on = coop && coop_mode != RA_HELPERS_OFF && (G == 1 || G == 2 || G == 4 || G == 8);
+    const int n_helpers = coop_on ? n_seq * n_kv : 0;
+    if (!coop) RA_FAIL(RA_EINVAL, "hand-over area missing");
 #define RA_DC_GO(DTV, GB)                                                                          \
     do {                                                                                           \
         RA_LDS_OPT_IN((decode_kernel<DTV, GB>), lds);                                              \
-        hipLaunchKernelGGL((decode_kernel<DTV, GB>), dim3(heads), dim3(SR_THREADS), lds, st, q,    \
-                           adj, entry, K, V, n_q, n_kv, Ng, N, kv_stride, wstart, deg, (int)s,     \
-                           topk, ef, expand, bitset, ids, stats, ids_off, scale, out, lse);        \
+        hipLaunchKernelGGL((decode_kernel<DTV, GB>), dim3(heads + n_helpers), dim3(SR_THREADS),    \
+                           lds, st, q, adj, entry, K, V, n_q, n_kv, Ng, N, kv_stride, wstart, deg, \
+                           (int)s, topk, ef, expand, bitset, ids, stats, ids_off, scale, out, lse, \
+                           coop, n_helpers, coop_mode, coop_spin);                                 \
     } while (0)
     if (dt == RA_BF16) {
         if (gb) RA_DC_GO(RA_BF16, true); else RA_DC_GO(RA_BF16, false);

@@ -9,7 +9,7 @@ __global__ __launch_bounds__(SR_THREADS) void search_kernel(
     ra_stats* __restrict__ stats) {
     extern __shared__ __align__(16) unsigned char lds_raw[];
     run_search<DT, GBITS>(lds_raw, xcd_aware_head(blockIdx.x, gridDim.x, n_q / n_kv), q, adj, entry, K, n_q, n_kv, N, N, deg, s, w, topk, ef,
-                          expand, gbits, ids, stats, nullptr);
+                          expand, gbits, ids, stats, nullptr, NoHook());
 }
 
 __global__ void fill_u32_kernel(uint32_t* p, size_t n, uint32_t v) {

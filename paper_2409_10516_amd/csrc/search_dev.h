@@ -202,12 +202,19 @@ __device__ __forceinline__ int xcd_aware_head(int block, int heads, int G) {
 // `lds_raw` is the workgroup's dynamic LDS (ra_search_lds_bytes of it). Writes ids/stats of
 // `head`; when `lds_ids` is not null the ids are also left there (LDS) for a fused consumer.
 // Returns the number of valid ids. Ends with the whole workgroup past a barrier.
-template <int DT, bool GBITS>
+// A caller's hook into run_search: before_output() is called by every thread when the walk has
+// ended, ahead of the phase in which the first wavefront writes the result (the others idle until
+// the closing barrier, which also publishes whatever the hook left in LDS).
+struct NoHook {
+    __device__ __forceinline__ void before_output() const {}
+};
+
+template <int DT, bool GBITS, typename Hook>
 __device__ __forceinline__ int run_search(
     unsigned char* lds_raw, int head, const void* __restrict__ q, const int32_t* __restrict__ adj,
     const int32_t* __restrict__ entry, const void* __restrict__ K, int n_q, int n_kv, int64_t N,
     int64_t kv_stride, int deg, int s, int w, int topk, int ef, int expand, uint32_t* __restrict__ gbits,
-    int32_t* __restrict__ ids, ra_stats* __restrict__ stats, int32_t* lds_ids) {
+    int32_t* __restrict__ ids, ra_stats* __restrict__ stats, int32_t* lds_ids, const Hook& hook) {
     const int tid = threadIdx.x, grp = tid >> 4, lane16 = tid & 15;
     const int lane = tid & (RA_WAVE - 1), wv = tid / RA_WAVE;
     const int seq = head / n_q, h = head % n_q, kvh = h / (n_q / n_kv);
@@ -448,6 +455,7 @@ __device__ __forceinline__ int run_search(
         picked = true;
     }
 
+    hook.before_output();
     // ---- result: best-first beam entries outside the static set W = [0,s) u [N-w,N)
     if (tid < RA_WAVE) {
         int32_t* out = ids + (size_t)head * topk;

@@ -116,6 +116,75 @@ def test_decode_step_end_to_end(name, expand):
                 assert out_close(out[s, h], r_out, tol) and lse_close(lse[s, h], r_lse, tol)
 
 
+@pytest.mark.parametrize("name", list(_cases()))
+def test_decode_step_helper_modes_agree_with_oracle(name):
+    """ra_index_configure: the attention over W by helper workgroups (default), by the heads
+    themselves (RA_HELPERS_OFF), and after a bounded wait that runs out (RA_HELPERS_SILENT with a
+    tiny spin limit: no helper ever reports, every head falls back and the handle stops using
+    helpers) all give the oracle's result; ids and counters stay bit-exact."""
+    from paper_2409_10516_amd import binding as B
+    w, adj, ent, idx, Kd, Vd = _prepared(name)
+    n_seq, n_kv, N, d = w.K.shape
+    n_q = w.Q_prefill.shape[1]
+    tol = tol_for(w.K.dtype)
+    q = w.q_decode[0].to(DEV)
+    ref = {}
+    for s in range(n_seq):
+        for h in range(n_q):
+            g = s * n_q + h
+            K = to_np(w.K[s, h // (n_q // n_kv)]); V = to_np(w.V[s, h // (n_q // n_kv)])
+            ref[s, h] = OD.decode_step(to_np(w.q_decode[0, s, h]), K, V, adj[g], ent[g], w.sink,
+                                       w.window, w.topk, w.ef, 8)
+
+    def check():
+        out, lse, ids, st = ra.ra_decode_step(q, idx, Kd, Vd, w.sink, w.window, w.topk, w.ef, 8)
+        out, lse, ids = out.cpu().numpy(), lse.cpu().numpy(), ids.cpu().numpy()
+        for (s, h), (r_out, r_lse, r_ids, _) in ref.items():
+            assert ids[s, h].tolist() == r_ids.tolist()
+            assert out_close(out[s, h], r_out, tol) and lse_close(lse[s, h], r_lse, tol)
+
+    try:
+        assert idx.helpers_active
+        check(); check()                      # twice: the ready words are cleared by their readers
+        assert idx.helpers_active
+        idx.configure(B.RA_CFG_HELPERS, B.RA_HELPERS_OFF)
+        assert not idx.helpers_active
+        check()
+        idx.configure(B.RA_CFG_HELPERS, B.RA_HELPERS_SILENT)
+        idx.configure(B.RA_CFG_HELPER_SPIN, 3)
+        check()                               # every head's wait runs out
+        idx.configure(B.RA_CFG_HELPERS, B.RA_HELPERS_ON)   # also forgets the wait that ran out
+        idx.configure(B.RA_CFG_HELPER_SPIN, 20000)
+        assert idx.helpers_active
+        check()
+    finally:
+        idx.configure(B.RA_CFG_HELPERS, B.RA_HELPERS_ON)
+        idx.configure(B.RA_CFG_HELPER_SPIN, 20000)
+
+
+def test_helpers_switch_off_after_a_wait_that_ran_out():
+    from paper_2409_10516_amd import binding as B
+    w, adj, ent, idx, Kd, Vd = _prepared(next(iter(_cases())))
+    q = w.q_decode[0].to(DEV)
+    try:
+        # mode ON with silent helpers cannot be had from outside; SILENT reports "not active", so
+        # look at the outputs instead: after the timed-out call the results must still be right
+        # with helpers nominally on, which they can only be if the heads no longer wait on them
+        a = ra.ra_decode_step(q, idx, Kd, Vd, w.sink, w.window, w.topk, w.ef, 8)
+        idx.configure(B.RA_CFG_HELPERS, B.RA_HELPERS_SILENT)
+        idx.configure(B.RA_CFG_HELPER_SPIN, 2)
+        b = ra.ra_decode_step(q, idx, Kd, Vd, w.sink, w.window, w.topk, w.ef, 8)
+        c = ra.ra_decode_step(q, idx, Kd, Vd, w.sink, w.window, w.topk, w.ef, 8)   # off word set: no waiting
+        tol = tol_for(w.K.dtype)
+        for x in (b, c):
+            assert torch.equal(x[2], a[2])
+            assert torch.allclose(x[0], a[0], rtol=0, atol=tol * float(a[0].abs().max()))
+            assert torch.allclose(x[1], a[1], rtol=tol, atol=tol)
+    finally:
+        idx.configure(B.RA_CFG_HELPERS, B.RA_HELPERS_ON)
+        idx.configure(B.RA_CFG_HELPER_SPIN, 20000)
+
+
 def test_exhaustive_beam_equals_bruteforce_and_full_attention():
     """ef >= N: the search returns the exact top-k; with topk covering every non-static key
     the decode output is Eq. 1 over the whole context."""
