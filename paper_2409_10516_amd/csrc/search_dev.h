@@ -259,6 +259,12 @@ __device__ __forceinline__ int run_search(
     }
     int bn = 1, n_visited = 1, n_expanded = 0, n_iters = 0;
     bool picked = false;             // the merge of the last step already chose this step's picks
+    // Adjacency rows likely to be expanded soon are touched ahead of time (one word of the row's
+    // first line), so that the row is in this XCD's L2 when its step reads it: the rows of the
+    // candidates a step keeps, touched while they are merged, and the rows of the beam entries that
+    // are next in line after the coming step's picks. The words land in early_a / early_b and only
+    // feed a test that never holds; they are consumed one phase later, when they have long arrived.
+    uint32_t early_a = 0u, early_b = 0u, early_acc = 0u;
     __syncthreads();
     SR_TICK(5);
 
@@ -336,6 +342,8 @@ __device__ __forceinline__ int run_search(
         n_visited += nc;
         SR_TICK(1);
         if (tid == 0) ctr[C_NUNEXP] = 0;     // everyone read it before the barrier above
+        early_acc ^= early_a ^ early_b;      // issued a phase or more ago
+        early_a = early_b = 0u;
 
         // ---- gather and score the new candidates; keep those that can enter the beam
         const u64 worst = bn == ef ? (cur[bn - 1] >> 1) : 0ull;
@@ -381,6 +389,10 @@ __device__ __forceinline__ int run_search(
             const int E = bn + nk;
             const int nch = (nk + 15) >> 4;
             const int items = nk * nch;
+#ifndef SR_NO_EARLY_TOUCH
+            if (tid < nk)
+                early_a = *reinterpret_cast<const uint32_t*>(adj_h + (size_t)key_id(ckey[tid]) * deg);
+#endif
             for (int c = tid; c < nk; c += SR_THREADS) {
                 const int b = count_better(cur, bn, ckey[c]);
                 if (b) atomicAdd(&cnt[c], b << 16);           // high half: beam entries above it
@@ -438,6 +450,11 @@ __device__ __forceinline__ int run_search(
                     picks[ur] = key_id(k);
                     k &= ~1ull;
                 }
+#ifndef SR_NO_EARLY_TOUCH
+                else if (beam && un && ur < 2 * expand) {         // next in line after those picks
+                    early_b = *reinterpret_cast<const uint32_t*>(adj_h + (size_t)key_id(k) * deg);
+                }
+#endif
                 if (pos < ef) {
                     nxt[pos] = k;
                     urank_nxt[pos] = (uint16_t)ur;
@@ -456,6 +473,8 @@ __device__ __forceinline__ int run_search(
     }
 
     hook.before_output();
+    early_acc ^= early_a ^ early_b;
+    if (early_acc == 0x9e3779b9u && N < 0) ids[(size_t)head * topk] = -1;    // never: keeps the early touches alive
     // ---- result: best-first beam entries outside the static set W = [0,s) u [N-w,N)
     if (tid < RA_WAVE) {
         int32_t* out = ids + (size_t)head * topk;
