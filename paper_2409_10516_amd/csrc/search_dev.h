@@ -22,11 +22,15 @@
 #pragma once
 #include "common.h"
 
+#ifndef SR_THREADS
 #define SR_THREADS 1024
+#endif
 #define SR_LDS_LIMIT (160 * 1024)     // LDS a workgroup can have on this part (above 64 KB: opt-in)
 #define SR_BITSET_LDS_MAX (64 * 1024) // a longer visited bitset lives in global memory
 #define RA_MAX_DEVICES 64
-#define SR_UNROLL 2               // key rows in flight per 16-lane group
+#ifndef SR_UNROLL
+#define SR_UNROLL 4               // key rows in flight per 16-lane group
+#endif
 
 #define SR_NG (SR_THREADS / 16)     // 16-lane groups per workgroup
 
@@ -172,7 +176,9 @@ __device__ __forceinline__ int count_above16_full(const u64* arr, u64 k) {
     return cnt;
 }
 
+#ifndef SR_TUNING_VARIANT
 static_assert(RA_MAX_EF <= SR_THREADS, "one beam entry per thread");
+#endif
 
 // number of the first min(n, 16) entries of arr that are larger than k; all 16 are read (the
 // caller's buffer has 16 entries of slack) so that the loads go out together.
