@@ -127,9 +127,11 @@ __device__ __forceinline__ uint32_t xwg_load(const uint32_t* p) {
     return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
 }
 
-// Combine the online-softmax states of a workgroup's 64 lane groups into one (max, sum, weighted
-// sum for output `tid`), valid in threads tid < 128: first the four groups of each wavefront by
-// lane exchange, then the 16 wavefronts through LDS (16 * 130 floats at `lds`). Two barriers.
+// Combine the online-softmax states of the lane groups of a workgroup of T threads into one (max,
+// sum, weighted sum for output `tid`), valid in threads tid < 128 (T >= 128): first the four
+// groups of each wavefront by lane exchange, then the T/64 wavefronts through LDS (T/64 * 130
+// floats at `lds`). Two barriers.
+template <int T>
 __device__ __forceinline__ void sm_combine(Softmax8 st, float* lds, int tid, float& mx, float& l, float& a) {
     const int lane = tid & (RA_WAVE - 1), wv = tid / RA_WAVE;
 #pragma unroll
@@ -141,8 +143,8 @@ __device__ __forceinline__ void sm_combine(Softmax8 st, float* lds, int tid, flo
         sm_merge(st, mo, lo, ao);
     }
     float* sm = lds;                                         // [16]
-    float* sl = sm + SR_THREADS / RA_WAVE;                   // [16]
-    float* sa = sl + SR_THREADS / RA_WAVE;                   // [16][128]
+    float* sl = sm + T / RA_WAVE;                   // [16]
+    float* sa = sl + T / RA_WAVE;                   // [16][128]
     __syncthreads();                                         // whatever was in `lds` is dead
     if (lane < 16) {
         if (lane == 0) {
@@ -158,10 +160,10 @@ __device__ __forceinline__ void sm_combine(Softmax8 st, float* lds, int tid, flo
     l = 0.f;
     if (tid < RA_D) {
 #pragma unroll
-        for (int j = 0; j < SR_THREADS / RA_WAVE; ++j) mx = fmaxf(mx, sm[j]);
+        for (int j = 0; j < T / RA_WAVE; ++j) mx = fmaxf(mx, sm[j]);
         if (mx > -INFINITY) {
 #pragma unroll
-            for (int j = 0; j < SR_THREADS / RA_WAVE; ++j) {
+            for (int j = 0; j < T / RA_WAVE; ++j) {
                 const float wgt = expf(sm[j] - mx);
                 a = fmaf(sa[j * RA_D + tid], wgt, a);
                 l = fmaf(sl[j], wgt, l);
@@ -172,7 +174,7 @@ __device__ __forceinline__ void sm_combine(Softmax8 st, float* lds, int tid, flo
 
 // Helper workgroup: Eq. 2 over W for NH query heads that share one KV head (heads head0 ..
 // head0 + NH - 1), each row of W read once; leaves one record per head and then its ready word.
-template <int DT, int NH>
+template <int DT, int NH, int T>
 __device__ __forceinline__ void static_helper(unsigned char* lds_raw, const void* q, int head0, const char* Kh,
                                               const char* Vh, int s, int64_t wstart, int64_t N, float scale,
                                               float* rec, uint32_t* ready) {
@@ -190,12 +192,12 @@ __device__ __forceinline__ void static_helper(unsigned char* lds_raw, const void
         for (int e = 0; e < 8; ++e) st[h].acc[e] = 0.f;
     }
     const int R = s + (int)(N - wstart);
-    for (int r0 = 0; r0 < R; r0 += SR_NG * ROWS) {
+    for (int r0 = 0; r0 < R; r0 += (T / 16) * ROWS) {
         bool live[ROWS];
         RowBits<DT> kb[ROWS], vb[ROWS];
 #pragma unroll
         for (int u = 0; u < ROWS; ++u) {
-            const int r = r0 + u * SR_NG + grp;
+            const int r = r0 + u * (T / 16) + grp;
             live[u] = r < R;
             const int64_t id = !live[u] ? 0 : r < s ? (int64_t)r : wstart + (r - s);   // loads stay unconditional
             kb[u] = load_key<DT>(Kh, id, lane16);
@@ -220,7 +222,7 @@ __device__ __forceinline__ void static_helper(unsigned char* lds_raw, const void
 #pragma unroll
     for (int h = 0; h < NH; ++h) {
         float mx, l, a;
-        sm_combine(st[h], reinterpret_cast<float*>(lds_raw), tid, mx, l, a);
+        sm_combine<T>(st[h], reinterpret_cast<float*>(lds_raw), tid, mx, l, a);
         if (tid < RA_D) {
             float* r = rec + (size_t)(head0 + h) * RA_COOP_REC;
             if (tid == 0) {
@@ -257,8 +259,8 @@ struct AwaitHelper {
     }
 };
 
-template <int DT, bool GBITS>
-__global__ __launch_bounds__(SR_THREADS) void decode_kernel(
+template <int DT, bool GBITS, int T>
+__global__ __launch_bounds__(T) void decode_kernel(
     const void* __restrict__ q, const int32_t* __restrict__ adj, const int32_t* __restrict__ entry,
     const void* __restrict__ K, const void* __restrict__ V, int n_q, int n_kv, int64_t Ng, int64_t N,
     int64_t kv_stride, int64_t wstart, int deg, int s, int topk, int ef, int expand,
@@ -284,9 +286,9 @@ __global__ __launch_bounds__(SR_THREADS) void decode_kernel(
         constexpr int PASS = DT == RA_BF16 ? 4 : 2;
         for (int h0 = 0; h0 < G; h0 += PASS) {
             const int head0 = g * G + h0;
-            if (G - h0 >= PASS) static_helper<DT, PASS>(lds_raw, q, head0, Kg, Vg, s, wstart, N, scale, coop, ready);
-            else if (G - h0 == 2) static_helper<DT, 2>(lds_raw, q, head0, Kg, Vg, s, wstart, N, scale, coop, ready);
-            else static_helper<DT, 1>(lds_raw, q, head0, Kg, Vg, s, wstart, N, scale, coop, ready);
+            if (G - h0 >= PASS) static_helper<DT, PASS, T>(lds_raw, q, head0, Kg, Vg, s, wstart, N, scale, coop, ready);
+            else if (G - h0 == 2) static_helper<DT, 2, T>(lds_raw, q, head0, Kg, Vg, s, wstart, N, scale, coop, ready);
+            else static_helper<DT, 1, T>(lds_raw, q, head0, Kg, Vg, s, wstart, N, scale, coop, ready);
         }
         return;
     }
@@ -298,7 +300,7 @@ __global__ __launch_bounds__(SR_THREADS) void decode_kernel(
     const char* Vh = reinterpret_cast<const char*>(V) + ((size_t)seq * n_kv + kvh) * kv_stride * RA_D * esz;
     // The graph covers the first Ng of the N tokens now in the cache; W = [0, s) u [wstart, N) with
     // wstart <= Ng, so every token appended after the build is attended densely.
-    const int cnt = run_search<DT, GBITS>(lds_raw, head, q, adj, entry, K, n_q, n_kv, Ng, kv_stride, deg,
+    const int cnt = run_search<DT, GBITS, T>(lds_raw, head, q, adj, entry, K, n_q, n_kv, Ng, kv_stride, deg,
                                           s, (int)(Ng - wstart), topk, ef, expand, gbits, ids, stats,
                                           lds_ids, AwaitHelper{ready + head, ready + n_heads, lds_word,
                                                                coop_spin, helpers});
@@ -328,12 +330,12 @@ __global__ __launch_bounds__(SR_THREADS) void decode_kernel(
     st.l = 0.f;
 #pragma unroll
     for (int e = 0; e < 8; ++e) st.acc[e] = 0.f;
-    for (int r0 = 0; r0 < R; r0 += SR_NG * DC_ROWS) {
+    for (int r0 = 0; r0 < R; r0 += (T / 16) * DC_ROWS) {
         int64_t rid[DC_ROWS];
         RowBits<DT> kb[DC_ROWS], vb[DC_ROWS];
 #pragma unroll
         for (int u = 0; u < DC_ROWS; ++u) {
-            const int r = r0 + u * SR_NG + grp;
+            const int r = r0 + u * (T / 16) + grp;
             int64_t id = -1;
             if (r < cnt) id = lds_ids[r];
             else if (r < R) id = r - cnt < s ? (int64_t)(r - cnt) : wstart + (r - cnt - s);
@@ -357,7 +359,7 @@ __global__ __launch_bounds__(SR_THREADS) void decode_kernel(
     }
     // ---- Eq. 4-5: the lane groups' partial results and the helper's record, re-scaled to one maximum
     float mx, l, a;
-    sm_combine(st, reinterpret_cast<float*>(lds_raw), tid, mx, l, a);
+    sm_combine<T>(st, reinterpret_cast<float*>(lds_raw), tid, mx, l, a);
     if (tid < RA_D) {
         const float m2 = fmaxf(mx, mw);
         if (m2 > -INFINITY) {
@@ -440,19 +442,27 @@ ra_status ra_launch_decode(const void* q, const int32_t* adj, const int32_t* ent
     const bool coop_on = coop && coop_mode != RA_HELPERS_OFF && (G == 1 || G == 2 || G == 4 || G == 8);
     const int n_helpers = coop_on ? n_seq * n_kv : 0;
     if (!coop) RA_FAIL(RA_EINVAL, "hand-over area missing");
-#define RA_DC_GO(DTV, GB)                                                                          \
+    const int threads = search_threads(heads, ef);
+#define RA_DC_GO_T(DTV, GB, TV)                                                                    \
     do {                                                                                           \
-        RA_LDS_OPT_IN((decode_kernel<DTV, GB>), lds);                                              \
-        hipLaunchKernelGGL((decode_kernel<DTV, GB>), dim3(heads + n_helpers), dim3(SR_THREADS),    \
-                           lds, st, q, adj, entry, K, V, n_q, n_kv, Ng, N, kv_stride, wstart, deg, \
+        RA_LDS_OPT_IN((decode_kernel<DTV, GB, TV>), lds);                                          \
+        hipLaunchKernelGGL((decode_kernel<DTV, GB, TV>), dim3(heads + n_helpers), dim3(TV), lds,   \
+                           st, q, adj, entry, K, V, n_q, n_kv, Ng, N, kv_stride, wstart, deg,      \
                            (int)s, topk, ef, expand, bitset, ids, stats, ids_off, scale, out, lse, \
                            coop, n_helpers, coop_mode, coop_spin);                                 \
+    } while (0)
+#define RA_DC_GO(DTV, GB)                                                                          \
+    do {                                                                                           \
+        if (threads == 1024) RA_DC_GO_T(DTV, GB, 1024);                                            \
+        else if (threads == 512) RA_DC_GO_T(DTV, GB, 512);                                         \
+        else RA_DC_GO_T(DTV, GB, 256);                                                             \
     } while (0)
     if (dt == RA_BF16) {
         if (gb) RA_DC_GO(RA_BF16, true); else RA_DC_GO(RA_BF16, false);
     } else {
         if (gb) RA_DC_GO(RA_F32, true); else RA_DC_GO(RA_F32, false);
     }
+#undef RA_DC_GO_T
 #undef RA_DC_GO
     RA_HIP(hipGetLastError());
     return RA_OK;

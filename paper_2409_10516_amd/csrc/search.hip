@@ -1,14 +1,14 @@
 // Stand-alone launch of the graph search (ra_search); the search itself is in search_dev.h.
 #include "search_dev.h"
 
-template <int DT, bool GBITS>
-__global__ __launch_bounds__(SR_THREADS) void search_kernel(
+template <int DT, bool GBITS, int T>
+__global__ __launch_bounds__(T) void search_kernel(
     const void* __restrict__ q, const int32_t* __restrict__ adj, const int32_t* __restrict__ entry,
     const void* __restrict__ K, int n_q, int n_kv, int64_t N, int deg, int s, int w, int topk,
     int ef, int expand, uint32_t* __restrict__ gbits, int32_t* __restrict__ ids,
     ra_stats* __restrict__ stats) {
     extern __shared__ __align__(16) unsigned char lds_raw[];
-    run_search<DT, GBITS>(lds_raw, xcd_aware_head(blockIdx.x, gridDim.x, n_q / n_kv), q, adj, entry, K, n_q, n_kv, N, N, deg, s, w, topk, ef,
+    run_search<DT, GBITS, T>(lds_raw, xcd_aware_head(blockIdx.x, gridDim.x, n_q / n_kv), q, adj, entry, K, n_q, n_kv, N, N, deg, s, w, topk, ef,
                           expand, gbits, ids, stats, nullptr, NoHook());
 }
 
@@ -46,18 +46,26 @@ ra_status ra_launch_search(const void* q, const int32_t* adj, const int32_t* ent
         const size_t words = (size_t)heads * ((N + 31) >> 5);
         hipLaunchKernelGGL(fill_u32_kernel, dim3(1024), dim3(256), 0, st, bitset, words, 0u);
     }
+    const int threads = search_threads(heads, ef);
+#define RA_SR_LAUNCH_T(DTV, GB, TV)                                                               \
+    do {                                                                                          \
+        RA_LDS_OPT_IN((search_kernel<DTV, GB, TV>), lds);                                         \
+        hipLaunchKernelGGL((search_kernel<DTV, GB, TV>), dim3(heads), dim3(TV), lds, st, q, adj,  \
+                           entry, K, n_q, n_kv, N, deg, (int)ss, (int)ww, topk, ef, expand,       \
+                           bitset, ids, stats);                                                   \
+    } while (0)
 #define RA_SR_LAUNCH(DTV, GB)                                                                     \
     do {                                                                                          \
-        RA_LDS_OPT_IN((search_kernel<DTV, GB>), lds);                                             \
-        hipLaunchKernelGGL((search_kernel<DTV, GB>), dim3(heads), dim3(SR_THREADS), lds, st, q,   \
-                           adj, entry, K, n_q, n_kv, N, deg, (int)ss, (int)ww, topk, ef, expand,  \
-                           bitset, ids, stats);                                                   \
+        if (threads == 1024) RA_SR_LAUNCH_T(DTV, GB, 1024);                                       \
+        else if (threads == 512) RA_SR_LAUNCH_T(DTV, GB, 512);                                    \
+        else RA_SR_LAUNCH_T(DTV, GB, 256);                                                        \
     } while (0)
     if (dt == RA_BF16) {
         if (gb) RA_SR_LAUNCH(RA_BF16, true); else RA_SR_LAUNCH(RA_BF16, false);
     } else {
         if (gb) RA_SR_LAUNCH(RA_F32, true); else RA_SR_LAUNCH(RA_F32, false);
     }
+#undef RA_SR_LAUNCH_T
 #undef RA_SR_LAUNCH
     RA_HIP(hipGetLastError());
     return RA_OK;

@@ -22,9 +22,7 @@
 #pragma once
 #include "common.h"
 
-#ifndef SR_THREADS
-#define SR_THREADS 1024
-#endif
+#define SR_THREADS 1024          // largest workgroup; the kernels are also built for 512 and 256 threads
 #define SR_LDS_LIMIT (160 * 1024)     // LDS a workgroup can have on this part (above 64 KB: opt-in)
 #define SR_BITSET_LDS_MAX (64 * 1024) // a longer visited bitset lives in global memory
 #define RA_MAX_DEVICES 64
@@ -32,7 +30,6 @@
 #define SR_UNROLL 4               // key rows in flight per 16-lane group
 #endif
 
-#define SR_NG (SR_THREADS / 16)     // 16-lane groups per workgroup
 
 enum { C_NCAND = 1, C_NKEEP = 2, C_NUNEXP = 3, C_WTOT = 8, C_COUNT = 8 + SR_THREADS / RA_WAVE };
 
@@ -176,9 +173,7 @@ __device__ __forceinline__ int count_above16_full(const u64* arr, u64 k) {
     return cnt;
 }
 
-#ifndef SR_TUNING_VARIANT
 static_assert(RA_MAX_EF <= SR_THREADS, "one beam entry per thread");
-#endif
 
 // number of the first min(n, 16) entries of arr that are larger than k; all 16 are read (the
 // caller's buffer has 16 entries of slack) so that the loads go out together.
@@ -202,7 +197,8 @@ __device__ __forceinline__ int xcd_aware_head(int block, int heads, int G) {
     return (block % n_groups) * G + block / n_groups;
 }
 
-// The whole search of one (sequence, query head) by one workgroup of SR_THREADS threads.
+// The whole search of one (sequence, query head) by one workgroup of T threads (T >= ef: the
+// beam has at most one entry per thread).
 // N is the number of keys the graph covers; the key rows of a (sequence, KV head) start every
 // kv_stride rows (kv_stride >= N: the cache may hold tokens appended after the index was built).
 // `lds_raw` is the workgroup's dynamic LDS (ra_search_lds_bytes of it). Writes ids/stats of
@@ -215,7 +211,7 @@ struct NoHook {
     __device__ __forceinline__ void before_output() const {}
 };
 
-template <int DT, bool GBITS, typename Hook>
+template <int DT, bool GBITS, int T, typename Hook>
 __device__ __forceinline__ int run_search(
     unsigned char* lds_raw, int head, const void* __restrict__ q, const int32_t* __restrict__ adj,
     const int32_t* __restrict__ entry, const void* __restrict__ K, int n_q, int n_kv, int64_t N,
@@ -249,8 +245,8 @@ __device__ __forceinline__ int run_search(
                            : reinterpret_cast<uint32_t*>(urank_nxt + ef + 1);
 
     if (!GBITS)
-        for (int i = tid; i < nwords; i += SR_THREADS) bits[i] = 0u;
-    for (int i = tid; i < maxc + 2 * ef + 2; i += SR_THREADS) cnt[i] = 0;      // cnt, hist, hist_nxt
+        for (int i = tid; i < nwords; i += T) bits[i] = 0u;
+    for (int i = tid; i < maxc + 2 * ef + 2; i += T) cnt[i] = 0;      // cnt, hist, hist_nxt
     float qv[8];
     load_q8<DT>(reinterpret_cast<const char*>(q) + (size_t)head * RA_D * esz, lane16, qv);
     const int e0 = entry[head];
@@ -292,7 +288,7 @@ __device__ __forceinline__ int run_search(
             }
             __syncthreads();
             int before = 0, total = 0;
-            for (int x = 0; x < SR_THREADS / RA_WAVE; ++x) {
+            for (int x = 0; x < T / RA_WAVE; ++x) {
                 const int c = wtot[x];
                 if (x < wv) before += c;
                 total += c;
@@ -321,13 +317,13 @@ __device__ __forceinline__ int run_search(
         //      claim unvisited neighbours
         {
             const int cells = np * deg;
-            for (int x0 = 0; x0 < cells; x0 += SR_THREADS * 2) {
+            for (int x0 = 0; x0 < cells; x0 += T * 2) {
                 int nbv[2];
 #pragma unroll
                 for (int u = 0; u < 2; ++u) {
                     // out-of-range slots re-read the last cell: loads without a branch around
                     // them can all be issued before the first one is consumed
-                    const int x = x0 + u * SR_THREADS + tid;
+                    const int x = x0 + u * T + tid;
                     const int xc = x < cells ? x : cells - 1;
                     const int v = adj_h[(size_t)picks[xc / deg] * deg + (xc % deg)];
                     nbv[u] = x < cells ? v : -1;
@@ -353,20 +349,20 @@ __device__ __forceinline__ int run_search(
 
         // ---- gather and score the new candidates; keep those that can enter the beam
         const u64 worst = bn == ef ? (cur[bn - 1] >> 1) : 0ull;
-        for (int c0 = 0; c0 < nc; c0 += SR_NG * SR_UNROLL) {
+        for (int c0 = 0; c0 < nc; c0 += (T / 16) * SR_UNROLL) {
             RowBits<DT> rows[SR_UNROLL];
             int cidv[SR_UNROLL];
 #pragma unroll
             for (int u = 0; u < SR_UNROLL; ++u) {
-                if (c0 + u * SR_NG >= nc) break;          // uniform over the workgroup
-                const int c = c0 + u * SR_NG + grp;
+                if (c0 + u * (T / 16) >= nc) break;          // uniform over the workgroup
+                const int c = c0 + u * (T / 16) + grp;
                 cidv[u] = c < nc ? cid[c] : -1;
                 // groups without a candidate re-read the entry row instead of branching
                 rows[u] = load_key<DT>(Kh, cidv[u] >= 0 ? cidv[u] : e0, lane16);
             }
 #pragma unroll
             for (int u = 0; u < SR_UNROLL; ++u) {
-                if (c0 + u * SR_NG >= nc) break;
+                if (c0 + u * (T / 16) >= nc) break;
                 const float sc = score_fixed<DT>(rows[u], qv);
                 if (lane16 == 0 && cidv[u] >= 0) {
                     const u64 key = make_key(sc, cidv[u]);
@@ -399,14 +395,14 @@ __device__ __forceinline__ int run_search(
             if (tid < nk)
                 early_a = *reinterpret_cast<const uint32_t*>(adj_h + (size_t)key_id(ckey[tid]) * deg);
 #endif
-            for (int c = tid; c < nk; c += SR_THREADS) {
+            for (int c = tid; c < nk; c += T) {
                 const int b = count_better(cur, bn, ckey[c]);
                 if (b) atomicAdd(&cnt[c], b << 16);           // high half: beam entries above it
                 atomicAdd(&hist[b], 1);
             }
             SR_TICK(8);
             const float inv_nk = 1.0f / (float)nk;
-            for (int a = tid; a < items; a += SR_THREADS) {
+            for (int a = tid; a < items; a += T) {
                 // a = ch * nk + c without an integer division: the float quotient is off by at most one
                 int ch = (int)((float)a * inv_nk), c = a - ch * nk;
                 if (c < 0) { --ch; c += nk; }
@@ -431,9 +427,9 @@ __device__ __forceinline__ int run_search(
                 before = __builtin_amdgcn_readlane(wave_incl_scan(before), RA_WAVE - 1);
                 cbeam = before + wave_incl_scan(tid < bn ? hist[tid] : 0);
             }
-            for (int i = tid; i <= ef; i += SR_THREADS) hist_nxt[i] = 0;
+            for (int i = tid; i <= ef; i += T) hist_nxt[i] = 0;
             SR_TICK(10);
-            for (int e = tid; e < E; e += SR_THREADS) {
+            for (int e = tid; e < E; e += T) {
                 const bool beam = e < bn;                         // only with e == tid
                 u64 k;
                 int c, b;                                         // candidates / beam entries above
@@ -530,6 +526,15 @@ __device__ __forceinline__ int run_search(
             granted_[dev_] = SR_LDS_LIMIT;                                                         \
         }                                                                                          \
     } while (0)
+
+// Threads per search. One search per compute unit or fewer (the latency-bound case): the largest
+// workgroup finishes a search soonest. More searches than compute units: smaller workgroups, so
+// that several searches share a compute unit and one's trips to HBM hide behind another's work
+// (measured at 512 searches of 32K keys: 111 us per launch with 1024 threads, 74 with 512, 68 with 256).
+static inline int search_threads(int heads, int ef) {
+    if (heads <= 256 || ef > 512) return 1024;
+    return ef > 256 ? 512 : 256;
+}
 
 // LDS bytes run_search needs.
 static inline size_t search_lds_bytes(int64_t N, int deg, int ef, int expand, bool global_bitset) {

@@ -185,6 +185,38 @@ def test_helpers_switch_off_after_a_wait_that_ran_out():
         idx.configure(B.RA_CFG_HELPER_SPIN, 20000)
 
 
+@pytest.mark.parametrize("ef,topk", [(48, 16), (300, 40)])
+def test_many_searches_use_smaller_workgroups(ef, topk):
+    """More searches than compute units: the launch switches to 256-thread (ef <= 256) or
+    512-thread workgroups. Ids and counters must not depend on that; attention within tolerance."""
+    w = synth.make_llama_layer(21, N=640, M=192, T=1, n_seq=40, n_q=8, n_kv=2, ef=ef, topk=topk,
+                               window=50, deg=16, knn=12)
+    adj, ent, _ = oracle_graphs(w)
+    n_seq, n_kv, N, d = w.K.shape
+    n_q = w.Q_prefill.shape[1]
+    assert n_seq * n_q > 256
+    idx = ra.ra_index_import(torch.from_numpy(adj), torch.from_numpy(ent), n_seq, n_q, n_kv)
+    Kd, Vd = w.K.to(DEV), w.V.to(DEV)
+    q = w.q_decode[0].to(DEV)
+    tol = tol_for(w.K.dtype)
+    W = OA.static_ids(N, w.sink, w.window)
+    ids_s, st_s = ra.ra_search(q, idx, Kd, w.sink, w.window, topk, ef, 8)
+    out, lse, ids, st = ra.ra_decode_step(q, idx, Kd, Vd, w.sink, w.window, topk, ef, 8)
+    ids_s, st_s, ids, st = ids_s.cpu().numpy(), st_s.cpu().numpy(), ids.cpu().numpy(), st.cpu().numpy()
+    out, lse = out.cpu().numpy(), lse.cpu().numpy()
+    for s in range(n_seq):
+        for h in range(n_q):
+            g = s * n_q + h
+            K = to_np(w.K[s, h // (n_q // n_kv)]); V = to_np(w.V[s, h // (n_q // n_kv)])
+            r_out, r_lse, r_ids, rst = OD.decode_step(to_np(w.q_decode[0, s, h]), K, V, adj[g], ent[g],
+                                                      w.sink, w.window, topk, ef, 8)
+            want = [rst["n_visited"], rst["n_expanded"], rst["n_iters"], rst["n_returned"]]
+            assert ids_s[s, h].tolist() == r_ids.tolist() and st_s[s, h].tolist() == want, (s, h)
+            assert ids[s, h].tolist() == r_ids.tolist() and st[s, h].tolist() == want, (s, h)
+            assert out_close(out[s, h], r_out, tol) and lse_close(lse[s, h], r_lse, tol), (s, h)
+    idx.free()
+
+
 def test_exhaustive_beam_equals_bruteforce_and_full_attention():
     """ef >= N: the search returns the exact top-k; with topk covering every non-static key
     the decode output is Eq. 1 over the whole context."""
