@@ -37,6 +37,7 @@ def parse():
                    choices=["config2", "config1", "config3", "config0"])
     p.add_argument("--layers", type=int, default=None, help="override the layer count (debug)")
     p.add_argument("--context", type=int, default=None, help="override N (debug)")
+    p.add_argument("--seqs", type=int, default=None, help="config3: number of sequences (default 16)")
     p.add_argument("--expand", type=int, default=64, help="search expansion width")
     p.add_argument("--tokens", type=int, default=8, help="distinct decode queries per head")
     p.add_argument("--recall-layers", type=int, default=2)
@@ -78,8 +79,8 @@ def main():
         n_layers, N, n_seq = 1, 32768, 1
         mk = lambda l: synth.make_config1(device=dev, N=N, T=a.tokens)
     elif a.workload == "config3":
-        n_layers, N, n_seq = 1, 32768, 16
-        mk = lambda l: synth.make_config3(device=dev, N=N, T=a.tokens)
+        n_layers, N, n_seq = 1, 32768, a.seqs or 16
+        mk = lambda l: synth.make_config3(device=dev, N=N, T=a.tokens, n_seq=n_seq)
     else:
         n_layers, N, n_seq = 1, 4096, 1
         mk = lambda l: synth.make_config0(device=dev)

@@ -58,9 +58,9 @@ typedef struct {
 /* Limits of this build (checked, RA_EUNSUP beyond them). */
 #define RA_MAX_DEG 64
 #define RA_MAX_KNN 64
-#define RA_MAX_EF 1024
+#define RA_MAX_EF 2048
 #define RA_MAX_EXPAND 64
-#define RA_MAX_TOPK 1024
+#define RA_MAX_TOPK 2048
 
 /* ---- index build (Sec. 3.2) -------------------------------------------------------- */
 

@@ -173,7 +173,7 @@ __device__ __forceinline__ int count_above16_full(const u64* arr, u64 k) {
     return cnt;
 }
 
-static_assert(RA_MAX_EF <= SR_THREADS, "one beam entry per thread");
+static_assert(RA_MAX_EF + RA_MAX_EXPAND * RA_MAX_DEG < 65536, "ranks and merge counts are kept in 16 bits");
 
 // number of the first min(n, 16) entries of arr that are larger than k; all 16 are read (the
 // caller's buffer has 16 entries of slack) so that the loads go out together.
@@ -197,8 +197,7 @@ __device__ __forceinline__ int xcd_aware_head(int block, int heads, int G) {
     return (block % n_groups) * G + block / n_groups;
 }
 
-// The whole search of one (sequence, query head) by one workgroup of T threads (T >= ef: the
-// beam has at most one entry per thread).
+// The whole search of one (sequence, query head) by one workgroup of T threads.
 // N is the number of keys the graph covers; the key rows of a (sequence, KV head) start every
 // kv_stride rows (kv_stride >= N: the cache may hold tokens appended after the index was built).
 // `lds_raw` is the workgroup's dynamic LDS (ra_search_lds_bytes of it). Writes ids/stats of
@@ -274,34 +273,40 @@ __device__ __forceinline__ int run_search(
         SR_TICK_ITER(n_iters);
         int np;
         if (!picked) {
-            // ---- pick the `expand` best unexpanded entries: the beam is sorted and has at most
-            //      one entry per thread, so the picks are the first `expand` set flags in thread
-            //      order (ballot prefix inside a wavefront, wavefront totals through LDS)
-            const u64 mykey = tid < bn ? cur[tid] : 0ull;
-            const bool un = (mykey & 1ull) != 0;
-            const u64 unmask = __ballot(un);
-            if (lane == 0) wtot[wv] = __popcll(unmask);
-            if (tid == 0) {
-                ctr[C_NCAND] = 0;
-                ctr[C_NKEEP] = 0;
-                ctr[C_NUNEXP] = 0;
-            }
-            __syncthreads();
-            int before = 0, total = 0;
-            for (int x = 0; x < T / RA_WAVE; ++x) {
-                const int c = wtot[x];
-                if (x < wv) before += c;
-                total += c;
+            // ---- pick the `expand` best unexpanded entries: the beam is sorted, so the picks are
+            //      the first `expand` set flags in beam order. T entries per round, one per
+            //      thread: ballot prefix inside a wavefront, wavefront totals through LDS, the
+            //      rounds before it carried in `total`. The round loop also covers index bn, one
+            //      past the end, whose rank is the number of unexpanded entries in all.
+            int total = 0;
+            for (int e0 = 0; e0 <= bn; e0 += T) {
+                const int e = e0 + tid;
+                const u64 mykey = e < bn ? cur[e] : 0ull;
+                const bool un = (mykey & 1ull) != 0;
+                const u64 unmask = __ballot(un);
+                if (lane == 0) wtot[wv] = __popcll(unmask);
+                if (tid == 0) {
+                    ctr[C_NCAND] = 0;
+                    ctr[C_NKEEP] = 0;
+                    ctr[C_NUNEXP] = 0;
+                }
+                __syncthreads();
+                int before = total;
+                for (int x = 0; x < T / RA_WAVE; ++x) {
+                    const int c = wtot[x];
+                    if (x < wv) before += c;
+                    total += c;
+                }
+                const int rank = before + __popcll(unmask & ((1ull << lane) - 1ull));
+                if (e <= bn) urank[e] = (uint16_t)rank;
+                if (un && rank < expand) {
+                    picks[rank] = key_id(mykey);
+                    cur[e] = mykey & ~1ull;
+                }
+                __syncthreads();
             }
             np = total < expand ? total : expand;
             if (np == 0) break;
-            const int rank = before + __popcll(unmask & ((1ull << lane) - 1ull));
-            if (tid <= bn) urank[tid] = (uint16_t)rank;
-            if (un && rank < expand) {
-                picks[rank] = key_id(mykey);
-                cur[tid] = mykey & ~1ull;
-            }
-            __syncthreads();
         } else {
             // the merge left the picks in place and counted the unexpanded entries
             const int total = ctr[C_NUNEXP];
@@ -418,48 +423,52 @@ __device__ __forceinline__ int run_search(
                 ctr[C_NCAND] = 0;
                 ctr[C_NKEEP] = 0;
             }
-            // candidates above beam entry `tid`: inclusive prefix sum of hist, by wavefront, each
-            // adding up the part of hist before its own 64 entries itself (no second barrier)
-            int cbeam = 0;
-            if (wv * RA_WAVE < bn) {
-                int before = 0;
-                for (int x = 0; x < wv; ++x) before += hist[x * RA_WAVE + lane];
-                before = __builtin_amdgcn_readlane(wave_incl_scan(before), RA_WAVE - 1);
-                cbeam = before + wave_incl_scan(tid < bn ? hist[tid] : 0);
-            }
             for (int i = tid; i <= ef; i += T) hist_nxt[i] = 0;
             SR_TICK(10);
-            for (int e = tid; e < E; e += T) {
-                const bool beam = e < bn;                         // only with e == tid
-                u64 k;
-                int c, b;                                         // candidates / beam entries above
-                if (beam) {
-                    k = cur[e];
-                    c = cbeam;
-                    b = e;
-                } else {
-                    const int both = cnt[e - bn];
-                    cnt[e - bn] = 0;
-                    k = ckey[e - bn];
-                    c = both & 0xffff;
-                    b = both >> 16;
+            for (int e0 = 0; e0 < E; e0 += T) {                   // T elements per round
+                const int e = e0 + tid;
+                // candidates above beam entry e: inclusive prefix sum of hist, by wavefront, each
+                // adding up the part of hist before its own 64 entries itself (no second barrier)
+                int cbeam = 0;
+                if (e0 + wv * RA_WAVE < bn) {                     // this wavefront has beam entries
+                    int before = 0;
+                    for (int x = 0; x < e0 / RA_WAVE + wv; ++x) before += hist[x * RA_WAVE + lane];
+                    before = __builtin_amdgcn_readlane(wave_incl_scan(before), RA_WAVE - 1);
+                    cbeam = before + wave_incl_scan(e < bn ? hist[e] : 0);
                 }
-                const int pos = b + c;
-                const int ub = (int)urank[b] - np;                // this step's picks are expanded now
-                const int ur = c + (ub > 0 ? ub : 0);             // unexpanded elements above this one
-                const bool un = pos < ef && (k & 1ull);
-                if (un && ur < expand) {
-                    picks[ur] = key_id(k);
-                    k &= ~1ull;
-                }
+                bool un = false;
+                if (e < E) {
+                    const bool beam = e < bn;
+                    u64 k;
+                    int c, b;                                     // candidates / beam entries above
+                    if (beam) {
+                        k = cur[e];
+                        c = cbeam;
+                        b = e;
+                    } else {
+                        const int both = cnt[e - bn];
+                        cnt[e - bn] = 0;
+                        k = ckey[e - bn];
+                        c = both & 0xffff;
+                        b = both >> 16;
+                    }
+                    const int pos = b + c;
+                    const int ub = (int)urank[b] - np;            // this step's picks are expanded now
+                    const int ur = c + (ub > 0 ? ub : 0);         // unexpanded elements above this one
+                    un = pos < ef && (k & 1ull);
+                    if (un && ur < expand) {
+                        picks[ur] = key_id(k);
+                        k &= ~1ull;
+                    }
 #ifndef SR_NO_EARLY_TOUCH
-                else if (beam && un && ur < 2 * expand) {         // next in line after those picks
-                    early_b = *reinterpret_cast<const uint32_t*>(adj_h + (size_t)key_id(k) * deg);
-                }
+                    else if (beam && un && ur < 2 * expand) {     // next in line after those picks
+                        early_b = *reinterpret_cast<const uint32_t*>(adj_h + (size_t)key_id(k) * deg);
+                    }
 #endif
-                if (pos < ef) {
-                    nxt[pos] = k;
-                    urank_nxt[pos] = (uint16_t)ur;
+                    if (pos < ef) {
+                        nxt[pos] = k;
+                        urank_nxt[pos] = (uint16_t)ur;
+                    }
                 }
                 const u64 um = __ballot(un);
                 if (lane == 0 && um) atomicAdd(&ctr[C_NUNEXP], __popcll(um));

@@ -63,7 +63,7 @@ def test_flat_topk_all_scores_equal_takes_lowest_ids(N):
     assert ids.tolist() == list(range(2, 52))
 
 
-@pytest.mark.parametrize("topk", [1, 100, 1024])
+@pytest.mark.parametrize("topk", [1, 100, 1024, 2048])
 def test_flat_topk_sampled_threshold_path(topk):
     """Contexts of 32K keys and more place the selection threshold from a sample."""
     w = synth.make_llama_layer(41, N=40000, M=8, T=1, n_q=4, n_kv=2, window=640)

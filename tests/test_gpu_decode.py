@@ -217,6 +217,32 @@ def test_many_searches_use_smaller_workgroups(ef, topk):
     idx.free()
 
 
+@pytest.mark.parametrize("expand", [16, 64])
+def test_beam_wider_than_the_workgroup(expand):
+    """ef = 1500 > 1024 threads (the top-2000 retrieval setting of Sec. 4 needs such beams): several
+    beam entries per thread in the pick and the merge. Ids and counters bit-exact, attention within
+    tolerance."""
+    w = synth.make_config0(N=4096, M=512, T=2, window=64)
+    adj, ent, _ = oracle_graphs(w)
+    idx = ra.ra_index_import(torch.from_numpy(adj), torch.from_numpy(ent), 1, 1, 1)
+    Kd, Vd = w.K.to(DEV), w.V.to(DEV)
+    K, V = to_np(w.K[0, 0]), to_np(w.V[0, 0])
+    tol = tol_for(w.K.dtype)
+    ef, topk = 1500, 1200
+    for t in range(2):
+        q = w.q_decode[t].to(DEV)
+        r_out, r_lse, r_ids, rst = OD.decode_step(to_np(w.q_decode[t, 0, 0]), K, V, adj[0], ent[0], w.sink,
+                                                  w.window, topk, ef, expand)
+        want = [rst["n_visited"], rst["n_expanded"], rst["n_iters"], rst["n_returned"]]
+        ids_s, st_s = ra.ra_search(q, idx, Kd, w.sink, w.window, topk, ef, expand)
+        assert ids_s[0, 0].tolist() == r_ids.tolist() and st_s[0, 0].tolist() == want
+        out, lse, ids, st = ra.ra_decode_step(q, idx, Kd, Vd, w.sink, w.window, topk, ef, expand)
+        assert ids[0, 0].tolist() == r_ids.tolist() and st[0, 0].tolist() == want
+        assert out_close(out[0, 0].cpu().numpy(), r_out, tol)
+        assert lse_close(lse[0, 0].cpu().numpy(), r_lse, tol)
+    idx.free()
+
+
 def test_exhaustive_beam_equals_bruteforce_and_full_attention():
     """ef >= N: the search returns the exact top-k; with topk covering every non-static key
     the decode output is Eq. 1 over the whole context."""
