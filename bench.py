@@ -38,6 +38,10 @@ def parse():
     p.add_argument("--layers", type=int, default=None, help="override the layer count (debug)")
     p.add_argument("--context", type=int, default=None, help="override N (debug)")
     p.add_argument("--seqs", type=int, default=None, help="config3: number of sequences (default 16)")
+    p.add_argument("--topk", type=int, default=None, help="override the retrieval size (e.g. 2000)")
+    p.add_argument("--ef", type=int, default=None, help="override the beam width")
+    p.add_argument("--deg", type=int, default=None, help="override the graph degree (config2)")
+    p.add_argument("--knn", type=int, default=None, help="override the KNN list length (config2)")
     p.add_argument("--expand", type=int, default=64, help="search expansion width")
     p.add_argument("--tokens", type=int, default=8, help="distinct decode queries per head")
     p.add_argument("--recall-layers", type=int, default=2)
@@ -74,7 +78,8 @@ def main():
     # ---- workload -------------------------------------------------------------------
     if a.workload == "config2":
         n_layers, N, n_seq = 32, 131072, 1
-        mk = lambda l: synth.make_config2_layer(l, device=dev, N=N, T=a.tokens)
+        kw = {k: v for k, v in (('deg', a.deg), ('knn', a.knn)) if v}
+        mk = lambda l: synth.make_config2_layer(l, device=dev, N=N, T=a.tokens, **kw)
     elif a.workload == "config1":
         n_layers, N, n_seq = 1, 32768, 1
         mk = lambda l: synth.make_config1(device=dev, N=N, T=a.tokens)
@@ -114,7 +119,7 @@ def main():
     w0 = layers[0]["w"]
     n_q, n_kv, d = layers[0]["q"].shape[2], w0.K.shape[1], w0.d
     T = layers[0]["q"].shape[0]
-    topk, ef, sink, window, deg = w0.topk, w0.ef, w0.sink, w0.window, w0.deg
+    topk, ef, sink, window, deg = a.topk or w0.topk, a.ef or w0.ef, w0.sink, w0.window, w0.deg
     esz = w0.K.element_size()
     heads = n_seq * n_q
     f32 = dict(dtype=torch.float32, device=dev)
