@@ -407,7 +407,9 @@ __device__ __forceinline__ int run_search(
             }
             SR_TICK(8);
             const float inv_nk = 1.0f / (float)nk;
-            for (int a = tid; a < items; a += T) {
+            // (tasks are dealt from the last thread down: the first threads, busy with the binary
+            // searches above, get the fewest)
+            for (int a = T - 1 - tid; a < items; a += T) {
                 // a = ch * nk + c without an integer division: the float quotient is off by at most one
                 int ch = (int)((float)a * inv_nk), c = a - ch * nk;
                 if (c < 0) { --ch; c += nk; }
