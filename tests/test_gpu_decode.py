@@ -243,6 +243,33 @@ def test_beam_wider_than_the_workgroup(expand):
     idx.free()
 
 
+@pytest.mark.parametrize("n_q,n_kv,dtype", [(8, 1, torch.bfloat16), (4, 2, torch.bfloat16), (8, 1, torch.float32),
+                                            (4, 1, torch.float32)])
+def test_decode_step_other_group_sizes(n_q, n_kv, dtype):
+    """GQA groups of 8 (the helper makes two passes over W; four with fp32), of 2, and of 4 with fp32
+    inputs, against the oracle."""
+    w = synth.make_llama_layer(31, N=900, M=256, T=2, n_q=n_q, n_kv=n_kv, dtype=dtype, ef=64, topk=24,
+                               window=70, deg=16, knn=12)
+    adj, ent, _ = oracle_graphs(w)
+    idx = ra.ra_index_import(torch.from_numpy(adj), torch.from_numpy(ent), 1, n_q, n_kv)
+    Kd, Vd = w.K.to(DEV), w.V.to(DEV)
+    tol = tol_for(w.K.dtype)
+    G = n_q // n_kv
+    assert idx.helpers_active
+    for t in range(2):
+        out, lse, ids, st = ra.ra_decode_step(w.q_decode[t].to(DEV), idx, Kd, Vd, w.sink, w.window, w.topk,
+                                              w.ef, 8)
+        out, lse, ids = out.cpu().numpy(), lse.cpu().numpy(), ids.cpu().numpy()
+        for h in range(n_q):
+            K = to_np(w.K[0, h // G]); V = to_np(w.V[0, h // G])
+            r_out, r_lse, r_ids, _ = OD.decode_step(to_np(w.q_decode[t, 0, h]), K, V, adj[h], ent[h], w.sink,
+                                                    w.window, w.topk, w.ef, 8)
+            assert ids[0, h].tolist() == r_ids.tolist()
+            assert out_close(out[0, h], r_out, tol) and lse_close(lse[0, h], r_lse, tol)
+    assert idx.helpers_active          # no wait ran out
+    idx.free()
+
+
 def test_exhaustive_beam_equals_bruteforce_and_full_attention():
     """ef >= N: the search returns the exact top-k; with topk covering every non-static key
     the decode output is Eq. 1 over the whole context."""
