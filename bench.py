@@ -42,7 +42,9 @@ def parse():
     p.add_argument("--ef", type=int, default=None, help="override the beam width")
     p.add_argument("--deg", type=int, default=None, help="override the graph degree (config2)")
     p.add_argument("--knn", type=int, default=None, help="override the KNN list length (config2)")
-    p.add_argument("--expand", type=int, default=64, help="search expansion width")
+    p.add_argument("--expand", type=int, default=None,
+                   help="search expansion width (default 64; 32 for config3, where the smaller "
+                        "candidate buffers let more searches share a compute unit)")
     p.add_argument("--tokens", type=int, default=8, help="distinct decode queries per head")
     p.add_argument("--recall-layers", type=int, default=2)
     p.add_argument("--cpu-heads", type=int, default=32, help="heads the CPU oracle is timed on")
@@ -71,6 +73,8 @@ def main():
     if not torch.cuda.is_available():
         print("bench.py needs a GPU", file=sys.stderr)
         sys.exit(2)
+    if a.expand is None:
+        a.expand = 32 if a.workload == "config3" else 64
     dev = "cuda:0"
     torch.cuda.set_device(0)
     ra.lib()                                    # fail loudly if the HIP library is missing
