@@ -254,12 +254,19 @@ __device__ __forceinline__ int run_search(
         const RowBits<DT> r = load_key<DT>(Kh, e0, lane16);
         const float sc = score_fixed<DT>(r, qv);
         if (tid == 0) {
-            cur[0] = make_key(sc, e0);
+            // the beam is the entry point alone, and the first step can only pick it: leave the
+            // state a merge would leave (pick in place, flag cleared, counts of unexpanded entries)
+            cur[0] = make_key(sc, e0) & ~1ull;
+            picks[0] = e0;
+            urank[0] = 0;
+            ctr[C_NCAND] = 0;
+            ctr[C_NKEEP] = 0;
+            ctr[C_NUNEXP] = 1;
             atomicOr(&bits[e0 >> 5], 1u << (e0 & 31));
         }
     }
     int bn = 1, n_visited = 1, n_expanded = 0, n_iters = 0;
-    bool picked = false;             // the merge of the last step already chose this step's picks
+    bool picked = true;              // the merge of the last step already chose this step's picks
     // Adjacency rows likely to be expanded soon are touched ahead of time (one word of the row's
     // first line), so that the row is in this XCD's L2 when its step reads it: the rows of the
     // candidates a step keeps, touched while they are merged, and the rows of the beam entries that
