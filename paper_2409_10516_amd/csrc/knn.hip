@@ -165,13 +165,11 @@ __global__ __launch_bounds__(KN_THREADS) void knn_kernel(
     // block's MFMAs are issued, so their latency hides behind a whole block of matrix work
     Operand<DT> a0, a1;
     load_keys(0, a0);
-    // (The requests are unconditional, the last ones re-reading the last block: with a branch
-    // around them the compiler waits for them before the current block's MFMAs.)
     for (int64_t kb = 0; kb < nblk; kb += 2) {
-        load_keys(kb + 1 < nblk ? kb + 1 : nblk - 1, a1);
+        if (kb + 1 < nblk) load_keys(kb + 1, a1);
         process(a0, kb);
         if (kb + 1 >= nblk) break;
-        load_keys(kb + 2 < nblk ? kb + 2 : nblk - 1, a0);
+        if (kb + 2 < nblk) load_keys(kb + 2, a0);
         process(a1, kb + 1);
     }
     // write the ids, best first
