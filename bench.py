@@ -9,7 +9,9 @@ sequential per-layer decode-step attention calls (search, sparse + static attent
 with all KV and graphs resident in HBM. Index build (exact KNN on the matrix cores +
 projection) runs before the timed region and is reported separately.
 
-Prints ONE JSON line (see README / DESIGN for the fields).
+Prints ONE JSON line: the metric and its value, the workload, `roofline` (the fused decode
+kernel's algorithmic bytes per launch over its measured launch time, against 8 TB/s, with the
+HBM traffic the counters read), `stages`, `exact_baselines`, `build`, `cpu_baseline`.
 """
 import argparse
 import json
@@ -62,7 +64,7 @@ def main():
     a = parse()
     if a.gpus != 1:
         print("bench.py: this build measures one GPU only (the path shards without exchange over "
-              "layers, heads and sequences; see DESIGN.md). Run with --gpus 1.", file=sys.stderr)
+              "layers, heads and sequences). Run with --gpus 1.", file=sys.stderr)
         sys.exit(2)
     import numpy as np
     import torch

@@ -1,12 +1,12 @@
-// One launch per layer for the whole decode step of Algorithm 1 (fixed static pattern): one
+// One launch per layer for the whole decode step of Algorithm 1 (fixed static pattern). A
 // workgroup per (sequence, query head) runs the graph search (search_dev.h) and then, without
-// leaving the compute unit, Eq. 2 over W u Omega for its head: the retrieved ids are still
-// in LDS, the 64 groups of 16 lanes share the rows of both sets round-robin, every group keeps
-// an online (max, sum, weighted sum) over its rows, and the groups' partial results are
-// combined with the re-scaling factors of Eq. 5 written for many sets (first across the four
-// groups of a wavefront by lane exchange, then across the 16 wavefronts through LDS). Carrying
-// the running maximum across both sets is the same arithmetic as computing o_W and o_Omega apart
-// and combining them by Eq. 4.
+// leaving the compute unit, Eq. 2 over the retrieved set Omega for its head: the retrieved ids
+// are still in LDS, the groups of 16 lanes share the rows round-robin, every group keeps an
+// online (max, sum, weighted sum) over its rows, and the groups' partial results are combined
+// with the re-scaling factors of Eq. 5 written for many sets (first across the four groups of a
+// wavefront by lane exchange, then across the wavefronts through LDS), together with the
+// (max, sum, weighted sum) of the static set W: carrying maxima across sets this way is the same
+// arithmetic as computing o_W and o_Omega apart and combining them by Eq. 4.
 //
 // The attention over the static set W does not depend on the search, so it is taken off the
 // head's critical path: the launch has one extra "helper" workgroup per (sequence, KV head) that

@@ -358,7 +358,7 @@ __device__ __forceinline__ void rows_for_graph(const int32_t* __restrict__ Lg, c
         // extract the best `want` candidates, one exact arg-max per round
         for (int r = 0; r < want; ++r) {
             Cand best; best.c = 0; best.pb = 0; best.b = -1;
-            const Cand prev = *s_prev;              // valid from round 1 on
+            const Cand prev = *s_prev;              // valid from r = 1 on
             for (int x = tid; x < nc; x += PJ_ROW_T) {
                 Cand cd;
                 cd.b = tb[x]; cd.c = tc[x]; cd.pb = tp[x];

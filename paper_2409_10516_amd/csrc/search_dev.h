@@ -1,7 +1,7 @@
 // VectorSearch(q) of Algorithm 1: bounded best-first walk over one head's key graph
 // (Sec. 2.4 describes proximity-graph search as a greedy walk towards the most similar
-// vectors). One workgroup of 1024 threads per (sequence, query head); the whole search state
-// lives in LDS:
+// vectors). One workgroup per (sequence, query head), of 1024 threads, or 512 / 256 when a launch
+// has more searches than the part has compute units; the whole search state lives in LDS:
 //   * visited: an exact bitset over the N keys (N/8 bytes; a global-memory bitset is used
 //     instead when the context is too long for LDS),
 //   * beam: at most ef entries, always sorted, as 64-bit keys
@@ -12,8 +12,12 @@
 // are read with one coalesced load per row, unvisited neighbours are claimed with an LDS
 // atomic-or (which also removes duplicates), their key rows are gathered by 16-lane
 // groups (16 B per lane; four rows per wavefront load), scored, filtered against the
-// beam's worst entry, and merged into the beam by rank (counting, no serial insertion). The beam after a step is the top-ef of a set union, so
-// it does not depend on the order in which candidates were claimed.
+// beam's worst entry, and merged into the beam by rank: a kept candidate's place is the
+// number of beam entries above it (binary search) plus the number of candidates above it
+// (counted); a beam entry's place is its index plus a prefix sum over the candidates' slots.
+// No sort, no serial insertion, and the next step's picks fall out of the same numbers. The
+// beam after a step is the top-ef of a set union, so it does not depend on the order in which
+// candidates were claimed.
 //
 // Scores decide integer results, so they are computed in one fixed float32 order: each
 // of 16 lanes sums its 8 contiguous products left to right, then the 16 partial sums are
