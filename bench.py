@@ -185,6 +185,18 @@ def main():
     wall = time.perf_counter() - t0
     ms_per_step = 1e3 * wall / a.steps
 
+    # spread of the step latency (a separate pass: one event pair per step, each step waited for)
+    lat = []
+    for t in range(max(a.steps, 20)):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        run(t)
+        e1.record()
+        e1.synchronize()
+        lat.append(e0.elapsed_time(e1))
+    lat.sort()
+    step_ms_p10_p50_p90 = [lat[int(0.1 * (len(lat) - 1))], lat[len(lat) // 2], lat[int(0.9 * (len(lat) - 1))]]
+
     # ---- dominant kernel: live HIP-event timing on the launch stream ----------------------
     # The timed region launches one fused kernel per layer (decode_kernel: search, sparse and
     # static attention, combination). It is timed here launch by launch; the stand-alone stage
@@ -330,7 +342,7 @@ def main():
     out = {
         "metric": "decode-step retrieval-attention latency (ms) @128K ctx, 1 GPU; recall@100",
         "value": ms_per_step, "unit": "ms", "n_gpus": 1, "steps": a.steps, "warmup": a.warmup,
-        "ms_per_step": ms_per_step, "higher_is_better": False, "scaling": "weak",
+        "ms_per_step": ms_per_step, "step_ms_p10_p50_p90": step_ms_p10_p50_p90, "higher_is_better": False, "scaling": "weak",
         "vs_baseline": None, "dtype": "bf16" if esz == 2 else "f32", "data": "synthetic",
         "recall_at_100": recall_device, "recall_at_100_cpu_oracle_sample": recall,
         "config": {"workload": f"{a.workload}: {len(layers)} layers x {n_seq} seq x {n_q} q heads / "
