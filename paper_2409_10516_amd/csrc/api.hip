@@ -108,6 +108,8 @@ static ra_status new_handle(int n_seq, int n_q, int n_kv, int64_t N, int deg, ra
     hipError_t e = hipGetDevice(&ix->device);
     if (e == hipSuccess) e = hipMalloc((void**)&ix->adj, ix->graph_bytes);
     if (e == hipSuccess) e = hipMalloc((void**)&ix->entry, graphs * sizeof(int32_t));
+    ix->root_cap = 3 + deg + deg * deg;
+    if (e == hipSuccess) e = hipMalloc((void**)&ix->roots, graphs * ix->root_cap * sizeof(int32_t));
     if (e == hipSuccess) e = hipMalloc((void**)&ix->coop, coop_bytes(ix));
     if (e == hipSuccess) e = hipMemset(ix->coop, 0, coop_bytes(ix));
     ix->coop_mode = RA_HELPERS_ON;
@@ -117,6 +119,7 @@ static ra_status new_handle(int n_seq, int n_q, int n_kv, int64_t N, int deg, ra
         if (ix->adj) (void)hipFree(ix->adj);
         if (ix->entry) (void)hipFree(ix->entry);
         if (ix->coop) (void)hipFree(ix->coop);
+        if (ix->roots) (void)hipFree(ix->roots);
         delete ix;
         return e == hipErrorOutOfMemory ? RA_ENOMEM : RA_EHIP;
     }
@@ -132,6 +135,7 @@ extern "C" void ra_index_free(ra_index* ix) {
     if (ix->ids_ws) (void)hipFree(ix->ids_ws);
     if (ix->bitset) (void)hipFree(ix->bitset);
     if (ix->coop) (void)hipFree(ix->coop);
+    if (ix->roots) (void)hipFree(ix->roots);
     delete ix;
 }
 
@@ -165,7 +169,8 @@ extern "C" int64_t ra_index_info(const ra_index* ix, int what) {
         case 3: return ix->N;
         case 4: return ix->deg;
         case 5: return (int64_t)(ix->graph_bytes + (size_t)ix->n_seq * ix->n_q * 4 +
-                                 ix->partials_bytes + ix->ids_bytes + ix->bitset_bytes + coop_bytes(ix));
+                                 ix->partials_bytes + ix->ids_bytes + ix->bitset_bytes + coop_bytes(ix) +
+                                 (size_t)ix->n_seq * ix->n_q * ix->root_cap * sizeof(int32_t));
         case 6: {
             if (ix->coop_mode != RA_HELPERS_ON) return 0;
             const size_t heads = (size_t)ix->n_seq * ix->n_q;
@@ -209,6 +214,15 @@ extern "C" ra_status ra_index_import(const int32_t* adj_host, const int32_t* ent
         ra_set_error("copying the graph to the device failed: %s", hipGetErrorString(e));
         ra_index_free(ix);
         return RA_EHIP;
+    }
+    ra_status rc = ra_launch_roots(ix->adj, ix->entry, (int)graphs, N, deg, ix->roots, ix->root_cap, nullptr);
+    if (rc == RA_OK && hipStreamSynchronize(nullptr) != hipSuccess) {
+        ra_set_error("listing the root sets failed: %s", hipGetErrorString(hipGetLastError()));
+        rc = RA_EHIP;
+    }
+    if (rc != RA_OK) {
+        ra_index_free(ix);
+        return rc;
     }
     *out = ix;
     return RA_OK;
@@ -275,6 +289,8 @@ extern "C" ra_status ra_build_index(const void* K, const void* Q, ra_dtype dt, i
     }
     ra_status rc = ra_launch_knn(K, Q, dt, n_seq, n_q, n_kv, N, M, knn, (hipStream_t)stream, L);
     if (rc == RA_OK) rc = ra_project(L, graphs, N, M, knn, deg, stream, ix->adj, ix->entry);
+    if (rc == RA_OK)
+        rc = ra_launch_roots(ix->adj, ix->entry, graphs, N, deg, ix->roots, ix->root_cap, (hipStream_t)stream);
     if (rc == RA_OK && hipStreamSynchronize((hipStream_t)stream) != hipSuccess) {
         ra_set_error("index build failed on the device: %s", hipGetErrorString(hipGetLastError()));
         rc = RA_EHIP;
@@ -302,8 +318,8 @@ extern "C" ra_status ra_search(const void* q, const ra_index* idx, const void* K
         RA_TRY(grow((void**)&ix->bitset, &ix->bitset_bytes, need));
     }
     return ra_launch_search(q, ix->adj, ix->entry, K, dt, ix->n_seq, ix->n_q, ix->n_kv, N, ix->deg,
-                            sink, window, topk, ef, expand, ix->bitset, (hipStream_t)stream, ids,
-                            stats);
+                            sink, window, topk, ef, expand, ix->bitset, ix->roots, ix->root_cap,
+                            (hipStream_t)stream, ids, stats);
 }
 
 extern "C" ra_status ra_attend(const void* q, const ra_index* idx, const void* K, const void* V,
@@ -348,7 +364,8 @@ extern "C" ra_status ra_decode_step_grown(const void* q, const ra_index* idx, co
         RA_TRY(grow((void**)&ix->bitset, &ix->bitset_bytes, heads * ((ix->N + 31) >> 5) * 4));
     return ra_launch_decode(q, ix->adj, ix->entry, K, V, dt, ix->n_seq, ix->n_q, ix->n_kv, ix->N, N,
                             kv_stride, ix->deg, sink, window, topk, ef, expand, ix->bitset, ix->coop,
-                            ix->coop_mode, ix->coop_spin, (hipStream_t)stream, out, lse, ids, stats);
+                            ix->coop_mode, ix->coop_spin, ix->roots, ix->root_cap, (hipStream_t)stream, out,
+                            lse, ids, stats);
 }
 
 extern "C" ra_status ra_decode_step(const void* q, const ra_index* idx, const void* K, const void* V,

@@ -48,6 +48,9 @@ struct ra_index {
     float* coop;
     int coop_mode;      // RA_HELPERS_*
     int coop_spin;      // polls of the ready word before a head gives up on its helper
+    // root sets: what the first two steps of every walk of a head visit ([n_seq*n_q][root_cap])
+    int32_t* roots;
+    int root_cap;
     size_t graph_bytes;
 };
 
@@ -57,7 +60,10 @@ struct ra_index {
 ra_status ra_launch_search(const void* q, const int32_t* adj, const int32_t* entry, const void* K,
                            ra_dtype dt, int n_seq, int n_q, int n_kv, int64_t N, int deg,
                            int sink, int window, int topk, int ef, int expand, uint32_t* bitset,
-                           hipStream_t st, int32_t* ids, ra_stats* stats);
+                           const int32_t* roots, int root_cap, hipStream_t st, int32_t* ids,
+                           ra_stats* stats);
+ra_status ra_launch_roots(const int32_t* adj, const int32_t* entry, int heads, int64_t N, int deg,
+                          int32_t* roots, int cap, hipStream_t st);
 size_t ra_search_lds_bytes(int64_t N, int deg, int ef, int expand, bool global_bitset);
 bool ra_search_needs_global_bitset(int64_t N, int deg, int ef, int expand);
 
@@ -73,7 +79,8 @@ bool ra_decode_needs_global_bitset(int64_t N, int deg, int ef, int expand, int t
 ra_status ra_launch_decode(const void* q, const int32_t* adj, const int32_t* entry, const void* K,
                            const void* V, ra_dtype dt, int n_seq, int n_q, int n_kv, int64_t Ng, int64_t N,
                            int64_t kv_stride, int deg, int sink, int window, int topk, int ef, int expand,
-                           uint32_t* bitset, float* coop, int coop_mode, int coop_spin, hipStream_t st, float* out, float* lse, int32_t* ids,
+                           uint32_t* bitset, float* coop, int coop_mode, int coop_spin,
+                           const int32_t* roots, int root_cap, hipStream_t st, float* out, float* lse, int32_t* ids,
                            ra_stats* stats);
 
 ra_status ra_launch_flat_topk(const void* q, const void* K, ra_dtype dt, int n_seq, int n_q, int n_kv,

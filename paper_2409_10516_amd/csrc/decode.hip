@@ -267,7 +267,7 @@ __global__ __launch_bounds__(T) void decode_kernel(
     uint32_t* __restrict__ gbits,
     int32_t* __restrict__ ids, ra_stats* __restrict__ stats, int ids_off, float scale,
     float* __restrict__ out, float* __restrict__ lse, float* coop, int n_helpers, int coop_mode,
-    int coop_spin) {
+    int coop_spin, const int32_t* __restrict__ roots, int root_cap) {
     extern __shared__ __align__(16) unsigned char lds_raw[];
     const int tid = threadIdx.x, grp = tid >> 4, lane16 = tid & 15;
     const size_t esz = DT == RA_BF16 ? 2 : 4;
@@ -302,7 +302,8 @@ __global__ __launch_bounds__(T) void decode_kernel(
     // wstart <= Ng, so every token appended after the build is attended densely.
     const int cnt = run_search<DT, GBITS, T>(lds_raw, head, q, adj, entry, K, n_q, n_kv, Ng, kv_stride, deg,
                                           s, (int)(Ng - wstart), topk, ef, expand, gbits, ids, stats,
-                                          lds_ids, AwaitHelper{ready + head, ready + n_heads, lds_word,
+                                          lds_ids, roots, root_cap,
+                                          AwaitHelper{ready + head, ready + n_heads, lds_word,
                                                                coop_spin, helpers});
 #ifdef SR_PHASE_CLOCKS
     const long long t_attn = clock64();
@@ -414,7 +415,8 @@ __global__ void dc_fill_u32_kernel(uint32_t* p, size_t n, uint32_t v) {
 ra_status ra_launch_decode(const void* q, const int32_t* adj, const int32_t* entry, const void* K,
                            const void* V, ra_dtype dt, int n_seq, int n_q, int n_kv, int64_t Ng, int64_t N,
                            int64_t kv_stride, int deg, int sink, int window, int topk, int ef, int expand,
-                           uint32_t* bitset, float* coop, int coop_mode, int coop_spin, hipStream_t st,
+                           uint32_t* bitset, float* coop, int coop_mode, int coop_spin,
+                           const int32_t* roots, int root_cap, hipStream_t st,
                            float* out, float* lse, int32_t* ids, ra_stats* stats) {
     // W = [0, s) u [wstart, N): the sink, the sliding window, and every token appended after the
     // index was built (wstart <= Ng); overlapping ranges make everything static
@@ -449,7 +451,7 @@ ra_status ra_launch_decode(const void* q, const int32_t* adj, const int32_t* ent
         hipLaunchKernelGGL((decode_kernel<DTV, GB, TV>), dim3(heads + n_helpers), dim3(TV), lds,   \
                            st, q, adj, entry, K, V, n_q, n_kv, Ng, N, kv_stride, wstart, deg,      \
                            (int)s, topk, ef, expand, bitset, ids, stats, ids_off, scale, out, lse, \
-                           coop, n_helpers, coop_mode, coop_spin);                                 \
+                           coop, n_helpers, coop_mode, coop_spin, roots, root_cap);                \
     } while (0)
 #define RA_DC_GO(DTV, GB)                                                                          \
     do {                                                                                           \

@@ -6,16 +6,79 @@ __global__ __launch_bounds__(T) void search_kernel(
     const void* __restrict__ q, const int32_t* __restrict__ adj, const int32_t* __restrict__ entry,
     const void* __restrict__ K, int n_q, int n_kv, int64_t N, int deg, int s, int w, int topk,
     int ef, int expand, uint32_t* __restrict__ gbits, int32_t* __restrict__ ids,
-    ra_stats* __restrict__ stats) {
+    ra_stats* __restrict__ stats, const int32_t* __restrict__ roots, int root_cap) {
     extern __shared__ __align__(16) unsigned char lds_raw[];
     run_search<DT, GBITS, T>(lds_raw, xcd_aware_head(blockIdx.x, gridDim.x, n_q / n_kv), q, adj, entry, K, n_q, n_kv, N, N, deg, s, w, topk, ef,
-                          expand, gbits, ids, stats, nullptr, NoHook());
+                          expand, gbits, ids, stats, nullptr, roots, root_cap, NoHook());
 }
 
 __global__ void fill_u32_kernel(uint32_t* p, size_t n, uint32_t v) {
     for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n;
          i += (size_t)gridDim.x * blockDim.x)
         p[i] = v;
+}
+
+
+// Root sets (see run_search): per head [0] the number of ids, [1] 1 + the number of the entry
+// point's neighbours, then the ids: the entry point, its distinct valid neighbours in row order,
+// then the distinct valid neighbours of those that are not among the former, in row order.
+// One workgroup per head; a build-time step, written for clarity rather than speed.
+#define RT_THREADS 256
+__global__ __launch_bounds__(RT_THREADS) void roots_kernel(const int32_t* __restrict__ adj,
+                                                           const int32_t* __restrict__ entry, int64_t N,
+                                                           int deg, int32_t* __restrict__ roots, int cap) {
+    __shared__ int l1[RA_MAX_DEG + 1];
+    __shared__ int l2[RA_MAX_DEG * RA_MAX_DEG];
+    __shared__ unsigned char keep[RA_MAX_DEG * RA_MAX_DEG];
+    __shared__ int n1s;
+    const int tid = threadIdx.x, head = blockIdx.x;
+    const int32_t* adj_h = adj + (size_t)head * N * deg;
+    int32_t* out = roots + (size_t)head * cap;
+    const int e0 = entry[head];
+    if (tid == 0) {
+        int n1 = 1;
+        l1[0] = e0;
+        for (int j = 0; j < deg; ++j) {
+            const int nb = adj_h[(size_t)e0 * deg + j];
+            bool ok = nb >= 0 && nb < N;
+            for (int x = 0; ok && x < n1; ++x) ok = l1[x] != nb;
+            if (ok) l1[n1++] = nb;
+        }
+        n1s = n1;
+    }
+    __syncthreads();
+    const int n1 = n1s, cells = (n1 - 1) * deg;
+    for (int x = tid; x < cells; x += RT_THREADS) {
+        int nb = adj_h[(size_t)l1[1 + x / deg] * deg + x % deg];
+        if (nb < 0 || nb >= N) nb = -1;
+        for (int y = 0; nb >= 0 && y < n1; ++y)
+            if (l1[y] == nb) nb = -1;
+        l2[x] = nb;
+    }
+    __syncthreads();
+    for (int x = tid; x < cells; x += RT_THREADS) {
+        const int nb = l2[x];
+        bool k = nb >= 0;
+        for (int y = 0; k && y < x; ++y) k = l2[y] != nb;
+        keep[x] = k;
+    }
+    __syncthreads();
+    if (tid == 0) {
+        int n = 0;
+        for (int x = 0; x < n1; ++x) out[2 + n++] = l1[x];
+        for (int x = 0; x < cells; ++x)
+            if (keep[x]) out[2 + n++] = l2[x];
+        out[0] = n;
+        out[1] = n1;
+    }
+}
+
+ra_status ra_launch_roots(const int32_t* adj, const int32_t* entry, int heads, int64_t N, int deg,
+                          int32_t* roots, int cap, hipStream_t st) {
+    if (deg > RA_MAX_DEG || cap < 3 + deg + deg * deg) RA_FAIL(RA_EINVAL, "root set buffer too small");
+    hipLaunchKernelGGL(roots_kernel, dim3(heads), dim3(RT_THREADS), 0, st, adj, entry, N, deg, roots, cap);
+    RA_HIP(hipGetLastError());
+    return RA_OK;
 }
 
 size_t ra_search_lds_bytes(int64_t N, int deg, int ef, int expand, bool global_bitset) {
@@ -30,7 +93,8 @@ bool ra_search_needs_global_bitset(int64_t N, int deg, int ef, int expand) {
 ra_status ra_launch_search(const void* q, const int32_t* adj, const int32_t* entry, const void* K,
                            ra_dtype dt, int n_seq, int n_q, int n_kv, int64_t N, int deg,
                            int sink, int window, int topk, int ef, int expand, uint32_t* bitset,
-                           hipStream_t st, int32_t* ids, ra_stats* stats) {
+                           const int32_t* roots, int root_cap, hipStream_t st, int32_t* ids,
+                           ra_stats* stats) {
     int64_t ss = sink < 0 ? 0 : sink, ww = window < 0 ? 0 : window;
     if (ss > N) ss = N;
     if (ww > N) ww = N;
@@ -52,7 +116,7 @@ ra_status ra_launch_search(const void* q, const int32_t* adj, const int32_t* ent
         RA_LDS_OPT_IN((search_kernel<DTV, GB, TV>), lds);                                         \
         hipLaunchKernelGGL((search_kernel<DTV, GB, TV>), dim3(heads), dim3(TV), lds, st, q, adj,  \
                            entry, K, n_q, n_kv, N, deg, (int)ss, (int)ww, topk, ef, expand,       \
-                           bitset, ids, stats);                                                   \
+                           bitset, ids, stats, roots, root_cap);                                  \
     } while (0)
 #define RA_SR_LAUNCH(DTV, GB)                                                                     \
     do {                                                                                          \

@@ -166,6 +166,17 @@ __device__ __forceinline__ int wave_incl_scan(int v) {
     return v;
 }
 
+// the same, counting only entries whose not-yet-expanded flag is clear
+__device__ __forceinline__ int count_above16_expanded(const u64* arr, int n, u64 k) {
+    u64 v[16];
+#pragma unroll
+    for (int u = 0; u < 16; ++u) v[u] = arr[u];
+    int cnt = 0;
+#pragma unroll
+    for (int u = 0; u < 16; ++u) cnt += (u < n && v[u] > k && !(v[u] & 1ull)) ? 1 : 0;
+    return cnt;
+}
+
 // the same when all 16 entries count
 __device__ __forceinline__ int count_above16_full(const u64* arr, u64 k) {
     u64 v[16];
@@ -219,7 +230,8 @@ __device__ __forceinline__ int run_search(
     unsigned char* lds_raw, int head, const void* __restrict__ q, const int32_t* __restrict__ adj,
     const int32_t* __restrict__ entry, const void* __restrict__ K, int n_q, int n_kv, int64_t N,
     int64_t kv_stride, int deg, int s, int w, int topk, int ef, int expand, uint32_t* __restrict__ gbits,
-    int32_t* __restrict__ ids, ra_stats* __restrict__ stats, int32_t* lds_ids, const Hook& hook) {
+    int32_t* __restrict__ ids, ra_stats* __restrict__ stats, int32_t* lds_ids,
+    const int32_t* __restrict__ roots, int root_cap, const Hook& hook) {
     const int tid = threadIdx.x, grp = tid >> 4, lane16 = tid & 15;
     const int lane = tid & (RA_WAVE - 1), wv = tid / RA_WAVE;
     const int seq = head / n_q, h = head % n_q, kvh = h / (n_q / n_kv);
@@ -253,23 +265,55 @@ __device__ __forceinline__ int run_search(
     float qv[8];
     load_q8<DT>(reinterpret_cast<const char*>(q) + (size_t)head * RA_D * esz, lane16, qv);
     const int e0 = entry[head];
-    __syncthreads();
-    if (grp == 0) {
-        const RowBits<DT> r = load_key<DT>(Kh, e0, lane16);
-        const float sc = score_fixed<DT>(r, qv);
-        if (tid == 0) {
-            // the beam is the entry point alone, and the first step can only pick it: leave the
-            // state a merge would leave (pick in place, flag cleared, counts of unexpanded entries)
-            cur[0] = make_key(sc, e0) & ~1ull;
-            picks[0] = e0;
-            urank[0] = 0;
-            ctr[C_NCAND] = 0;
-            ctr[C_NKEEP] = 0;
-            ctr[C_NUNEXP] = 1;
-            atomicOr(&bits[e0 >> 5], 1u << (e0 & 31));
-        }
+    // The first two steps of a walk do not depend on the query: the entry point is expanded, then
+    // all its neighbours are (when `expand` and ef are at least their number). What they visit,
+    // the entry point's root set, is listed with the index (ra_launch_roots): [0] its size,
+    // [1] 1 + the number of the entry point's neighbours, then the ids, those first. With it the
+    // two steps become one: every key of the set is scored in one gather and the beam is the
+    // top ef of them, the entry point and its neighbours marked expanded. Same beam, same visited
+    // set, same counters as the two steps taken one after the other.
+    const int32_t* root = roots ? roots + (size_t)head * root_cap : nullptr;
+    int n_root = 0, n_first = 0, my_root = -1;
+    if (root) {
+        n_root = root[0];
+        n_first = root[1];
+        my_root = root[2 + (tid < root_cap - 2 ? tid : 0)];      // unconditional: same trip as the header
     }
-    int bn = 1, n_visited = 1, n_expanded = 0, n_iters = 0;
+    const bool fill = root && n_first > 1 && expand >= n_first - 1 && ef >= n_first && n_root <= maxc;
+    __syncthreads();                                             // the LDS state is cleared
+    int bn, n_visited, n_expanded, n_iters;
+    bool first = fill;               // the coming step is that doubled first step
+    if (fill) {
+        for (int c = tid; c < n_root; c += T) {
+            const int id = c == tid ? my_root : root[2 + c];
+            cid[c] = id;
+            atomicOr(&bits[id >> 5], 1u << (id & 31));
+        }
+        if (tid == 0) {
+            urank[0] = 0;
+            ctr[C_NCAND] = n_root;
+            ctr[C_NKEEP] = 0;
+            ctr[C_NUNEXP] = 0;
+        }
+        bn = 0; n_visited = 0; n_expanded = 0; n_iters = 0;
+    } else {
+        if (grp == 0) {
+            const RowBits<DT> r = load_key<DT>(Kh, e0, lane16);
+            const float sc = score_fixed<DT>(r, qv);
+            if (tid == 0) {
+                // the beam is the entry point alone, and the first step can only pick it: leave the
+                // state a merge would leave (pick in place, flag cleared, counts of unexpanded entries)
+                cur[0] = make_key(sc, e0) & ~1ull;
+                picks[0] = e0;
+                urank[0] = 0;
+                ctr[C_NCAND] = 0;
+                ctr[C_NKEEP] = 0;
+                ctr[C_NUNEXP] = 1;
+                atomicOr(&bits[e0 >> 5], 1u << (e0 & 31));
+            }
+        }
+        bn = 1; n_visited = 1; n_expanded = 0; n_iters = 0;
+    }
     bool picked = true;              // the merge of the last step already chose this step's picks
     // Adjacency rows likely to be expanded soon are touched ahead of time (one word of the row's
     // first line), so that the row is in this XCD's L2 when its step reads it: the rows of the
@@ -283,7 +327,9 @@ __device__ __forceinline__ int run_search(
     for (;;) {
         SR_TICK_ITER(n_iters);
         int np;
-        if (!picked) {
+        if (first) {
+            np = 0;                  // nothing of the (empty) beam is expanded: see the set-up
+        } else if (!picked) {
             // ---- pick the `expand` best unexpanded entries: the beam is sorted, so the picks are
             //      the first `expand` set flags in beam order. T entries per round, one per
             //      thread: ballot prefix inside a wavefront, wavefront totals through LDS, the
@@ -326,12 +372,17 @@ __device__ __forceinline__ int run_search(
             if (tid == 0) urank[bn] = (uint16_t)total;
         }
         SR_TICK(0);
-        ++n_iters;
-        n_expanded += np;
+        if (first) {
+            n_iters = 2;             // the entry point's step and its neighbours' step
+            n_expanded = n_first;
+        } else {
+            ++n_iters;
+            n_expanded += np;
+        }
 
         // ---- read the picked adjacency rows (all loads issued before any is consumed),
-        //      claim unvisited neighbours
-        {
+        //      claim unvisited neighbours (the doubled first step has its candidates already)
+        if (!first) {
             const int cells = np * deg;
             for (int x0 = 0; x0 < cells; x0 += T * 2) {
                 int nbv[2];
@@ -381,7 +432,10 @@ __device__ __forceinline__ int run_search(
                 if (c0 + u * (T / 16) >= nc) break;
                 const float sc = score_fixed<DT>(rows[u], qv);
                 if (lane16 == 0 && cidv[u] >= 0) {
-                    const u64 key = make_key(sc, cidv[u]);
+                    u64 key = make_key(sc, cidv[u]);
+                    // in the doubled first step the entry point and its neighbours, the first
+                    // n_first candidates, enter the beam as expanded
+                    if (first && c0 + u * (T / 16) + grp < n_first) key &= ~1ull;
                     if ((key >> 1) > worst) ckey[atomicAdd(&ctr[C_NKEEP], 1)] = key;
                 }
             }
@@ -428,6 +482,12 @@ __device__ __forceinline__ int run_search(
                 const int above = ch + 1 < nch ? count_above16_full(ckey + ch * 16, ckey[c])
                                                : count_above16(ckey + ch * 16, nk - ch * 16, ckey[c]);
                 if (above) atomicAdd(&cnt[c], above);
+                if (first) {
+                    // the doubled first step has expanded candidates too: how many of those beat
+                    // this one goes into the counter's high half (the beam is empty, so it is free)
+                    const int exp_above = count_above16_expanded(ckey + ch * 16, nk - ch * 16, ckey[c]);
+                    if (exp_above) atomicAdd(&cnt[c], exp_above << 16);
+                }
             }
             SR_TICK(9);
             __syncthreads();
@@ -465,9 +525,16 @@ __device__ __forceinline__ int run_search(
                         c = both & 0xffff;
                         b = both >> 16;
                     }
-                    const int pos = b + c;
-                    const int ub = (int)urank[b] - np;            // this step's picks are expanded now
-                    const int ur = c + (ub > 0 ? ub : 0);         // unexpanded elements above this one
+                    int pos, ur;                                  // ur: unexpanded elements above this one
+                    if (first) {                                  // empty beam; b counts expanded candidates above
+                        pos = c;
+                        ur = c - b;
+                        b = 0;
+                    } else {
+                        pos = b + c;
+                        const int ub = (int)urank[b] - np;        // this step's picks are expanded now
+                        ur = c + (ub > 0 ? ub : 0);
+                    }
                     un = pos < ef && (k & 1ull);
                     if (un && ur < expand) {
                         picks[ur] = key_id(k);
@@ -494,6 +561,7 @@ __device__ __forceinline__ int run_search(
         uint16_t* tu = urank; urank = urank_nxt; urank_nxt = tu;
         int* th = hist; hist = hist_nxt; hist_nxt = th;
         picked = true;
+        first = false;
     }
 
     hook.before_output();
