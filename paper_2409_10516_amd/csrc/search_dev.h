@@ -259,9 +259,6 @@ __device__ __forceinline__ int run_search(
     uint32_t* bits = GBITS ? gbits + (size_t)head * nwords
                            : reinterpret_cast<uint32_t*>(urank_nxt + ef + 1);
 
-    if (!GBITS)
-        for (int i = tid; i < nwords; i += T) bits[i] = 0u;
-    for (int i = tid; i < maxc + 2 * ef + 2; i += T) cnt[i] = 0;      // cnt, hist, hist_nxt
     float qv[8];
     load_q8<DT>(reinterpret_cast<const char*>(q) + (size_t)head * RA_D * esz, lane16, qv);
     const int e0 = entry[head];
@@ -279,6 +276,10 @@ __device__ __forceinline__ int run_search(
         n_first = root[1];
         my_root = root[2 + (tid < root_cap - 2 ? tid : 0)];      // unconditional: same trip as the header
     }
+    // (the loads above are in flight while the LDS state is cleared)
+    if (!GBITS)
+        for (int i = tid; i < nwords; i += T) bits[i] = 0u;
+    for (int i = tid; i < maxc + 2 * ef + 2; i += T) cnt[i] = 0;      // cnt, hist, hist_nxt
     const bool fill = root && n_first > 1 && expand >= n_first - 1 && ef >= n_first && n_root <= maxc;
     __syncthreads();                                             // the LDS state is cleared
     int bn, n_visited, n_expanded, n_iters;
