@@ -53,6 +53,8 @@ def parse():
     p.add_argument("--cpu-tokens", type=int, default=8, help="decode queries per head the CPU oracle is timed on")
     p.add_argument("--no-cpu-baseline", action="store_true")
     p.add_argument("--graph", type=int, default=1, help="replay the step from a captured HIP graph")
+    p.add_argument("--q8", type=int, default=0,
+                   help="1: the graph walk reads an 8-bit copy of the keys (ra_decode_step_q8)")
     p.add_argument("--helpers", type=int, default=1,
                    help="0: every head attends to the static set itself (no helper workgroups)")
     p.add_argument("--copy-calibration", action="store_true",
@@ -77,6 +79,10 @@ def main():
         sys.exit(2)
     if a.expand is None:
         a.expand = 32 if a.workload == "config3" else 64
+    if a.q8 and not a.no_cpu_baseline:
+        print("bench.py: --q8 runs skip the CPU baseline (it times the oracle's walk over the keys as stored)",
+              file=sys.stderr)
+        a.no_cpu_baseline = True
     dev = "cuda:0"
     torch.cuda.set_device(0)
     ra.lib()                                    # fail loudly if the HIP library is missing
@@ -111,13 +117,14 @@ def main():
         idx = ra.ra_build_index(w.K, w.Q_prefill, w.deg, w.knn)
         if not a.helpers:
             idx.configure(ra.binding.RA_CFG_HELPERS, ra.binding.RA_HELPERS_OFF)
+        k8 = ra.ra_quantize_keys(w.K) if a.q8 else None
         torch.cuda.synchronize()
         t2 = time.time()
         t_gen += t1 - t0
         t_build += t2 - t1
         n_q = w.Q_prefill.shape[1]
         build_flop += 2.0 * w.Q_prefill.shape[0] * n_q * w.Q_prefill.shape[2] * w.K.shape[2] * w.d
-        layers.append(dict(K=w.K, V=w.V, q=w.q_decode, idx=idx, w=w))
+        layers.append(dict(K=w.K, V=w.V, q=w.q_decode, idx=idx, w=w, k8=k8))
         w.Q_prefill = None
         if l == 0 or (l + 1) % 8 == 0:
             print(f"[bench] layer {l + 1}/{n_layers}: generate {t1 - t0:.2f}s build {t2 - t1:.2f}s",
@@ -138,7 +145,7 @@ def main():
     def step(t):
         for L in layers:
             ra.ra_decode_step(L["q"][t % T], L["idx"], L["K"], L["V"], sink, window, topk, ef,
-                              a.expand, out=L["out"], lse=L["lse"], ids=L["ids"], stats=L["st"])
+                              a.expand, out=L["out"], lse=L["lse"], ids=L["ids"], stats=L["st"], k8=L["k8"])
 
     dt_code = 1 if esz == 2 else 0
     L_ = ra.lib()
@@ -216,7 +223,7 @@ def main():
 
     def fused_only(L, t):
         ra.ra_decode_step(L["q"][t % T], L["idx"], L["K"], L["V"], sink, window, topk, ef, a.expand,
-                          out=L["out"], lse=L["lse"], ids=L["ids"], stats=L["st"])
+                          out=L["out"], lse=L["lse"], ids=L["ids"], stats=L["st"], k8=L["k8"])
 
     stats_sum = np.zeros(4, np.float64)
     decode_ms = timed_pass(fused_only)
@@ -231,7 +238,8 @@ def main():
     visited, expanded, iters, returned = stats_sum / n_launch      # per launch (all heads)
     # algorithmic bytes of one launch: key rows scored + adjacency rows read + q + ids (search),
     # retrieved K/V rows per query head + static K/V rows per KV head (attention)
-    search_bytes = visited * d * esz + expanded * deg * 4 + heads * (d * esz + topk * 4)
+    key_row_bytes = d * (1 if a.q8 else esz)           # what the walk reads per scored key
+    search_bytes = visited * key_row_bytes + expanded * deg * 4 + heads * (d * esz + topk * 4)
     W = min(N, sink + window)
     attend_bytes = returned * 2 * d * esz + n_seq * n_kv * W * 2 * d * esz
     decode_bytes = search_bytes + attend_bytes
@@ -269,7 +277,7 @@ def main():
     hits = total = 0
     for L in layers:
         ra.ra_decode_step(L["q"][t_last], L["idx"], L["K"], L["V"], sink, window, topk, ef, a.expand,
-                          out=L["out"], lse=L["lse"], ids=L["ids"], stats=L["st"])
+                          out=L["out"], lse=L["lse"], ids=L["ids"], stats=L["st"], k8=L["k8"])
         ra.ra_flat_topk(L["q"][t_last], L["K"], sink, window, topk, workspace=flat_ws, ids=flat_ids)
         got, ref = L["ids"].long(), flat_ids.long()
         match = (got.unsqueeze(-1) == ref.unsqueeze(-2)) & (ref.unsqueeze(-2) >= 0)
@@ -348,7 +356,7 @@ def main():
         "config": {"workload": f"{a.workload}: {len(layers)} layers x {n_seq} seq x {n_q} q heads / "
                                f"{n_kv} kv heads, d={d}, N={N}, M={N} prefill queries/head",
                    "topk": topk, "ef": ef, "expand": a.expand, "deg": deg, "knn": w0.knn,
-                   "sink": sink, "window": window, "hip_graph": bool(a.graph)},
+                   "sink": sink, "window": window, "hip_graph": bool(a.graph), "search_keys": "int8" if a.q8 else "as stored"},
         "roofline": {"bound": "hbm", "kernel": "decode_kernel", "achieved": decode_gbs,
                      "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": decode_gbs / HBM_PEAK_GBS,
                      "traffic": (DECODE_TRAFFIC_BYTES_CONFIG2 if (a.workload == "config2"

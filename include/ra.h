@@ -161,6 +161,30 @@ ra_status ra_index_import(const int32_t* adj_host, const int32_t* entries_host, 
 ra_status ra_index_export(const ra_index* idx, int seq, int q_head, int32_t* adj_host,
                           int32_t* entry_host);
 
+/* 8-bit keys for the search. Appendix C names 8-bit scalar quantisation of the KV vectors as the
+ * paper's next step and gives no scheme; here the keys get an 8-bit copy that only the graph walk
+ * reads (half the bytes per scored key), attention keeps using K and V as they are:
+ *     scale[d] = max_i |K[i][d]| / 127 (1 for an all-zero column), per (sequence, KV head),
+ *     K8[i][d] = clamp(round_half_even(K[i][d] / scale[d]), -127, 127),
+ * float32 arithmetic, each division rounded once. The walk scores <q * scale, K8> in the same
+ * fixed summation order as ra_search, so its ids and counters are reproducible bit for bit.
+ *
+ * ra_quantize_keys: K [n_seq][n_kv_heads][N][128] (dt) -> K8 [n_seq][n_kv_heads][N][128] int8,
+ * scale [n_seq][n_kv_heads][128] float32; device pointers, caller-owned; enqueued on `stream`.
+ * ra_search_q8 / ra_decode_step_q8: ra_search / ra_decode_step with the walk reading K8 and scale
+ * (`dtq` is the type of q); N must equal the number of keys the index was built over. The ids are
+ * the best topk of the beam under the 8-bit scores; out / lse are Eq. 2 and Eq. 4-5 over those
+ * ids and W with the original K and V. Errors as for ra_search / ra_decode_step. */
+ra_status ra_quantize_keys(const void* K, ra_dtype dt, int n_seq, int n_kv_heads, int64_t N, void* stream,
+                           int8_t* K8, float* scale);
+ra_status ra_search_q8(const void* q, const ra_index* idx, const int8_t* K8, const float* scale,
+                       ra_dtype dtq, int64_t N, int sink, int window, int topk, int ef, int expand,
+                       void* stream, int32_t* ids, ra_stats* stats);
+ra_status ra_decode_step_q8(const void* q, const ra_index* idx, const void* K, const void* V, ra_dtype dt,
+                            const int8_t* K8, const float* scale, int64_t N, int sink, int window,
+                            int topk, int ef, int expand, void* stream, float* out, float* lse,
+                            int32_t* ids, ra_stats* stats);
+
 /* what: 0 n_seq, 1 n_q_heads, 2 n_kv_heads, 3 N, 4 deg, 5 bytes of device memory owned,
  * 6 whether ra_decode_step will use helper workgroups (1 / 0; synchronises the device). */
 int64_t ra_index_info(const ra_index* idx, int what);

@@ -50,6 +50,13 @@ def lib() -> C.CDLL:
     L.ra_build_index.argtypes = [vp, vp, i32, i32, i32, i32, i64, i64, i32, i32, i32, vp,
                                  C.POINTER(vp)]
     L.ra_search.argtypes = [vp, vp, vp, i32, i64, i32, i32, i32, i32, i32, vp, vp, vp]
+    L.ra_quantize_keys.argtypes = [vp, i32, i32, i32, i64, vp, vp, vp]
+    L.ra_quantize_keys.restype = i32
+    L.ra_search_q8.argtypes = [vp, vp, vp, vp, i32, i64, i32, i32, i32, i32, i32, vp, vp, vp]
+    L.ra_search_q8.restype = i32
+    L.ra_decode_step_q8.argtypes = [vp, vp, vp, vp, i32, vp, vp, i64, i32, i32, i32, i32, i32, vp, vp, vp,
+                                    vp, vp]
+    L.ra_decode_step_q8.restype = i32
     L.ra_attend.argtypes = [vp, vp, vp, vp, i32, i64, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp]
     L.ra_decode_step.argtypes = [vp, vp, vp, vp, i32, i64, i32, i32, i32, i32, i32, vp, vp, vp,
                                  vp, vp]
@@ -213,16 +220,34 @@ def _stats_tensor(n_heads, device):
     return torch.zeros((n_heads, 4), dtype=torch.int32, device=device)
 
 
+def ra_quantize_keys(K, stream=None):
+    """8-bit copy of the keys for the search -> (K8 int8 [n_seq][n_kv][N][128], scale float32
+    [n_seq][n_kv][128])."""
+    _dev(K)
+    n_seq, n_kv, N, d = K.shape
+    K8 = torch.empty((n_seq, n_kv, N, d), dtype=torch.int8, device=K.device)
+    scale = torch.empty((n_seq, n_kv, d), dtype=torch.float32, device=K.device)
+    _check(lib().ra_quantize_keys(_ptr(K), _dt(K), n_seq, n_kv, N, _stream(stream), _ptr(K8), _ptr(scale)))
+    return K8, scale
+
+
 def ra_search(q, idx: Index, K, sink: int, window: int, topk: int, ef: int, expand: int = 1,
-              stream=None, with_stats: bool = True):
+              stream=None, with_stats: bool = True, k8=None):
     """-> (ids int32 [n_seq][n_q][topk], stats int32 [n_seq][n_q][4] = visited, expanded,
-    iters, returned)."""
-    _dev(q, K)
+    iters, returned). With k8 = (K8, scale) from ra_quantize_keys the walk reads the 8-bit keys
+    (ra_search_q8) and K may be None."""
     n_seq, n_q, d = q.shape
     ids = torch.empty((n_seq, n_q, topk), dtype=torch.int32, device=q.device)
     st = _stats_tensor(n_seq * n_q, q.device) if with_stats else None
-    _check(lib().ra_search(_ptr(q), idx.handle, _ptr(K), _dt(K), K.shape[2], sink, window, topk,
-                           ef, expand, _stream(stream), _ptr(ids), _ptr(st)))
+    if k8 is None:
+        _dev(q, K)
+        _check(lib().ra_search(_ptr(q), idx.handle, _ptr(K), _dt(K), K.shape[2], sink, window, topk,
+                               ef, expand, _stream(stream), _ptr(ids), _ptr(st)))
+    else:
+        K8, scale = k8
+        _dev(q, K8, scale)
+        _check(lib().ra_search_q8(_ptr(q), idx.handle, _ptr(K8), _ptr(scale), _dt(q), K8.shape[2], sink,
+                                  window, topk, ef, expand, _stream(stream), _ptr(ids), _ptr(st)))
     return ids, (st.view(n_seq, n_q, 4) if with_stats else None)
 
 
@@ -246,10 +271,11 @@ def ra_attend(q, idx: Index, K, V, sink: int, window: int, ids: torch.Tensor, st
 
 def ra_decode_step(q, idx: Index, K, V, sink: int, window: int, topk: int, ef: int,
                    expand: int = 1, stream=None, out=None, lse=None, ids=None, stats=None,
-                   n_tokens: Optional[int] = None):
+                   n_tokens: Optional[int] = None, k8=None):
     """One layer's decode-step attention. Output tensors may be passed in to avoid
     allocation; -> (out, lse, ids, stats). With n_tokens given, K/V are caches of capacity
-    K.shape[2] rows per head holding n_tokens >= idx.N valid tokens (ra_decode_step_grown)."""
+    K.shape[2] rows per head holding n_tokens >= idx.N valid tokens (ra_decode_step_grown). With
+    k8 = (K8, scale) from ra_quantize_keys the walk reads the 8-bit keys (ra_decode_step_q8)."""
     _dev(q, K, V, out, lse, ids, stats)
     n_seq, n_q, d = q.shape
     f = dict(dtype=torch.float32, device=q.device)
@@ -261,7 +287,13 @@ def ra_decode_step(q, idx: Index, K, V, sink: int, window: int, topk: int, ef: i
         ids = torch.empty((n_seq, n_q, topk), dtype=torch.int32, device=q.device)
     if stats is None:
         stats = _stats_tensor(n_seq * n_q, q.device).view(n_seq, n_q, 4)
-    if n_tokens is None:
+    if k8 is not None:
+        K8, scale = k8
+        _dev(K8, scale)
+        _check(lib().ra_decode_step_q8(_ptr(q), idx.handle, _ptr(K), _ptr(V), _dt(K), _ptr(K8), _ptr(scale),
+                                       K.shape[2], sink, window, topk, ef, expand, _stream(stream),
+                                       _ptr(out), _ptr(lse), _ptr(ids), _ptr(stats)))
+    elif n_tokens is None:
         _check(lib().ra_decode_step(_ptr(q), idx.handle, _ptr(K), _ptr(V), _dt(K), K.shape[2], sink,
                                     window, topk, ef, expand, _stream(stream), _ptr(out), _ptr(lse),
                                     _ptr(ids), _ptr(stats)))

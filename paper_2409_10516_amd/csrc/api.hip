@@ -305,8 +305,9 @@ extern "C" ra_status ra_build_index(const void* K, const void* Q, ra_dtype dt, i
 }
 
 // ---- decode step -----------------------------------------------------------------------
-extern "C" ra_status ra_search(const void* q, const ra_index* idx, const void* K, ra_dtype dt,
-                               int64_t N, int sink, int window, int topk, int ef, int expand,
+// `K` holds the keys the walk scores: the cache's own (kscale == NULL) or their 8-bit copy
+static ra_status search_common(const void* q, const ra_index* idx, const void* K, const float* kscale,
+                               ra_dtype dt, int64_t N, int sink, int window, int topk, int ef, int expand,
                                void* stream, int32_t* ids, ra_stats* stats) {
     if (!q || !K || !ids) RA_FAIL(RA_EINVAL, "NULL argument");
     RA_TRY(check_dtype(dt));
@@ -318,8 +319,31 @@ extern "C" ra_status ra_search(const void* q, const ra_index* idx, const void* K
         RA_TRY(grow((void**)&ix->bitset, &ix->bitset_bytes, need));
     }
     return ra_launch_search(q, ix->adj, ix->entry, K, dt, ix->n_seq, ix->n_q, ix->n_kv, N, ix->deg,
-                            sink, window, topk, ef, expand, ix->bitset, ix->roots, ix->root_cap,
+                            sink, window, topk, ef, expand, ix->bitset, ix->roots, ix->root_cap, kscale,
                             (hipStream_t)stream, ids, stats);
+}
+
+extern "C" ra_status ra_search(const void* q, const ra_index* idx, const void* K, ra_dtype dt,
+                               int64_t N, int sink, int window, int topk, int ef, int expand,
+                               void* stream, int32_t* ids, ra_stats* stats) {
+    return search_common(q, idx, K, nullptr, dt, N, sink, window, topk, ef, expand, stream, ids, stats);
+}
+
+extern "C" ra_status ra_search_q8(const void* q, const ra_index* idx, const int8_t* K8, const float* scale,
+                                  ra_dtype dtq, int64_t N, int sink, int window, int topk, int ef,
+                                  int expand, void* stream, int32_t* ids, ra_stats* stats) {
+    if (!scale) RA_FAIL(RA_EINVAL, "NULL argument");
+    return search_common(q, idx, K8, scale, dtq, N, sink, window, topk, ef, expand, stream, ids, stats);
+}
+
+extern "C" ra_status ra_quantize_keys(const void* K, ra_dtype dt, int n_seq, int n_kv, int64_t N,
+                                      void* stream, int8_t* K8, float* scale) {
+    if (!K || !K8 || !scale) RA_FAIL(RA_EINVAL, "NULL argument");
+    RA_TRY(check_dtype(dt));
+    if (n_seq < 1 || n_kv < 1) RA_FAIL(RA_EINVAL, "n_seq and n_kv_heads must be positive");
+    if (N < 1) RA_FAIL(RA_EINVAL, "N must be positive");
+    if ((int64_t)n_seq * n_kv > 65535) RA_FAIL(RA_EUNSUP, "more than 65535 (sequence, KV head) pairs");
+    return ra_launch_quantize(K, dt, n_seq * n_kv, N, (hipStream_t)stream, K8, scale);
 }
 
 extern "C" ra_status ra_attend(const void* q, const ra_index* idx, const void* K, const void* V,
@@ -338,11 +362,11 @@ extern "C" ra_status ra_attend(const void* q, const ra_index* idx, const void* K
                             lse_w);
 }
 
-extern "C" ra_status ra_decode_step_grown(const void* q, const ra_index* idx, const void* K,
-                                          const void* V, ra_dtype dt, int64_t N, int64_t kv_stride,
-                                          int sink, int window, int topk, int ef, int expand,
-                                          void* stream, float* out, float* lse, int32_t* ids,
-                                          ra_stats* stats) {
+// K8 / kscale: the 8-bit copy of the keys the walk scores, or NULL for the keys themselves
+static ra_status decode_common(const void* q, const ra_index* idx, const void* K, const void* V,
+                               ra_dtype dt, const int8_t* K8, const float* kscale, int64_t N,
+                               int64_t kv_stride, int sink, int window, int topk, int ef, int expand,
+                               void* stream, float* out, float* lse, int32_t* ids, ra_stats* stats) {
     if (!q || !K || !V || !out || !lse) RA_FAIL(RA_EINVAL, "NULL argument");
     RA_TRY(check_dtype(dt));
     if (!idx) RA_FAIL(RA_EINVAL, "index handle is NULL");
@@ -364,8 +388,29 @@ extern "C" ra_status ra_decode_step_grown(const void* q, const ra_index* idx, co
         RA_TRY(grow((void**)&ix->bitset, &ix->bitset_bytes, heads * ((ix->N + 31) >> 5) * 4));
     return ra_launch_decode(q, ix->adj, ix->entry, K, V, dt, ix->n_seq, ix->n_q, ix->n_kv, ix->N, N,
                             kv_stride, ix->deg, sink, window, topk, ef, expand, ix->bitset, ix->coop,
-                            ix->coop_mode, ix->coop_spin, ix->roots, ix->root_cap, (hipStream_t)stream, out,
-                            lse, ids, stats);
+                            ix->coop_mode, ix->coop_spin, ix->roots, ix->root_cap, K8, kscale,
+                            (hipStream_t)stream, out, lse, ids, stats);
+}
+
+extern "C" ra_status ra_decode_step_grown(const void* q, const ra_index* idx, const void* K,
+                                          const void* V, ra_dtype dt, int64_t N, int64_t kv_stride,
+                                          int sink, int window, int topk, int ef, int expand,
+                                          void* stream, float* out, float* lse, int32_t* ids,
+                                          ra_stats* stats) {
+    return decode_common(q, idx, K, V, dt, nullptr, nullptr, N, kv_stride, sink, window, topk, ef, expand,
+                         stream, out, lse, ids, stats);
+}
+
+extern "C" ra_status ra_decode_step_q8(const void* q, const ra_index* idx, const void* K, const void* V,
+                                       ra_dtype dt, const int8_t* K8, const float* scale, int64_t N,
+                                       int sink, int window, int topk, int ef, int expand, void* stream,
+                                       float* out, float* lse, int32_t* ids, ra_stats* stats) {
+    if (!K8 || !scale) RA_FAIL(RA_EINVAL, "NULL argument");
+    if (idx && N != idx->N)
+        RA_FAIL(RA_ESHAPE, "N = %lld but the index was built over %lld keys", (long long)N,
+                (long long)idx->N);
+    return decode_common(q, idx, K, V, dt, K8, scale, N, N, sink, window, topk, ef, expand, stream, out,
+                         lse, ids, stats);
 }
 
 extern "C" ra_status ra_decode_step(const void* q, const ra_index* idx, const void* K, const void* V,

@@ -55,13 +55,16 @@ struct ra_index {
 };
 
 #define RA_COOP_REC 132
+#define RA_KEYS_I8 2          /* key type of a search over 8-bit keys (beside RA_F32, RA_BF16) */
 
 // ---- launchers implemented in the .hip files (all enqueue on `st`, no sync) ----------
 ra_status ra_launch_search(const void* q, const int32_t* adj, const int32_t* entry, const void* K,
                            ra_dtype dt, int n_seq, int n_q, int n_kv, int64_t N, int deg,
                            int sink, int window, int topk, int ef, int expand, uint32_t* bitset,
-                           const int32_t* roots, int root_cap, hipStream_t st, int32_t* ids,
-                           ra_stats* stats);
+                           const int32_t* roots, int root_cap, const float* kscale, hipStream_t st,
+                           int32_t* ids, ra_stats* stats);
+ra_status ra_launch_quantize(const void* K, ra_dtype dt, int n_groups, int64_t N, hipStream_t st,
+                             int8_t* K8, float* scale);
 ra_status ra_launch_roots(const int32_t* adj, const int32_t* entry, int heads, int64_t N, int deg,
                           int32_t* roots, int cap, hipStream_t st);
 size_t ra_search_lds_bytes(int64_t N, int deg, int ef, int expand, bool global_bitset);
@@ -80,7 +83,8 @@ ra_status ra_launch_decode(const void* q, const int32_t* adj, const int32_t* ent
                            const void* V, ra_dtype dt, int n_seq, int n_q, int n_kv, int64_t Ng, int64_t N,
                            int64_t kv_stride, int deg, int sink, int window, int topk, int ef, int expand,
                            uint32_t* bitset, float* coop, int coop_mode, int coop_spin,
-                           const int32_t* roots, int root_cap, hipStream_t st, float* out, float* lse, int32_t* ids,
+                           const int32_t* roots, int root_cap, const void* K8, const float* kscale,
+                           hipStream_t st, float* out, float* lse, int32_t* ids,
                            ra_stats* stats);
 
 ra_status ra_launch_flat_topk(const void* q, const void* K, ra_dtype dt, int n_seq, int n_q, int n_kv,

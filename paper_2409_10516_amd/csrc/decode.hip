@@ -259,7 +259,7 @@ struct AwaitHelper {
     }
 };
 
-template <int DT, bool GBITS, int T>
+template <int DT, int KT, bool GBITS, int T>
 __global__ __launch_bounds__(T) void decode_kernel(
     const void* __restrict__ q, const int32_t* __restrict__ adj, const int32_t* __restrict__ entry,
     const void* __restrict__ K, const void* __restrict__ V, int n_q, int n_kv, int64_t Ng, int64_t N,
@@ -267,7 +267,8 @@ __global__ __launch_bounds__(T) void decode_kernel(
     uint32_t* __restrict__ gbits,
     int32_t* __restrict__ ids, ra_stats* __restrict__ stats, int ids_off, float scale,
     float* __restrict__ out, float* __restrict__ lse, float* coop, int n_helpers, int coop_mode,
-    int coop_spin, const int32_t* __restrict__ roots, int root_cap) {
+    int coop_spin, const int32_t* __restrict__ roots, int root_cap, const void* __restrict__ Ksearch,
+    const float* __restrict__ kscale) {
     extern __shared__ __align__(16) unsigned char lds_raw[];
     const int tid = threadIdx.x, grp = tid >> 4, lane16 = tid & 15;
     const size_t esz = DT == RA_BF16 ? 2 : 4;
@@ -300,9 +301,10 @@ __global__ __launch_bounds__(T) void decode_kernel(
     const char* Vh = reinterpret_cast<const char*>(V) + ((size_t)seq * n_kv + kvh) * kv_stride * RA_D * esz;
     // The graph covers the first Ng of the N tokens now in the cache; W = [0, s) u [wstart, N) with
     // wstart <= Ng, so every token appended after the build is attended densely.
-    const int cnt = run_search<DT, GBITS, T>(lds_raw, head, q, adj, entry, K, n_q, n_kv, Ng, kv_stride, deg,
+    // the walk scores Ksearch: K itself, or its 8-bit copy (with kscale)
+    const int cnt = run_search<DT, KT, GBITS, T>(lds_raw, head, q, adj, entry, Ksearch, n_q, n_kv, Ng, kv_stride, deg,
                                           s, (int)(Ng - wstart), topk, ef, expand, gbits, ids, stats,
-                                          lds_ids, roots, root_cap,
+                                          lds_ids, roots, root_cap, kscale,
                                           AwaitHelper{ready + head, ready + n_heads, lds_word,
                                                                coop_spin, helpers});
 #ifdef SR_PHASE_CLOCKS
@@ -416,8 +418,8 @@ ra_status ra_launch_decode(const void* q, const int32_t* adj, const int32_t* ent
                            const void* V, ra_dtype dt, int n_seq, int n_q, int n_kv, int64_t Ng, int64_t N,
                            int64_t kv_stride, int deg, int sink, int window, int topk, int ef, int expand,
                            uint32_t* bitset, float* coop, int coop_mode, int coop_spin,
-                           const int32_t* roots, int root_cap, hipStream_t st,
-                           float* out, float* lse, int32_t* ids, ra_stats* stats) {
+                           const int32_t* roots, int root_cap, const void* K8, const float* kscale,
+                           hipStream_t st, float* out, float* lse, int32_t* ids, ra_stats* stats) {
     // W = [0, s) u [wstart, N): the sink, the sliding window, and every token appended after the
     // index was built (wstart <= Ng); overlapping ranges make everything static
     int64_t s = sink < 0 ? 0 : sink, ww = window < 0 ? 0 : window;
@@ -445,24 +447,29 @@ ra_status ra_launch_decode(const void* q, const int32_t* adj, const int32_t* ent
     const int n_helpers = coop_on ? n_seq * n_kv : 0;
     if (!coop) RA_FAIL(RA_EINVAL, "hand-over area missing");
     const int threads = search_threads(heads, ef);
-#define RA_DC_GO_T(DTV, GB, TV)                                                                    \
+    const void* Ksearch = kscale ? K8 : K;
+    if (kscale && !K8) RA_FAIL(RA_EINVAL, "8-bit keys missing");
+#define RA_DC_GO_T(DTV, KTV, GB, TV)                                                               \
     do {                                                                                           \
-        RA_LDS_OPT_IN((decode_kernel<DTV, GB, TV>), lds);                                          \
-        hipLaunchKernelGGL((decode_kernel<DTV, GB, TV>), dim3(heads + n_helpers), dim3(TV), lds,   \
-                           st, q, adj, entry, K, V, n_q, n_kv, Ng, N, kv_stride, wstart, deg,      \
+        RA_LDS_OPT_IN((decode_kernel<DTV, KTV, GB, TV>), lds);                                     \
+        hipLaunchKernelGGL((decode_kernel<DTV, KTV, GB, TV>), dim3(heads + n_helpers), dim3(TV),   \
+                           lds, st, q, adj, entry, K, V, n_q, n_kv, Ng, N, kv_stride, wstart, deg, \
                            (int)s, topk, ef, expand, bitset, ids, stats, ids_off, scale, out, lse, \
-                           coop, n_helpers, coop_mode, coop_spin, roots, root_cap);                \
+                           coop, n_helpers, coop_mode, coop_spin, roots, root_cap, Ksearch,        \
+                           kscale);                                                                \
     } while (0)
-#define RA_DC_GO(DTV, GB)                                                                          \
+#define RA_DC_GO(DTV, KTV, GB)                                                                     \
     do {                                                                                           \
-        if (threads == 1024) RA_DC_GO_T(DTV, GB, 1024);                                            \
-        else if (threads == 512) RA_DC_GO_T(DTV, GB, 512);                                         \
-        else RA_DC_GO_T(DTV, GB, 256);                                                             \
+        if (threads == 1024) RA_DC_GO_T(DTV, KTV, GB, 1024);                                       \
+        else if (threads == 512) RA_DC_GO_T(DTV, KTV, GB, 512);                                    \
+        else RA_DC_GO_T(DTV, KTV, GB, 256);                                                        \
     } while (0)
     if (dt == RA_BF16) {
-        if (gb) RA_DC_GO(RA_BF16, true); else RA_DC_GO(RA_BF16, false);
+        if (kscale) { if (gb) RA_DC_GO(RA_BF16, RA_KEYS_I8, true); else RA_DC_GO(RA_BF16, RA_KEYS_I8, false); }
+        else if (gb) RA_DC_GO(RA_BF16, RA_BF16, true); else RA_DC_GO(RA_BF16, RA_BF16, false);
     } else {
-        if (gb) RA_DC_GO(RA_F32, true); else RA_DC_GO(RA_F32, false);
+        if (kscale) { if (gb) RA_DC_GO(RA_F32, RA_KEYS_I8, true); else RA_DC_GO(RA_F32, RA_KEYS_I8, false); }
+        else if (gb) RA_DC_GO(RA_F32, RA_F32, true); else RA_DC_GO(RA_F32, RA_F32, false);
     }
 #undef RA_DC_GO_T
 #undef RA_DC_GO

@@ -1,15 +1,16 @@
 // Stand-alone launch of the graph search (ra_search); the search itself is in search_dev.h.
 #include "search_dev.h"
 
-template <int DT, bool GBITS, int T>
+template <int DT, int KT, bool GBITS, int T>
 __global__ __launch_bounds__(T) void search_kernel(
     const void* __restrict__ q, const int32_t* __restrict__ adj, const int32_t* __restrict__ entry,
     const void* __restrict__ K, int n_q, int n_kv, int64_t N, int deg, int s, int w, int topk,
     int ef, int expand, uint32_t* __restrict__ gbits, int32_t* __restrict__ ids,
-    ra_stats* __restrict__ stats, const int32_t* __restrict__ roots, int root_cap) {
+    ra_stats* __restrict__ stats, const int32_t* __restrict__ roots, int root_cap,
+    const float* __restrict__ kscale) {
     extern __shared__ __align__(16) unsigned char lds_raw[];
-    run_search<DT, GBITS, T>(lds_raw, xcd_aware_head(blockIdx.x, gridDim.x, n_q / n_kv), q, adj, entry, K, n_q, n_kv, N, N, deg, s, w, topk, ef,
-                          expand, gbits, ids, stats, nullptr, roots, root_cap, NoHook());
+    run_search<DT, KT, GBITS, T>(lds_raw, xcd_aware_head(blockIdx.x, gridDim.x, n_q / n_kv), q, adj, entry, K, n_q, n_kv, N, N, deg, s, w, topk, ef,
+                          expand, gbits, ids, stats, nullptr, roots, root_cap, kscale, NoHook());
 }
 
 __global__ void fill_u32_kernel(uint32_t* p, size_t n, uint32_t v) {
@@ -93,8 +94,8 @@ bool ra_search_needs_global_bitset(int64_t N, int deg, int ef, int expand) {
 ra_status ra_launch_search(const void* q, const int32_t* adj, const int32_t* entry, const void* K,
                            ra_dtype dt, int n_seq, int n_q, int n_kv, int64_t N, int deg,
                            int sink, int window, int topk, int ef, int expand, uint32_t* bitset,
-                           const int32_t* roots, int root_cap, hipStream_t st, int32_t* ids,
-                           ra_stats* stats) {
+                           const int32_t* roots, int root_cap, const float* kscale, hipStream_t st,
+                           int32_t* ids, ra_stats* stats) {
     int64_t ss = sink < 0 ? 0 : sink, ww = window < 0 ? 0 : window;
     if (ss > N) ss = N;
     if (ww > N) ww = N;
@@ -111,23 +112,26 @@ ra_status ra_launch_search(const void* q, const int32_t* adj, const int32_t* ent
         hipLaunchKernelGGL(fill_u32_kernel, dim3(1024), dim3(256), 0, st, bitset, words, 0u);
     }
     const int threads = search_threads(heads, ef);
-#define RA_SR_LAUNCH_T(DTV, GB, TV)                                                               \
+#define RA_SR_LAUNCH_T(DTV, KTV, GB, TV)                                                          \
     do {                                                                                          \
-        RA_LDS_OPT_IN((search_kernel<DTV, GB, TV>), lds);                                         \
-        hipLaunchKernelGGL((search_kernel<DTV, GB, TV>), dim3(heads), dim3(TV), lds, st, q, adj,  \
-                           entry, K, n_q, n_kv, N, deg, (int)ss, (int)ww, topk, ef, expand,       \
-                           bitset, ids, stats, roots, root_cap);                                  \
+        RA_LDS_OPT_IN((search_kernel<DTV, KTV, GB, TV>), lds);                                    \
+        hipLaunchKernelGGL((search_kernel<DTV, KTV, GB, TV>), dim3(heads), dim3(TV), lds, st, q,  \
+                           adj, entry, K, n_q, n_kv, N, deg, (int)ss, (int)ww, topk, ef, expand,  \
+                           bitset, ids, stats, roots, root_cap, kscale);                          \
     } while (0)
-#define RA_SR_LAUNCH(DTV, GB)                                                                     \
+#define RA_SR_LAUNCH(DTV, KTV, GB)                                                                \
     do {                                                                                          \
-        if (threads == 1024) RA_SR_LAUNCH_T(DTV, GB, 1024);                                       \
-        else if (threads == 512) RA_SR_LAUNCH_T(DTV, GB, 512);                                    \
-        else RA_SR_LAUNCH_T(DTV, GB, 256);                                                        \
+        if (threads == 1024) RA_SR_LAUNCH_T(DTV, KTV, GB, 1024);                                  \
+        else if (threads == 512) RA_SR_LAUNCH_T(DTV, KTV, GB, 512);                               \
+        else RA_SR_LAUNCH_T(DTV, KTV, GB, 256);                                                   \
     } while (0)
+    // K holds 8-bit keys when kscale is given (the query keeps its own type dt)
     if (dt == RA_BF16) {
-        if (gb) RA_SR_LAUNCH(RA_BF16, true); else RA_SR_LAUNCH(RA_BF16, false);
+        if (kscale) { if (gb) RA_SR_LAUNCH(RA_BF16, RA_KEYS_I8, true); else RA_SR_LAUNCH(RA_BF16, RA_KEYS_I8, false); }
+        else if (gb) RA_SR_LAUNCH(RA_BF16, RA_BF16, true); else RA_SR_LAUNCH(RA_BF16, RA_BF16, false);
     } else {
-        if (gb) RA_SR_LAUNCH(RA_F32, true); else RA_SR_LAUNCH(RA_F32, false);
+        if (kscale) { if (gb) RA_SR_LAUNCH(RA_F32, RA_KEYS_I8, true); else RA_SR_LAUNCH(RA_F32, RA_KEYS_I8, false); }
+        else if (gb) RA_SR_LAUNCH(RA_F32, RA_F32, true); else RA_SR_LAUNCH(RA_F32, RA_F32, false);
     }
 #undef RA_SR_LAUNCH_T
 #undef RA_SR_LAUNCH

@@ -86,7 +86,12 @@ template <int DT> struct RowBits { uint4 a; uint4 b; };
 template <int DT>
 __device__ __forceinline__ RowBits<DT> load_key(const void* Kh, int64_t row, int lane16) {
     RowBits<DT> r;
-    if (DT == RA_BF16) {
+    if (DT == RA_KEYS_I8) {
+        // 8 of the row's 128 signed bytes
+        const uint2 u = reinterpret_cast<const uint2*>(reinterpret_cast<const int8_t*>(Kh) + row * RA_D)[lane16];
+        r.a = make_uint4(u.x, u.y, 0u, 0u);
+        r.b = r.a;
+    } else if (DT == RA_BF16) {
         r.a = reinterpret_cast<const uint4*>(reinterpret_cast<const uint16_t*>(Kh) + row * RA_D)[lane16];
         r.b = r.a;
     } else {
@@ -107,7 +112,17 @@ __device__ __forceinline__ float dpp_f32(float v) {
 template <int DT>
 __device__ __forceinline__ float score_fixed(const RowBits<DT>& r, const float* qv) {
     float acc;
-    if (DT == RA_BF16) {
+    if (DT == RA_KEYS_I8) {
+        // qv holds query * scale; the key bytes convert to float32 exactly; product rounded, then added
+        acc = __fmul_rn(qv[0], (float)(int8_t)(r.a.x));
+        acc = __fadd_rn(acc, __fmul_rn(qv[1], (float)(int8_t)(r.a.x >> 8)));
+        acc = __fadd_rn(acc, __fmul_rn(qv[2], (float)(int8_t)(r.a.x >> 16)));
+        acc = __fadd_rn(acc, __fmul_rn(qv[3], (float)(int8_t)(r.a.x >> 24)));
+        acc = __fadd_rn(acc, __fmul_rn(qv[4], (float)(int8_t)(r.a.y)));
+        acc = __fadd_rn(acc, __fmul_rn(qv[5], (float)(int8_t)(r.a.y >> 8)));
+        acc = __fadd_rn(acc, __fmul_rn(qv[6], (float)(int8_t)(r.a.y >> 16)));
+        acc = __fadd_rn(acc, __fmul_rn(qv[7], (float)(int8_t)(r.a.y >> 24)));
+    } else if (DT == RA_BF16) {
         // bf16 x bf16 products are exact in float32, so fma == multiply-then-add here
         acc = qv[0] * bf16_lo(r.a.x);
         acc = fmaf(qv[1], bf16_hi(r.a.x), acc);
@@ -225,18 +240,19 @@ struct NoHook {
     __device__ __forceinline__ void before_output() const {}
 };
 
-template <int DT, bool GBITS, int T, typename Hook>
+template <int DT, int KT, bool GBITS, int T, typename Hook>
 __device__ __forceinline__ int run_search(
     unsigned char* lds_raw, int head, const void* __restrict__ q, const int32_t* __restrict__ adj,
     const int32_t* __restrict__ entry, const void* __restrict__ K, int n_q, int n_kv, int64_t N,
     int64_t kv_stride, int deg, int s, int w, int topk, int ef, int expand, uint32_t* __restrict__ gbits,
     int32_t* __restrict__ ids, ra_stats* __restrict__ stats, int32_t* lds_ids,
-    const int32_t* __restrict__ roots, int root_cap, const Hook& hook) {
+    const int32_t* __restrict__ roots, int root_cap, const float* __restrict__ kscale, const Hook& hook) {
     const int tid = threadIdx.x, grp = tid >> 4, lane16 = tid & 15;
     const int lane = tid & (RA_WAVE - 1), wv = tid / RA_WAVE;
     const int seq = head / n_q, h = head % n_q, kvh = h / (n_q / n_kv);
-    const size_t esz = DT == RA_BF16 ? 2 : 4;
-    const char* Kh = reinterpret_cast<const char*>(K) + ((size_t)seq * n_kv + kvh) * kv_stride * RA_D * esz;
+    const size_t esz = DT == RA_BF16 ? 2 : 4;                                   // of the query
+    const size_t ksz = KT == RA_KEYS_I8 ? 1 : KT == RA_BF16 ? 2 : 4;            // of the keys the walk scores
+    const char* Kh = reinterpret_cast<const char*>(K) + ((size_t)seq * n_kv + kvh) * kv_stride * RA_D * ksz;
     const int32_t* adj_h = adj + (size_t)head * N * deg;
     const int maxc = expand * deg;
     const int nwords = (int)((N + 31) >> 5);
@@ -261,6 +277,12 @@ __device__ __forceinline__ int run_search(
 
     float qv[8];
     load_q8<DT>(reinterpret_cast<const char*>(q) + (size_t)head * RA_D * esz, lane16, qv);
+    if (KT == RA_KEYS_I8) {
+        // 8-bit keys: k ~ k8 * scale per dimension, so the walk scores <q * scale, k8>
+        const float* sc = kscale + ((size_t)seq * n_kv + kvh) * RA_D + lane16 * 8;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) qv[e] = __fmul_rn(qv[e], sc[e]);
+    }
     const int e0 = entry[head];
     // The first two steps of a walk do not depend on the query: the entry point is expanded, then
     // all its neighbours are (when `expand` and ef are at least their number). What they visit,
@@ -299,8 +321,8 @@ __device__ __forceinline__ int run_search(
         bn = 0; n_visited = 0; n_expanded = 0; n_iters = 0;
     } else {
         if (grp == 0) {
-            const RowBits<DT> r = load_key<DT>(Kh, e0, lane16);
-            const float sc = score_fixed<DT>(r, qv);
+            const RowBits<KT> r = load_key<KT>(Kh, e0, lane16);
+            const float sc = score_fixed<KT>(r, qv);
             if (tid == 0) {
                 // the beam is the entry point alone, and the first step can only pick it: leave the
                 // state a merge would leave (pick in place, flag cleared, counts of unexpanded entries)
@@ -418,7 +440,7 @@ __device__ __forceinline__ int run_search(
         // ---- gather and score the new candidates; keep those that can enter the beam
         const u64 worst = bn == ef ? (cur[bn - 1] >> 1) : 0ull;
         for (int c0 = 0; c0 < nc; c0 += (T / 16) * SR_UNROLL) {
-            RowBits<DT> rows[SR_UNROLL];
+            RowBits<KT> rows[SR_UNROLL];
             int cidv[SR_UNROLL];
 #pragma unroll
             for (int u = 0; u < SR_UNROLL; ++u) {
@@ -426,12 +448,12 @@ __device__ __forceinline__ int run_search(
                 const int c = c0 + u * (T / 16) + grp;
                 cidv[u] = c < nc ? cid[c] : -1;
                 // groups without a candidate re-read the entry row instead of branching
-                rows[u] = load_key<DT>(Kh, cidv[u] >= 0 ? cidv[u] : e0, lane16);
+                rows[u] = load_key<KT>(Kh, cidv[u] >= 0 ? cidv[u] : e0, lane16);
             }
 #pragma unroll
             for (int u = 0; u < SR_UNROLL; ++u) {
                 if (c0 + u * (T / 16) >= nc) break;
-                const float sc = score_fixed<DT>(rows[u], qv);
+                const float sc = score_fixed<KT>(rows[u], qv);
                 if (lane16 == 0 && cidv[u] >= 0) {
                     u64 key = make_key(sc, cidv[u]);
                     // in the doubled first step the entry point and its neighbours, the first

@@ -1,0 +1,100 @@
+"""8-bit keys for the search: the device's quantised bytes and scales, the walk over them, and the
+decode step built on it, element by element against the oracle (oracle/quant.py + search.py)."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2409_10516_amd as ra
+from oracle import attention as OA, mips as OM, quant as OQ, search as OS
+from paper_2409_10516_amd import synth
+from tests.util import lse_close, oracle_graphs, out_close, to_np, tol_for
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def _cases():
+    return {
+        "llama_bf16": lambda: synth.make_llama_layer(51, N=1536, M=512, T=2, n_q=8, n_kv=2, ef=64, topk=20,
+                                                     window=100),
+        "llama_f32_2seq": lambda: synth.make_llama_layer(52, N=700, M=300, T=2, n_seq=2, n_q=4, n_kv=2,
+                                                         dtype=torch.float32, ef=48, topk=16, window=37,
+                                                         deg=12, knn=9),
+        "integer_ties": lambda: synth.make_integer_case(6, N=300, M=64, T=3, d=128, n_q=2, n_kv=1, deg=8,
+                                                        knn=6, topk=9, ef=20, sink=3, window=10),
+    }
+
+
+@pytest.mark.parametrize("name", list(_cases()))
+def test_quantised_bytes_and_scales_are_the_oracles(name):
+    w = _cases()[name]()
+    K8, scale = ra.ra_quantize_keys(w.K.to(DEV))
+    K8, scale = K8.cpu().numpy(), scale.cpu().numpy()
+    n_seq, n_kv = w.K.shape[:2]
+    for s in range(n_seq):
+        for g in range(n_kv):
+            r8, rs = OQ.quantize_keys(to_np(w.K[s, g]))
+            assert np.array_equal(scale[s, g].view(np.uint32), rs.view(np.uint32)), (s, g)
+            assert np.array_equal(K8[s, g], r8), (s, g)
+
+
+def test_quantise_zero_column_and_ragged_row_count():
+    K = torch.randn(1, 1, 1001, 128).bfloat16()
+    K[0, 0, :, 5] = 0
+    K8, scale = ra.ra_quantize_keys(K.to(DEV))
+    r8, rs = OQ.quantize_keys(to_np(K[0, 0]))
+    assert float(scale[0, 0, 5]) == 1.0 and int(K8[0, 0, :, 5].abs().max()) == 0
+    assert np.array_equal(K8[0, 0].cpu().numpy(), r8) and np.array_equal(scale[0, 0].cpu().numpy(), rs)
+
+
+@pytest.mark.parametrize("name", list(_cases()))
+@pytest.mark.parametrize("expand", [1, 16])
+def test_search_and_decode_over_8bit_keys(name, expand):
+    """Ids and counters bit-exact against the oracle's walk on (q * scale, K8); the decode output is
+    Eq. 2 / Eq. 4-5 over those ids and W with the original K and V, within the usual tolerance."""
+    w = _cases()[name]()
+    adj, ent, _ = oracle_graphs(w)
+    n_seq, n_kv, N, d = w.K.shape
+    n_q = w.Q_prefill.shape[1]
+    G = n_q // n_kv
+    idx = ra.ra_index_import(torch.from_numpy(adj), torch.from_numpy(ent), n_seq, n_q, n_kv)
+    Kd, Vd = w.K.to(DEV), w.V.to(DEV)
+    k8 = ra.ra_quantize_keys(Kd)
+    tol = tol_for(w.K.dtype)
+    W = OA.static_ids(N, w.sink, w.window)
+    quant = {(s, g): OQ.quantize_keys(to_np(w.K[s, g])) for s in range(n_seq) for g in range(n_kv)}
+    for t in range(w.q_decode.shape[0]):
+        q = w.q_decode[t].to(DEV)
+        ids_s, st_s = ra.ra_search(q, idx, None, w.sink, w.window, w.topk, w.ef, expand, k8=k8)
+        out, lse, ids, st = ra.ra_decode_step(q, idx, Kd, Vd, w.sink, w.window, w.topk, w.ef, expand, k8=k8)
+        for s in range(n_seq):
+            for h in range(n_q):
+                g = s * n_q + h
+                r8, rs = quant[s, h // G]
+                qh = to_np(w.q_decode[t, s, h])
+                r_ids, rst = OS.greedy_search(OQ.scaled_query(qh, rs), r8.astype(np.float32), adj[g], ent[g],
+                                              w.ef, w.topk, expand, exclude=W)
+                want = [rst["n_visited"], rst["n_expanded"], rst["n_iters"], rst["n_returned"]]
+                assert ids_s[s, h].tolist() == r_ids.tolist() and st_s[s, h].tolist() == want, (t, s, h)
+                assert ids[s, h].tolist() == r_ids.tolist() and st[s, h].tolist() == want, (t, s, h)
+                K, V = to_np(w.K[s, h // G]), to_np(w.V[s, h // G])
+                o_o, l_o = OA.partial_attention(qh, K, V, r_ids[r_ids >= 0])
+                o_w, l_w = OA.partial_attention(qh, K, V, W)
+                r_out, r_lse = OA.merge(o_w, l_w, o_o, l_o)
+                assert out_close(out[s, h].cpu().numpy(), r_out, tol)
+                assert lse_close(lse[s, h].cpu().numpy(), r_lse, tol)
+    idx.free()
+
+
+def test_8bit_walk_keeps_recall_on_a_32k_layer():
+    w = synth.make_llama_layer(53, N=32768, M=32768, T=2, n_q=4, n_kv=1, device=DEV)
+    idx = ra.ra_build_index(w.K, w.Q_prefill, w.deg, w.knn)
+    k8 = ra.ra_quantize_keys(w.K)
+    rec = []
+    for t in range(2):
+        ids, _ = ra.ra_search(w.q_decode[t], idx, None, w.sink, w.window, w.topk, w.ef, 32, k8=k8)
+        truth = ra.ra_flat_topk(w.q_decode[t], w.K, w.sink, w.window, w.topk)
+        for h in range(4):
+            rec.append(OM.recall(ids[0, h].cpu().numpy(), truth[0, h].cpu().numpy()))
+    assert np.mean(rec) > 0.9, np.mean(rec)
+    idx.free()
