@@ -59,6 +59,21 @@ def knn_lists(Q, K, knn, chunk=2048):
     return out, sc
 
 
+def rerank(q, K, cand, k, score_fn=None):
+    """Re-ranking of a candidate list with the keys themselves (what follows a walk over 8-bit
+    keys): the best k of the distinct ids in `cand` (-1 entries ignored) under <q, K[id]>, best
+    first, padded with -1 to length k. Scores as in topk_bruteforce."""
+    cand = np.asarray([c for c in np.asarray(cand).tolist() if c >= 0], np.int64)
+    out = np.full(k, -1, np.int32)
+    if cand.size == 0:
+        return out
+    rows = np.asarray(K)[cand]
+    s = scores_f64(q, rows) if score_fn is None else np.asarray(score_fn(q, rows))
+    order = rank_order(s, cand)[:k]
+    out[:order.size] = cand[order]
+    return out
+
+
 def recall(retrieved, truth):
     """Overlap ratio between retrieved ids and the ground-truth top-k (Sec. 2.4)."""
     truth = [int(t) for t in truth if t >= 0]

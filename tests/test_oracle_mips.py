@@ -65,3 +65,19 @@ def test_recall():
     assert mips.recall([4, 3, 2, 1], [1, 2, 3, 4]) == 1.0
     assert mips.recall([], [1, 2]) == 0.0
     assert mips.recall([7, 8], [-1, -1]) == 1.0
+
+
+def test_rerank_is_bruteforce_restricted_to_the_candidates():
+    """rerank(q, K, cand, k) must equal the exact top-k over all keys with everything outside
+    `cand` excluded; -1 entries are ignored and short lists are padded."""
+    rng = np.random.default_rng(11)
+    K = rng.standard_normal((400, 32))
+    q = rng.standard_normal(32)
+    cand = rng.choice(400, size=60, replace=False)
+    outside = np.setdiff1d(np.arange(400), cand)
+    want = mips.topk_bruteforce(q, K, 10, exclude=outside)
+    got = mips.rerank(q, K, np.concatenate([cand[:30], [-1, -1], cand[30:]]), 10)
+    assert got.tolist() == want.tolist()
+    short = mips.rerank(q, K, [5, -1, 9], 4)
+    assert sorted(short[:2].tolist()) == [5, 9] and short[2:].tolist() == [-1, -1]
+    assert mips.rerank(q, K, [-1, -1], 3).tolist() == [-1, -1, -1]
