@@ -180,6 +180,13 @@ ra_status ra_quantize_keys(const void* K, ra_dtype dt, int n_seq, int n_kv_heads
 ra_status ra_search_q8(const void* q, const ra_index* idx, const int8_t* K8, const float* scale,
                        ra_dtype dtq, int64_t N, int sink, int window, int topk, int ef, int expand,
                        void* stream, int32_t* ids, ra_stats* stats);
+/* Re-ranking with the keys themselves, for a candidate list that came from the 8-bit walk (call
+ * ra_search_q8 with a topk of n_cand, then this, then ra_attend): of the distinct ids in cand
+ * [n_seq][n_q_heads][n_cand] (-1 and ids >= N are skipped) the best topk under <q, K[id]>, the
+ * fixed-order float32 score of ra_search, score descending then id ascending -> ids
+ * [n_seq][n_q_heads][topk], padded with -1. 1 <= topk <= n_cand <= RA_MAX_TOPK. */
+ra_status ra_rerank(const void* q, const void* K, ra_dtype dt, int n_seq, int n_q_heads, int n_kv_heads,
+                    int64_t N, int d, const int32_t* cand, int n_cand, int topk, void* stream, int32_t* ids);
 ra_status ra_decode_step_q8(const void* q, const ra_index* idx, const void* K, const void* V, ra_dtype dt,
                             const int8_t* K8, const float* scale, int64_t N, int sink, int window,
                             int topk, int ef, int expand, void* stream, float* out, float* lse,

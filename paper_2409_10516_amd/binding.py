@@ -57,6 +57,8 @@ def lib() -> C.CDLL:
     L.ra_decode_step_q8.argtypes = [vp, vp, vp, vp, i32, vp, vp, i64, i32, i32, i32, i32, i32, vp, vp, vp,
                                     vp, vp]
     L.ra_decode_step_q8.restype = i32
+    L.ra_rerank.argtypes = [vp, vp, i32, i32, i32, i32, i64, i32, vp, i32, i32, vp, vp]
+    L.ra_rerank.restype = i32
     L.ra_attend.argtypes = [vp, vp, vp, vp, i32, i64, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp]
     L.ra_decode_step.argtypes = [vp, vp, vp, vp, i32, i64, i32, i32, i32, i32, i32, vp, vp, vp,
                                  vp, vp]
@@ -249,6 +251,17 @@ def ra_search(q, idx: Index, K, sink: int, window: int, topk: int, ef: int, expa
         _check(lib().ra_search_q8(_ptr(q), idx.handle, _ptr(K8), _ptr(scale), _dt(q), K8.shape[2], sink,
                                   window, topk, ef, expand, _stream(stream), _ptr(ids), _ptr(st)))
     return ids, (st.view(n_seq, n_q, 4) if with_stats else None)
+
+
+def ra_rerank(q, K, cand, topk: int, stream=None):
+    """Best topk of the candidate ids [n_seq][n_q][n_cand] under the exact scores <q, K[id]>
+    -> ids int32 [n_seq][n_q][topk]."""
+    _dev(q, K, cand)
+    n_seq, n_q, d = q.shape
+    ids = torch.empty((n_seq, n_q, topk), dtype=torch.int32, device=q.device)
+    _check(lib().ra_rerank(_ptr(q), _ptr(K), _dt(K), n_seq, n_q, K.shape[1], K.shape[2], d, _ptr(cand),
+                           cand.shape[-1], topk, _stream(stream), _ptr(ids)))
+    return ids
 
 
 def ra_attend(q, idx: Index, K, V, sink: int, window: int, ids: torch.Tensor, stream=None,

@@ -424,6 +424,19 @@ extern "C" ra_status ra_decode_step(const void* q, const ra_index* idx, const vo
                                 ids, stats);
 }
 
+extern "C" ra_status ra_rerank(const void* q, const void* K, ra_dtype dt, int n_seq, int n_q, int n_kv,
+                               int64_t N, int d, const int32_t* cand, int n_cand, int topk, void* stream,
+                               int32_t* ids) {
+    if (!q || !K || !cand || !ids) RA_FAIL(RA_EINVAL, "NULL argument");
+    RA_TRY(check_dtype(dt));
+    RA_TRY(check_heads(n_seq, n_q, n_kv));
+    RA_TRY(check_dim(d));
+    if (N < 1) RA_FAIL(RA_EINVAL, "N must be positive");
+    if (topk < 1 || n_cand < topk) RA_FAIL(RA_EINVAL, "need 1 <= topk <= n_cand (got %d, %d)", topk, n_cand);
+    if (n_cand > RA_MAX_TOPK) RA_FAIL(RA_EUNSUP, "n_cand %d exceeds RA_MAX_TOPK %d", n_cand, RA_MAX_TOPK);
+    return ra_launch_rerank(q, K, dt, n_seq, n_q, n_kv, N, cand, n_cand, topk, (hipStream_t)stream, ids);
+}
+
 // ---- exact baselines (the paper's "Flat" retrieval and full attention) ---------------------
 extern "C" size_t ra_flat_workspace_bytes(int n_seq, int n_q_heads, int64_t N) {
     if (n_seq < 1 || n_q_heads < 1 || N < 1) return 0;

@@ -226,6 +226,74 @@ __global__ __launch_bounds__(FL_SEL_T) void flat_select_kernel(const uint32_t* _
         out[i] = i < n ? (int32_t)(0xffffffffu - (uint32_t)sel[i]) : -1;
 }
 
+// Re-ranking of a candidate list with the keys themselves (what follows a walk over 8-bit keys):
+// one workgroup per (sequence, query head) scores its candidates with the search's fixed-order
+// inner product (16 lanes per key row), ranks them by counting, and writes the best topk.
+#define RR_THREADS 256
+#define RR_ROWS 4                  // key rows in flight per 16-lane group
+template <int DT>
+__global__ __launch_bounds__(RR_THREADS) void rerank_kernel(const void* __restrict__ q,
+                                                            const void* __restrict__ K, int n_q, int n_kv,
+                                                            int64_t N, const int32_t* __restrict__ cand,
+                                                            int n_cand, int topk, int32_t* __restrict__ ids) {
+    __shared__ unsigned long long keys[RA_MAX_TOPK];
+    __shared__ int n_valid;
+    const int tid = threadIdx.x, grp = tid >> 4, lane16 = tid & 15;
+    const int head = blockIdx.x, seq = head / n_q, kvh = (head % n_q) / (n_q / n_kv);
+    const size_t esz = DT == RA_BF16 ? 2 : 4;
+    const char* Kh = reinterpret_cast<const char*>(K) + ((size_t)seq * n_kv + kvh) * N * RA_D * esz;
+    const int32_t* ch = cand + (size_t)head * n_cand;
+    int32_t* out = ids + (size_t)head * topk;
+    float qv[8];
+    load_q8<DT>(reinterpret_cast<const char*>(q) + (size_t)head * RA_D * esz, lane16, qv);
+    if (tid == 0) n_valid = 0;
+    __syncthreads();
+    for (int c0 = 0; c0 < n_cand; c0 += 16 * RR_ROWS) {
+        RowBits<DT> rows[RR_ROWS];
+        int id[RR_ROWS];
+#pragma unroll
+        for (int u = 0; u < RR_ROWS; ++u) {
+            const int c = c0 + u * 16 + grp;
+            id[u] = c < n_cand ? ch[c] : -1;
+            if (id[u] >= N) id[u] = -1;
+            rows[u] = load_key<DT>(Kh, id[u] >= 0 ? id[u] : 0, lane16);       // loads stay unconditional
+        }
+#pragma unroll
+        for (int u = 0; u < RR_ROWS; ++u) {
+            const int c = c0 + u * 16 + grp;
+            const float sc = score_fixed<DT>(rows[u], qv);
+            if (lane16 == 0 && c < n_cand) {
+                // [ordered(score)][~id]: larger key = (score descending, id ascending); 0 = no candidate
+                keys[c] = id[u] < 0 ? 0ull
+                                    : ((unsigned long long)f32_ordered(sc) << 32) | (0xffffffffu - (uint32_t)id[u]);
+                if (id[u] >= 0) atomicAdd(&n_valid, 1);
+            }
+        }
+    }
+    __syncthreads();
+    const int nv = n_valid;
+    for (int c = tid; c < n_cand; c += RR_THREADS) {
+        const unsigned long long k = keys[c];
+        if (k == 0ull) continue;
+        int rank = 0;
+        for (int x = 0; x < n_cand; ++x) rank += keys[x] > k ? 1 : 0;
+        if (rank < topk) out[rank] = (int32_t)(0xffffffffu - (uint32_t)k);
+    }
+    for (int i = (nv < topk ? nv : topk) + tid; i < topk; i += RR_THREADS) out[i] = -1;
+}
+
+ra_status ra_launch_rerank(const void* q, const void* K, ra_dtype dt, int n_seq, int n_q, int n_kv, int64_t N,
+                           const int32_t* cand, int n_cand, int topk, hipStream_t st, int32_t* ids) {
+    if (dt == RA_BF16)
+        hipLaunchKernelGGL(rerank_kernel<RA_BF16>, dim3(n_seq * n_q), dim3(RR_THREADS), 0, st, q, K, n_q, n_kv,
+                           N, cand, n_cand, topk, ids);
+    else
+        hipLaunchKernelGGL(rerank_kernel<RA_F32>, dim3(n_seq * n_q), dim3(RR_THREADS), 0, st, q, K, n_q, n_kv,
+                           N, cand, n_cand, topk, ids);
+    RA_HIP(hipGetLastError());
+    return RA_OK;
+}
+
 ra_status ra_launch_flat_topk(const void* q, const void* K, ra_dtype dt, int n_seq, int n_q, int n_kv,
                               int64_t N, int sink, int window, int topk, uint32_t* keys_ws,
                               hipStream_t st, int32_t* ids) {

@@ -98,3 +98,54 @@ def test_8bit_walk_keeps_recall_on_a_32k_layer():
             rec.append(OM.recall(ids[0, h].cpu().numpy(), truth[0, h].cpu().numpy()))
     assert np.mean(rec) > 0.9, np.mean(rec)
     idx.free()
+
+
+@pytest.mark.parametrize("name", list(_cases()))
+def test_rerank_matches_the_oracle(name):
+    """ra_rerank on the 8-bit walk's longer list: the oracle's rerank with the same fixed-order
+    scores, id for id; lists with -1 padding and out-of-range ids are handled."""
+    w = _cases()[name]()
+    adj, ent, _ = oracle_graphs(w)
+    n_seq, n_kv, N, d = w.K.shape
+    n_q = w.Q_prefill.shape[1]
+    G = n_q // n_kv
+    idx = ra.ra_index_import(torch.from_numpy(adj), torch.from_numpy(ent), n_seq, n_q, n_kv)
+    Kd = w.K.to(DEV)
+    k8 = ra.ra_quantize_keys(Kd)
+    n_cand = min(w.ef, 2 * w.topk)
+    q = w.q_decode[0].to(DEV)
+    cand, _ = ra.ra_search(q, idx, None, w.sink, w.window, n_cand, w.ef, 8, k8=k8)
+    cand[:, :, 1] = -1                                   # a hole, as padding would leave
+    ids = ra.ra_rerank(q, Kd, cand, w.topk).cpu().numpy()
+    cand = cand.cpu().numpy()
+    for s in range(n_seq):
+        for h in range(n_q):
+            want = OM.rerank(to_np(w.q_decode[0, s, h]), to_np(w.K[s, h // G]), cand[s, h], w.topk,
+                             score_fn=OS.score32)
+            assert ids[s, h].tolist() == want.tolist(), (s, h)
+    short = torch.full((n_seq, n_q, 4), -1, dtype=torch.int32, device=DEV)
+    short[:, :, 2] = 7
+    assert ra.ra_rerank(q, Kd, short, 3).cpu().numpy()[0, 0].tolist() == [7, -1, -1]
+    idx.free()
+
+
+def test_rerank_recovers_the_recall_of_the_8bit_walk():
+    w = synth.make_llama_layer(53, N=32768, M=32768, T=2, n_q=4, n_kv=1, device=DEV)
+    idx = ra.ra_build_index(w.K, w.Q_prefill, w.deg, w.knn)
+    k8 = ra.ra_quantize_keys(w.K)
+    r_plain, r_q8, r_rr = [], [], []
+    for t in range(2):
+        q = w.q_decode[t]
+        truth = ra.ra_flat_topk(q, w.K, w.sink, w.window, w.topk)
+        plain, _ = ra.ra_search(q, idx, w.K, w.sink, w.window, w.topk, w.ef, 32)
+        q8, _ = ra.ra_search(q, idx, None, w.sink, w.window, w.topk, w.ef, 32, k8=k8)
+        wide, _ = ra.ra_search(q, idx, None, w.sink, w.window, 2 * w.topk, w.ef, 32, k8=k8)
+        rr = ra.ra_rerank(q, w.K, wide, w.topk)
+        for h in range(4):
+            tr = truth[0, h].cpu().numpy()
+            r_plain.append(OM.recall(plain[0, h].cpu().numpy(), tr))
+            r_q8.append(OM.recall(q8[0, h].cpu().numpy(), tr))
+            r_rr.append(OM.recall(rr[0, h].cpu().numpy(), tr))
+    assert np.mean(r_rr) >= np.mean(r_q8) and np.mean(r_rr) >= np.mean(r_plain) - 0.01, (
+        np.mean(r_plain), np.mean(r_q8), np.mean(r_rr))
+    idx.free()
