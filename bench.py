@@ -36,7 +36,7 @@ def parse():
     p.add_argument("--steps", type=int, default=20)
     p.add_argument("--warmup", type=int, default=3)
     p.add_argument("--workload", default="config2",
-                   choices=["config2", "config1", "config3", "config0"])
+                   choices=["config2", "config1", "config3", "config0", "config4"])
     p.add_argument("--layers", type=int, default=None, help="override the layer count (debug)")
     p.add_argument("--context", type=int, default=None, help="override N (debug)")
     p.add_argument("--seqs", type=int, default=None, help="config3: number of sequences (default 16)")
@@ -98,6 +98,9 @@ def main():
     elif a.workload == "config3":
         n_layers, N, n_seq = 1, 32768, a.seqs or 16
         mk = lambda l: synth.make_config3(device=dev, N=N, T=a.tokens, n_seq=n_seq)
+    elif a.workload == "config4":
+        n_layers, N, n_seq = 1, 1 << 20, 1
+        mk = lambda l: synth.make_config4(device=dev, N=N, T=a.tokens)
     else:
         n_layers, N, n_seq = 1, 4096, 1
         mk = lambda l: synth.make_config0(device=dev)
@@ -123,6 +126,7 @@ def main():
         t_gen += t1 - t0
         t_build += t2 - t1
         n_q = w.Q_prefill.shape[1]
+        m_prefill = w.Q_prefill.shape[2]
         build_flop += 2.0 * w.Q_prefill.shape[0] * n_q * w.Q_prefill.shape[2] * w.K.shape[2] * w.d
         layers.append(dict(K=w.K, V=w.V, q=w.q_decode, idx=idx, w=w, k8=k8))
         w.Q_prefill = None
@@ -131,6 +135,7 @@ def main():
                   file=sys.stderr, flush=True)
     w0 = layers[0]["w"]
     n_q, n_kv, d = layers[0]["q"].shape[2], w0.K.shape[1], w0.d
+    M_prefill = m_prefill
     T = layers[0]["q"].shape[0]
     topk, ef, sink, window, deg = a.topk or w0.topk, a.ef or w0.ef, w0.sink, w0.window, w0.deg
     esz = w0.K.element_size()
@@ -354,7 +359,7 @@ def main():
         "vs_baseline": None, "dtype": "bf16" if esz == 2 else "f32", "data": "synthetic",
         "recall_at_100": recall_device, "recall_at_100_cpu_oracle_sample": recall,
         "config": {"workload": f"{a.workload}: {len(layers)} layers x {n_seq} seq x {n_q} q heads / "
-                               f"{n_kv} kv heads, d={d}, N={N}, M={N} prefill queries/head",
+                               f"{n_kv} kv heads, d={d}, N={N}, M={M_prefill} prefill queries/head",
                    "topk": topk, "ef": ef, "expand": a.expand, "deg": deg, "knn": w0.knn,
                    "sink": sink, "window": window, "hip_graph": bool(a.graph), "search_keys": "int8" if a.q8 else "as stored"},
         "roofline": {"bound": "hbm", "kernel": "decode_kernel", "achieved": decode_gbs,

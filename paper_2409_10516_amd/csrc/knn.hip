@@ -8,17 +8,36 @@
 // 32x32 accumulator layout a lane holds ONE query column (lane % 32) and 16 key rows, so the
 // selection threshold of a query is a single per-lane register: the common case is a
 // max-tree over the lane's 16 scores and one compare. Only scores that reach the threshold
-// (about knn * ln(N / knn) per query over the whole stream) take the insertion path, where the
-// wavefront inserts them one at a time into the query's sorted list in LDS.
+// (about knn * ln(N / knn) per query over the whole stream) go further. For knn <= KN_BUFFERED_KNN a
+// query owns KN_CAP list slots in LDS: its best knn keys so far, then two runs of pending slots,
+// one per lane that scores for it. A lane appends a qualifying key to its own run with a single
+// LDS write (its fill count is a register); when a run is nearly full the wavefront sorts the 64
+// slots of that query across its lanes (bitonic network), keeps the best knn and raises the
+// threshold. Between two such merges the threshold is stale but valid (never above the true one),
+// so nothing is lost and a query is merged only ~ln(N/knn) / ln(1 + pending/knn) times. Longer
+// lists use sorted insertion, one key at a time, by the whole wavefront.
 //
 // A wavefront owns NQ x 32 queries for the whole key stream (their B operands stay in registers,
-// and every key operand fetched feeds NQ MFMA chains); a workgroup is 4 wavefronts. Lists hold 64-bit keys
-// [ordered(score):32][~id:32], so "larger key" is "(score descending, id ascending)".
+// and every key operand fetched feeds NQ MFMA chains); a workgroup is WAVES wavefronts. Lists hold
+// 64-bit keys [ordered(score):32][~id:32], so "larger key" is "(score descending, id ascending)".
 // The inner-product summation order is the hardware's; identical key rows still score
 // identically for a given query because they go through the same instruction sequence.
+//
+// Key rows reach the matrix cores through LDS. In the operand layout a lane holds 16 bytes of
+// its own row per step, so a load straight from memory touches 64 cache lines per instruction
+// and the vector cache's line rate, not the matrix cores, sets the pace. Instead the workgroup
+// copies the key stream in 16 KB stages with fully coalesced loads (16 lanes per 256-byte row,
+// each stage fetched once for all its wavefronts and one whole stage ahead of its use), stores
+// them with the 16-byte chunks of a row XOR-swizzled by the row number, and every wavefront
+// reads its operands from there with conflict-free 16-byte LDS reads. Two stage buffers
+// alternate; one barrier per stage.
 #include "common.h"
 
-#define KN_THREADS 256
+#define KN_STAGE_BYTES 16384
+#define KN_CAP 64                 // list slots of a query in the buffered selection (one per lane)
+#define KN_BUFFERED_KNN 48        // longest list that leaves room for pending slots
+#define KN_LDS_LIMIT (160 * 1024)
+#define KN_MAX_DEVICES 64
 
 typedef unsigned long long u64;
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
@@ -40,6 +59,52 @@ __device__ __forceinline__ float knn_insert(u64* lst, int knn, float score, int 
         if (lane == pos) lst[pos] = nk;
     }
     const u64 last = lst[knn - 1];
+    return last == 0ull ? -INFINITY : f32_from_ordered((uint32_t)(last >> 32));
+}
+
+// The value lane (lane ^ J) holds. Distances below 16 stay inside a row of 16 lanes and use DPP
+// moves (quad permutes for 1 and 2, a pair of masked row shifts for 4, a row rotation for 8);
+// 16 and 32 cross rows and go through the LDS crossbar.
+template <int J>
+__device__ __forceinline__ uint32_t lane_xor32(uint32_t x) {
+    if constexpr (J == 1) return (uint32_t)__builtin_amdgcn_update_dpp((int)x, (int)x, 0xB1, 0xF, 0xF, false);
+    else if constexpr (J == 2) return (uint32_t)__builtin_amdgcn_update_dpp((int)x, (int)x, 0x4E, 0xF, 0xF, false);
+    else if constexpr (J == 4) {
+        // lanes 0-3 and 8-11 of a row read four lanes up (row_shl:4), the others four lanes down (row_shr:4)
+        const int t = __builtin_amdgcn_update_dpp((int)x, (int)x, 0x104, 0xF, 0x5, false);
+        return (uint32_t)__builtin_amdgcn_update_dpp(t, (int)x, 0x114, 0xF, 0xA, false);
+    } else if constexpr (J == 8) return (uint32_t)__builtin_amdgcn_update_dpp((int)x, (int)x, 0x128, 0xF, 0xF, false);
+    else return (uint32_t)__shfl_xor((int)x, J);
+}
+
+// 64 keys, one per lane, sorted descending across the wavefront (bitonic network). Keys are
+// distinct or zero, so "the other one is larger" decides every exchange.
+__device__ __forceinline__ u64 wave_sort_desc(u64 v, int lane) {
+#define KN_EXCHANGE(K_, J_)                                                                   \
+    {                                                                                         \
+        const u64 o = ((u64)lane_xor32<J_>((uint32_t)(v >> 32)) << 32) |                      \
+                      (u64)lane_xor32<J_>((uint32_t)v);                                       \
+        const bool keep_max = ((lane & J_) == 0) == ((lane & K_) == 0);                       \
+        v = ((o > v) == keep_max) ? o : v;                                                    \
+    }
+    KN_EXCHANGE(2, 1)
+    KN_EXCHANGE(4, 2) KN_EXCHANGE(4, 1)
+    KN_EXCHANGE(8, 4) KN_EXCHANGE(8, 2) KN_EXCHANGE(8, 1)
+    KN_EXCHANGE(16, 8) KN_EXCHANGE(16, 4) KN_EXCHANGE(16, 2) KN_EXCHANGE(16, 1)
+    KN_EXCHANGE(32, 16) KN_EXCHANGE(32, 8) KN_EXCHANGE(32, 4) KN_EXCHANGE(32, 2) KN_EXCHANGE(32, 1)
+    KN_EXCHANGE(64, 32) KN_EXCHANGE(64, 16) KN_EXCHANGE(64, 8) KN_EXCHANGE(64, 4) KN_EXCHANGE(64, 2)
+    KN_EXCHANGE(64, 1)
+#undef KN_EXCHANGE
+    return v;
+}
+
+// Fold the pending keys of one query into its list: afterwards slots [0, knn) hold its best knn
+// keys in descending order and the pending slots are empty (all 64 lanes cooperate).
+// Returns the new threshold: the score of slot knn - 1, or -inf while the list is not full.
+__device__ __forceinline__ float knn_fold(u64* lst, int knn, int lane) {
+    const u64 v = wave_sort_desc(lst[lane], lane);
+    lst[lane] = lane < knn ? v : 0ull;
+    const u64 last = __shfl(v, knn - 1);
     return last == 0ull ? -INFINITY : f32_from_ordered((uint32_t)(last >> 32));
 }
 
@@ -86,15 +151,70 @@ __device__ __forceinline__ f32x16 block_scores(const Operand<DT>& a, const Opera
     return c;
 }
 
-// grid: x = block of NQ * 128 queries, y = graph (seq * n_q + h). A wavefront owns NQ sets of 32
-// queries, so every key operand it loads feeds NQ MFMA chains.
-template <int DT, int NQ>
-__global__ __launch_bounds__(KN_THREADS) void knn_kernel(
+// A staged key row keeps its 16-byte chunks at (chunk ^ (row & 15)): the 16 lanes that write one
+// row, and the 16 lanes that read the same chunk of 16 consecutive rows, both cover all 64 banks.
+template <int DT>
+__device__ __forceinline__ void read_operand(const unsigned char* buf, int row, int half, Operand<DT>& o) {
+    constexpr int ROWB = DT == RA_BF16 ? 256 : 512, CPH = ROWB / 32;   // chunks per half row
+    const unsigned char* r = buf + row * ROWB;
+    const int sw = row & 15;
+    if constexpr (DT == RA_BF16) {
+#pragma unroll
+        for (int s = 0; s < 8; ++s) {
+            const uint4 u = *reinterpret_cast<const uint4*>(r + (((half * CPH + s) ^ sw) << 4));
+            o.v[s] = __builtin_bit_cast(bf16x8, u);
+        }
+    } else {
+#pragma unroll
+        for (int s = 0; s < 16; ++s) {
+            const float4 f = *reinterpret_cast<const float4*>(r + (((half * CPH + s) ^ sw) << 4));
+            o.v[4 * s] = f.x; o.v[4 * s + 1] = f.y; o.v[4 * s + 2] = f.z; o.v[4 * s + 3] = f.w;
+        }
+    }
+}
+
+// Stage copy: chunk x of a stage is 16 bytes of row x / (chunks per row); consecutive threads take
+// consecutive chunks, thread tid the chunks tid + i * THREADS. Rows beyond N repeat row N - 1
+// (their scores are masked by the caller). One chunk per call so that the values in flight stay
+// in named registers.
+template <int DT, int THREADS>
+__device__ __forceinline__ uint4 fetch_chunk(const char* Kh, int64_t st, int64_t N, int tid, int i) {
+    constexpr int ROWB = DT == RA_BF16 ? 256 : 512, CPR = ROWB / 16, SROWS = KN_STAGE_BYTES / ROWB;
+    const int x = tid + i * THREADS;
+    int64_t kr = st * SROWS + x / CPR;
+    if (kr >= N) kr = N - 1;
+    return *reinterpret_cast<const uint4*>(Kh + (size_t)kr * ROWB + (size_t)(x % CPR) * 16);
+}
+template <int DT, int THREADS>
+__device__ __forceinline__ void store_chunk(unsigned char* buf, int tid, int i, const uint4& v) {
+    constexpr int ROWB = DT == RA_BF16 ? 256 : 512, CPR = ROWB / 16;
+    const int x = tid + i * THREADS;
+    const int row = x / CPR, c = x % CPR;
+    *reinterpret_cast<uint4*>(buf + row * ROWB + ((c ^ (row & 15)) << 4)) = v;
+}
+
+// grid: x = block of NQ * 32 * WAVES queries, y = graph (seq * n_q + h). A wavefront owns NQ sets
+// of 32 queries, so every key operand it reads feeds NQ MFMA chains.
+// LDS: [NQ * 32 * WAVES][BUF ? KN_CAP : knn] lists, then two stage buffers of KN_STAGE_BYTES.
+// BUF selects the buffered selection (knn <= KN_BUFFERED_KNN) or sorted insertion.
+template <int DT, int NQ, int WAVES, bool BUF>
+__global__ __launch_bounds__(WAVES * RA_WAVE) void knn_kernel(
     const void* __restrict__ K, const void* __restrict__ Q, int n_q, int n_kv, int64_t N, int64_t M,
     int knn, int32_t* __restrict__ L_out) {
     extern __shared__ __align__(16) unsigned char lds_raw[];
-    constexpr int QPW = 32 * NQ, QPB = QPW * (KN_THREADS / RA_WAVE);
-    u64* lists = reinterpret_cast<u64*>(lds_raw);           // [QPB][knn]
+    constexpr int KN_THREADS = WAVES * RA_WAVE;
+    constexpr int QPW = 32 * NQ, QPB = QPW * WAVES;
+    constexpr int ROWB = DT == RA_BF16 ? 256 : 512;          // bytes of a key row
+    constexpr int CPR = ROWB / 16;                            // 16-byte chunks per row
+    constexpr int SROWS = KN_STAGE_BYTES / ROWB;              // key rows per stage
+    constexpr int SBLK = SROWS / 32;                          // 32-key blocks per stage
+    constexpr int CPT = KN_STAGE_BYTES / 16 / KN_THREADS;     // chunks a thread copies per stage
+    static_assert(SBLK == 1 || SBLK == 2, "a stage holds one or two key blocks");
+    static_assert(CPT * KN_THREADS * 16 == KN_STAGE_BYTES, "threads must tile a stage");
+    const int lstride = BUF ? KN_CAP : knn;                   // list slots per query
+    const int pend = (KN_CAP - knn) / 2;                      // pending slots per lane (BUF)
+    u64* lists = reinterpret_cast<u64*>(lds_raw);           // [QPB][lstride]
+    unsigned char* stage_buf = lds_raw + (size_t)QPB * lstride * sizeof(u64);   // 16-byte aligned: QPB is even
     const int tid = threadIdx.x, wv = tid / RA_WAVE, lane = tid % RA_WAVE;
     const int col = lane & 31, half = lane >> 5;
     const int graph = blockIdx.y, seq = graph / n_q, h = graph % n_q, kvh = h / (n_q / n_kv);
@@ -103,8 +223,8 @@ __global__ __launch_bounds__(KN_THREADS) void knn_kernel(
     const char* Qh = reinterpret_cast<const char*>(Q) + (size_t)graph * M * RA_D * esz;
     const int64_t q0 = (int64_t)blockIdx.x * QPB + wv * QPW;   // first query of this wave
 
-    for (int i = tid; i < QPB * knn; i += KN_THREADS) lists[i] = 0ull;
-    u64* my_lists = lists + (size_t)wv * QPW * knn;
+    for (int i = tid; i < QPB * lstride; i += KN_THREADS) lists[i] = 0ull;
+    u64* my_lists = lists + (size_t)wv * QPW * lstride;
 
     Operand<DT> b[NQ];
 #pragma unroll
@@ -116,14 +236,27 @@ __global__ __launch_bounds__(KN_THREADS) void knn_kernel(
     __syncthreads();
 
     float tau[NQ];
+    int fill[NQ];                                  // BUF: keys in this lane's pending run
 #pragma unroll
-    for (int sidx = 0; sidx < NQ; ++sidx) tau[sidx] = -INFINITY;
-    const int64_t nblk = (N + 31) / 32;
+    for (int sidx = 0; sidx < NQ; ++sidx) { tau[sidx] = -INFINITY; fill[sidx] = 0; }
 
-    auto load_keys = [&](int64_t kb, Operand<DT>& dst) {
-        int64_t kr = kb * 32 + col;
-        if (kr >= N) kr = N - 1;
-        load_operand<DT>(Kh, kr, half, dst);
+    static_assert(CPT == 2 || CPT == 4, "two or four chunks per thread and stage");
+    uint4 h0, h1, h2, h3;
+    auto fetch_stage = [&](int64_t st) {
+        h0 = fetch_chunk<DT, KN_THREADS>(Kh, st, N, tid, 0);
+        h1 = fetch_chunk<DT, KN_THREADS>(Kh, st, N, tid, 1);
+        if constexpr (CPT == 4) {
+            h2 = fetch_chunk<DT, KN_THREADS>(Kh, st, N, tid, 2);
+            h3 = fetch_chunk<DT, KN_THREADS>(Kh, st, N, tid, 3);
+        }
+    };
+    auto store_stage = [&](unsigned char* buf) {
+        store_chunk<DT, KN_THREADS>(buf, tid, 0, h0);
+        store_chunk<DT, KN_THREADS>(buf, tid, 1, h1);
+        if constexpr (CPT == 4) {
+            store_chunk<DT, KN_THREADS>(buf, tid, 2, h2);
+            store_chunk<DT, KN_THREADS>(buf, tid, 3, h3);
+        }
     };
     // scores of one 32-key block against the wave's NQ query sets, then the selection
     auto process = [&](const Operand<DT>& a, int64_t kb) {
@@ -139,6 +272,35 @@ __global__ __launch_bounds__(KN_THREADS) void knn_kernel(
                 for (int r = 0; r < 16; ++r)
                     if (kbase + (r / 4) * 8 + half * 4 + (r % 4) >= N) cs[r] = -INFINITY;
             }
+            if constexpr (BUF) {
+                float gm[4];
+#pragma unroll
+                for (int g = 0; g < 4; ++g)
+                    gm[g] = fmaxf(fmaxf(cs[4 * g], cs[4 * g + 1]), fmaxf(cs[4 * g + 2], cs[4 * g + 3]));
+                const float mx = fmaxf(fmaxf(gm[0], gm[1]), fmaxf(gm[2], gm[3]));
+                if (__ballot(mx >= tau[sidx]) == 0ull) continue;
+                u64* set_lists = my_lists + (size_t)sidx * 32 * KN_CAP;
+                u64* mine = set_lists + (size_t)col * KN_CAP + knn + half * pend;
+#pragma unroll
+                for (int g = 0; g < 4; ++g) {
+                    if (__ballot(gm[g] >= tau[sidx]) == 0ull) continue;
+                    // a lane that may append needs room for four keys: fold the queries short of it
+                    u64 need = __ballot(gm[g] >= tau[sidx] && fill[sidx] > pend - 4);
+                    while (need) {
+                        const int jq = (__ffsll((long long)need) - 1) & 31;
+                        const float nt = knn_fold(set_lists + (size_t)jq * KN_CAP, knn, lane);
+                        if (col == jq) { tau[sidx] = nt; fill[sidx] = 0; }
+                        need = __ballot(gm[g] >= tau[sidx] && fill[sidx] > pend - 4);
+                    }
+#pragma unroll
+                    for (int r = 4 * g; r < 4 * g + 4; ++r) {
+                        if (cs[r] >= tau[sidx] && cs[r] > -INFINITY) {
+                            const int id = (int)(kbase + (r / 4) * 8 + half * 4 + (r % 4));
+                            mine[fill[sidx]++] = knn_key(cs[r], id);
+                        }
+                    }
+                }
+            } else {
             float mx = fmaxf(cs[0], cs[1]);
 #pragma unroll
             for (int r = 2; r < 16; ++r) mx = fmaxf(mx, cs[r]);
@@ -159,44 +321,82 @@ __global__ __launch_bounds__(KN_THREADS) void knn_kernel(
                     mask &= __ballot(cs[r] >= tau[sidx] && cs[r] > -INFINITY);
                 }
             }
+            }
         }
     };
-    // two key-operand register sets: the next block's rows are requested before the current
-    // block's MFMAs are issued, so their latency hides behind a whole block of matrix work
-    Operand<DT> a0, a1;
-    load_keys(0, a0);
-    for (int64_t kb = 0; kb < nblk; kb += 2) {
-        if (kb + 1 < nblk) load_keys(kb + 1, a1);
-        process(a0, kb);
-        if (kb + 1 >= nblk) break;
-        if (kb + 2 < nblk) load_keys(kb + 2, a0);
-        process(a1, kb + 1);
+    // every thread runs every stage (the barrier needs all of them); the loads of the stage
+    // after the current one are in flight while the current one is multiplied. The last
+    // iteration fetches its own stage again instead of branching around the loads.
+    const int64_t nstage = (N + SROWS - 1) / SROWS;
+    fetch_stage(0);
+    store_stage(stage_buf);
+    __syncthreads();
+    for (int64_t st = 0; st < nstage; ++st) {
+        fetch_stage(st + 1 < nstage ? st + 1 : st);
+        const unsigned char* cur = stage_buf + (st & 1) * KN_STAGE_BYTES;
+        Operand<DT> a0;
+        read_operand<DT>(cur, col, half, a0);
+        if constexpr (SBLK == 2) {
+            Operand<DT> a1;
+            read_operand<DT>(cur, 32 + col, half, a1);
+            process(a0, st * 2);
+            process(a1, st * 2 + 1);          // a block at or beyond N is all masked
+        } else {
+            process(a0, st);
+        }
+        store_stage(stage_buf + ((st + 1) & 1) * KN_STAGE_BYTES);
+        __syncthreads();
     }
     // write the ids, best first
     for (int jq = 0; jq < QPW; ++jq) {
         const int64_t qr = q0 + jq;
         if (qr >= M) break;
+        if constexpr (BUF) knn_fold(my_lists + (size_t)jq * KN_CAP, knn, lane);
         if (lane < knn)
-            L_out[((size_t)graph * M + qr) * knn + lane] = knn_key_id(my_lists[(size_t)jq * knn + lane]);
+            L_out[((size_t)graph * M + qr) * knn + lane] = knn_key_id(my_lists[(size_t)jq * lstride + lane]);
     }
 }
 
-ra_status ra_launch_knn(const void* K, const void* Q, ra_dtype dt, int n_seq, int n_q, int n_kv,
-                        int64_t N, int64_t M, int knn, hipStream_t st, int32_t* L) {
-    if (dt == RA_BF16) {
-        constexpr int NQ = 2;
-        constexpr int QPB = 32 * NQ * (KN_THREADS / RA_WAVE);
-        const dim3 grid((unsigned)((M + QPB - 1) / QPB), (unsigned)(n_seq * n_q));
-        const size_t lds = (size_t)QPB * knn * sizeof(u64);
-        hipLaunchKernelGGL((knn_kernel<RA_BF16, NQ>), grid, dim3(KN_THREADS), lds, st, K, Q, n_q, n_kv,
-                           N, M, knn, L);
-    } else {
-        constexpr int QPB = 32 * (KN_THREADS / RA_WAVE);
-        const dim3 grid((unsigned)((M + QPB - 1) / QPB), (unsigned)(n_seq * n_q));
-        const size_t lds = (size_t)QPB * knn * sizeof(u64);
-        hipLaunchKernelGGL((knn_kernel<RA_F32, 1>), grid, dim3(KN_THREADS), lds, st, K, Q, n_q, n_kv,
-                           N, M, knn, L);
+// Dynamic LDS above 64 KB needs an opt-in per kernel and device.
+template <typename Kern>
+static ra_status knn_lds_opt_in(Kern kern, size_t bytes, size_t* granted) {
+    int dev = 0;
+    RA_HIP(hipGetDevice(&dev));
+    if (dev < 0 || dev >= KN_MAX_DEVICES) RA_FAIL(RA_EUNSUP, "device %d out of range", dev);
+    if (bytes > 64 * 1024 && granted[dev] < bytes) {
+        RA_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
+                                   hipFuncAttributeMaxDynamicSharedMemorySize, KN_LDS_LIMIT));
+        granted[dev] = KN_LDS_LIMIT;
     }
+    return RA_OK;
+}
+
+template <int DT, int NQ, int WAVES, bool BUF>
+static ra_status knn_launch_as(const void* K, const void* Q, int n_seq, int n_q, int n_kv, int64_t N,
+                               int64_t M, int knn, hipStream_t st, int32_t* L) {
+    static size_t granted[KN_MAX_DEVICES];
+    constexpr int QPB = 32 * NQ * WAVES;
+    const size_t lds = (size_t)QPB * (BUF ? KN_CAP : knn) * sizeof(u64) + 2 * KN_STAGE_BYTES;
+    if (lds > KN_LDS_LIMIT)
+        RA_FAIL(RA_EUNSUP, "knn %d needs %zu bytes of LDS (limit %d)", knn, lds, KN_LDS_LIMIT);
+    ra_status rc = knn_lds_opt_in(&knn_kernel<DT, NQ, WAVES, BUF>, lds, granted);
+    if (rc != RA_OK) return rc;
+    const dim3 grid((unsigned)((M + QPB - 1) / QPB), (unsigned)(n_seq * n_q));
+    hipLaunchKernelGGL((knn_kernel<DT, NQ, WAVES, BUF>), grid, dim3(WAVES * RA_WAVE), lds, st, K, Q, n_q,
+                       n_kv, N, M, knn, L);
     RA_HIP(hipGetLastError());
     return RA_OK;
+}
+
+// 8 wavefronts per workgroup (one workgroup per compute unit, two wavefronts per SIMD) and one
+// set of 32 queries per wavefront: 256 queries x 64 slots x 8 bytes of lists beside the stage buffers.
+ra_status ra_launch_knn(const void* K, const void* Q, ra_dtype dt, int n_seq, int n_q, int n_kv,
+                        int64_t N, int64_t M, int knn, hipStream_t st, int32_t* L) {
+    const bool buf = knn <= KN_BUFFERED_KNN;
+    if (dt == RA_BF16) {
+        if (buf) return knn_launch_as<RA_BF16, 1, 8, true>(K, Q, n_seq, n_q, n_kv, N, M, knn, st, L);
+        return knn_launch_as<RA_BF16, 1, 8, false>(K, Q, n_seq, n_q, n_kv, N, M, knn, st, L);
+    }
+    if (buf) return knn_launch_as<RA_F32, 1, 4, true>(K, Q, n_seq, n_q, n_kv, N, M, knn, st, L);
+    return knn_launch_as<RA_F32, 1, 4, false>(K, Q, n_seq, n_q, n_kv, N, M, knn, st, L);
 }
