@@ -33,7 +33,6 @@
 // alternate; one barrier per stage.
 #include "common.h"
 
-#define KN_STAGE_BYTES 16384
 #define KN_CAP 64                 // list slots of a query in the buffered selection (one per lane)
 #define KN_BUFFERED_KNN 48        // longest list that leaves room for pending slots
 #define KN_LDS_LIMIT (160 * 1024)
@@ -64,9 +63,11 @@ __device__ __forceinline__ float knn_insert(u64* lst, int knn, float score, int 
 
 // The value lane (lane ^ J) holds. Distances below 16 stay inside a row of 16 lanes and use DPP
 // moves (quad permutes for 1 and 2, a pair of masked row shifts for 4, a row rotation for 8);
-// 16 and 32 cross rows and go through the LDS crossbar.
+// 16 and 32 use the row and half-wave swap instructions: swapping x with itself leaves one result
+// with the even rows (lower half) duplicated and the other with the odd rows (upper half), and
+// each lane picks the one that came from its partner.
 template <int J>
-__device__ __forceinline__ uint32_t lane_xor32(uint32_t x) {
+__device__ __forceinline__ uint32_t lane_xor32(uint32_t x, int lane) {
     if constexpr (J == 1) return (uint32_t)__builtin_amdgcn_update_dpp((int)x, (int)x, 0xB1, 0xF, 0xF, false);
     else if constexpr (J == 2) return (uint32_t)__builtin_amdgcn_update_dpp((int)x, (int)x, 0x4E, 0xF, 0xF, false);
     else if constexpr (J == 4) {
@@ -74,7 +75,14 @@ __device__ __forceinline__ uint32_t lane_xor32(uint32_t x) {
         const int t = __builtin_amdgcn_update_dpp((int)x, (int)x, 0x104, 0xF, 0x5, false);
         return (uint32_t)__builtin_amdgcn_update_dpp(t, (int)x, 0x114, 0xF, 0xA, false);
     } else if constexpr (J == 8) return (uint32_t)__builtin_amdgcn_update_dpp((int)x, (int)x, 0x128, 0xF, 0xF, false);
-    else return (uint32_t)__shfl_xor((int)x, J);
+    else if constexpr (J == 16) {
+        const auto r = __builtin_amdgcn_permlane16_swap(x, x, false, false);
+        return (lane & 16) ? r[0] : r[1];
+    } else {
+        static_assert(J == 32, "lane distances are powers of two below 64");
+        const auto r = __builtin_amdgcn_permlane32_swap(x, x, false, false);
+        return (lane & 32) ? r[0] : r[1];
+    }
 }
 
 // 64 keys, one per lane, sorted descending across the wavefront (bitonic network). Keys are
@@ -82,8 +90,8 @@ __device__ __forceinline__ uint32_t lane_xor32(uint32_t x) {
 __device__ __forceinline__ u64 wave_sort_desc(u64 v, int lane) {
 #define KN_EXCHANGE(K_, J_)                                                                   \
     {                                                                                         \
-        const u64 o = ((u64)lane_xor32<J_>((uint32_t)(v >> 32)) << 32) |                      \
-                      (u64)lane_xor32<J_>((uint32_t)v);                                       \
+        const u64 o = ((u64)lane_xor32<J_>((uint32_t)(v >> 32), lane) << 32) |                \
+                      (u64)lane_xor32<J_>((uint32_t)v, lane);                                 \
         const bool keep_max = ((lane & J_) == 0) == ((lane & K_) == 0);                       \
         v = ((o > v) == keep_max) ? o : v;                                                    \
     }
@@ -177,9 +185,9 @@ __device__ __forceinline__ void read_operand(const unsigned char* buf, int row, 
 // consecutive chunks, thread tid the chunks tid + i * THREADS. Rows beyond N repeat row N - 1
 // (their scores are masked by the caller). One chunk per call so that the values in flight stay
 // in named registers.
-template <int DT, int THREADS>
+template <int DT, int THREADS, int STAGE>
 __device__ __forceinline__ uint4 fetch_chunk(const char* Kh, int64_t st, int64_t N, int tid, int i) {
-    constexpr int ROWB = DT == RA_BF16 ? 256 : 512, CPR = ROWB / 16, SROWS = KN_STAGE_BYTES / ROWB;
+    constexpr int ROWB = DT == RA_BF16 ? 256 : 512, CPR = ROWB / 16, SROWS = STAGE / ROWB;
     const int x = tid + i * THREADS;
     int64_t kr = st * SROWS + x / CPR;
     if (kr >= N) kr = N - 1;
@@ -195,9 +203,9 @@ __device__ __forceinline__ void store_chunk(unsigned char* buf, int tid, int i, 
 
 // grid: x = block of NQ * 32 * WAVES queries, y = graph (seq * n_q + h). A wavefront owns NQ sets
 // of 32 queries, so every key operand it reads feeds NQ MFMA chains.
-// LDS: [NQ * 32 * WAVES][BUF ? KN_CAP : knn] lists, then two stage buffers of KN_STAGE_BYTES.
+// LDS: [NQ * 32 * WAVES][BUF ? KN_CAP : knn] lists, then two stage buffers of STAGE bytes.
 // BUF selects the buffered selection (knn <= KN_BUFFERED_KNN) or sorted insertion.
-template <int DT, int NQ, int WAVES, bool BUF>
+template <int DT, int NQ, int WAVES, bool BUF, int STAGE>
 __global__ __launch_bounds__(WAVES * RA_WAVE) void knn_kernel(
     const void* __restrict__ K, const void* __restrict__ Q, int n_q, int n_kv, int64_t N, int64_t M,
     int knn, int32_t* __restrict__ L_out) {
@@ -206,11 +214,11 @@ __global__ __launch_bounds__(WAVES * RA_WAVE) void knn_kernel(
     constexpr int QPW = 32 * NQ, QPB = QPW * WAVES;
     constexpr int ROWB = DT == RA_BF16 ? 256 : 512;          // bytes of a key row
     constexpr int CPR = ROWB / 16;                            // 16-byte chunks per row
-    constexpr int SROWS = KN_STAGE_BYTES / ROWB;              // key rows per stage
+    constexpr int SROWS = STAGE / ROWB;              // key rows per stage
     constexpr int SBLK = SROWS / 32;                          // 32-key blocks per stage
-    constexpr int CPT = KN_STAGE_BYTES / 16 / KN_THREADS;     // chunks a thread copies per stage
+    constexpr int CPT = STAGE / 16 / KN_THREADS;     // chunks a thread copies per stage
     static_assert(SBLK == 1 || SBLK == 2, "a stage holds one or two key blocks");
-    static_assert(CPT * KN_THREADS * 16 == KN_STAGE_BYTES, "threads must tile a stage");
+    static_assert(CPT * KN_THREADS * 16 == STAGE, "threads must tile a stage");
     const int lstride = BUF ? KN_CAP : knn;                   // list slots per query
     const int pend = (KN_CAP - knn) / 2;                      // pending slots per lane (BUF)
     u64* lists = reinterpret_cast<u64*>(lds_raw);           // [QPB][lstride]
@@ -241,21 +249,23 @@ __global__ __launch_bounds__(WAVES * RA_WAVE) void knn_kernel(
     for (int sidx = 0; sidx < NQ; ++sidx) { tau[sidx] = -INFINITY; fill[sidx] = 0; }
 
     static_assert(CPT == 2 || CPT == 4, "two or four chunks per thread and stage");
-    uint4 h0, h1, h2, h3;
-    auto fetch_stage = [&](int64_t st) {
-        h0 = fetch_chunk<DT, KN_THREADS>(Kh, st, N, tid, 0);
-        h1 = fetch_chunk<DT, KN_THREADS>(Kh, st, N, tid, 1);
+    const int64_t nstage = (N + SROWS - 1) / SROWS;
+    struct Held { uint4 c0, c1, c2, c3; };         // a thread's share of one stage, in registers
+    auto fetch_stage = [&](Held& h, int64_t st) {
+        if (st >= nstage) st = nstage - 1;          // past the end: fetch the last stage again, unused
+        h.c0 = fetch_chunk<DT, KN_THREADS, STAGE>(Kh, st, N, tid, 0);
+        h.c1 = fetch_chunk<DT, KN_THREADS, STAGE>(Kh, st, N, tid, 1);
         if constexpr (CPT == 4) {
-            h2 = fetch_chunk<DT, KN_THREADS>(Kh, st, N, tid, 2);
-            h3 = fetch_chunk<DT, KN_THREADS>(Kh, st, N, tid, 3);
+            h.c2 = fetch_chunk<DT, KN_THREADS, STAGE>(Kh, st, N, tid, 2);
+            h.c3 = fetch_chunk<DT, KN_THREADS, STAGE>(Kh, st, N, tid, 3);
         }
     };
-    auto store_stage = [&](unsigned char* buf) {
-        store_chunk<DT, KN_THREADS>(buf, tid, 0, h0);
-        store_chunk<DT, KN_THREADS>(buf, tid, 1, h1);
+    auto store_stage = [&](const Held& h, unsigned char* buf) {
+        store_chunk<DT, KN_THREADS>(buf, tid, 0, h.c0);
+        store_chunk<DT, KN_THREADS>(buf, tid, 1, h.c1);
         if constexpr (CPT == 4) {
-            store_chunk<DT, KN_THREADS>(buf, tid, 2, h2);
-            store_chunk<DT, KN_THREADS>(buf, tid, 3, h3);
+            store_chunk<DT, KN_THREADS>(buf, tid, 2, h.c2);
+            store_chunk<DT, KN_THREADS>(buf, tid, 3, h.c3);
         }
     };
     // scores of one 32-key block against the wave's NQ query sets, then the selection
@@ -324,16 +334,8 @@ __global__ __launch_bounds__(WAVES * RA_WAVE) void knn_kernel(
             }
         }
     };
-    // every thread runs every stage (the barrier needs all of them); the loads of the stage
-    // after the current one are in flight while the current one is multiplied. The last
-    // iteration fetches its own stage again instead of branching around the loads.
-    const int64_t nstage = (N + SROWS - 1) / SROWS;
-    fetch_stage(0);
-    store_stage(stage_buf);
-    __syncthreads();
-    for (int64_t st = 0; st < nstage; ++st) {
-        fetch_stage(st + 1 < nstage ? st + 1 : st);
-        const unsigned char* cur = stage_buf + (st & 1) * KN_STAGE_BYTES;
+    // one stage of keys against the wave's queries
+    auto multiply_stage = [&](const unsigned char* cur, int64_t st) {
         Operand<DT> a0;
         read_operand<DT>(cur, col, half, a0);
         if constexpr (SBLK == 2) {
@@ -344,8 +346,27 @@ __global__ __launch_bounds__(WAVES * RA_WAVE) void knn_kernel(
         } else {
             process(a0, st);
         }
-        store_stage(stage_buf + ((st + 1) & 1) * KN_STAGE_BYTES);
+    };
+    // Every thread runs every stage (the barrier needs all of them). Key rows are requested two
+    // stages before they are multiplied: a stage sits in registers for one stage time, then in
+    // its LDS buffer for the next. Loads are never branched around (a conditional load makes
+    // every later wait conservative); past the end the last stage is fetched again and dropped.
+    Held ha, hb;
+    fetch_stage(ha, 0);
+    store_stage(ha, stage_buf);
+    fetch_stage(ha, 1);
+    fetch_stage(hb, 2);
+    __syncthreads();
+    for (int64_t st = 0; st < nstage; st += 2) {
+        multiply_stage(stage_buf, st);
+        store_stage(ha, stage_buf + STAGE);             // stage st + 1
         __syncthreads();
+        fetch_stage(ha, st + 3);
+        if (st + 1 >= nstage) break;
+        multiply_stage(stage_buf + STAGE, st + 1);
+        store_stage(hb, stage_buf);                              // stage st + 2
+        __syncthreads();
+        fetch_stage(hb, st + 4);
     }
     // write the ids, best first
     for (int jq = 0; jq < QPW; ++jq) {
@@ -371,18 +392,18 @@ static ra_status knn_lds_opt_in(Kern kern, size_t bytes, size_t* granted) {
     return RA_OK;
 }
 
-template <int DT, int NQ, int WAVES, bool BUF>
+template <int DT, int NQ, int WAVES, bool BUF, int STAGE>
 static ra_status knn_launch_as(const void* K, const void* Q, int n_seq, int n_q, int n_kv, int64_t N,
                                int64_t M, int knn, hipStream_t st, int32_t* L) {
     static size_t granted[KN_MAX_DEVICES];
     constexpr int QPB = 32 * NQ * WAVES;
-    const size_t lds = (size_t)QPB * (BUF ? KN_CAP : knn) * sizeof(u64) + 2 * KN_STAGE_BYTES;
+    const size_t lds = (size_t)QPB * (BUF ? KN_CAP : knn) * sizeof(u64) + 2 * STAGE;
     if (lds > KN_LDS_LIMIT)
         RA_FAIL(RA_EUNSUP, "knn %d needs %zu bytes of LDS (limit %d)", knn, lds, KN_LDS_LIMIT);
-    ra_status rc = knn_lds_opt_in(&knn_kernel<DT, NQ, WAVES, BUF>, lds, granted);
+    ra_status rc = knn_lds_opt_in(&knn_kernel<DT, NQ, WAVES, BUF, STAGE>, lds, granted);
     if (rc != RA_OK) return rc;
     const dim3 grid((unsigned)((M + QPB - 1) / QPB), (unsigned)(n_seq * n_q));
-    hipLaunchKernelGGL((knn_kernel<DT, NQ, WAVES, BUF>), grid, dim3(WAVES * RA_WAVE), lds, st, K, Q, n_q,
+    hipLaunchKernelGGL((knn_kernel<DT, NQ, WAVES, BUF, STAGE>), grid, dim3(WAVES * RA_WAVE), lds, st, K, Q, n_q,
                        n_kv, N, M, knn, L);
     RA_HIP(hipGetLastError());
     return RA_OK;
@@ -394,9 +415,9 @@ ra_status ra_launch_knn(const void* K, const void* Q, ra_dtype dt, int n_seq, in
                         int64_t N, int64_t M, int knn, hipStream_t st, int32_t* L) {
     const bool buf = knn <= KN_BUFFERED_KNN;
     if (dt == RA_BF16) {
-        if (buf) return knn_launch_as<RA_BF16, 1, 8, true>(K, Q, n_seq, n_q, n_kv, N, M, knn, st, L);
-        return knn_launch_as<RA_BF16, 1, 8, false>(K, Q, n_seq, n_q, n_kv, N, M, knn, st, L);
+        if (buf) return knn_launch_as<RA_BF16, 1, 8, true, 16384>(K, Q, n_seq, n_q, n_kv, N, M, knn, st, L);
+        return knn_launch_as<RA_BF16, 1, 8, false, 16384>(K, Q, n_seq, n_q, n_kv, N, M, knn, st, L);
     }
-    if (buf) return knn_launch_as<RA_F32, 1, 4, true>(K, Q, n_seq, n_q, n_kv, N, M, knn, st, L);
-    return knn_launch_as<RA_F32, 1, 4, false>(K, Q, n_seq, n_q, n_kv, N, M, knn, st, L);
+    if (buf) return knn_launch_as<RA_F32, 1, 4, true, 16384>(K, Q, n_seq, n_q, n_kv, N, M, knn, st, L);
+    return knn_launch_as<RA_F32, 1, 4, false, 16384>(K, Q, n_seq, n_q, n_kv, N, M, knn, st, L);
 }
