@@ -27,7 +27,7 @@
 // its own row per step, so a load straight from memory touches 64 cache lines per instruction
 // and the vector cache's line rate, not the matrix cores, sets the pace. Instead the workgroup
 // copies the key stream in 16 KB stages with fully coalesced loads (16 lanes per 256-byte row,
-// each stage fetched once for all its wavefronts and one whole stage ahead of its use), stores
+// each stage fetched once for all its wavefronts and two stages ahead of its use), stores
 // them with the 16-byte chunks of a row XOR-swizzled by the row number, and every wavefront
 // reads its operands from there with conflict-free 16-byte LDS reads. Two stage buffers
 // alternate; one barrier per stage.
@@ -112,7 +112,8 @@ __device__ __forceinline__ u64 wave_sort_desc(u64 v, int lane) {
 __device__ __forceinline__ float knn_fold(u64* lst, int knn, int lane) {
     const u64 v = wave_sort_desc(lst[lane], lane);
     lst[lane] = lane < knn ? v : 0ull;
-    const u64 last = __shfl(v, knn - 1);
+    const u64 last = ((u64)(uint32_t)__builtin_amdgcn_readlane((int)(v >> 32), knn - 1) << 32) |
+                     (u64)(uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)v, knn - 1);
     return last == 0ull ? -INFINITY : f32_from_ordered((uint32_t)(last >> 32));
 }
 
