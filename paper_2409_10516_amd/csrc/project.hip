@@ -20,9 +20,11 @@
 //      they stream the lists that hold a, bump a counter per co-listed key (table indexed by
 //      pos, so it is as small as the populated set: in LDS when it fits, else in global
 //      scratch), collect first-touched keys as the candidate list, gather each candidate's
-//      (count, popularity, id) once while resetting its counter, then extract the best `deg`
-//      candidates by repeated exact arg-max (fractions compared by 64-bit cross-multiplication)
-//      and write the row.
+//      (count, popularity, id) once while resetting its counter, then select the best 64 in rank
+//      order: every wavefront runs its share of the candidates, 64 at a time, through a bitonic
+//      network across its lanes (fractions compared by 64-bit cross-multiplication) and merges
+//      each sorted chunk into its running best 64; chunks that cannot beat the 64th are skipped;
+//      the first wavefront merges the four results and writes the row.
 // No global sort of the M*knn*(knn-1) co-occurrence pairs is needed: the skewed keys that sit
 // in nearly every list are simply the longest-running work items and are scheduled first.
 #include "common.h"
@@ -307,6 +309,52 @@ __device__ __forceinline__ bool cand_before(const Cand& x, const Cand& y, uint32
     return x.b < y.b;
 }
 
+// "no candidate": count 0 ranks after every real candidate (whose count is at least 1)
+__device__ __forceinline__ Cand cand_none() {
+    Cand x; x.c = 0u; x.pb = 0u; x.b = 0x7fffffff;
+    return x;
+}
+__device__ __forceinline__ Cand cand_lane(const Cand& x, int src) {
+    Cand y;
+    y.c = (uint32_t)__builtin_amdgcn_readlane((int)x.c, src);
+    y.pb = (uint32_t)__builtin_amdgcn_readlane((int)x.pb, src);
+    y.b = __builtin_amdgcn_readlane(x.b, src);
+    return y;
+}
+// one compare-exchange step of a bitonic network over the 64 lanes: partner lane ^ J; the lane
+// keeps the better of the two when keep_best, else the worse
+template <int J>
+__device__ __forceinline__ Cand cand_exchange(const Cand& v, bool keep_best, uint32_t pa) {
+    Cand o;
+    o.c = (uint32_t)__shfl_xor((int)v.c, J);
+    o.pb = (uint32_t)__shfl_xor((int)v.pb, J);
+    o.b = __shfl_xor(v.b, J);
+    return (cand_before(o, v, pa) == keep_best) ? o : v;
+}
+// 64 candidates, one per lane, into rank order (DESC: lane 0 the best; else lane 63 the best)
+template <bool DESC>
+__device__ __forceinline__ Cand cand_sort64(Cand v, uint32_t pa, int lane) {
+#define PJ_STEP(K_, J_) v = cand_exchange<J_>(v, (((lane & J_) == 0) == ((lane & K_) == 0)) == DESC, pa);
+    PJ_STEP(2, 1)
+    PJ_STEP(4, 2) PJ_STEP(4, 1)
+    PJ_STEP(8, 4) PJ_STEP(8, 2) PJ_STEP(8, 1)
+    PJ_STEP(16, 8) PJ_STEP(16, 4) PJ_STEP(16, 2) PJ_STEP(16, 1)
+    PJ_STEP(32, 16) PJ_STEP(32, 8) PJ_STEP(32, 4) PJ_STEP(32, 2) PJ_STEP(32, 1)
+    PJ_STEP(64, 32) PJ_STEP(64, 16) PJ_STEP(64, 8) PJ_STEP(64, 4) PJ_STEP(64, 2) PJ_STEP(64, 1)
+#undef PJ_STEP
+    return v;
+}
+// a bitonic sequence of 64 into descending rank order
+__device__ __forceinline__ Cand cand_merge64(Cand v, uint32_t pa, int lane) {
+    v = cand_exchange<32>(v, (lane & 32) == 0, pa);
+    v = cand_exchange<16>(v, (lane & 16) == 0, pa);
+    v = cand_exchange<8>(v, (lane & 8) == 0, pa);
+    v = cand_exchange<4>(v, (lane & 4) == 0, pa);
+    v = cand_exchange<2>(v, (lane & 2) == 0, pa);
+    v = cand_exchange<1>(v, (lane & 1) == 0, pa);
+    return v;
+}
+
 #define PJ_LDS_CNT 8192           // co-occurrence counters kept in LDS when the populated set fits
 #define PJ_LDS_TUP 2048           // candidate tuples kept in LDS when the candidate list fits
 
@@ -320,14 +368,13 @@ __device__ __forceinline__ void rows_for_graph(const int32_t* __restrict__ Lg, c
                                                uint32_t* tp_g, uint32_t* tc_l, uint32_t* tp_l,
                                                int32_t* tb_l, int64_t N, int knn, int deg, int H,
                                                int32_t* __restrict__ adj_g, int* s_ncand,
-                                               Cand* s_red, Cand* s_prev, int32_t* s_sel,
-                                               int* s_nsel) {
+                                               Cand (*s_best)[64]) {
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
     for (int t = blockIdx.x; t < H; t += gridDim.x) {
         const int a = w.pi[t];
         const uint32_t pa = (uint32_t)w.pop[a];
         const int o0 = w.off[a];
-        if (tid == 0) { *s_ncand = 0; *s_nsel = 0; }
+        if (tid == 0) *s_ncand = 0;
         __syncthreads();
         // count co-listed keys; the first touch of a counter appends the key to the candidates
         const int64_t work = (int64_t)pa * knn;
@@ -355,49 +402,42 @@ __device__ __forceinline__ void rows_for_graph(const int32_t* __restrict__ Lg, c
             if (tl) tb[x] = b;
         }
         __syncthreads();
-        // extract the best `want` candidates, one exact arg-max per round
-        for (int r = 0; r < want; ++r) {
-            Cand best; best.c = 0; best.pb = 0; best.b = -1;
-            const Cand prev = *s_prev;              // valid from r = 1 on
-            for (int x = tid; x < nc; x += PJ_ROW_T) {
-                Cand cd;
-                cd.b = tb[x]; cd.c = tc[x]; cd.pb = tp[x];
-                if (r > 0 && !cand_before(prev, cd, pa)) continue;     // already taken
-                if (best.b < 0 || cand_before(cd, best, pa)) best = cd;
-            }
-#pragma unroll
-            for (int d = 32; d > 0; d >>= 1) {
-                Cand o;
-                o.c = __shfl_xor(best.c, d); o.pb = __shfl_xor(best.pb, d); o.b = __shfl_xor(best.b, d);
-                if (o.b >= 0 && (best.b < 0 || cand_before(o, best, pa))) best = o;
-            }
-            if (lane == 0) s_red[wv] = best;
-            __syncthreads();
-            if (tid == 0) {
-                Cand bb = s_red[0];
-                for (int x = 1; x < PJ_ROW_T / 64; ++x) {
-                    const Cand o = s_red[x];
-                    if (o.b >= 0 && (bb.b < 0 || cand_before(o, bb, pa))) bb = o;
-                }
-                *s_prev = bb;
-                s_sel[(*s_nsel)++] = bb.b;
-            }
-            __syncthreads();
+        // best 64 of this wavefront's chunks, sorted: lane l holds its l-th best
+        Cand best = cand_none();
+        for (int x0 = wv * 64; x0 < nc; x0 += PJ_ROW_T) {
+            Cand cd = cand_none();
+            if (x0 + lane < nc) { cd.b = tb[x0 + lane]; cd.c = tc[x0 + lane]; cd.pb = tp[x0 + lane]; }
+            const Cand last = cand_lane(best, 63);
+            if (__ballot(cand_before(cd, last, pa)) == 0ull) continue;     // nothing here makes the 64
+            cd = cand_sort64<false>(cd, pa, lane);                          // ascending: lane l = (63-l)-th best
+            if (cand_before(cd, best, pa)) best = cd;                      // bitonic: the best 64 of the 128
+            best = cand_merge64(best, pa, lane);
         }
+        if (wv > 0) {
+            s_best[wv - 1][lane] = best;
+        }
+        __syncthreads();
         // row = backbone children, then ranked candidates not already present
-        if (tid == 0) {
+        if (wv == 0) {
+            for (int o = 0; o < PJ_ROW_T / 64 - 1; ++o) {
+                Cand cd = s_best[o][63 - lane];                             // descending list, reversed
+                if (cand_before(cd, best, pa)) best = cd;
+                best = cand_merge64(best, pa, lane);
+            }
             int32_t* row = adj_g + (size_t)a * deg;
-            int n = 0;
             int32_t kids[2] = {-1, -1};
-            for (int s = 0; s < 2 && n < deg; ++s) {
+            int nk = 0;
+            for (int s = 0; s < 2 && nk < deg; ++s) {
                 const int64_t ch = 2 * (int64_t)t + 1 + s;
-                if (ch < N) { kids[s] = w.pi[ch]; row[n++] = kids[s]; }
+                if (ch < N) kids[nk++] = w.pi[ch];
             }
-            for (int x = 0; x < *s_nsel && n < deg; ++x) {
-                const int32_t b = s_sel[x];
-                if (b != kids[0] && b != kids[1]) row[n++] = b;
-            }
-            for (; n < deg; ++n) row[n] = -1;
+            const bool keep = best.c > 0u && lane < want && best.b != kids[0] && best.b != kids[1];
+            const unsigned long long km = __ballot(keep);
+            const int at = nk + __popcll(km & ((1ull << lane) - 1ull));
+            const int total = nk + __popcll(km);
+            if (lane < nk) row[lane] = kids[lane];
+            if (keep && at < deg) row[at] = best.b;
+            if (lane >= total && lane < deg) row[lane] = -1;
         }
         __syncthreads();
     }
@@ -408,10 +448,7 @@ __global__ __launch_bounds__(PJ_ROW_T) void pj_rows_kernel(const int32_t* __rest
                                                            int knn, int deg,
                                                            int32_t* __restrict__ adj) {
     __shared__ int s_ncand;
-    __shared__ Cand s_red[PJ_ROW_T / 64];
-    __shared__ Cand s_prev;
-    __shared__ int32_t s_sel[RA_MAX_DEG];
-    __shared__ int s_nsel;
+    __shared__ Cand s_best[PJ_ROW_T / 64 - 1][64];
     __shared__ uint32_t s_cnt[PJ_LDS_CNT];
     __shared__ uint32_t s_tc[PJ_LDS_TUP], s_tp[PJ_LDS_TUP];
     __shared__ int32_t s_tb[PJ_LDS_TUP];
@@ -430,10 +467,10 @@ __global__ __launch_bounds__(PJ_ROW_T) void pj_rows_kernel(const int32_t* __rest
         for (int i = threadIdx.x; i < H; i += PJ_ROW_T) s_cnt[i] = 0u;
         __syncthreads();
         rows_for_graph<true>(Lg, w, s_cnt, cand, tc_g, tp_g, s_tc, s_tp, s_tb, N, knn, deg, H, adj_g,
-                             &s_ncand, s_red, &s_prev, s_sel, &s_nsel);
+                             &s_ncand, s_best);
     } else {
         rows_for_graph<false>(Lg, w, cnt_g, cand, tc_g, tp_g, s_tc, s_tp, s_tb, N, knn, deg, H, adj_g,
-                              &s_ncand, s_red, &s_prev, s_sel, &s_nsel);
+                              &s_ncand, s_best);
     }
 }
 
