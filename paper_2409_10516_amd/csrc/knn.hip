@@ -61,30 +61,6 @@ __device__ __forceinline__ float knn_insert(u64* lst, int knn, float score, int 
     return last == 0ull ? -INFINITY : f32_from_ordered((uint32_t)(last >> 32));
 }
 
-// The value lane (lane ^ J) holds. Distances below 16 stay inside a row of 16 lanes and use DPP
-// moves (quad permutes for 1 and 2, a pair of masked row shifts for 4, a row rotation for 8);
-// 16 and 32 use the row and half-wave swap instructions: swapping x with itself leaves one result
-// with the even rows (lower half) duplicated and the other with the odd rows (upper half), and
-// each lane picks the one that came from its partner.
-template <int J>
-__device__ __forceinline__ uint32_t lane_xor32(uint32_t x, int lane) {
-    if constexpr (J == 1) return (uint32_t)__builtin_amdgcn_update_dpp((int)x, (int)x, 0xB1, 0xF, 0xF, false);
-    else if constexpr (J == 2) return (uint32_t)__builtin_amdgcn_update_dpp((int)x, (int)x, 0x4E, 0xF, 0xF, false);
-    else if constexpr (J == 4) {
-        // lanes 0-3 and 8-11 of a row read four lanes up (row_shl:4), the others four lanes down (row_shr:4)
-        const int t = __builtin_amdgcn_update_dpp((int)x, (int)x, 0x104, 0xF, 0x5, false);
-        return (uint32_t)__builtin_amdgcn_update_dpp(t, (int)x, 0x114, 0xF, 0xA, false);
-    } else if constexpr (J == 8) return (uint32_t)__builtin_amdgcn_update_dpp((int)x, (int)x, 0x128, 0xF, 0xF, false);
-    else if constexpr (J == 16) {
-        const auto r = __builtin_amdgcn_permlane16_swap(x, x, false, false);
-        return (lane & 16) ? r[0] : r[1];
-    } else {
-        static_assert(J == 32, "lane distances are powers of two below 64");
-        const auto r = __builtin_amdgcn_permlane32_swap(x, x, false, false);
-        return (lane & 32) ? r[0] : r[1];
-    }
-}
-
 // 64 keys, one per lane, sorted descending across the wavefront (bitonic network). Keys are
 // distinct or zero, so "the other one is larger" decides every exchange.
 __device__ __forceinline__ u64 wave_sort_desc(u64 v, int lane) {

@@ -75,10 +75,10 @@ static ProjLayout proj_layout(int n_graphs, int64_t N, int64_t M, int knn) {
     l.per_graph = o;
     // row kernel scratch: per workgroup four int arrays of `cap` entries
     l.scratch_per_wg = align256((size_t)l.cap * 4) * 4;     // counters, candidates, two tuple columns
-    int per_graph_wg = 64;
+    int per_graph_wg = 128;
     while (per_graph_wg > 1 &&
            ((size_t)per_graph_wg * n_graphs > PJ_MAX_WG ||
-            (size_t)per_graph_wg * n_graphs * l.scratch_per_wg > ((size_t)3 << 30)))
+            (size_t)per_graph_wg * n_graphs * l.scratch_per_wg > ((size_t)8 << 30)))
         per_graph_wg >>= 1;
     l.n_wg = per_graph_wg;
     l.o_scratch = l.per_graph * n_graphs;
@@ -324,17 +324,17 @@ __device__ __forceinline__ Cand cand_lane(const Cand& x, int src) {
 // one compare-exchange step of a bitonic network over the 64 lanes: partner lane ^ J; the lane
 // keeps the better of the two when keep_best, else the worse
 template <int J>
-__device__ __forceinline__ Cand cand_exchange(const Cand& v, bool keep_best, uint32_t pa) {
+__device__ __forceinline__ Cand cand_exchange(const Cand& v, bool keep_best, uint32_t pa, int lane) {
     Cand o;
-    o.c = (uint32_t)__shfl_xor((int)v.c, J);
-    o.pb = (uint32_t)__shfl_xor((int)v.pb, J);
-    o.b = __shfl_xor(v.b, J);
+    o.c = lane_xor32<J>(v.c, lane);
+    o.pb = lane_xor32<J>(v.pb, lane);
+    o.b = (int32_t)lane_xor32<J>((uint32_t)v.b, lane);
     return (cand_before(o, v, pa) == keep_best) ? o : v;
 }
 // 64 candidates, one per lane, into rank order (DESC: lane 0 the best; else lane 63 the best)
 template <bool DESC>
 __device__ __forceinline__ Cand cand_sort64(Cand v, uint32_t pa, int lane) {
-#define PJ_STEP(K_, J_) v = cand_exchange<J_>(v, (((lane & J_) == 0) == ((lane & K_) == 0)) == DESC, pa);
+#define PJ_STEP(K_, J_) v = cand_exchange<J_>(v, (((lane & J_) == 0) == ((lane & K_) == 0)) == DESC, pa, lane);
     PJ_STEP(2, 1)
     PJ_STEP(4, 2) PJ_STEP(4, 1)
     PJ_STEP(8, 4) PJ_STEP(8, 2) PJ_STEP(8, 1)
@@ -346,12 +346,12 @@ __device__ __forceinline__ Cand cand_sort64(Cand v, uint32_t pa, int lane) {
 }
 // a bitonic sequence of 64 into descending rank order
 __device__ __forceinline__ Cand cand_merge64(Cand v, uint32_t pa, int lane) {
-    v = cand_exchange<32>(v, (lane & 32) == 0, pa);
-    v = cand_exchange<16>(v, (lane & 16) == 0, pa);
-    v = cand_exchange<8>(v, (lane & 8) == 0, pa);
-    v = cand_exchange<4>(v, (lane & 4) == 0, pa);
-    v = cand_exchange<2>(v, (lane & 2) == 0, pa);
-    v = cand_exchange<1>(v, (lane & 1) == 0, pa);
+    v = cand_exchange<32>(v, (lane & 32) == 0, pa, lane);
+    v = cand_exchange<16>(v, (lane & 16) == 0, pa, lane);
+    v = cand_exchange<8>(v, (lane & 8) == 0, pa, lane);
+    v = cand_exchange<4>(v, (lane & 4) == 0, pa, lane);
+    v = cand_exchange<2>(v, (lane & 2) == 0, pa, lane);
+    v = cand_exchange<1>(v, (lane & 1) == 0, pa, lane);
     return v;
 }
 
@@ -370,19 +370,36 @@ __device__ __forceinline__ void rows_for_graph(const int32_t* __restrict__ Lg, c
                                                int32_t* __restrict__ adj_g, int* s_ncand,
                                                Cand (*s_best)[64]) {
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+    const int kp = knn <= 32 ? 32 : 64;
     for (int t = blockIdx.x; t < H; t += gridDim.x) {
         const int a = w.pi[t];
         const uint32_t pa = (uint32_t)w.pop[a];
         const int o0 = w.off[a];
         if (tid == 0) *s_ncand = 0;
         __syncthreads();
-        // count co-listed keys; the first touch of a counter appends the key to the candidates
-        const int64_t work = (int64_t)pa * knn;
-        for (int64_t x = tid; x < work; x += PJ_ROW_T) {
-            const int j = w.inv[o0 + (int)(x / knn)];
-            const int b = Lg[(size_t)j * knn + (int)(x % knn)];
-            if (b != a && b >= 0 && b < N) {
-                if (atomicAdd(&cnt[w.pos[b]], 1u) == 0u) cand[atomicAdd(s_ncand, 1)] = b;
+        // count co-listed keys; the first touch of a counter appends the key to the candidates.
+        // A run of kp lanes (kp = 32 or 64 >= knn) reads one list, lane e its e-th entry (one
+        // coalesced row); four lists per lane are in flight at a time.
+        {
+            const int e = tid & (kp - 1), r0 = tid / kp, rstep = PJ_ROW_T / kp;
+            for (int li0 = r0; li0 < (int)pa; li0 += 4 * rstep) {
+                int bb[4], pp[4];
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const int li = li0 + u * rstep;
+                    const int j = w.inv[o0 + (li < (int)pa ? li : (int)pa - 1)];
+                    bb[u] = (li < (int)pa && e < knn) ? Lg[(size_t)j * knn + (e < knn ? e : 0)] : -1;
+                }
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    const bool ok = bb[u] != a && bb[u] >= 0 && bb[u] < N;
+                    pp[u] = ok ? w.pos[bb[u]] : -1;
+                }
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    if (pp[u] >= 0 && atomicAdd(&cnt[pp[u]], 1u) == 0u)
+                        cand[atomicAdd(s_ncand, 1)] = bb[u];
+                }
             }
         }
         __syncthreads();
