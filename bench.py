@@ -26,7 +26,7 @@ HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
 # HBM bytes per decode_kernel launch of the default workload, from the two rocprofv3 --pmc runs
 # summarised under profiles/ (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0, KiB per dispatch, scale factors
 # from a 1 GiB device copy in the same runs).
-DECODE_TRAFFIC_BYTES_CONFIG2 = 13989755
+DECODE_TRAFFIC_BYTES_CONFIG2 = 13987929
 MFMA_BF16_PEAK_TFLOPS = 2500.0
 
 
@@ -336,7 +336,7 @@ def main():
         qs = L["q"].float().cpu().numpy()
         tc = time.perf_counter()
         ref_last = {}
-        for t in range(n_tok):
+        for t in [(t_last + i) % T for i in range(n_tok)]:      # starts with the token the GPU ids are from
             for h, Kh, Vh, adj, ent in prepared:
                 _, _, r_ids, _ = OD.decode_step(qs[t, 0, h], Kh, Vh, adj, ent, sink, window, topk, ef,
                                                 a.expand)
