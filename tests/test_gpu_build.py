@@ -31,6 +31,12 @@ def _cases():
         "integer_bf16_knn64": lambda: synth.make_integer_case(6, N=333, M=150, T=2, d=128, n_q=1,
                                                               n_kv=1, dtype=torch.bfloat16, deg=64,
                                                               knn=64, topk=9, ef=20),
+        "integer_bf16_knn48": lambda: synth.make_integer_case(7, N=777, M=130, T=2, d=128, n_q=2,
+                                                              n_kv=1, dtype=torch.bfloat16, deg=48,
+                                                              knn=48, topk=9, ef=20),
+        "integer_f32_knn40": lambda: synth.make_integer_case(8, N=450, M=70, T=2, d=128, n_q=1,
+                                                             n_kv=1, dtype=torch.float32, deg=16,
+                                                             knn=40, topk=9, ef=20),
     }
 
 
@@ -51,6 +57,26 @@ def test_knn_lists(name):
         diff = knn_equivalent(L[s, h], ref, Q, K)
         if name.startswith("integer"):
             assert diff == 0          # integer-valued inputs: every score is exact
+
+
+@pytest.mark.parametrize("dtype", [torch.bfloat16, torch.float32])
+@pytest.mark.parametrize("knn", [5, 32, 48, 64])
+@pytest.mark.parametrize("rising", [True, False])
+def test_knn_monotone_stream(dtype, knn, rising):
+    """Scores that rise with the key id make every key of the stream qualify (the selection folds or
+    inserts all the time); falling scores make none qualify after the first knn. Key i scores exactly
+    +-i for every query (i = 256 * K[i,1] + K[i,0], both exact in bf16), so the lists are known."""
+    N, M = 3001, 77
+    K = torch.zeros((1, 1, N, 128), dtype=torch.float32)
+    i = torch.arange(N)
+    K[0, 0, :, 0] = (i % 256).float()
+    K[0, 0, :, 1] = (i // 256).float()
+    Q = torch.zeros((1, 1, M, 128), dtype=torch.float32)
+    Q[0, 0, :, 0] = 1.0 if rising else -1.0
+    Q[0, 0, :, 1] = 256.0 if rising else -256.0
+    L = ra.ra_knn(K.to(dtype).to(DEV), Q.to(dtype).to(DEV), knn).cpu().numpy()[0, 0]
+    want = np.arange(N - 1, N - 1 - knn, -1) if rising else np.arange(knn)
+    assert np.array_equal(L, np.broadcast_to(want, (M, knn)))
 
 
 def test_projection_hand_worked_example():
