@@ -61,6 +61,40 @@ __device__ __forceinline__ float at_dpp(float v) {
     return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xF, 0xF, true));
 }
 
+// The 8 values of a row that a lane owns, as loaded (16 bytes of bf16 or 32 bytes of fp32).
+template <int DT> struct Row8;
+template <> struct Row8<RA_BF16> { uint4 a; };
+template <> struct Row8<RA_F32> { float4 a, b; };
+
+template <int DT>
+__device__ __forceinline__ Row8<DT> load_row8_raw(const void* base, int64_t row, int lane16) {
+    Row8<DT> r;
+    if constexpr (DT == RA_BF16) {
+        r.a = *reinterpret_cast<const uint4*>(reinterpret_cast<const uint16_t*>(base) + row * RA_D +
+                                              lane16 * 8);
+    } else {
+        const float4* p = reinterpret_cast<const float4*>(reinterpret_cast<const float*>(base) +
+                                                          row * RA_D + lane16 * 8);
+        r.a = p[0];
+        r.b = p[1];
+    }
+    return r;
+}
+template <int DT>
+__device__ __forceinline__ void row8_floats(const Row8<DT>& r, float* o) {
+    if constexpr (DT == RA_BF16) {
+        o[0] = bf16_lo(r.a.x); o[1] = bf16_hi(r.a.x); o[2] = bf16_lo(r.a.y); o[3] = bf16_hi(r.a.y);
+        o[4] = bf16_lo(r.a.z); o[5] = bf16_hi(r.a.z); o[6] = bf16_lo(r.a.w); o[7] = bf16_hi(r.a.w);
+    } else {
+        o[0] = r.a.x; o[1] = r.a.y; o[2] = r.a.z; o[3] = r.a.w;
+        o[4] = r.b.x; o[5] = r.b.y; o[6] = r.b.z; o[7] = r.b.w;
+    }
+}
+// exp for the softmax weights: the hardware exponential for bf16 data (its error is far below the
+// inputs'), the library one for fp32
+template <int DT>
+__device__ __forceinline__ float at_exp(float x) { return DT == RA_BF16 ? __expf(x) : expf(x); }
+
 // One chunk for NH query heads that share the same K/V rows.
 // A call covers `n_sub` consecutive sub-chunks of 64 rows (1 for the decode step; more when a
 // long dense range is streamed, so that the number of partial records stays small).
@@ -83,44 +117,83 @@ __device__ void attend_chunk(int tid, bool active, const void* q0, const void* K
         for (int e = 0; e < 8; ++e) acc[g][e] = 0.f;
     }
     constexpr int RPG = AT_CH / 16;    // rows per 16-lane group and sub-chunk
-    // the call covers sub-chunks [chunk * n_sub, (chunk + 1) * n_sub) of 64 rows each
-    for (int sub = chunk * n_sub; sub < (chunk + 1) * n_sub; ++sub) {
-    int64_t rid[RPG];
-    float kv[RPG][8], vv[RPG][8];
+    // The call covers sub-chunks [chunk * n_sub, (chunk + 1) * n_sub) of 64 rows each. The rows of
+    // the next sub-chunk are requested (raw, 16 or 32 bytes per lane and row) before the current
+    // one is worked through. Loads are never branched around: a row that does not exist reads
+    // row 0 and is skipped, a sub-chunk past the end repeats the last one and is not used.
+    const int sub_end = (chunk + 1) * n_sub;
+    auto rows_of = [&](int sub, int64_t (&rid)[RPG]) {
+        if (sub >= sub_end) sub = sub_end - 1;
 #pragma unroll
-    for (int i = 0; i < RPG; ++i) {
-        const int r = src.interleave
-            ? (sub / src.interleave) * AT_CH * src.interleave + (sub % src.interleave) * 16 + grp +
-                  16 * src.interleave * i
-            : sub * AT_CH + grp + 16 * i;
-        rid[i] = chunk_row(src, r);
-        if (rid[i] >= 0) {
-            load_row8<DT>(Kh, rid[i], lane16, kv[i]);
-            load_row8<DT>(Vh, rid[i], lane16, vv[i]);
+        for (int i = 0; i < RPG; ++i) {
+            const int r = src.interleave
+                ? (sub / src.interleave) * AT_CH * src.interleave + (sub % src.interleave) * 16 + grp +
+                      16 * src.interleave * i
+                : sub * AT_CH + grp + 16 * i;
+            rid[i] = chunk_row(src, r);
         }
-    }
+    };
+    auto fetch = [&](const int64_t (&rid)[RPG], Row8<DT> (&kr)[RPG], Row8<DT> (&vr)[RPG]) {
 #pragma unroll
-    for (int i = 0; i < RPG; ++i) {
-        if (rid[i] < 0) continue;
-#pragma unroll
-        for (int g = 0; g < NH; ++g) {
-            float dot = 0.f;
-#pragma unroll
-            for (int e = 0; e < 8; ++e) dot = fmaf(qv[g][e], kv[i][e], dot);
-            dot += at_dpp<0xB1>(dot);      // xor 1
-            dot += at_dpp<0x4E>(dot);      // xor 2
-            dot += at_dpp<0x141>(dot);     // half-mirror: the other quad pair of the row of 8
-            dot += at_dpp<0x140>(dot);     // mirror: the other half of the row of 16
-            const float z = dot * scale;
-            const float mn = fmaxf(m[g], z);
-            const float corr = expf(m[g] - mn);      // exp(-inf) = 0 on the first row
-            const float p = expf(z - mn);
-            l[g] = l[g] * corr + p;
-#pragma unroll
-            for (int e = 0; e < 8; ++e) acc[g][e] = fmaf(p, vv[i][e], acc[g][e] * corr);
-            m[g] = mn;
+        for (int i = 0; i < RPG; ++i) {
+            const int64_t row = rid[i] >= 0 ? rid[i] : 0;
+            kr[i] = load_row8_raw<DT>(Kh, row, lane16);
+            vr[i] = load_row8_raw<DT>(Vh, row, lane16);
         }
-    }
+    };
+    auto consume = [&](const int64_t (&rid)[RPG], const Row8<DT> (&kr)[RPG], const Row8<DT> (&vr)[RPG]) {
+#pragma unroll
+        for (int i = 0; i < RPG; ++i) {
+            float kv[8], vv[8];
+            row8_floats<DT>(kr[i], kv);
+            row8_floats<DT>(vr[i], vv);
+            const bool have = rid[i] >= 0;
+#pragma unroll
+            for (int g = 0; g < NH; ++g) {
+                float dot = 0.f;
+#pragma unroll
+                for (int e = 0; e < 8; ++e) dot = fmaf(qv[g][e], kv[e], dot);
+                dot += at_dpp<0xB1>(dot);      // xor 1
+                dot += at_dpp<0x4E>(dot);      // xor 2
+                dot += at_dpp<0x141>(dot);     // half-mirror: the other quad pair of the row of 8
+                dot += at_dpp<0x140>(dot);     // mirror: the other half of the row of 16
+                const float z = have ? dot * scale : -INFINITY;
+                // the running maximum settles after a few rows: the sums are rescaled only when
+                // some lane of the wavefront sees a larger logit
+                if (__builtin_amdgcn_ballot_w64(z > m[g]) != 0ull) {
+                    const bool up = z > m[g];                     // other lanes keep their sums
+                    const float corr = up ? at_exp<DT>(m[g] - z) : 1.f;   // exp(-inf) = 0 on the first row
+                    l[g] *= corr;
+#pragma unroll
+                    for (int e = 0; e < 8; ++e) acc[g][e] *= corr;
+                    m[g] = up ? z : m[g];
+                }
+                const float p = have ? at_exp<DT>(z - m[g]) : 0.f;
+                l[g] += p;
+#pragma unroll
+                for (int e = 0; e < 8; ++e) acc[g][e] = fmaf(p, vv[e], acc[g][e]);
+            }
+        }
+    };
+    {
+        int64_t rid_a[RPG], rid_b[RPG];
+        Row8<DT> k_a[RPG], v_a[RPG], k_b[RPG], v_b[RPG];
+        int sub = chunk * n_sub;
+        rows_of(sub, rid_a);
+        fetch(rid_a, k_a, v_a);
+        if (n_sub == 1) {                     // the decode step's short sets: nothing to run ahead of
+            consume(rid_a, k_a, v_a);
+            sub = sub_end;
+        }
+        for (; sub < sub_end; sub += 2) {
+            rows_of(sub + 1, rid_b);
+            fetch(rid_b, k_b, v_b);
+            consume(rid_a, k_a, v_a);
+            if (sub + 1 >= sub_end) break;
+            rows_of(sub + 2, rid_a);
+            fetch(rid_a, k_a, v_a);
+            consume(rid_b, k_b, v_b);
+        }
     }
     // combine the 16 row-groups of the workgroup, one head at a time
     float* sm = smem;                       // [16]
