@@ -7,25 +7,33 @@
 //   1. flat_scores_kernel: streams K once per KV head and scores every key against the query
 //      heads of its GQA group (16 lanes per key row, the same fixed-order float32 inner product
 //      as the graph search, so both rank keys identically); writes one order-preserving uint32
-//      per (head, key), 0 for keys of the static set W, which retrieval must not return.
-//   2. flat_select_kernel: one workgroup per head. A threshold placed from a strided sample
-//      lets one pass collect a few hundred candidates that provably contain the top-k; they are
-//      sorted by (score descending, id ascending) with a bitonic network in LDS. When the
-//      sample cannot place a safe threshold, an exact radix select over all keys (four 8-bit
-//      histogram passes) finds the k-th largest key, and the keys above it plus the lowest ids
-//      among its ties are taken.
+//      per (head, key), 0 for keys of the static set W, which retrieval must not return, and
+//      the largest of them per tile: the FL_TILE keys that one 16-lane group scores in a chunk
+//      (ids congruent modulo 16 within the chunk of FL_CHUNK), so a tile maximum is one
+//      register that never leaves its lane until it is written.
+//   2. flat_select_kernel: one workgroup per head. The topk-th largest tile maximum is a
+//      threshold that at least topk keys reach, so every key of the answer (and every tie of
+//      its last one) lies at or above it, in a tile whose maximum does: only those tiles (about
+//      topk of them) are read again, their keys at or above the threshold are collected and
+//      sorted by (score descending, id ascending) with a bitonic network in LDS. With too few
+//      tiles for that, a threshold placed from a strided sample and one pass over all keys do
+//      the same; when neither can place a safe threshold, an exact radix select over all keys
+//      (four 8-bit histogram passes) finds the k-th largest key, and the keys above it plus the
+//      lowest ids among its ties are taken.
 #include "search_dev.h"
 
 #define FL_THREADS 256
 #define FL_CHUNK 512               // keys per workgroup of the scoring kernel
 #define FL_SEL_T 1024
 #define FL_ROWS 8                  // key rows in flight per 16-lane group
+#define FL_TILE (FL_CHUNK / 16)     // keys per tile maximum: chunk base + group + 16 j, j < FL_TILE
+#define FL_TILES_MAX 8192          // tiles per head the select kernel can list (256K keys)
 
 // grid: x = chunk of FL_CHUNK keys, y = KV head, z = seq
 template <int DT, int G>
 __global__ __launch_bounds__(FL_THREADS) void flat_scores_kernel(
     const void* __restrict__ q, const void* __restrict__ K, int n_q, int n_kv, int64_t N, int s, int w,
-    uint32_t* __restrict__ keys) {
+    uint32_t* __restrict__ keys, uint32_t* __restrict__ tile_max, int64_t n_tiles) {
     const int tid = threadIdx.x, grp = tid >> 4, lane16 = tid & 15;
     const int kvh = blockIdx.y, seq = blockIdx.z, h0 = seq * n_q + kvh * G;
     const size_t esz = DT == RA_BF16 ? 2 : 4;
@@ -35,6 +43,9 @@ __global__ __launch_bounds__(FL_THREADS) void flat_scores_kernel(
     for (int g = 0; g < G; ++g)
         load_q8<DT>(reinterpret_cast<const char*>(q) + (size_t)(h0 + g) * RA_D * esz, lane16, qv[g]);
     const int64_t base = (int64_t)blockIdx.x * FL_CHUNK;
+    uint32_t best[G];
+#pragma unroll
+    for (int g = 0; g < G; ++g) best[g] = 0u;
     for (int r0 = 0; r0 < FL_CHUNK; r0 += 16 * FL_ROWS) {
         RowBits<DT> rows[FL_ROWS];
         int64_t id[FL_ROWS];
@@ -50,10 +61,17 @@ __global__ __launch_bounds__(FL_THREADS) void flat_scores_kernel(
                 const float sc = score_fixed<DT>(rows[u], qv[g]);
                 if (lane16 == 0 && id[u] < N) {
                     const bool is_static = id[u] < s || id[u] >= N - w;
-                    keys[(size_t)(h0 + g) * N + id[u]] = is_static ? 0u : f32_ordered(sc);
+                    const uint32_t key = is_static ? 0u : f32_ordered(sc);
+                    keys[(size_t)(h0 + g) * N + id[u]] = key;
+                    best[g] = key > best[g] ? key : best[g];
                 }
             }
         }
+    }
+    if (lane16 == 0) {
+        const int64_t tile = (int64_t)blockIdx.x * 16 + grp;
+#pragma unroll
+        for (int g = 0; g < G; ++g) tile_max[(size_t)(h0 + g) * n_tiles + tile] = best[g];
     }
 }
 
@@ -123,9 +141,12 @@ __device__ __forceinline__ void radix_select(const uint32_t* __restrict__ kh, in
 // collected, sorting them gives the exact answer (all ties of the k-th key are in the set).
 // Otherwise (tiny or adversarial inputs) the exact radix select over all keys decides.
 __global__ __launch_bounds__(FL_SEL_T) void flat_select_kernel(const uint32_t* __restrict__ keys,
-                                                               int64_t N, int topk,
+                                                               const uint32_t* __restrict__ tile_max,
+                                                               int64_t n_tiles, int64_t N, int topk,
                                                                int32_t* __restrict__ ids_out) {
     __shared__ unsigned hist[256], wsum4[4];
+    __shared__ unsigned s_ntl;
+    __shared__ unsigned short s_tl[FL_TILES_MAX];
     __shared__ unsigned s_prefix, s_need, s_cnt, s_eq_total, s_run;
     __shared__ unsigned long long sel[FL_CAND];
     __shared__ int wtot[FL_SEL_T / RA_WAVE];
@@ -133,8 +154,51 @@ __global__ __launch_bounds__(FL_SEL_T) void flat_select_kernel(const uint32_t* _
     const uint32_t* kh = keys + (size_t)blockIdx.x * N;
     int32_t* out = ids_out + (size_t)blockIdx.x * topk;
     int n = -1;                                  // number of selected entries once known
+    if (n_tiles >= 2 * (int64_t)topk && n_tiles <= FL_TILES_MAX) {
+        // ---- tile path: T0 = the topk-th largest tile maximum (exact), then only the tiles at or above it
+        // the head's tile maxima, copied into LDS (the candidate array is not in use yet)
+        uint32_t* tm = reinterpret_cast<uint32_t*>(sel);
+        for (int64_t t = tid; t < n_tiles; t += FL_SEL_T) tm[t] = tile_max[(size_t)blockIdx.x * n_tiles + t];
+        __syncthreads();
+        radix_select(tm, n_tiles, 1, (unsigned)topk, hist, wsum4, &s_prefix, &s_need, &s_eq_total);
+        const uint32_t T0 = s_prefix;
+        if (tid == 0) { s_cnt = 0u; s_ntl = 0u; }
+        __syncthreads();
+        if (T0 != 0u) {
+            for (int64_t t = tid; t < n_tiles; t += FL_SEL_T)
+                if (tm[t] >= T0) s_tl[atomicAdd(&s_ntl, 1u)] = (unsigned short)t;
+            __syncthreads();
+            const int ntl = (int)s_ntl;
+            // thread = (tile of the list, key of the tile); four tiles of the list per thread in flight
+            constexpr int TPI = FL_SEL_T / FL_TILE;              // list entries per pass of the workgroup
+            const int sub = tid / FL_TILE, kk = tid % FL_TILE;
+            for (int l0 = 0; l0 < ntl; l0 += 4 * TPI) {
+                uint32_t kv[4];
+                int64_t ki[4];
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {                 // loads first, all in flight
+                    const int l = l0 + u * TPI + sub;
+                    const int64_t tl = s_tl[l < ntl ? l : ntl - 1];
+                    ki[u] = (tl / 16) * FL_CHUNK + (tl % 16) + 16 * kk;
+                    kv[u] = kh[ki[u] < N ? ki[u] : N - 1];
+                }
+#pragma unroll
+                for (int u = 0; u < 4; ++u) {
+                    if (l0 + u * TPI + sub < ntl && ki[u] < N && kv[u] >= T0) {
+                        const unsigned at = atomicAdd(&s_cnt, 1u);
+                        if (at < FL_CAND)
+                            sel[at] = ((unsigned long long)kv[u] << 32) | (0xffffffffu - (uint32_t)ki[u]);
+                    }
+                }
+            }
+        }
+        __syncthreads();
+        const unsigned c = s_cnt;
+        if (T0 != 0u && c >= (unsigned)topk && c <= FL_CAND) n = (int)c;
+        __syncthreads();
+    }
     const int64_t stride = N / FL_SAMPLE;
-    if (stride >= 8 && (int64_t)topk * 4 <= N / 4) {
+    if (n < 0 && stride >= 8 && (int64_t)topk * 4 <= N / 4) {
         const unsigned want = (unsigned)((4 * (int64_t)topk + stride - 1) / stride) + 2u;
         radix_select(kh, N / stride, stride, want, hist, wsum4, &s_prefix, &s_need, &s_eq_total);
         const uint32_t T0 = s_prefix;
@@ -204,7 +268,16 @@ __global__ __launch_bounds__(FL_SEL_T) void flat_select_kernel(const uint32_t* _
         __syncthreads();
         n = (int)s_cnt;                          // <= topk (fewer when W leaves fewer eligible keys)
     }
-    // ---- sort (score descending, id ascending) = 64-bit key descending
+    // ---- order by (score descending, id ascending) = 64-bit key descending
+    if (n <= FL_SEL_T) {
+        // few candidates (the usual case): a thread's candidate goes where the count of larger keys says
+        const unsigned long long mine = tid < n ? sel[tid] : 0ull;
+        int rank = 0;
+        for (int x = 0; x < n; ++x) rank += sel[x] > mine ? 1 : 0;
+        if (tid < n && rank < topk) out[rank] = (int32_t)(0xffffffffu - (uint32_t)mine);
+        for (int i = n + tid; i < topk; i += FL_SEL_T) out[i] = -1;
+        return;
+    }
     int n2 = 1;
     while (n2 < n) n2 <<= 1;
     for (int i = n + tid; i < n2; i += FL_SEL_T) sel[i] = 0ull;
@@ -297,6 +370,8 @@ ra_status ra_launch_rerank(const void* q, const void* K, ra_dtype dt, int n_seq,
 ra_status ra_launch_flat_topk(const void* q, const void* K, ra_dtype dt, int n_seq, int n_q, int n_kv,
                               int64_t N, int sink, int window, int topk, uint32_t* keys_ws,
                               hipStream_t st, int32_t* ids) {
+    const int64_t n_tiles = 16 * ((N + FL_CHUNK - 1) / FL_CHUNK);
+    uint32_t* tile_max = keys_ws + (size_t)n_seq * n_q * N;      // [heads][n_tiles], after the keys
     int64_t ss = sink < 0 ? 0 : sink, ww = window < 0 ? 0 : window;
     if (ss > N) ss = N;
     if (ww > N) ww = N;
@@ -306,7 +381,7 @@ ra_status ra_launch_flat_topk(const void* q, const void* K, ra_dtype dt, int n_s
 #define RA_FL_CASE(DTV, GG)                                                                     \
     case GG:                                                                                    \
         hipLaunchKernelGGL((flat_scores_kernel<DTV, GG>), grid, dim3(FL_THREADS), 0, st, q, K, n_q, \
-                           n_kv, N, (int)ss, (int)ww, keys_ws);                                 \
+                           n_kv, N, (int)ss, (int)ww, keys_ws, tile_max, n_tiles);              \
         break;
     if (dt == RA_BF16) {
         switch (G) { RA_FL_CASE(RA_BF16, 1) RA_FL_CASE(RA_BF16, 2) RA_FL_CASE(RA_BF16, 4) RA_FL_CASE(RA_BF16, 8)
@@ -317,8 +392,8 @@ ra_status ra_launch_flat_topk(const void* q, const void* K, ra_dtype dt, int n_s
     }
 #undef RA_FL_CASE
     RA_HIP(hipGetLastError());
-    hipLaunchKernelGGL(flat_select_kernel, dim3(n_seq * n_q), dim3(FL_SEL_T), 0, st, keys_ws, N, topk,
-                       ids);
+    hipLaunchKernelGGL(flat_select_kernel, dim3(n_seq * n_q), dim3(FL_SEL_T), 0, st, keys_ws, tile_max,
+                       n_tiles, N, topk, ids);
     RA_HIP(hipGetLastError());
     return RA_OK;
 }
