@@ -65,7 +65,8 @@ def test_flat_topk_all_scores_equal_takes_lowest_ids(N):
 
 @pytest.mark.parametrize("topk", [1, 100, 1024, 2048])
 def test_flat_topk_sampled_threshold_path(topk):
-    """Contexts of 32K keys and more place the selection threshold from a sample."""
+    """40000 keys are 1264 tiles: topk 1 and 100 take their threshold from the tile maxima, 1024 and
+    2048 (more than half as many as there are tiles) from a strided sample."""
     w = synth.make_llama_layer(41, N=40000, M=8, T=1, n_q=4, n_kv=2, window=640)
     ids = ra.ra_flat_topk(w.q_decode[0].to(DEV), w.K.to(DEV), 4, 640, topk).cpu().numpy()
     W = OA.static_ids(40000, 4, 640)
