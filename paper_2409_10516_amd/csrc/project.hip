@@ -27,6 +27,8 @@
 //      the first wavefront merges the four results and writes the row.
 // No global sort of the M*knn*(knn-1) co-occurrence pairs is needed: the skewed keys that sit
 // in nearly every list are simply the longest-running work items and are scheduled first.
+#include <type_traits>
+
 #include "common.h"
 
 #define PJ_T 1024                 // threads of the ordering kernel
@@ -42,6 +44,7 @@ struct ProjWs {                   // per-graph device arrays, carved from one wo
     int32_t* off;                 // [N+1] CSR offsets of inverted lists
     int32_t* cur;                 // [N]   fill cursors
     int32_t* inv;                 // [M*knn]
+    int32_t* lp;                  // [M*knn] the lists with every key replaced by its position in pi (-1: none)
     int32_t* hk[2];               // [cap] radix ping-pong: keys
     int32_t* hi[2];               // [cap] radix ping-pong: ids
     int32_t* H;                   // [1]   number of populated keys
@@ -50,7 +53,7 @@ struct ProjWs {                   // per-graph device arrays, carved from one wo
 static size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 
 struct ProjLayout {
-    size_t per_graph, o_pop, o_pos, o_pi, o_off, o_cur, o_inv, o_hk0, o_hk1, o_hi0, o_hi1, o_H;
+    size_t per_graph, o_pop, o_pos, o_pi, o_off, o_cur, o_inv, o_lp, o_hk0, o_hk1, o_hi0, o_hi1, o_H;
     size_t scratch_per_wg, o_scratch;
     int n_wg;
     int64_t cap;
@@ -67,6 +70,7 @@ static ProjLayout proj_layout(int n_graphs, int64_t N, int64_t M, int knn) {
     l.o_off = o; o += align256((size_t)(N + 1) * 4);
     l.o_cur = o; o += align256((size_t)N * 4);
     l.o_inv = o; o += align256((size_t)cells * 4);
+    l.o_lp = o; o += align256((size_t)cells * 4);
     l.o_hk0 = o; o += align256((size_t)l.cap * 4);
     l.o_hk1 = o; o += align256((size_t)l.cap * 4);
     l.o_hi0 = o; o += align256((size_t)l.cap * 4);
@@ -95,6 +99,7 @@ __device__ __forceinline__ ProjWs carve(char* ws, const ProjLayout& l, int g) {
     ProjWs w;
     w.pop = (int32_t*)(b + l.o_pop); w.pos = (int32_t*)(b + l.o_pos); w.pi = (int32_t*)(b + l.o_pi);
     w.off = (int32_t*)(b + l.o_off); w.cur = (int32_t*)(b + l.o_cur); w.inv = (int32_t*)(b + l.o_inv);
+    w.lp = (int32_t*)(b + l.o_lp);
     w.hk[0] = (int32_t*)(b + l.o_hk0); w.hk[1] = (int32_t*)(b + l.o_hk1);
     w.hi[0] = (int32_t*)(b + l.o_hi0); w.hi[1] = (int32_t*)(b + l.o_hi1);
     w.H = (int32_t*)(b + l.o_H);
@@ -250,6 +255,7 @@ __global__ __launch_bounds__(PJ_T) void pj_order_kernel(char* ws, ProjLayout l, 
         const int id = w.hi[src][t];
         w.pi[t] = id;
         w.pos[id] = t;
+        w.hk[0][t] = w.pop[id];        // from here on hk[0] is the popularity by position
     }
     for (int64_t i = tid; i < N; i += PJ_T) {
         if (w.pop[i] == 0) {
@@ -270,10 +276,13 @@ __global__ void pj_inv_kernel(const int32_t* __restrict__ L, char* ws, ProjLayou
     for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < cells;
          i += (int64_t)gridDim.x * blockDim.x) {
         const int32_t k = Lg[i];
+        int32_t p = -1;
         if (k >= 0 && k < N) {
             const int slot = atomicAdd(&w.cur[k], 1);
             w.inv[w.off[k] + slot] = (int32_t)(i / knn);
+            p = w.pos[k];
         }
+        w.lp[i] = p;
     }
 }
 
@@ -377,30 +386,34 @@ __device__ __forceinline__ void rows_for_graph(const int32_t* __restrict__ Lg, c
         const int o0 = w.off[a];
         if (tid == 0) *s_ncand = 0;
         __syncthreads();
-        // count co-listed keys; the first touch of a counter appends the key to the candidates.
-        // A run of kp lanes (kp = 32 or 64 >= knn) reads one list, lane e its e-th entry (one
-        // coalesced row); four lists per lane are in flight at a time.
+        // count co-listed keys; the first touch of a counter appends the key (its position in pi)
+        // to the candidates. A run of kp lanes (kp = 32 or 64 >= knn) reads one list, lane e its
+        // e-th entry (one coalesced row of the position-translated lists, so no lookup per
+        // entry is left).
         {
             const int e = tid & (kp - 1), r0 = tid / kp, rstep = PJ_ROW_T / kp;
-            for (int li0 = r0; li0 < (int)pa; li0 += 4 * rstep) {
-                int bb[4], pp[4];
+            auto count_lists = [&](auto unroll_tag, int li_begin, int li_end) {
+                constexpr int U = decltype(unroll_tag)::value;
+                for (int li0 = li_begin + r0; li0 < li_end; li0 += U * rstep) {
+                    int pp[U];
 #pragma unroll
-                for (int u = 0; u < 4; ++u) {
-                    const int li = li0 + u * rstep;
-                    const int j = w.inv[o0 + (li < (int)pa ? li : (int)pa - 1)];
-                    bb[u] = (li < (int)pa && e < knn) ? Lg[(size_t)j * knn + (e < knn ? e : 0)] : -1;
-                }
+                    for (int u = 0; u < U; ++u) {
+                        const int li = li0 + u * rstep;
+                        const int j = w.inv[o0 + (li < li_end ? li : li_end - 1)];
+                        pp[u] = (li < li_end && e < knn) ? w.lp[(size_t)j * knn + (e < knn ? e : 0)] : -1;
+                    }
 #pragma unroll
-                for (int u = 0; u < 4; ++u) {
-                    const bool ok = bb[u] != a && bb[u] >= 0 && bb[u] < N;
-                    pp[u] = ok ? w.pos[bb[u]] : -1;
+                    for (int u = 0; u < U; ++u) {
+                        if (pp[u] >= 0 && pp[u] != t && atomicAdd(&cnt[pp[u]], 1u) == 0u)
+                            cand[atomicAdd(s_ncand, 1)] = pp[u];
+                    }
                 }
-#pragma unroll
-                for (int u = 0; u < 4; ++u) {
-                    if (pp[u] >= 0 && atomicAdd(&cnt[pp[u]], 1u) == 0u)
-                        cand[atomicAdd(s_ncand, 1)] = bb[u];
-                }
-            }
+            };
+            // a hub sits in tens of thousands of lists and one workgroup walks them all: sixteen
+            // lists per lane in flight there, four for the many small keys
+            const int bulk = (int)pa >= 16 * rstep * 8 ? ((int)pa / (16 * rstep)) * (16 * rstep) : 0;
+            if (bulk) count_lists(std::integral_constant<int, 16>{}, 0, bulk);
+            count_lists(std::integral_constant<int, 4>{}, bulk, (int)pa);
         }
         __syncthreads();
         const int nc = *s_ncand;
@@ -411,12 +424,11 @@ __device__ __forceinline__ void rows_for_graph(const int32_t* __restrict__ Lg, c
         uint32_t* tp = tl ? tp_l : tp_g;
         int32_t* tb = tl ? tb_l : cand;
         for (int x = tid; x < nc; x += PJ_ROW_T) {
-            const int b = cand[x];
-            const int pb = w.pos[b];
+            const int pb = cand[x];
             tc[x] = cnt[pb];
             cnt[pb] = 0u;
-            tp[x] = (uint32_t)w.pop[b];
-            if (tl) tb[x] = b;
+            tp[x] = (uint32_t)w.hk[0][pb];
+            tb[x] = w.pi[pb];            // the candidate list itself, when the tuples stay in global memory
         }
         __syncthreads();
         // best 64 of this wavefront's chunks, sorted: lane l holds its l-th best
