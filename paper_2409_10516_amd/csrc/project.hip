@@ -409,11 +409,41 @@ __device__ __forceinline__ void rows_for_graph(const int32_t* __restrict__ Lg, c
                     }
                 }
             };
-            // a hub sits in tens of thousands of lists and one workgroup walks them all: sixteen
-            // lists per lane in flight there, four for the many small keys
-            const int bulk = (int)pa >= 16 * rstep * 8 ? ((int)pa / (16 * rstep)) * (16 * rstep) : 0;
-            if (bulk) count_lists(std::integral_constant<int, 16>{}, 0, bulk);
-            count_lists(std::integral_constant<int, 4>{}, bulk, (int)pa);
+            // A hub sits in tens of thousands of lists and one workgroup walks them all. Its lists
+            // go through a three-deep pipeline, sixteen per lane and stage: the list numbers of
+            // pass i + 2 and the rows of pass i + 1 are in flight while pass i bumps its counters
+            // (a pass that ran list number -> row -> counters in sequence would be two memory
+            // latencies long). Indices past the end are clamped, never branched around.
+            constexpr int UB = 16;
+            const int per_pass = UB * rstep;
+            const int n_pass = (int)pa >= 8 * per_pass ? (int)pa / per_pass : 0;
+            if (n_pass) {
+                int j0[UB], j1[UB], j2[UB], p0[UB], p1[UB];
+                auto load_inv = [&](int pass, int (&jj)[UB]) {
+                    if (pass >= n_pass) pass = n_pass - 1;
+#pragma unroll
+                    for (int u = 0; u < UB; ++u) jj[u] = w.inv[o0 + pass * per_pass + r0 + u * rstep];
+                };
+                auto load_rows = [&](const int (&jj)[UB], int (&pp)[UB]) {
+#pragma unroll
+                    for (int u = 0; u < UB; ++u) pp[u] = w.lp[(size_t)jj[u] * knn + (e < knn ? e : 0)];
+                };
+                load_inv(0, j0);
+                load_inv(1, j1);
+                load_rows(j0, p0);
+                for (int pass = 0; pass < n_pass; ++pass) {
+                    load_inv(pass + 2, j2);
+                    load_rows(j1, p1);
+#pragma unroll
+                    for (int u = 0; u < UB; ++u) {
+                        if (e < knn && p0[u] >= 0 && p0[u] != t && atomicAdd(&cnt[p0[u]], 1u) == 0u)
+                            cand[atomicAdd(s_ncand, 1)] = p0[u];
+                    }
+#pragma unroll
+                    for (int u = 0; u < UB; ++u) { p0[u] = p1[u]; j1[u] = j2[u]; }
+                }
+            }
+            count_lists(std::integral_constant<int, 4>{}, n_pass * per_pass, (int)pa);
         }
         __syncthreads();
         const int nc = *s_ncand;
