@@ -125,16 +125,33 @@ __global__ void pj_zero_kernel(char* ws, ProjLayout l, int64_t N, int n_graphs) 
 }
 
 // ---- 1. pop ----------------------------------------------------------------------------
-__global__ void pj_pop_kernel(const int32_t* __restrict__ L, char* ws, ProjLayout l, int64_t cells,
-                              int64_t N) {
+// The queries share their favourite keys (a hub is in nearly every list), so plain atomic adds
+// would queue up on a handful of addresses. Each workgroup counts in a small direct-mapped table
+// in LDS first (slot = key mod PJ_HOT, owned by the first key that claims it; other keys that
+// map there go straight to memory) and adds every owned slot to memory once at the end.
+#define PJ_HOT 2048
+__global__ __launch_bounds__(256) void pj_pop_kernel(const int32_t* __restrict__ L, char* ws,
+                                                     ProjLayout l, int64_t cells, int64_t N) {
+    __shared__ int s_tag[PJ_HOT];
+    __shared__ int s_num[PJ_HOT];
     const int g = blockIdx.y;
     ProjWs w = carve(ws, l, g);
     const int32_t* Lg = L + (size_t)g * cells;
+    for (int x = threadIdx.x; x < PJ_HOT; x += blockDim.x) { s_tag[x] = -1; s_num[x] = 0; }
+    __syncthreads();
     for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < cells;
          i += (int64_t)gridDim.x * blockDim.x) {
         const int32_t k = Lg[i];
-        if (k >= 0 && k < N) atomicAdd(&w.pop[k], 1);
+        if (k >= 0 && k < N) {
+            const int x = k & (PJ_HOT - 1);
+            const int owner = atomicCAS(&s_tag[x], -1, k);
+            if (owner == -1 || owner == k) atomicAdd(&s_num[x], 1);
+            else atomicAdd(&w.pop[k], 1);
+        }
     }
+    __syncthreads();
+    for (int x = threadIdx.x; x < PJ_HOT; x += blockDim.x)
+        if (s_tag[x] >= 0) atomicAdd(&w.pop[s_tag[x]], s_num[x]);
 }
 
 // ---- 2. ordering -----------------------------------------------------------------------
@@ -268,17 +285,43 @@ __global__ __launch_bounds__(PJ_T) void pj_order_kernel(char* ws, ProjLayout l, 
 }
 
 // ---- 3. inverted lists -----------------------------------------------------------------
-__global__ void pj_inv_kernel(const int32_t* __restrict__ L, char* ws, ProjLayout l, int64_t cells,
-                              int knn, int64_t N) {
+// Same trick for the fill cursors: a workgroup first counts its cells per hot key in LDS, takes
+// one range of every such key's inverted list with a single atomic add, and hands out the places
+// inside its ranges with LDS atomics in a second pass over the same cells. The order of the
+// entries inside an inverted list is immaterial (only co-occurrence counts come out of them).
+__global__ __launch_bounds__(256) void pj_inv_kernel(const int32_t* __restrict__ L, char* ws,
+                                                     ProjLayout l, int64_t cells, int knn, int64_t N) {
+    __shared__ int s_tag[PJ_HOT];
+    __shared__ int s_num[PJ_HOT];
+    __shared__ int s_base[PJ_HOT];
     const int g = blockIdx.y;
     ProjWs w = carve(ws, l, g);
     const int32_t* Lg = L + (size_t)g * cells;
+    for (int x = threadIdx.x; x < PJ_HOT; x += blockDim.x) { s_tag[x] = -1; s_num[x] = 0; }
+    __syncthreads();
+    for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < cells;
+         i += (int64_t)gridDim.x * blockDim.x) {
+        const int32_t k = Lg[i];
+        if (k >= 0 && k < N) {
+            const int x = k & (PJ_HOT - 1);
+            const int owner = atomicCAS(&s_tag[x], -1, k);
+            if (owner == -1 || owner == k) atomicAdd(&s_num[x], 1);
+        }
+    }
+    __syncthreads();
+    for (int x = threadIdx.x; x < PJ_HOT; x += blockDim.x) {
+        if (s_tag[x] >= 0) s_base[x] = atomicAdd(&w.cur[s_tag[x]], s_num[x]);
+        s_num[x] = 0;                                  // now the cursor inside the range
+    }
+    __syncthreads();
     for (int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x; i < cells;
          i += (int64_t)gridDim.x * blockDim.x) {
         const int32_t k = Lg[i];
         int32_t p = -1;
         if (k >= 0 && k < N) {
-            const int slot = atomicAdd(&w.cur[k], 1);
+            const int x = k & (PJ_HOT - 1);
+            const int slot = s_tag[x] == k ? s_base[x] + atomicAdd(&s_num[x], 1)
+                                           : atomicAdd(&w.cur[k], 1);
             w.inv[w.off[k] + slot] = (int32_t)(i / knn);
             p = w.pos[k];
         }
