@@ -407,6 +407,46 @@ __device__ __forceinline__ Cand cand_merge64(Cand v, uint32_t pa, int lane) {
     return v;
 }
 
+// Row of the key at position t: its backbone children pi[2t+1], pi[2t+2], then the ranked
+// candidates (lane l of `best` holds the l-th best, `want` of them count) that are not among
+// the children, until deg entries; -1 beyond. One wavefront.
+__device__ __forceinline__ void write_row(int32_t* row, const Cand& best, int want, int t,
+                                          const int32_t* pi, int64_t N, int deg, int lane) {
+    int32_t kids[2] = {-1, -1};
+    int nk = 0;
+    for (int s = 0; s < 2 && nk < deg; ++s) {
+        const int64_t ch = 2 * (int64_t)t + 1 + s;
+        if (ch < N) kids[nk++] = pi[ch];
+    }
+    const bool keep = best.c > 0u && lane < want && best.b != kids[0] && best.b != kids[1];
+    const unsigned long long km = __ballot(keep);
+    const int at = nk + __popcll(km & ((1ull << lane) - 1ull));
+    const int total = nk + __popcll(km);
+    if (lane < nk) row[lane] = kids[lane];
+    if (keep && at < deg) row[at] = best.b;
+    if (lane >= total && lane < deg) row[lane] = -1;
+}
+
+// Keys with few lists are handled one per wavefront (pj_rows_small_kernel), the others one per
+// workgroup: the first position in pi (popularity descending) whose key has at most `limit` lists.
+#define PJ_SMALL_TOUCH 1024       // list cells (lists x knn) of a key the wavefront kernel takes
+#define PJ_SMALL_SLOTS 2048       // its hash table: at most half full
+#define PJ_SMALL_WAVES 4
+__device__ __forceinline__ int small_limit(int knn) {
+    const int lim = PJ_SMALL_TOUCH / knn;
+    return lim < 127 ? lim : 127;                 // a count must fit the 7 bits of a table entry
+}
+__device__ __forceinline__ int first_small(const int32_t* pop_by_pos, int H, int knn) {
+    if (H >= (1 << 24)) return H;                 // a position must fit the other 25 bits
+    const int limit = small_limit(knn);
+    int lo = 0, hi = H;
+    while (lo < hi) {
+        const int mid = (lo + hi) >> 1;
+        if (pop_by_pos[mid] > limit) lo = mid + 1; else hi = mid;
+    }
+    return lo;
+}
+
 #define PJ_LDS_CNT 8192           // co-occurrence counters kept in LDS when the populated set fits
 #define PJ_LDS_TUP 2048           // candidate tuples kept in LDS when the candidate list fits
 
@@ -423,7 +463,8 @@ __device__ __forceinline__ void rows_for_graph(const int32_t* __restrict__ Lg, c
                                                Cand (*s_best)[64]) {
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
     const int kp = knn <= 32 ? 32 : 64;
-    for (int t = blockIdx.x; t < H; t += gridDim.x) {
+    const int t_end = first_small(w.hk[0], H, knn);       // the rest is pj_rows_small_kernel's
+    for (int t = blockIdx.x; t < t_end; t += gridDim.x) {
         const int a = w.pi[t];
         const uint32_t pa = (uint32_t)w.pop[a];
         const int o0 = w.off[a];
@@ -526,20 +567,7 @@ __device__ __forceinline__ void rows_for_graph(const int32_t* __restrict__ Lg, c
                 if (cand_before(cd, best, pa)) best = cd;
                 best = cand_merge64(best, pa, lane);
             }
-            int32_t* row = adj_g + (size_t)a * deg;
-            int32_t kids[2] = {-1, -1};
-            int nk = 0;
-            for (int s = 0; s < 2 && nk < deg; ++s) {
-                const int64_t ch = 2 * (int64_t)t + 1 + s;
-                if (ch < N) kids[nk++] = w.pi[ch];
-            }
-            const bool keep = best.c > 0u && lane < want && best.b != kids[0] && best.b != kids[1];
-            const unsigned long long km = __ballot(keep);
-            const int at = nk + __popcll(km & ((1ull << lane) - 1ull));
-            const int total = nk + __popcll(km);
-            if (lane < nk) row[lane] = kids[lane];
-            if (keep && at < deg) row[at] = best.b;
-            if (lane >= total && lane < deg) row[lane] = -1;
+            write_row(adj_g + (size_t)a * deg, best, want, t, w.pi, N, deg, lane);
         }
         __syncthreads();
     }
@@ -576,6 +604,92 @@ __global__ __launch_bounds__(PJ_ROW_T) void pj_rows_kernel(const int32_t* __rest
     }
 }
 
+// Rows of the keys with few lists, one key per wavefront, no workgroup barrier. Co-occurrence
+// counts go into an open-addressing table in LDS (entry = (position + 1) << 7 | count, sized to
+// twice the key's list cells), which is then packed in place into the candidate list; the
+// candidates' popularity and id are gathered, and the same bitonic selection as above ranks them.
+__global__ __launch_bounds__(PJ_SMALL_WAVES * 64) void pj_rows_small_kernel(
+    char* ws, ProjLayout l, int64_t N, int knn, int deg, int32_t* __restrict__ adj) {
+    __shared__ uint32_t s_slot[PJ_SMALL_WAVES][PJ_SMALL_SLOTS];
+    __shared__ uint32_t s_tp[PJ_SMALL_WAVES][PJ_SMALL_TOUCH];
+    __shared__ int32_t s_tb[PJ_SMALL_WAVES][PJ_SMALL_TOUCH];
+    const int g = blockIdx.y;
+    ProjWs w = carve(ws, l, g);
+    int32_t* adj_g = adj + (size_t)g * N * deg;
+    const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
+    uint32_t* slot = s_slot[wv];
+    uint32_t* tp = s_tp[wv];
+    int32_t* tb = s_tb[wv];
+    const int H = *w.H;
+    const int32_t* ppop = w.hk[0];
+    const int kp = knn <= 32 ? 32 : 64, e = lane & (kp - 1), lpp = 64 / kp;     // lists per pass
+    for (int x = lane; x < PJ_SMALL_SLOTS; x += 64) slot[x] = 0u;
+    const int t_small = first_small(ppop, H, knn);
+    for (int t = t_small + blockIdx.x * PJ_SMALL_WAVES + wv; t < H; t += gridDim.x * PJ_SMALL_WAVES) {
+        const int a = w.pi[t];
+        const int pa = ppop[t];
+        const int o0 = w.off[a];
+        int slots = 128;
+        while (slots < 2 * pa * knn) slots <<= 1;           // <= PJ_SMALL_SLOTS by small_limit()
+        const uint32_t mask = (uint32_t)slots - 1u;
+        // count
+        for (int li0 = lane / kp; li0 < pa; li0 += 4 * lpp) {
+            int pp[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int li = li0 + u * lpp;
+                const int j = w.inv[o0 + (li < pa ? li : pa - 1)];
+                pp[u] = (li < pa && e < knn) ? w.lp[(size_t)j * knn + (e < knn ? e : 0)] : -1;
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                if (pp[u] < 0 || pp[u] == t) continue;
+                const uint32_t key = (uint32_t)pp[u] + 1u;
+                uint32_t h = ((key * 2654435761u) >> 12) & mask;
+                for (int probe = 0; probe < slots; ++probe) {
+                    uint32_t v = __hip_atomic_load(&slot[h], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+                    if (v == 0u) {
+                        v = atomicCAS(&slot[h], 0u, (key << 7) | 1u);
+                        if (v == 0u) break;                      // claimed, count 1
+                    }
+                    if ((v >> 7) == key) { atomicAdd(&slot[h], 1u); break; }
+                    h = (h + 1u) & mask;
+                }
+            }
+        }
+        __builtin_amdgcn_wave_barrier();
+        // pack the table in place: entry q moves to the number of entries before it
+        int nc = 0;
+        for (int q0 = 0; q0 < slots; q0 += 64) {
+            const uint32_t v = slot[q0 + lane];
+            slot[q0 + lane] = 0u;
+            const unsigned long long m = __ballot(v != 0u);
+            if (v != 0u) slot[nc + __popcll(m & ((1ull << lane) - 1ull))] = v;
+            nc += __popcll(m);
+        }
+        __builtin_amdgcn_wave_barrier();
+        for (int x = lane; x < nc; x += 64) {
+            const int pb = (int)(slot[x] >> 7) - 1;
+            tp[x] = (uint32_t)ppop[pb];
+            tb[x] = w.pi[pb];
+        }
+        __builtin_amdgcn_wave_barrier();
+        Cand best = cand_none();
+        for (int x0 = 0; x0 < nc; x0 += 64) {
+            Cand cd = cand_none();
+            if (x0 + lane < nc) { cd.b = tb[x0 + lane]; cd.c = slot[x0 + lane] & 127u; cd.pb = tp[x0 + lane]; }
+            const Cand last = cand_lane(best, 63);
+            if (__ballot(cand_before(cd, last, (uint32_t)pa)) == 0ull) continue;
+            cd = cand_sort64<false>(cd, (uint32_t)pa, lane);
+            if (cand_before(cd, best, (uint32_t)pa)) best = cd;
+            best = cand_merge64(best, (uint32_t)pa, lane);
+        }
+        __builtin_amdgcn_wave_barrier();
+        for (int x = lane; x < nc; x += 64) slot[x] = 0u;       // the table is empty again
+        write_row(adj_g + (size_t)a * deg, best, nc < deg ? nc : deg, t, w.pi, N, deg, lane);
+    }
+}
+
 ra_status ra_launch_project(const int32_t* L, int n_graphs, int64_t N, int64_t M, int knn, int deg,
                             void* workspace, hipStream_t st, int32_t* adj, int32_t* entry) {
     if (M * (int64_t)knn >= ((int64_t)1 << 31))
@@ -591,6 +705,9 @@ ra_status ra_launch_project(const int32_t* L, int n_graphs, int64_t N, int64_t M
     hipLaunchKernelGGL(pj_backbone_kernel, dim3(gx, n_graphs), dim3(256), 0, st, ws, l, N, deg, adj);
     hipLaunchKernelGGL(pj_rows_kernel, dim3(l.n_wg, n_graphs), dim3(PJ_ROW_T), 0, st, L, ws, l, N, M,
                        knn, deg, adj);
+    const unsigned small_wg = n_graphs >= 512 ? 1u : (unsigned)(512 / n_graphs);   // 2 per compute unit
+    hipLaunchKernelGGL(pj_rows_small_kernel, dim3(small_wg, n_graphs), dim3(PJ_SMALL_WAVES * 64), 0, st,
+                       ws, l, N, knn, deg, adj);
     RA_HIP(hipGetLastError());
     return RA_OK;
 }
