@@ -447,6 +447,22 @@ __device__ __forceinline__ int first_small(const int32_t* pop_by_pos, int H, int
     return lo;
 }
 
+// One more co-occurrence of the key at position `key - 1` in an open-addressing table of `slots`
+// (a power of two) LDS words, entry = key << 7 | count; the table is never more than half full.
+__device__ __forceinline__ void lds_table_bump(uint32_t* tab, int slots, uint32_t key) {
+    const uint32_t mask = (uint32_t)slots - 1u;
+    uint32_t h = ((key * 2654435761u) >> 12) & mask;
+    for (int probe = 0; probe < slots; ++probe) {
+        uint32_t v = __hip_atomic_load(&tab[h], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+        if (v == 0u) {
+            v = atomicCAS(&tab[h], 0u, (key << 7) | 1u);
+            if (v == 0u) return;                      // claimed, count 1
+        }
+        if ((v >> 7) == key) { atomicAdd(&tab[h], 1u); return; }
+        h = (h + 1u) & mask;
+    }
+}
+
 #define PJ_LDS_CNT 8192           // co-occurrence counters kept in LDS when the populated set fits
 #define PJ_LDS_TUP 2048           // candidate tuples kept in LDS when the candidate list fits
 
@@ -460,7 +476,7 @@ __device__ __forceinline__ void rows_for_graph(const int32_t* __restrict__ Lg, c
                                                uint32_t* tp_g, uint32_t* tc_l, uint32_t* tp_l,
                                                int32_t* tb_l, int64_t N, int knn, int deg, int H,
                                                int32_t* __restrict__ adj_g, int* s_ncand,
-                                               Cand (*s_best)[64]) {
+                                               Cand (*s_best)[64], uint32_t* lds_tab) {
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
     const int kp = knn <= 32 ? 32 : 64;
     const int t_end = first_small(w.hk[0], H, knn);       // the rest is pj_rows_small_kernel's
@@ -468,6 +484,10 @@ __device__ __forceinline__ void rows_for_graph(const int32_t* __restrict__ Lg, c
         const int a = w.pi[t];
         const uint32_t pa = (uint32_t)w.pop[a];
         const int o0 = w.off[a];
+        // With more populated keys than LDS counters, a key of moderate size still counts in LDS:
+        // the counter array serves as an open-addressing table (entry = (position + 1) << 7 |
+        // count, at most half full); only the hubs of such a graph count in device memory.
+        const bool hashed = !LDSCNT && pa <= 127u && (int)pa * knn <= PJ_LDS_CNT / 2 && H < (1 << 24);
         if (tid == 0) *s_ncand = 0;
         __syncthreads();
         // count co-listed keys; the first touch of a counter appends the key (its position in pi)
@@ -488,8 +508,12 @@ __device__ __forceinline__ void rows_for_graph(const int32_t* __restrict__ Lg, c
                     }
 #pragma unroll
                     for (int u = 0; u < U; ++u) {
-                        if (pp[u] >= 0 && pp[u] != t && atomicAdd(&cnt[pp[u]], 1u) == 0u)
+                        if (pp[u] < 0 || pp[u] == t) continue;
+                        if (hashed) {
+                            lds_table_bump(lds_tab, PJ_LDS_CNT, (uint32_t)pp[u] + 1u);
+                        } else if (atomicAdd(&cnt[pp[u]], 1u) == 0u) {
                             cand[atomicAdd(s_ncand, 1)] = pp[u];
+                        }
                     }
                 }
             };
@@ -530,6 +554,16 @@ __device__ __forceinline__ void rows_for_graph(const int32_t* __restrict__ Lg, c
             count_lists(std::integral_constant<int, 4>{}, n_pass * per_pass, (int)pa);
         }
         __syncthreads();
+        if (hashed) {                    // empty the table into the candidate list (entries as they are)
+            for (int q = tid; q < PJ_LDS_CNT; q += PJ_ROW_T) {
+                const uint32_t v = lds_tab[q];
+                if (v != 0u) {
+                    lds_tab[q] = 0u;
+                    cand[atomicAdd(s_ncand, 1)] = (int32_t)v;
+                }
+            }
+            __syncthreads();
+        }
         const int nc = *s_ncand;
         const int want = nc < deg ? nc : deg;
         // gather (count, popularity, id) of every candidate once; reset its counter on the way
@@ -538,9 +572,14 @@ __device__ __forceinline__ void rows_for_graph(const int32_t* __restrict__ Lg, c
         uint32_t* tp = tl ? tp_l : tp_g;
         int32_t* tb = tl ? tb_l : cand;
         for (int x = tid; x < nc; x += PJ_ROW_T) {
-            const int pb = cand[x];
-            tc[x] = cnt[pb];
-            cnt[pb] = 0u;
+            int pb = cand[x];
+            if (hashed) {
+                tc[x] = (uint32_t)pb & 127u;
+                pb = (int)((uint32_t)pb >> 7) - 1;
+            } else {
+                tc[x] = cnt[pb];
+                cnt[pb] = 0u;
+            }
             tp[x] = (uint32_t)w.hk[0][pb];
             tb[x] = w.pi[pb];            // the candidate list itself, when the tuples stay in global memory
         }
@@ -597,10 +636,12 @@ __global__ __launch_bounds__(PJ_ROW_T) void pj_rows_kernel(const int32_t* __rest
         for (int i = threadIdx.x; i < H; i += PJ_ROW_T) s_cnt[i] = 0u;
         __syncthreads();
         rows_for_graph<true>(Lg, w, s_cnt, cand, tc_g, tp_g, s_tc, s_tp, s_tb, N, knn, deg, H, adj_g,
-                             &s_ncand, s_best);
+                             &s_ncand, s_best, s_cnt);
     } else {
+        for (int i = threadIdx.x; i < PJ_LDS_CNT; i += PJ_ROW_T) s_cnt[i] = 0u;
+        __syncthreads();
         rows_for_graph<false>(Lg, w, cnt_g, cand, tc_g, tp_g, s_tc, s_tp, s_tb, N, knn, deg, H, adj_g,
-                              &s_ncand, s_best);
+                              &s_ncand, s_best, s_cnt);
     }
 }
 
@@ -631,7 +672,6 @@ __global__ __launch_bounds__(PJ_SMALL_WAVES * 64) void pj_rows_small_kernel(
         const int o0 = w.off[a];
         int slots = 128;
         while (slots < 2 * pa * knn) slots <<= 1;           // <= PJ_SMALL_SLOTS by small_limit()
-        const uint32_t mask = (uint32_t)slots - 1u;
         // count
         for (int li0 = lane / kp; li0 < pa; li0 += 4 * lpp) {
             int pp[4];
@@ -644,17 +684,7 @@ __global__ __launch_bounds__(PJ_SMALL_WAVES * 64) void pj_rows_small_kernel(
 #pragma unroll
             for (int u = 0; u < 4; ++u) {
                 if (pp[u] < 0 || pp[u] == t) continue;
-                const uint32_t key = (uint32_t)pp[u] + 1u;
-                uint32_t h = ((key * 2654435761u) >> 12) & mask;
-                for (int probe = 0; probe < slots; ++probe) {
-                    uint32_t v = __hip_atomic_load(&slot[h], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
-                    if (v == 0u) {
-                        v = atomicCAS(&slot[h], 0u, (key << 7) | 1u);
-                        if (v == 0u) break;                      // claimed, count 1
-                    }
-                    if ((v >> 7) == key) { atomicAdd(&slot[h], 1u); break; }
-                    h = (h + 1u) & mask;
-                }
+                lds_table_bump(slot, slots, (uint32_t)pp[u] + 1u);
             }
         }
         __builtin_amdgcn_wave_barrier();
