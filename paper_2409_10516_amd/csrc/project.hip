@@ -10,21 +10,28 @@
 //             overlap c / (pop(a) + pop(b) - c), ties by larger c, then lower id, until deg.
 //
 // Device plan, all stream-ordered, no host round trip:
-//   1. pop by atomic histogram over the list cells.
+//   1. pop by atomic histogram over the list cells, through a per-workgroup LDS table so that a
+//      hub costs one atomic per workgroup instead of one per list.
 //   2. one workgroup per graph: prefix sums over the keys (CSR offsets of the inverted lists,
 //      compaction of the keys with pop > 0), a stable 4-bit LSD radix sort of those keys by
-//      descending pop, and from it pi, its inverse pos, and the entry point.
-//   3. inverted lists (key -> the lists that hold it) filled through per-key cursors.
+//      descending pop, and from it pi, its inverse pos, pop by position, and the entry point.
+//   3. inverted lists (key -> the lists that hold it) filled through per-key cursors (ranges
+//      reserved per workgroup through the same kind of LDS table), and a copy of the lists with
+//      every key replaced by its position in pi.
 //   4. backbone children and -1 padding for every row (fully coalesced).
-//   5. persistent workgroups walk the populated keys in pi order (largest first): for key a
-//      they stream the lists that hold a, bump a counter per co-listed key (table indexed by
-//      pos, so it is as small as the populated set: in LDS when it fits, else in global
-//      scratch), collect first-touched keys as the candidate list, gather each candidate's
-//      (count, popularity, id) once while resetting its counter, then select the best 64 in rank
-//      order: every wavefront runs its share of the candidates, 64 at a time, through a bitonic
-//      network across its lanes (fractions compared by 64-bit cross-multiplication) and merges
-//      each sorted chunk into its running best 64; chunks that cannot beat the 64th are skipped;
-//      the first wavefront merges the four results and writes the row.
+//   5. rows of the populated keys, in pi order (largest first). For key a: stream the lists that
+//      hold a (whole rows of the translated lists, coalesced), count each co-listed key, collect
+//      the candidates with (count, popularity, id), and select the best 64 in rank order: 64
+//      candidates at a time go through a bitonic network across the lanes of a wavefront
+//      (fractions compared by 64-bit cross-multiplication) and are merged into its running best
+//      64; chunks that cannot beat the 64th are skipped. Three regimes by the number of lists:
+//        - few (lists x knn <= 1024): one key per wavefront, counts in an LDS hash table, no
+//          workgroup barrier (pj_rows_small_kernel);
+//        - the rest: one key per workgroup (pj_rows_kernel), counts in an LDS table indexed by
+//          position when the graph has at most 8192 populated keys, else in an LDS hash table
+//          (moderate keys) or in the workgroup's scratch in device memory (hubs); the four
+//          wavefronts share the candidates and the first one merges their results;
+//        - hubs (thousands of lists) run their lists through a three-deep load pipeline.
 // No global sort of the M*knn*(knn-1) co-occurrence pairs is needed: the skewed keys that sit
 // in nearly every list are simply the longest-running work items and are scheduled first.
 #include <type_traits>
