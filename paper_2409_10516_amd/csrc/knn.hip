@@ -271,13 +271,18 @@ __global__ __launch_bounds__(WAVES * RA_WAVE) void knn_kernel(
 #pragma unroll
                 for (int g = 0; g < 4; ++g) {
                     if (__ballot(gm[g] >= tau[sidx]) == 0ull) continue;
-                    // a lane that may append needs room for four keys: fold the queries short of it
-                    u64 need = __ballot(gm[g] >= tau[sidx] && fill[sidx] > pend - 4);
+                    // a lane needs room for the keys of this group that reach its threshold: fold the
+                    // queries short of it (the count can only fall when a fold raises the threshold)
+                    int n4 = 0;
+#pragma unroll
+                    for (int r = 4 * g; r < 4 * g + 4; ++r) n4 += cs[r] >= tau[sidx] ? 1 : 0;
+                    u64 need = __ballot(fill[sidx] + n4 > pend);
                     while (need) {
                         const int jq = (__ffsll((long long)need) - 1) & 31;
                         const float nt = knn_fold(set_lists + (size_t)jq * KN_CAP, knn, lane);
                         if (col == jq) { tau[sidx] = nt; fill[sidx] = 0; }
-                        need = __ballot(gm[g] >= tau[sidx] && fill[sidx] > pend - 4);
+                        need &= need - 1;
+                        need &= ~(1ull << (jq + 32)) & ~(1ull << jq);
                     }
 #pragma unroll
                     for (int r = 4 * g; r < 4 * g + 4; ++r) {
