@@ -87,6 +87,30 @@ def test_projection_hand_worked_example():
     assert adj[0].cpu().tolist() == g["adj"]
 
 
+def test_projection_regimes_of_a_large_graph():
+    """More populated keys than the row kernel has LDS counters, with the three kinds of key such a
+    graph holds: hubs (in half of all lists: counters in device memory, pipelined list walk), keys of
+    about 60 lists (LDS hash table, one workgroup per key) and keys of a handful of lists (one
+    wavefront per key). Every hub and middle key and a sample of the small ones against the oracle."""
+    rng = np.random.default_rng(17)
+    N, M, knn, deg = 20000, 3000, 48, 16
+    hubs, mids, rest = np.arange(10), np.arange(10, 310), np.arange(310, N)
+    L = np.empty((M, knn), np.int32)
+    for j in range(M):
+        row = np.concatenate([rng.choice(hubs, 5, replace=False), rng.choice(mids, 6, replace=False),
+                              rng.choice(rest, knn - 11, replace=False)])
+        L[j] = rng.permutation(row)
+    adj, entry = ra.ra_project(torch.from_numpy(L[None]).to(DEV), N, deg)
+    adj = adj[0].cpu().numpy()
+    rows = np.concatenate([hubs, mids, rng.choice(rest, 400, replace=False)])
+    radj, rent = OP.project(L, N, deg, rows=rows)
+    assert int(entry[0]) == rent
+    pop = np.bincount(L.ravel(), minlength=N)
+    assert (pop > 0).sum() > 8192 and pop[hubs].min() > 1000 and 21 < pop[mids].min() and pop[mids].max() <= 85
+    for a in rows:
+        assert np.array_equal(adj[a], radj[a]), (a, adj[a], radj[a])
+
+
 @pytest.mark.parametrize("name", list(_cases()))
 @pytest.mark.parametrize("deg", [None, 2, 5])
 def test_projection_bit_exact_on_oracle_lists(name, deg):
