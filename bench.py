@@ -11,7 +11,8 @@ projection) runs before the timed region and is reported separately.
 
 Prints ONE JSON line: the metric and its value, the workload, `roofline` (the fused decode
 kernel's algorithmic bytes per launch over its measured launch time, against 8 TB/s, with the
-HBM traffic the counters read), `stages`, `exact_baselines`, `build`, `cpu_baseline`.
+HBM traffic the counters read), `stages`, `exact_baselines`, `build` (with `knn_kernel`: the
+index-build GEMM's live time for one layer against the dense MFMA peak), `cpu_baseline`.
 """
 import argparse
 import json
@@ -28,6 +29,7 @@ HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
 # from a 1 GiB device copy in the same runs).
 DECODE_TRAFFIC_BYTES_CONFIG2 = 13988512
 MFMA_BF16_PEAK_TFLOPS = 2500.0
+MFMA_F32_PEAK_TFLOPS = 157.3
 
 
 def parse():
@@ -117,6 +119,19 @@ def main():
         w = mk(l)
         torch.cuda.synchronize()
         t1 = time.time()
+        if l == 0:
+            # the index-build GEMM alone (exact KNN with the fused selection), HIP events on the launch stream
+            ra.ra_knn(w.K, w.Q_prefill, w.knn)
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            ra.ra_knn(w.K, w.Q_prefill, w.knn)
+            e1.record()
+            e1.synchronize()
+            knn_ms = e0.elapsed_time(e1)
+            knn_flop = 2.0 * w.Q_prefill.shape[0] * w.Q_prefill.shape[1] * w.Q_prefill.shape[2] * w.K.shape[2] * w.d
+            knn_peak = MFMA_BF16_PEAK_TFLOPS if w.K.element_size() == 2 else MFMA_F32_PEAK_TFLOPS
+            torch.cuda.synchronize()
+            t1 = time.time()
         idx = ra.ra_build_index(w.K, w.Q_prefill, w.deg, w.knn)
         if not a.helpers:
             idx.configure(ra.binding.RA_CFG_HELPERS, ra.binding.RA_HELPERS_OFF)
@@ -381,7 +396,10 @@ def main():
                                "frac_of_hbm_peak": 2 * key_bytes / (full_ms * 1e-3) / 1e9 / HBM_PEAK_GBS},
             "graph_decode_ms_per_layer": decode_ms},
         "build": {"seconds": t_build, "generate_seconds": t_gen,
-                  "knn_TFLOPs_incl_projection": build_flop / max(t_build, 1e-9) / 1e12},
+                  "knn_TFLOPs_incl_projection": build_flop / max(t_build, 1e-9) / 1e12,
+                  "knn_kernel": {"bound": "mfma", "ms_layer0": knn_ms, "achieved": knn_flop / (knn_ms * 1e-3) / 1e12,
+                                 "peak": knn_peak, "unit": "TFLOP/s",
+                                 "frac": knn_flop / (knn_ms * 1e-3) / 1e12 / knn_peak}},
         "cpu_baseline": cpu,
     }
     print(json.dumps(out))
