@@ -11,7 +11,8 @@
 // (about knn * ln(N / knn) per query over the whole stream) go further. For knn <= KN_BUFFERED_KNN a
 // query owns KN_CAP list slots in LDS: its best knn keys so far, then two runs of pending slots,
 // one per lane that scores for it. A lane appends a qualifying key to its own run with a single
-// LDS write (its fill count is a register); when a run is nearly full the wavefront sorts the 64
+// LDS write (its fill count is a register); when a run cannot take what a lane is about to append
+// (keys come four at a time) the wavefront sorts the 64
 // slots of that query across its lanes (bitonic network), keeps the best knn and raises the
 // threshold. Between two such merges the threshold is stale but valid (never above the true one),
 // so nothing is lost and a query is merged only ~ln(N/knn) / ln(1 + pending/knn) times. Longer
