@@ -28,6 +28,23 @@ void ra_set_error(const char* fmt, ...);
         }                                                                         \
     } while (0)
 
+// ---- LDS above 64 KB ------------------------------------------------------------------
+#define RA_LDS_LIMIT (160 * 1024)     // LDS a workgroup can have on this part (above 64 KB: opt-in)
+#define RA_MAX_DEVICES 64
+// A kernel that wants more than 64 KB of dynamic LDS has to say so once per device (host side).
+#define RA_LDS_OPT_IN(KERNEL, BYTES)                                                               \
+    do {                                                                                           \
+        static size_t granted_[RA_MAX_DEVICES];                                                    \
+        int dev_ = 0;                                                                              \
+        RA_HIP(hipGetDevice(&dev_));                                                               \
+        if (dev_ < 0 || dev_ >= RA_MAX_DEVICES) RA_FAIL(RA_EUNSUP, "device %d out of range", dev_); \
+        if ((size_t)(BYTES) > 64 * 1024 && granted_[dev_] < (size_t)(BYTES)) {                      \
+            RA_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&KERNEL),                     \
+                                       hipFuncAttributeMaxDynamicSharedMemorySize, RA_LDS_LIMIT)); \
+            granted_[dev_] = RA_LDS_LIMIT;                                                         \
+        }                                                                                          \
+    } while (0)
+
 // ---- handle --------------------------------------------------------------------------
 struct ra_index {
     int n_seq, n_q, n_kv, deg;

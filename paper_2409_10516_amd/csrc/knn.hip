@@ -36,8 +36,6 @@
 
 #define KN_CAP 64                 // list slots of a query in the buffered selection (one per lane)
 #define KN_BUFFERED_KNN 48        // longest list that leaves room for pending slots
-#define KN_LDS_LIMIT (160 * 1024)
-#define KN_MAX_DEVICES 64
 
 typedef unsigned long long u64;
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
@@ -361,30 +359,14 @@ __global__ __launch_bounds__(WAVES * RA_WAVE) void knn_kernel(
     }
 }
 
-// Dynamic LDS above 64 KB needs an opt-in per kernel and device.
-template <typename Kern>
-static ra_status knn_lds_opt_in(Kern kern, size_t bytes, size_t* granted) {
-    int dev = 0;
-    RA_HIP(hipGetDevice(&dev));
-    if (dev < 0 || dev >= KN_MAX_DEVICES) RA_FAIL(RA_EUNSUP, "device %d out of range", dev);
-    if (bytes > 64 * 1024 && granted[dev] < bytes) {
-        RA_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(kern),
-                                   hipFuncAttributeMaxDynamicSharedMemorySize, KN_LDS_LIMIT));
-        granted[dev] = KN_LDS_LIMIT;
-    }
-    return RA_OK;
-}
-
 template <int DT, int NQ, int WAVES, bool BUF, int STAGE>
 static ra_status knn_launch_as(const void* K, const void* Q, int n_seq, int n_q, int n_kv, int64_t N,
                                int64_t M, int knn, hipStream_t st, int32_t* L) {
-    static size_t granted[KN_MAX_DEVICES];
     constexpr int QPB = 32 * NQ * WAVES;
     const size_t lds = (size_t)QPB * (BUF ? KN_CAP : knn) * sizeof(u64) + 2 * STAGE;
-    if (lds > KN_LDS_LIMIT)
-        RA_FAIL(RA_EUNSUP, "knn %d needs %zu bytes of LDS (limit %d)", knn, lds, KN_LDS_LIMIT);
-    ra_status rc = knn_lds_opt_in(&knn_kernel<DT, NQ, WAVES, BUF, STAGE>, lds, granted);
-    if (rc != RA_OK) return rc;
+    if (lds > RA_LDS_LIMIT)
+        RA_FAIL(RA_EUNSUP, "knn %d needs %zu bytes of LDS (limit %d)", knn, lds, RA_LDS_LIMIT);
+    RA_LDS_OPT_IN((knn_kernel<DT, NQ, WAVES, BUF, STAGE>), lds);
     const dim3 grid((unsigned)((M + QPB - 1) / QPB), (unsigned)(n_seq * n_q));
     hipLaunchKernelGGL((knn_kernel<DT, NQ, WAVES, BUF, STAGE>), grid, dim3(WAVES * RA_WAVE), lds, st, K, Q, n_q,
                        n_kv, N, M, knn, L);

@@ -27,9 +27,8 @@
 #include "common.h"
 
 #define SR_THREADS 1024          // largest workgroup; the kernels are also built for 512 and 256 threads
-#define SR_LDS_LIMIT (160 * 1024)     // LDS a workgroup can have on this part (above 64 KB: opt-in)
+#define SR_LDS_LIMIT RA_LDS_LIMIT
 #define SR_BITSET_LDS_MAX (64 * 1024) // a longer visited bitset lives in global memory
-#define RA_MAX_DEVICES 64
 #ifndef SR_UNROLL
 #define SR_UNROLL 4               // key rows in flight per 16-lane group
 #endif
@@ -626,19 +625,6 @@ __device__ __forceinline__ int run_search(
     return ctr[C_NKEEP];
 }
 
-// A kernel that wants more than 64 KB of dynamic LDS has to say so once per device (host side).
-#define RA_LDS_OPT_IN(KERNEL, BYTES)                                                               \
-    do {                                                                                           \
-        static size_t granted_[RA_MAX_DEVICES];                                                    \
-        int dev_ = 0;                                                                              \
-        RA_HIP(hipGetDevice(&dev_));                                                               \
-        if (dev_ < 0 || dev_ >= RA_MAX_DEVICES) RA_FAIL(RA_EUNSUP, "device %d out of range", dev_); \
-        if ((size_t)(BYTES) > 64 * 1024 && granted_[dev_] < (size_t)(BYTES)) {                      \
-            RA_HIP(hipFuncSetAttribute(reinterpret_cast<const void*>(&KERNEL),                     \
-                                       hipFuncAttributeMaxDynamicSharedMemorySize, SR_LDS_LIMIT)); \
-            granted_[dev_] = SR_LDS_LIMIT;                                                         \
-        }                                                                                          \
-    } while (0)
 
 // Threads per search. One search per compute unit or fewer (the latency-bound case): the largest
 // workgroup finishes a search soonest. More searches than compute units: smaller workgroups, so
