@@ -28,7 +28,7 @@
 
 #define SR_THREADS 1024          // largest workgroup; the kernels are also built for 512 and 256 threads
 #define SR_LDS_LIMIT RA_LDS_LIMIT
-#define SR_BITSET_LDS_MAX (64 * 1024) // a longer visited bitset lives in global memory
+#define SR_BITSET_LDS_MAX (128 * 1024) // a longer visited bitset (over 2^20 keys) lives in global memory
 #ifndef SR_UNROLL
 #define SR_UNROLL 4               // key rows in flight per 16-lane group
 #endif

@@ -14,7 +14,7 @@ pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
 
 
-def _check_sampled(w, samples, expand, knn_rows=24, adj_rows=40, seed=0):
+def _check_sampled(w, samples, expand, knn_rows=24, adj_rows=40, seed=0, also_expand=()):
     """samples: list of (seq, q_head). Checks, for each: sampled KNN rows against the exact
     float64 lists; sampled adjacency rows (hubs, mid-popularity and cold keys) against the
     oracle's projection of the device's own lists; ids, counters and attention of a decode
@@ -68,6 +68,16 @@ def _check_sampled(w, samples, expand, knn_rows=24, adj_rows=40, seed=0):
         assert out_close(out[s, h], r_out, tol) and lse_close(lse[s, h], r_lse, tol)
         truth = OM.topk_bruteforce(to_np(q[s, h]), K, w.topk, exclude=W)
         recalls.append(OM.recall(ids[s, h], truth))
+        # the same step at other expansion widths (another placement of the visited bitset, say)
+        for e2 in (also_expand if (s, h) == tuple(samples[0]) else ()):
+            o2, l2, i2, s2 = [x.cpu().numpy() for x in ra.ra_decode_step(
+                q, idx, w.K, w.V, w.sink, w.window, w.topk, w.ef, e2)]
+            r_out, r_lse, r_ids, rst = OD.decode_step(to_np(q[s, h]), K, V, adj, ent, w.sink, w.window,
+                                                      w.topk, w.ef, e2)
+            assert i2[s, h].tolist() == r_ids.tolist(), e2
+            assert s2[s, h].tolist() == [rst["n_visited"], rst["n_expanded"], rst["n_iters"],
+                                         rst["n_returned"]], e2
+            assert out_close(o2[s, h], r_out, tol) and lse_close(l2[s, h], r_lse, tol), e2
     idx.free()
     return float(np.mean(recalls))
 
@@ -91,10 +101,10 @@ def test_config3_batched_16x32k():
 
 
 def test_config4_stress_1m_global_bitset():
-    """N = 2^20 does not fit the LDS visited bitset: exercises the global-memory variant;
-    degree 48, knn 48, topk 200, ef 512."""
+    """N = 2^20: at expand 32 the 128 KB visited bitset does not fit into LDS beside the candidate
+    arrays and lives in device memory; at expand 16 it does. Degree 48, knn 48, topk 200, ef 512."""
     w = synth.make_config4(device=DEV, T=1)
-    r = _check_sampled(w, [(0, 0), (0, 3)], expand=16, knn_rows=6, adj_rows=16)
+    r = _check_sampled(w, [(0, 0), (0, 3)], expand=32, knn_rows=6, adj_rows=16, also_expand=(16,))
     assert r > 0.0
 
 
