@@ -47,7 +47,7 @@ def parse():
     p.add_argument("--deg", type=int, default=None, help="override the graph degree (config2)")
     p.add_argument("--knn", type=int, default=None, help="override the KNN list length (config2)")
     p.add_argument("--expand", type=int, default=None,
-                   help="search expansion width (default 64; 32 for config3, where the smaller "
+                   help="search expansion width (default 64; 16 for config4; 32 for config3, where the smaller "
                         "candidate buffers let more searches share a compute unit)")
     p.add_argument("--tokens", type=int, default=8, help="distinct decode queries per head")
     p.add_argument("--recall-layers", type=int, default=2)
@@ -80,7 +80,7 @@ def main():
         print("bench.py needs a GPU", file=sys.stderr)
         sys.exit(2)
     if a.expand is None:
-        a.expand = 32 if a.workload == "config3" else 64
+        a.expand = {"config3": 32, "config4": 16}.get(a.workload, 64)
     if a.q8 and not a.no_cpu_baseline:
         print("bench.py: --q8 runs skip the CPU baseline (it times the oracle's walk over the keys as stored)",
               file=sys.stderr)
