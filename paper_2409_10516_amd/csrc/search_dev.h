@@ -30,7 +30,7 @@
 #define SR_LDS_LIMIT RA_LDS_LIMIT
 #define SR_BITSET_LDS_MAX (128 * 1024) // a longer visited bitset (over 2^20 keys) lives in global memory
 #ifndef SR_UNROLL
-#define SR_UNROLL 4               // key rows in flight per 16-lane group
+#define SR_UNROLL 8               // key rows in flight per 16-lane group
 #endif
 
 
