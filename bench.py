@@ -27,7 +27,7 @@ HBM_PEAK_GBS = 8000.0          # MI355X published HBM3E bandwidth
 # HBM bytes per decode_kernel launch of the default workload, from the two rocprofv3 --pmc runs
 # summarised under profiles/ (FETCH_SIZE x 2.0 + WRITE_SIZE x 1.0, KiB per dispatch, scale factors
 # from a 1 GiB device copy in the same runs).
-DECODE_TRAFFIC_BYTES_CONFIG2 = 13988512
+DECODE_TRAFFIC_BYTES_CONFIG2 = 13988278
 MFMA_BF16_PEAK_TFLOPS = 2500.0
 MFMA_F32_PEAK_TFLOPS = 157.3
 
