@@ -96,3 +96,16 @@ def test_binding_refuses_cpu_tensors():
     import torch
     with pytest.raises(ValueError):
         ra.ra_knn(torch.zeros(1, 1, 8, 128), torch.zeros(1, 1, 4, 128), 2)
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """bench.py measures one GPU: --gpus 2 ends with a message and a non-zero status before anything
+    touches a device."""
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"],
+                       capture_output=True, text=True, timeout=120)
+    assert r.returncode != 0
+    assert "one GPU" in r.stderr
+    assert r.stdout.strip() == ""
