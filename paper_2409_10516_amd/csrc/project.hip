@@ -436,8 +436,8 @@ __device__ __forceinline__ void write_row(int32_t* row, const Cand& best, int wa
 
 // Keys with few lists are handled one per wavefront (pj_rows_small_kernel), the others one per
 // workgroup: the first position in pi (popularity descending) whose key has at most `limit` lists.
-#define PJ_SMALL_TOUCH 1024       // list cells (lists x knn) of a key the wavefront kernel takes
-#define PJ_SMALL_SLOTS 2048       // its hash table: at most half full
+#define PJ_SMALL_TOUCH 2048       // list cells (lists x knn) of a key the wavefront kernel takes
+#define PJ_SMALL_SLOTS 4096       // its hash table: at most half full
 #define PJ_SMALL_WAVES 4
 __device__ __forceinline__ int small_limit(int knn) {
     const int lim = PJ_SMALL_TOUCH / knn;
@@ -654,20 +654,17 @@ __global__ __launch_bounds__(PJ_ROW_T) void pj_rows_kernel(const int32_t* __rest
 
 // Rows of the keys with few lists, one key per wavefront, no workgroup barrier. Co-occurrence
 // counts go into an open-addressing table in LDS (entry = (position + 1) << 7 | count, sized to
-// twice the key's list cells), which is then packed in place into the candidate list; the
-// candidates' popularity and id are gathered, and the same bitonic selection as above ranks them.
+// twice the key's list cells), which is then packed in place into the candidate list; the same
+// bitonic selection as above ranks the candidates, whose popularity and id are fetched by position
+// one chunk ahead.
 __global__ __launch_bounds__(PJ_SMALL_WAVES * 64) void pj_rows_small_kernel(
     char* ws, ProjLayout l, int64_t N, int knn, int deg, int32_t* __restrict__ adj) {
     __shared__ uint32_t s_slot[PJ_SMALL_WAVES][PJ_SMALL_SLOTS];
-    __shared__ uint32_t s_tp[PJ_SMALL_WAVES][PJ_SMALL_TOUCH];
-    __shared__ int32_t s_tb[PJ_SMALL_WAVES][PJ_SMALL_TOUCH];
     const int g = blockIdx.y;
     ProjWs w = carve(ws, l, g);
     int32_t* adj_g = adj + (size_t)g * N * deg;
     const int tid = threadIdx.x, lane = tid & 63, wv = tid >> 6;
     uint32_t* slot = s_slot[wv];
-    uint32_t* tp = s_tp[wv];
-    int32_t* tb = s_tb[wv];
     const int H = *w.H;
     const int32_t* ppop = w.hk[0];
     const int kp = knn <= 32 ? 32 : 64, e = lane & (kp - 1), lpp = 64 / kp;     // lists per pass
@@ -705,21 +702,28 @@ __global__ __launch_bounds__(PJ_SMALL_WAVES * 64) void pj_rows_small_kernel(
             nc += __popcll(m);
         }
         __builtin_amdgcn_wave_barrier();
-        for (int x = lane; x < nc; x += 64) {
-            const int pb = (int)(slot[x] >> 7) - 1;
-            tp[x] = (uint32_t)ppop[pb];
-            tb[x] = w.pi[pb];
-        }
-        __builtin_amdgcn_wave_barrier();
-        Cand best = cand_none();
+        // rank the candidates 64 at a time; a chunk's popularity and id are fetched (by position)
+        // while the chunk before it is sorted and merged
+        auto fetch = [&](int x0, Cand& cd) {
+            cd = cand_none();
+            const int x = x0 + lane < nc ? x0 + lane : (nc > 0 ? nc - 1 : 0);
+            const uint32_t v = nc > 0 ? slot[x] : 0u;
+            const int pb = v ? (int)(v >> 7) - 1 : 0;
+            const uint32_t pbv = (uint32_t)ppop[pb];
+            const int32_t bv = w.pi[pb];
+            if (x0 + lane < nc) { cd.c = v & 127u; cd.pb = pbv; cd.b = bv; }
+        };
+        Cand best = cand_none(), cur, nxt;
+        fetch(0, cur);
         for (int x0 = 0; x0 < nc; x0 += 64) {
-            Cand cd = cand_none();
-            if (x0 + lane < nc) { cd.b = tb[x0 + lane]; cd.c = slot[x0 + lane] & 127u; cd.pb = tp[x0 + lane]; }
+            fetch(x0 + 64, nxt);
             const Cand last = cand_lane(best, 63);
-            if (__ballot(cand_before(cd, last, (uint32_t)pa)) == 0ull) continue;
-            cd = cand_sort64<false>(cd, (uint32_t)pa, lane);
-            if (cand_before(cd, best, (uint32_t)pa)) best = cd;
-            best = cand_merge64(best, (uint32_t)pa, lane);
+            if (__ballot(cand_before(cur, last, (uint32_t)pa)) != 0ull) {
+                cur = cand_sort64<false>(cur, (uint32_t)pa, lane);
+                if (cand_before(cur, best, (uint32_t)pa)) best = cur;
+                best = cand_merge64(best, (uint32_t)pa, lane);
+            }
+            cur = nxt;
         }
         __builtin_amdgcn_wave_barrier();
         for (int x = lane; x < nc; x += 64) slot[x] = 0u;       // the table is empty again
