@@ -7,7 +7,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libra.so")
-SOURCES = ["api.hip", "attend.hip", "search.hip", "decode.hip", "flat.hip", "knn.hip", "project.hip",
+SOURCES = ["api.hip", "attend.hip", "search.hip", "decode.hip", "flat.hip", "knn.hip", "knn_order.hip", "project.hip",
            "quant.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-ffp-contract=off",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

@@ -250,7 +250,14 @@ extern "C" ra_status ra_knn(const void* K, const void* Q, ra_dtype dt, int n_seq
     RA_TRY(check_heads(n_seq, n_q, n_kv));
     RA_TRY(check_dim(d));
     RA_TRY(check_build_args(N, M, 2, knn, false));
-    return ra_launch_knn(K, Q, dt, n_seq, n_q, n_kv, N, M, knn, (hipStream_t)stream, L_out);
+    void* ws = nullptr;                                    // the order the keys are streamed in
+    RA_HIP(hipMalloc(&ws, ra_knn_order_bytes(n_seq * n_q, N)));
+    ra_status rc = ra_launch_knn(K, Q, dt, n_seq, n_q, n_kv, N, M, knn, ws, (hipStream_t)stream, L_out);
+    hipError_t e = hipStreamSynchronize((hipStream_t)stream);
+    (void)hipFree(ws);
+    if (rc != RA_OK) return rc;
+    RA_HIP(e);
+    return RA_OK;
 }
 
 extern "C" ra_status ra_project(const int32_t* L, int n_graphs, int64_t N, int64_t M, int knn,
@@ -281,13 +288,16 @@ extern "C" ra_status ra_build_index(const void* K, const void* Q, ra_dtype dt, i
     ra_index* ix = nullptr;
     RA_TRY(new_handle(n_seq, n_q, n_kv, N, deg, &ix));
     int32_t* L = nullptr;
+    void* order_ws = nullptr;
     hipError_t e = hipMalloc((void**)&L, (size_t)graphs * M * knn * sizeof(int32_t));
+    if (e == hipSuccess) e = hipMalloc(&order_ws, ra_knn_order_bytes(graphs, N));
     if (e != hipSuccess) {
         ra_set_error("allocating the KNN lists failed: %s", hipGetErrorString(e));
+        if (L) (void)hipFree(L);
         ra_index_free(ix);
         return e == hipErrorOutOfMemory ? RA_ENOMEM : RA_EHIP;
     }
-    ra_status rc = ra_launch_knn(K, Q, dt, n_seq, n_q, n_kv, N, M, knn, (hipStream_t)stream, L);
+    ra_status rc = ra_launch_knn(K, Q, dt, n_seq, n_q, n_kv, N, M, knn, order_ws, (hipStream_t)stream, L);
     if (rc == RA_OK) rc = ra_project(L, graphs, N, M, knn, deg, stream, ix->adj, ix->entry);
     if (rc == RA_OK)
         rc = ra_launch_roots(ix->adj, ix->entry, graphs, N, deg, ix->roots, ix->root_cap, (hipStream_t)stream);
@@ -296,6 +306,7 @@ extern "C" ra_status ra_build_index(const void* K, const void* Q, ra_dtype dt, i
         rc = RA_EHIP;
     }
     (void)hipFree(L);
+    (void)hipFree(order_ws);
     if (rc != RA_OK) {
         ra_index_free(ix);
         return rc;

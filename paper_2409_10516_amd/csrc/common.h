@@ -110,8 +110,14 @@ ra_status ra_launch_flat_topk(const void* q, const void* K, ra_dtype dt, int n_s
                               int64_t N, int sink, int window, int topk, uint32_t* keys_ws,
                               hipStream_t st, int32_t* ids);
 
+// `workspace`: ra_knn_order_bytes(n_seq * n_q, N) bytes of device memory, free again once the
+// stream has run the launch
 ra_status ra_launch_knn(const void* K, const void* Q, ra_dtype dt, int n_seq, int n_q, int n_kv,
-                        int64_t N, int64_t M, int knn, hipStream_t st, int32_t* L);
+                        int64_t N, int64_t M, int knn, void* workspace, hipStream_t st, int32_t* L);
+size_t ra_knn_order_bytes(int n_graphs, int64_t N);
+int64_t ra_knn_order_stride(int64_t N);
+ra_status ra_launch_knn_order(const void* K, const void* Q, ra_dtype dt, int n_seq, int n_q, int n_kv,
+                              int64_t N, int64_t M, void* workspace, hipStream_t st);
 
 size_t ra_project_workspace_bytes(int n_graphs, int64_t N, int64_t M, int knn);
 ra_status ra_launch_project(const int32_t* L, int n_graphs, int64_t N, int64_t M, int knn, int deg,

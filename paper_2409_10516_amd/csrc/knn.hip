@@ -157,17 +157,15 @@ __device__ __forceinline__ void read_operand(const unsigned char* buf, int row, 
     }
 }
 
-// Stage copy: chunk x of a stage is 16 bytes of row x / (chunks per row); consecutive threads take
-// consecutive chunks, thread tid the chunks tid + i * THREADS. Rows beyond N repeat row N - 1
-// (their scores are masked by the caller). One chunk per call so that the values in flight stay
-// in named registers.
-template <int DT, int THREADS, int STAGE>
-__device__ __forceinline__ uint4 fetch_chunk(const char* Kh, int64_t st, int64_t N, int tid, int i) {
-    constexpr int ROWB = DT == RA_BF16 ? 256 : 512, CPR = ROWB / 16, SROWS = STAGE / ROWB;
-    const int x = tid + i * THREADS;
-    int64_t kr = st * SROWS + x / CPR;
-    if (kr >= N) kr = N - 1;
-    return *reinterpret_cast<const uint4*>(Kh + (size_t)kr * ROWB + (size_t)(x % CPR) * 16);
+// Stage copy: chunk x of a stage is 16 bytes of the stage's row x / (chunks per row); consecutive
+// threads take consecutive chunks, thread tid the chunks tid + i * THREADS, so a thread copies the
+// same 16-byte column of one row in every THREADS / (chunks per row) rows. The caller passes the
+// key id of the row (stream positions beyond N repeat the last one; their scores are masked
+// later). One chunk per call so that the values in flight stay in named registers.
+template <int DT>
+__device__ __forceinline__ uint4 fetch_chunk(const char* Kh, int key_id, int column) {
+    constexpr int ROWB = DT == RA_BF16 ? 256 : 512;
+    return *reinterpret_cast<const uint4*>(Kh + (size_t)key_id * ROWB + (size_t)column * 16);
 }
 template <int DT, int THREADS>
 __device__ __forceinline__ void store_chunk(unsigned char* buf, int tid, int i, const uint4& v) {
@@ -183,8 +181,9 @@ __device__ __forceinline__ void store_chunk(unsigned char* buf, int tid, int i, 
 // BUF selects the buffered selection (knn <= KN_BUFFERED_KNN) or sorted insertion.
 template <int DT, int NQ, int WAVES, bool BUF, int STAGE>
 __global__ __launch_bounds__(WAVES * RA_WAVE) void knn_kernel(
-    const void* __restrict__ K, const void* __restrict__ Q, int n_q, int n_kv, int64_t N, int64_t M,
-    int knn, int32_t* __restrict__ L_out) {
+    const void* __restrict__ K, const void* __restrict__ Q, const u64* __restrict__ order,
+    int64_t order_stride, int n_q, int n_kv, int64_t N, int64_t M, int knn,
+    int32_t* __restrict__ L_out) {
     extern __shared__ __align__(16) unsigned char lds_raw[];
     constexpr int KN_THREADS = WAVES * RA_WAVE;
     constexpr int QPW = 32 * NQ, QPB = QPW * WAVES;
@@ -195,6 +194,7 @@ __global__ __launch_bounds__(WAVES * RA_WAVE) void knn_kernel(
     constexpr int CPT = STAGE / 16 / KN_THREADS;     // chunks a thread copies per stage
     static_assert(SBLK == 1 || SBLK == 2, "a stage holds one or two key blocks");
     static_assert(CPT * KN_THREADS * 16 == STAGE, "threads must tile a stage");
+    static_assert(KN_THREADS % CPR == 0, "a thread keeps its 16-byte column");
     const int lstride = BUF ? KN_CAP : knn;                   // list slots per query
     const int pend = (KN_CAP - knn) / 2;                      // pending slots per lane (BUF)
     u64* lists = reinterpret_cast<u64*>(lds_raw);           // [QPB][lstride]
@@ -206,6 +206,9 @@ __global__ __launch_bounds__(WAVES * RA_WAVE) void knn_kernel(
     const char* Kh = reinterpret_cast<const char*>(K) + ((size_t)seq * n_kv + kvh) * N * RA_D * esz;
     const char* Qh = reinterpret_cast<const char*>(Q) + (size_t)graph * M * RA_D * esz;
     const int64_t q0 = (int64_t)blockIdx.x * QPB + wv * QPW;   // first query of this wave
+    // the key streamed p-th: low word of the head's p-th order entry holds ~id
+    const uint32_t* ord = reinterpret_cast<const uint32_t*>(order + (size_t)graph * order_stride);
+    auto stream_id = [&](int64_t p) { return (int)(0xffffffffu - ord[2 * (p < N ? p : N - 1)]); };
 
     for (int i = tid; i < QPB * lstride; i += KN_THREADS) lists[i] = 0ull;
     u64* my_lists = lists + (size_t)wv * QPW * lstride;
@@ -227,13 +230,29 @@ __global__ __launch_bounds__(WAVES * RA_WAVE) void knn_kernel(
     static_assert(CPT == 2 || CPT == 4, "two or four chunks per thread and stage");
     const int64_t nstage = (N + SROWS - 1) / SROWS;
     struct Held { uint4 c0, c1, c2, c3; };         // a thread's share of one stage, in registers
-    auto fetch_stage = [&](Held& h, int64_t st) {
-        if (st >= nstage) st = nstage - 1;          // past the end: fetch the last stage again, unused
-        h.c0 = fetch_chunk<DT, KN_THREADS, STAGE>(Kh, st, N, tid, 0);
-        h.c1 = fetch_chunk<DT, KN_THREADS, STAGE>(Kh, st, N, tid, 1);
+    struct Rows { int r0, r1, r2, r3; };           // key ids of the rows that share comes from
+    constexpr int RSTEP = KN_THREADS / CPR;        // rows between two chunks of a thread
+    auto load_rows = [&](Rows& r, int64_t st) {
+        if (st >= nstage) st = nstage - 1;          // past the end: the last stage again, unused
+        const int64_t p = st * SROWS + tid / CPR;
+        r.r0 = stream_id(p);
+        r.r1 = stream_id(p + RSTEP);
         if constexpr (CPT == 4) {
-            h.c2 = fetch_chunk<DT, KN_THREADS, STAGE>(Kh, st, N, tid, 2);
-            h.c3 = fetch_chunk<DT, KN_THREADS, STAGE>(Kh, st, N, tid, 3);
+            r.r2 = stream_id(p + 2 * RSTEP);
+            r.r3 = stream_id(p + 3 * RSTEP);
+        }
+    };
+    // lane l of every wavefront: the key id of row l of the stage (row l % 32 when a stage has 32)
+    auto stage_ids = [&](int64_t st) {
+        if (st >= nstage) st = nstage - 1;
+        return stream_id(st * SROWS + lane % SROWS);
+    };
+    auto fetch_stage = [&](Held& h, const Rows& r) {
+        h.c0 = fetch_chunk<DT>(Kh, r.r0, tid % CPR);
+        h.c1 = fetch_chunk<DT>(Kh, r.r1, tid % CPR);
+        if constexpr (CPT == 4) {
+            h.c2 = fetch_chunk<DT>(Kh, r.r2, tid % CPR);
+            h.c3 = fetch_chunk<DT>(Kh, r.r3, tid % CPR);
         }
     };
     auto store_stage = [&](const Held& h, unsigned char* buf) {
@@ -245,7 +264,8 @@ __global__ __launch_bounds__(WAVES * RA_WAVE) void knn_kernel(
         }
     };
     // scores of one 32-key block against the wave's NQ query sets, then the selection
-    auto process = [&](const Operand<DT>& a, int64_t kb) {
+    // (kb: the block's place in the stream; ids: stage_ids of its stage; first: its first row there)
+    auto process = [&](const Operand<DT>& a, int64_t kb, int ids, int first) {
         f32x16 c[NQ];
 #pragma unroll
         for (int sidx = 0; sidx < NQ; ++sidx) c[sidx] = block_scores<DT>(a, b[sidx]);
@@ -286,7 +306,9 @@ __global__ __launch_bounds__(WAVES * RA_WAVE) void knn_kernel(
 #pragma unroll
                     for (int r = 4 * g; r < 4 * g + 4; ++r) {
                         if (cs[r] >= tau[sidx] && cs[r] > -INFINITY) {
-                            const int id = (int)(kbase + (r / 4) * 8 + half * 4 + (r % 4));
+                            const int row = first + (r / 4) * 8 + (r % 4);
+                            const int id = half ? __builtin_amdgcn_readlane(ids, row + 4)
+                                                : __builtin_amdgcn_readlane(ids, row);
                             mine[fill[sidx]++] = knn_key(cs[r], id);
                         }
                     }
@@ -304,7 +326,8 @@ __global__ __launch_bounds__(WAVES * RA_WAVE) void knn_kernel(
                 while (mask) {
                     const int src = __ffsll((long long)mask) - 1;
                     const float sc = __shfl(cs[r], src);
-                    const int id = (int)(kbase + (r / 4) * 8 + (src >> 5) * 4 + (r % 4));
+                    const int id =
+                        __builtin_amdgcn_readlane(ids, first + (r / 4) * 8 + (src >> 5) * 4 + (r % 4));
                     const int jq = src & 31;
                     const float nt = knn_insert(set_lists + (size_t)jq * knn, knn, sc, id, lane);
                     if (col == jq) tau[sidx] = nt;
@@ -316,38 +339,56 @@ __global__ __launch_bounds__(WAVES * RA_WAVE) void knn_kernel(
         }
     };
     // one stage of keys against the wave's queries
-    auto multiply_stage = [&](const unsigned char* cur, int64_t st) {
+    auto multiply_stage = [&](const unsigned char* cur, int64_t st, int ids) {
         Operand<DT> a0;
         read_operand<DT>(cur, col, half, a0);
         if constexpr (SBLK == 2) {
             Operand<DT> a1;
             read_operand<DT>(cur, 32 + col, half, a1);
-            process(a0, st * 2);
-            process(a1, st * 2 + 1);          // a block at or beyond N is all masked
+            process(a0, st * 2, ids, 0);
+            process(a1, st * 2 + 1, ids, 32);   // a block at or beyond N is all masked
         } else {
-            process(a0, st);
+            process(a0, st, ids, 0);
         }
     };
     // Every thread runs every stage (the barrier needs all of them). Key rows are requested two
     // stages before they are multiplied: a stage sits in registers for one stage time, then in
-    // its LDS buffer for the next. Loads are never branched around (a conditional load makes
-    // every later wait conservative); past the end the last stage is fetched again and dropped.
+    // its LDS buffer for the next; the key ids of the rows to request are read two requests
+    // ahead, the ids a wavefront needs for the keys it keeps two stages ahead. Loads are never
+    // branched around (a conditional load makes every later wait conservative) and the lead-in
+    // issues them in the order the loop does; past the end the last stage is fetched again and dropped.
     Held ha, hb;
-    fetch_stage(ha, 0);
-    store_stage(ha, stage_buf);
-    fetch_stage(ha, 1);
-    fetch_stage(hb, 2);
+    Rows ra, rb;
+    int ida, idb;
+    {
+        Rows r1, r2;
+        load_rows(ra, 0);
+        load_rows(r1, 1);
+        load_rows(r2, 2);
+        fetch_stage(ha, ra);
+        store_stage(ha, stage_buf);
+        ida = stage_ids(0);
+        fetch_stage(ha, r1);
+        load_rows(ra, 3);
+        idb = stage_ids(1);
+        fetch_stage(hb, r2);
+        load_rows(rb, 4);
+    }
     __syncthreads();
     for (int64_t st = 0; st < nstage; st += 2) {
-        multiply_stage(stage_buf, st);
+        multiply_stage(stage_buf, st, ida);
         store_stage(ha, stage_buf + STAGE);             // stage st + 1
         __syncthreads();
-        fetch_stage(ha, st + 3);
+        ida = stage_ids(st + 2);
+        fetch_stage(ha, ra);                            // stage st + 3
+        load_rows(ra, st + 5);
         if (st + 1 >= nstage) break;
-        multiply_stage(stage_buf + STAGE, st + 1);
-        store_stage(hb, stage_buf);                              // stage st + 2
+        multiply_stage(stage_buf + STAGE, st + 1, idb);
+        store_stage(hb, stage_buf);                     // stage st + 2
         __syncthreads();
-        fetch_stage(hb, st + 4);
+        idb = stage_ids(st + 3);
+        fetch_stage(hb, rb);                            // stage st + 4
+        load_rows(rb, st + 6);
     }
     // write the ids, best first
     for (int jq = 0; jq < QPW; ++jq) {
@@ -360,16 +401,16 @@ __global__ __launch_bounds__(WAVES * RA_WAVE) void knn_kernel(
 }
 
 template <int DT, int NQ, int WAVES, bool BUF, int STAGE>
-static ra_status knn_launch_as(const void* K, const void* Q, int n_seq, int n_q, int n_kv, int64_t N,
-                               int64_t M, int knn, hipStream_t st, int32_t* L) {
+static ra_status knn_launch_as(const void* K, const void* Q, const void* order, int n_seq, int n_q, int n_kv,
+                               int64_t N, int64_t M, int knn, hipStream_t st, int32_t* L) {
     constexpr int QPB = 32 * NQ * WAVES;
     const size_t lds = (size_t)QPB * (BUF ? KN_CAP : knn) * sizeof(u64) + 2 * STAGE;
     if (lds > RA_LDS_LIMIT)
         RA_FAIL(RA_EUNSUP, "knn %d needs %zu bytes of LDS (limit %d)", knn, lds, RA_LDS_LIMIT);
     RA_LDS_OPT_IN((knn_kernel<DT, NQ, WAVES, BUF, STAGE>), lds);
     const dim3 grid((unsigned)((M + QPB - 1) / QPB), (unsigned)(n_seq * n_q));
-    hipLaunchKernelGGL((knn_kernel<DT, NQ, WAVES, BUF, STAGE>), grid, dim3(WAVES * RA_WAVE), lds, st, K, Q, n_q,
-                       n_kv, N, M, knn, L);
+    hipLaunchKernelGGL((knn_kernel<DT, NQ, WAVES, BUF, STAGE>), grid, dim3(WAVES * RA_WAVE), lds, st, K, Q,
+                       reinterpret_cast<const u64*>(order), ra_knn_order_stride(N), n_q, n_kv, N, M, knn, L);
     RA_HIP(hipGetLastError());
     return RA_OK;
 }
@@ -377,12 +418,16 @@ static ra_status knn_launch_as(const void* K, const void* Q, int n_seq, int n_q,
 // 8 wavefronts per workgroup (one workgroup per compute unit, two wavefronts per SIMD) and one
 // set of 32 queries per wavefront: 256 queries x 64 slots x 8 bytes of lists beside the stage buffers.
 ra_status ra_launch_knn(const void* K, const void* Q, ra_dtype dt, int n_seq, int n_q, int n_kv,
-                        int64_t N, int64_t M, int knn, hipStream_t st, int32_t* L) {
+                        int64_t N, int64_t M, int knn, void* workspace, hipStream_t st, int32_t* L) {
+    // the order the keys are streamed in (knn_order.hip), at the start of the workspace
+    ra_status rc = ra_launch_knn_order(K, Q, dt, n_seq, n_q, n_kv, N, M, workspace, st);
+    if (rc != RA_OK) return rc;
     const bool buf = knn <= KN_BUFFERED_KNN;
     if (dt == RA_BF16) {
-        if (buf) return knn_launch_as<RA_BF16, 1, 8, true, 16384>(K, Q, n_seq, n_q, n_kv, N, M, knn, st, L);
-        return knn_launch_as<RA_BF16, 1, 8, false, 16384>(K, Q, n_seq, n_q, n_kv, N, M, knn, st, L);
+        if (buf)
+            return knn_launch_as<RA_BF16, 1, 8, true, 16384>(K, Q, workspace, n_seq, n_q, n_kv, N, M, knn, st, L);
+        return knn_launch_as<RA_BF16, 1, 8, false, 16384>(K, Q, workspace, n_seq, n_q, n_kv, N, M, knn, st, L);
     }
-    if (buf) return knn_launch_as<RA_F32, 1, 4, true, 16384>(K, Q, n_seq, n_q, n_kv, N, M, knn, st, L);
-    return knn_launch_as<RA_F32, 1, 4, false, 16384>(K, Q, n_seq, n_q, n_kv, N, M, knn, st, L);
+    if (buf) return knn_launch_as<RA_F32, 1, 4, true, 16384>(K, Q, workspace, n_seq, n_q, n_kv, N, M, knn, st, L);
+    return knn_launch_as<RA_F32, 1, 4, false, 16384>(K, Q, workspace, n_seq, n_q, n_kv, N, M, knn, st, L);
 }
