@@ -40,6 +40,7 @@
 typedef unsigned long long u64;
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
 __device__ __forceinline__ u64 knn_key(float score, int id) {
     return ((u64)f32_ordered(score) << 32) | (u64)(0xffffffffu - (uint32_t)id);
@@ -120,6 +121,25 @@ __device__ __forceinline__ void load_operand(const void* base, int64_t row, int 
     }
 }
 
+// A use of every register of an operand (an empty asm statement that only reads them): its loads
+// are complete here and cannot sink below later ones. The key stream's waits count loads in
+// flight, and an operand load still counted there would turn every one of them into a wait for
+// the newest load.
+template <int DT>
+__device__ __forceinline__ void settle_operand(const Operand<DT>& o) {
+    if constexpr (DT == RA_BF16) {
+        asm volatile("; operand loaded" ::"v"(o.v[0]), "v"(o.v[1]), "v"(o.v[2]), "v"(o.v[3]), "v"(o.v[4]),
+                     "v"(o.v[5]), "v"(o.v[6]), "v"(o.v[7]));
+    } else {
+#pragma unroll
+        for (int s = 0; s < 64; s += 16)
+            asm volatile("; operand loaded" ::"v"(o.v[s]), "v"(o.v[s + 1]), "v"(o.v[s + 2]), "v"(o.v[s + 3]),
+                         "v"(o.v[s + 4]), "v"(o.v[s + 5]), "v"(o.v[s + 6]), "v"(o.v[s + 7]), "v"(o.v[s + 8]),
+                         "v"(o.v[s + 9]), "v"(o.v[s + 10]), "v"(o.v[s + 11]), "v"(o.v[s + 12]),
+                         "v"(o.v[s + 13]), "v"(o.v[s + 14]), "v"(o.v[s + 15]));
+    }
+}
+
 template <int DT>
 __device__ __forceinline__ f32x16 block_scores(const Operand<DT>& a, const Operand<DT>& b) {
     f32x16 c = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
@@ -163,16 +183,16 @@ __device__ __forceinline__ void read_operand(const unsigned char* buf, int row, 
 // key id of the row (stream positions beyond N repeat the last one; their scores are masked
 // later). One chunk per call so that the values in flight stay in named registers.
 template <int DT>
-__device__ __forceinline__ uint4 fetch_chunk(const char* Kh, int key_id, int column) {
+__device__ __forceinline__ u32x4 fetch_chunk(const char* Kh, int key_id, int column) {
     constexpr int ROWB = DT == RA_BF16 ? 256 : 512;
-    return *reinterpret_cast<const uint4*>(Kh + (size_t)key_id * ROWB + (size_t)column * 16);
+    return *reinterpret_cast<const u32x4*>(Kh + (size_t)key_id * ROWB + (size_t)column * 16);
 }
 template <int DT, int THREADS>
-__device__ __forceinline__ void store_chunk(unsigned char* buf, int tid, int i, const uint4& v) {
+__device__ __forceinline__ void store_chunk(unsigned char* buf, int tid, int i, const u32x4& v) {
     constexpr int ROWB = DT == RA_BF16 ? 256 : 512, CPR = ROWB / 16;
     const int x = tid + i * THREADS;
     const int row = x / CPR, c = x % CPR;
-    *reinterpret_cast<uint4*>(buf + row * ROWB + ((c ^ (row & 15)) << 4)) = v;
+    *reinterpret_cast<u32x4*>(buf + row * ROWB + ((c ^ (row & 15)) << 4)) = v;
 }
 
 // grid: x = block of NQ * 32 * WAVES queries, y = graph (seq * n_q + h). A wavefront owns NQ sets
@@ -206,9 +226,10 @@ __global__ __launch_bounds__(WAVES * RA_WAVE) void knn_kernel(
     const char* Kh = reinterpret_cast<const char*>(K) + ((size_t)seq * n_kv + kvh) * N * RA_D * esz;
     const char* Qh = reinterpret_cast<const char*>(Q) + (size_t)graph * M * RA_D * esz;
     const int64_t q0 = (int64_t)blockIdx.x * QPB + wv * QPW;   // first query of this wave
-    // the key streamed p-th: low word of the head's p-th order entry holds ~id
-    const uint32_t* ord = reinterpret_cast<const uint32_t*>(order + (size_t)graph * order_stride);
-    auto stream_id = [&](int64_t p) { return (int)(0xffffffffu - ord[2 * (p < N ? p : N - 1)]); };
+    // the key streamed p-th: the low word of the head's p-th order entry (used as loaded: arithmetic
+    // on it would sit right behind the load and wait for it)
+    const int* ord = reinterpret_cast<const int*>(order + (size_t)graph * order_stride);
+    auto stream_id = [&](int64_t p) { return ord[2 * (p < N ? p : N - 1)]; };
 
     for (int i = tid; i < QPB * lstride; i += KN_THREADS) lists[i] = 0ull;
     u64* my_lists = lists + (size_t)wv * QPW * lstride;
@@ -220,6 +241,8 @@ __global__ __launch_bounds__(WAVES * RA_WAVE) void knn_kernel(
         if (qr >= M) qr = M - 1;                   // clamp loads; such columns are never written
         load_operand<DT>(Qh, qr, half, b[sidx]);
     }
+#pragma unroll
+    for (int sidx = 0; sidx < NQ; ++sidx) settle_operand<DT>(b[sidx]);
     __syncthreads();
 
     float tau[NQ];
@@ -229,7 +252,7 @@ __global__ __launch_bounds__(WAVES * RA_WAVE) void knn_kernel(
 
     static_assert(CPT == 2 || CPT == 4, "two or four chunks per thread and stage");
     const int64_t nstage = (N + SROWS - 1) / SROWS;
-    struct Held { uint4 c0, c1, c2, c3; };         // a thread's share of one stage, in registers
+    struct Held { u32x4 c0, c1, c2, c3; };         // a thread's share of one stage, in registers
     struct Rows { int r0, r1, r2, r3; };           // key ids of the rows that share comes from
     constexpr int RSTEP = KN_THREADS / CPR;        // rows between two chunks of a thread
     auto load_rows = [&](Rows& r, int64_t st) {
@@ -355,8 +378,11 @@ __global__ __launch_bounds__(WAVES * RA_WAVE) void knn_kernel(
     // stages before they are multiplied: a stage sits in registers for one stage time, then in
     // its LDS buffer for the next; the key ids of the rows to request are read two requests
     // ahead, the ids a wavefront needs for the keys it keeps two stages ahead. Loads are never
-    // branched around (a conditional load makes every later wait conservative) and the lead-in
-    // issues them in the order the loop does; past the end the last stage is fetched again and dropped.
+    // branched around (a conditional load makes every later wait conservative); past the end the
+    // last stage is fetched again and dropped. The lead-in ends with a use of everything it
+    // loaded (an empty asm statement that only reads the registers), so all its loads are complete
+    // there: the compiler orders the lead-in's loads as it likes, and any of them still in flight
+    // at the loop's entry would make the loop's waits count for that order.
     Held ha, hb;
     Rows ra, rb;
     int ida, idb;
@@ -373,6 +399,13 @@ __global__ __launch_bounds__(WAVES * RA_WAVE) void knn_kernel(
         idb = stage_ids(1);
         fetch_stage(hb, r2);
         load_rows(rb, 4);
+        if constexpr (CPT == 4)
+            asm volatile("; lead-in loads complete" ::"v"(ha.c0), "v"(ha.c1), "v"(ha.c2), "v"(ha.c3),
+                         "v"(hb.c0), "v"(hb.c1), "v"(hb.c2), "v"(hb.c3), "v"(ra.r0), "v"(ra.r1), "v"(ra.r2),
+                         "v"(ra.r3), "v"(rb.r0), "v"(rb.r1), "v"(rb.r2), "v"(rb.r3), "v"(ida), "v"(idb));
+        else
+            asm volatile("; lead-in loads complete" ::"v"(ha.c0), "v"(ha.c1), "v"(hb.c0), "v"(hb.c1),
+                         "v"(ra.r0), "v"(ra.r1), "v"(rb.r0), "v"(rb.r1), "v"(ida), "v"(idb));
     }
     __syncthreads();
     for (int64_t st = 0; st < nstage; st += 2) {

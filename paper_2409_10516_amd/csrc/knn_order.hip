@@ -10,9 +10,10 @@
 //
 // Three steps per head, none of which can change a result:
 //   ko_meanq_kernel   sum of a strided sample of the head's prefill queries (fixed order)
-//   ko_proxy_kernel   64-bit sort keys [ordered(<mean, k_i>):32][~i:32], zero beyond N
-//   ko_sort_*         bitonic sort, descending: chunks in LDS, the wider exchanges in memory
-// The KNN kernel reads the key id of stream position p from the low word of entry p.
+//   ko_proxy_kernel   64-bit sort keys [~ordered(<mean, k_i>):32][i:32], all ones beyond N
+//   ko_sort_*         bitonic sort, ascending: chunks in LDS, the wider exchanges in memory
+// so entry p is the key of p-th largest inner product (lower id first among equals) and the KNN
+// kernel reads the id of stream position p as the low word of entry p, ready to use.
 #include "common.h"
 
 typedef unsigned long long u64;
@@ -80,17 +81,17 @@ __global__ __launch_bounds__(KO_THREADS) void ko_proxy_kernel(const void* __rest
     p += __uint_as_float(lane_xor32<4>(__float_as_uint(p), lane));
     p += __uint_as_float(lane_xor32<8>(__float_as_uint(p), lane));
     if (p != p) p = 0.f;                        // an order is all that is wanted: any place will do
-    // low word ~i is at least 2^31 for a key, so the zero entries beyond N sort behind every key
+    // ids stay below 2^31, so the all-ones entries beyond N sort behind every key
     if (l16 == 0)
         keys[(size_t)graph * N_pad + i] =
-            i < N ? ((u64)f32_ordered(p) << 32) | (u64)(0xffffffffu - (uint32_t)i) : 0ull;
+            i < N ? ((u64)(~f32_ordered(p)) << 32) | (u64)(uint32_t)i : ~0ull;
 }
 
-// One exchange of the bitonic network on a chunk in LDS: element e and e ^ j, descending overall
-// (the run that holds global index g ascends when g & k is set).
-__device__ __forceinline__ void ko_exchange(u64* s, int e, int j, bool descending) {
+// One exchange of the bitonic network on a chunk in LDS: element e and e ^ j, ascending overall
+// (the run that holds global index g descends when g & k is set).
+__device__ __forceinline__ void ko_exchange(u64* s, int e, int j, bool ascending) {
     const u64 a = s[e], b = s[e | j];
-    if ((a < b) == descending) { s[e] = b; s[e | j] = a; }
+    if ((a > b) == ascending) { s[e] = b; s[e | j] = a; }
 }
 
 // grid: x = chunk, y = head. k_first == 0: sorts the chunk (all k up to its length); otherwise
@@ -125,8 +126,8 @@ __global__ __launch_bounds__(KO_THREADS) void ko_sort_far_kernel(u64* __restrict
     const int64_t e = ((t & ~(j - 1)) << 1) | (t & (j - 1));
     u64* g = keys + (size_t)blockIdx.y * N_pad;
     const u64 a = g[e], b = g[e | j];
-    const bool descending = (e & k) == 0;
-    if ((a < b) == descending) { g[e] = b; g[e | j] = a; }
+    const bool ascending = (e & k) == 0;
+    if ((a > b) == ascending) { g[e] = b; g[e | j] = a; }
 }
 
 static int64_t ko_padded(int64_t N) {
@@ -143,7 +144,7 @@ size_t ra_knn_order_bytes(int n_graphs, int64_t N) {
 int64_t ra_knn_order_stride(int64_t N) { return ko_padded(N); }
 
 // Fills workspace with the stream order of every head: entry p of head g, at
-// workspace[g * ra_knn_order_stride(N) + p], holds ~id of the key streamed p-th in its low word.
+// workspace[g * ra_knn_order_stride(N) + p], holds the id of the key streamed p-th in its low word.
 ra_status ra_launch_knn_order(const void* K, const void* Q, ra_dtype dt, int n_seq, int n_q, int n_kv,
                               int64_t N, int64_t M, void* workspace, hipStream_t st) {
     const int graphs = n_seq * n_q;
