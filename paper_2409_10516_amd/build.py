@@ -13,6 +13,10 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-ffp-contract=o
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-Wno-unused-command-line-argument",
          "-I", os.path.join(ROOT, "include"), "-I", CSRC]
+# knn.hip: scores are compared as numbers (a NaN score, from non-finite inputs, never reaches a
+# list either way); without this every fmaxf of the selection's max tree first canonicalises
+# its inputs with an instruction of its own
+EXTRA = {"knn.hip": ["-fno-honor-nans"]}
 
 
 def build(verbose=True):
@@ -22,7 +26,7 @@ def build(verbose=True):
     for s in SOURCES:
         o = os.path.join(CSRC, s.replace(".hip", ".o"))
         objs.append(o)
-        cmd = [hipcc, *FLAGS, "-c", os.path.join(CSRC, s), "-o", o]
+        cmd = [hipcc, *FLAGS, *EXTRA.get(s, []), "-c", os.path.join(CSRC, s), "-o", o]
         if verbose:
             print(" ".join(cmd), flush=True)
         procs.append((s, subprocess.Popen(cmd, stdout=subprocess.PIPE, stderr=subprocess.STDOUT)))

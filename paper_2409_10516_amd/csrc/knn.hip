@@ -157,21 +157,30 @@ __device__ __forceinline__ f32x16 block_scores(const Operand<DT>& a, const Opera
 
 // A staged key row keeps its 16-byte chunks at (chunk ^ (row & 15)): the 16 lanes that write one
 // row, and the 16 lanes that read the same chunk of 16 consecutive rows, both cover all 64 banks.
+// A lane reads the same chunks of the same row (lane % 32, or 32 rows on: same swizzle) in every
+// stage, so the byte offsets are computed once (operand_offsets) and a read is one instruction
+// with the stage buffer and the block as a constant displacement.
+template <int DT> struct OperandAt { int at[DT == RA_BF16 ? 8 : 16]; };
 template <int DT>
-__device__ __forceinline__ void read_operand(const unsigned char* buf, int row, int half, Operand<DT>& o) {
+__device__ __forceinline__ void operand_offsets(int base, int row, int half, OperandAt<DT>& o) {
     constexpr int ROWB = DT == RA_BF16 ? 256 : 512, CPH = ROWB / 32;   // chunks per half row
-    const unsigned char* r = buf + row * ROWB;
     const int sw = row & 15;
+#pragma unroll
+    for (int s = 0; s < CPH; ++s) o.at[s] = base + row * ROWB + (((half * CPH + s) ^ sw) << 4);
+}
+template <int DT>
+__device__ __forceinline__ void read_operand(const unsigned char* lds, const OperandAt<DT>& at, int disp,
+                                             Operand<DT>& o) {
     if constexpr (DT == RA_BF16) {
 #pragma unroll
         for (int s = 0; s < 8; ++s) {
-            const uint4 u = *reinterpret_cast<const uint4*>(r + (((half * CPH + s) ^ sw) << 4));
+            const uint4 u = *reinterpret_cast<const uint4*>(lds + at.at[s] + disp);
             o.v[s] = __builtin_bit_cast(bf16x8, u);
         }
     } else {
 #pragma unroll
         for (int s = 0; s < 16; ++s) {
-            const float4 f = *reinterpret_cast<const float4*>(r + (((half * CPH + s) ^ sw) << 4));
+            const float4 f = *reinterpret_cast<const float4*>(lds + at.at[s] + disp);
             o.v[4 * s] = f.x; o.v[4 * s + 1] = f.y; o.v[4 * s + 2] = f.z; o.v[4 * s + 3] = f.w;
         }
     }
@@ -229,7 +238,8 @@ __global__ __launch_bounds__(WAVES * RA_WAVE) void knn_kernel(
     // the key streamed p-th: the low word of the head's p-th order entry (used as loaded: arithmetic
     // on it would sit right behind the load and wait for it)
     const int* ord = reinterpret_cast<const int*>(order + (size_t)graph * order_stride);
-    auto stream_id = [&](int64_t p) { return ord[2 * (p < N ? p : N - 1)]; };
+    const int last_pos = (int)N - 1;               // ids and stream positions fit 31 bits
+    auto stream_id = [&](int p) __attribute__((always_inline)) { return ord[2 * (size_t)(unsigned)(p < last_pos ? p : last_pos)]; };
 
     for (int i = tid; i < QPB * lstride; i += KN_THREADS) lists[i] = 0ull;
     u64* my_lists = lists + (size_t)wv * QPW * lstride;
@@ -255,9 +265,9 @@ __global__ __launch_bounds__(WAVES * RA_WAVE) void knn_kernel(
     struct Held { u32x4 c0, c1, c2, c3; };         // a thread's share of one stage, in registers
     struct Rows { int r0, r1, r2, r3; };           // key ids of the rows that share comes from
     constexpr int RSTEP = KN_THREADS / CPR;        // rows between two chunks of a thread
-    auto load_rows = [&](Rows& r, int64_t st) {
+    auto load_rows = [&](Rows& r, int64_t st) __attribute__((always_inline)) {
         if (st >= nstage) st = nstage - 1;          // past the end: the last stage again, unused
-        const int64_t p = st * SROWS + tid / CPR;
+        const int p = (int)st * SROWS + tid / CPR;
         r.r0 = stream_id(p);
         r.r1 = stream_id(p + RSTEP);
         if constexpr (CPT == 4) {
@@ -266,11 +276,11 @@ __global__ __launch_bounds__(WAVES * RA_WAVE) void knn_kernel(
         }
     };
     // lane l of every wavefront: the key id of row l of the stage (row l % 32 when a stage has 32)
-    auto stage_ids = [&](int64_t st) {
+    auto stage_ids = [&](int64_t st) __attribute__((always_inline)) {
         if (st >= nstage) st = nstage - 1;
-        return stream_id(st * SROWS + lane % SROWS);
+        return stream_id((int)st * SROWS + lane % SROWS);
     };
-    auto fetch_stage = [&](Held& h, const Rows& r) {
+    auto fetch_stage = [&](Held& h, const Rows& r) __attribute__((always_inline)) {
         h.c0 = fetch_chunk<DT>(Kh, r.r0, tid % CPR);
         h.c1 = fetch_chunk<DT>(Kh, r.r1, tid % CPR);
         if constexpr (CPT == 4) {
@@ -278,7 +288,7 @@ __global__ __launch_bounds__(WAVES * RA_WAVE) void knn_kernel(
             h.c3 = fetch_chunk<DT>(Kh, r.r3, tid % CPR);
         }
     };
-    auto store_stage = [&](const Held& h, unsigned char* buf) {
+    auto store_stage = [&](const Held& h, unsigned char* buf) __attribute__((always_inline)) {
         store_chunk<DT, KN_THREADS>(buf, tid, 0, h.c0);
         store_chunk<DT, KN_THREADS>(buf, tid, 1, h.c1);
         if constexpr (CPT == 4) {
@@ -288,7 +298,7 @@ __global__ __launch_bounds__(WAVES * RA_WAVE) void knn_kernel(
     };
     // scores of one 32-key block against the wave's NQ query sets, then the selection
     // (kb: the block's place in the stream; ids: stage_ids of its stage; first: its first row there)
-    auto process = [&](const Operand<DT>& a, int64_t kb, int ids, int first) {
+    auto process = [&](const Operand<DT>& a, int64_t kb, int ids, int first) __attribute__((always_inline)) {
         f32x16 c[NQ];
 #pragma unroll
         for (int sidx = 0; sidx < NQ; ++sidx) c[sidx] = block_scores<DT>(a, b[sidx]);
@@ -329,10 +339,12 @@ __global__ __launch_bounds__(WAVES * RA_WAVE) void knn_kernel(
 #pragma unroll
                     for (int r = 4 * g; r < 4 * g + 4; ++r) {
                         if (cs[r] >= tau[sidx] && cs[r] > -INFINITY) {
+                            // the row's id sits in lane `row` of ids (lower half-wave) or four lanes
+                            // on (upper): both are read as scalars, then chosen without a branch
                             const int row = first + (r / 4) * 8 + (r % 4);
-                            const int id = half ? __builtin_amdgcn_readlane(ids, row + 4)
-                                                : __builtin_amdgcn_readlane(ids, row);
-                            mine[fill[sidx]++] = knn_key(cs[r], id);
+                            const int lo = __builtin_amdgcn_readlane(ids, row);
+                            const int hi = __builtin_amdgcn_readlane(ids, row + 4);
+                            mine[fill[sidx]++] = knn_key(cs[r], lo ^ ((lo ^ hi) & -half));
                         }
                     }
                 }
@@ -362,12 +374,14 @@ __global__ __launch_bounds__(WAVES * RA_WAVE) void knn_kernel(
         }
     };
     // one stage of keys against the wave's queries
-    auto multiply_stage = [&](const unsigned char* cur, int64_t st, int ids) {
+    OperandAt<DT> a_at;                            // where this lane's key operand sits in a stage buffer
+    operand_offsets<DT>((int)(stage_buf - lds_raw), col, half, a_at);
+    auto multiply_stage = [&](int cur, int64_t st, int ids) __attribute__((always_inline)) {      // cur: byte offset of the stage buffer
         Operand<DT> a0;
-        read_operand<DT>(cur, col, half, a0);
+        read_operand<DT>(lds_raw, a_at, cur, a0);
         if constexpr (SBLK == 2) {
             Operand<DT> a1;
-            read_operand<DT>(cur, 32 + col, half, a1);
+            read_operand<DT>(lds_raw, a_at, cur + 32 * ROWB, a1);
             process(a0, st * 2, ids, 0);
             process(a1, st * 2 + 1, ids, 32);   // a block at or beyond N is all masked
         } else {
@@ -409,14 +423,14 @@ __global__ __launch_bounds__(WAVES * RA_WAVE) void knn_kernel(
     }
     __syncthreads();
     for (int64_t st = 0; st < nstage; st += 2) {
-        multiply_stage(stage_buf, st, ida);
+        multiply_stage(0, st, ida);
         store_stage(ha, stage_buf + STAGE);             // stage st + 1
         __syncthreads();
         ida = stage_ids(st + 2);
         fetch_stage(ha, ra);                            // stage st + 3
         load_rows(ra, st + 5);
         if (st + 1 >= nstage) break;
-        multiply_stage(stage_buf + STAGE, st + 1, idb);
+        multiply_stage(STAGE, st + 1, idb);
         store_stage(hb, stage_buf);                     // stage st + 2
         __syncthreads();
         idb = stage_ids(st + 3);
