@@ -79,6 +79,38 @@ def test_knn_monotone_stream(dtype, knn, rising):
     assert np.array_equal(L, np.broadcast_to(want, (M, knn)))
 
 
+@pytest.mark.parametrize("dtype", [torch.bfloat16, torch.float32])
+@pytest.mark.parametrize("knn", [7, 32, 64])
+def test_knn_stream_order_against_a_minority_of_queries(dtype, knn):
+    """The keys are streamed by descending inner product with the head's mean query. Here 60 % of
+    the queries are -u and 40 % are +u, so the stream is in the best order for the majority and in
+    the worst (every key beats the threshold) for the minority; the lists must not depend on it."""
+    N, M = 2500, 90
+    K = torch.zeros((1, 1, N, 128), dtype=torch.float32)
+    i = torch.arange(N)
+    K[0, 0, :, 0] = (i % 256).float()
+    K[0, 0, :, 1] = (i // 256).float()
+    sign = torch.where(torch.arange(M) % 5 < 3, -1.0, 1.0)
+    Q = torch.zeros((1, 1, M, 128), dtype=torch.float32)
+    Q[0, 0, :, 0] = sign
+    Q[0, 0, :, 1] = 256.0 * sign
+    L = ra.ra_knn(K.to(dtype).to(DEV), Q.to(dtype).to(DEV), knn).cpu().numpy()[0, 0]
+    for j in range(M):
+        want = np.arange(N - 1, N - 1 - knn, -1) if sign[j] > 0 else np.arange(knn)
+        assert np.array_equal(L[j], want), j
+
+
+@pytest.mark.parametrize("N,knn", [(1, 1), (3, 3), (5, 2), (33, 33), (64, 48), (65, 64)])
+def test_knn_tiny_key_sets(N, knn):
+    """Fewer keys than a stage, than a block, than the sort's smallest chunk: all equal scores, so
+    the lists are the lowest ids in order."""
+    M = 9
+    K = torch.ones((1, 1, N, 128), dtype=torch.bfloat16)
+    Q = torch.ones((1, 1, M, 128), dtype=torch.bfloat16)
+    L = ra.ra_knn(K.to(DEV), Q.to(DEV), knn).cpu().numpy()[0, 0]
+    assert np.array_equal(L, np.broadcast_to(np.arange(knn), (M, knn)))
+
+
 def test_projection_hand_worked_example():
     g = json.load(open(os.path.join(GOLD, "projection_hand.json")))
     L = torch.tensor([g["L"]], dtype=torch.int32, device=DEV)
