@@ -36,6 +36,12 @@
 
 #define KN_CAP 64                 // list slots of a query in the buffered selection (one per lane)
 #define KN_BUFFERED_KNN 48        // longest list that leaves room for pending slots
+#define KN_REG_KNN 32             // longest list of the selection that keeps pending keys in registers
+#define KN_REG_PEND 4             // pending keys a lane holds there
+// how the top-knn selection keeps keys that reached a threshold until they are merged into a list
+#define KN_SEL_INSERT 0           // not at all: sorted insertion, one key at a time
+#define KN_SEL_LDS 1              // in pending runs behind the list in LDS (KN_CAP slots per query)
+#define KN_SEL_REG 2              // in registers of the lane that scored them (32 slots per query in LDS)
 
 typedef unsigned long long u64;
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
@@ -90,6 +96,46 @@ __device__ __forceinline__ float knn_fold(u64* lst, int knn, int lane) {
     lst[lane] = lane < knn ? v : 0ull;
     const u64 last = ((u64)(uint32_t)__builtin_amdgcn_readlane((int)(v >> 32), knn - 1) << 32) |
                      (u64)(uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)v, knn - 1);
+    return last == 0ull ? -INFINITY : f32_from_ordered((uint32_t)(last >> 32));
+}
+
+__device__ __forceinline__ u64 readlane64(u64 x, int l) {
+    return ((u64)(uint32_t)__builtin_amdgcn_readlane((int)(x >> 32), l) << 32) |
+           (u64)(uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)x, l);
+}
+
+// The same for a query (number jq of its set) whose pending keys sit in registers: p0..p3 and fill
+// are every lane's own, the query's are those of lanes jq and jq + 32. With at most 8 keys to merge
+// into a sorted list of 32 a sort is not needed: the list goes to the lower half-wave, the pending
+// keys (zero where a lane holds fewer than four) to lanes 32..39 and, one by one as scalars, to
+// everyone; a list entry moves down by the number of pending keys above it, a pending key lands at
+// the number of keys above it, and every slot below 32 is written exactly once (keys are distinct
+// or zero; a zero pending key writes nothing). The caller resets the fill counts of the query's lanes.
+__device__ __forceinline__ float knn_fold_reg(u64* lst, int knn, int lane, int jq, u64 p0, u64 p1, u64 p2,
+                                              u64 p3, int fill) {
+    u64 v = lane < 32 ? lst[lane & 31] : 0ull;
+    const int f_lo = __builtin_amdgcn_readlane(fill, jq), f_hi = __builtin_amdgcn_readlane(fill, jq + 32);
+    u64 x[8];
+    x[0] = readlane64(p0, jq); x[1] = readlane64(p1, jq); x[2] = readlane64(p2, jq); x[3] = readlane64(p3, jq);
+    x[4] = readlane64(p0, jq + 32); x[5] = readlane64(p1, jq + 32);
+    x[6] = readlane64(p2, jq + 32); x[7] = readlane64(p3, jq + 32);
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+        if (!(k < 4 ? k < f_lo : k - 4 < f_hi)) x[k] = 0ull;
+        if (lane == 32 + k) v = x[k];
+    }
+    int pos = lane;
+#pragma unroll
+    for (int k = 0; k < 8; ++k) {
+        const int above = __popcll(__ballot(v > x[k]));      // keys that beat pending key k
+        if (lane < 32) pos += v < x[k] ? 1 : 0;
+        if (lane == 32 + k) pos = above;
+    }
+    const bool writes = lane < 32 || (lane < 40 && v != 0ull);
+    if (writes && pos < 32) lst[pos] = pos < knn ? v : 0ull;
+    const u64 at_end = __ballot(writes && pos == knn - 1);
+    const int src = at_end ? __ffsll((long long)at_end) - 1 : 0;
+    const u64 last = readlane64(v, src);
     return last == 0ull ? -INFINITY : f32_from_ordered((uint32_t)(last >> 32));
 }
 
@@ -206,9 +252,11 @@ __device__ __forceinline__ void store_chunk(unsigned char* buf, int tid, int i, 
 
 // grid: x = block of NQ * 32 * WAVES queries, y = graph (seq * n_q + h). A wavefront owns NQ sets
 // of 32 queries, so every key operand it reads feeds NQ MFMA chains.
-// LDS: [NQ * 32 * WAVES][BUF ? KN_CAP : knn] lists, then two stage buffers of STAGE bytes.
-// BUF selects the buffered selection (knn <= KN_BUFFERED_KNN) or sorted insertion.
-template <int DT, int NQ, int WAVES, bool BUF, int STAGE>
+// LDS: [NQ * 32 * WAVES][list slots] lists, then two stage buffers of STAGE bytes.
+// SEL (KN_SEL_*) selects how keys wait for their list: KN_SEL_REG (knn <= KN_REG_KNN) leaves LDS for
+// the lists of twice as many queries, so NQ = 2 and every operand read from LDS feeds two MFMAs;
+// KN_SEL_LDS (knn <= KN_BUFFERED_KNN) and sorted insertion run with NQ = 1.
+template <int DT, int NQ, int WAVES, int SEL, int STAGE>
 __global__ __launch_bounds__(WAVES * RA_WAVE) void knn_kernel(
     const void* __restrict__ K, const void* __restrict__ Q, const u64* __restrict__ order,
     int64_t order_stride, int n_q, int n_kv, int64_t N, int64_t M, int knn,
@@ -224,8 +272,9 @@ __global__ __launch_bounds__(WAVES * RA_WAVE) void knn_kernel(
     static_assert(SBLK == 1 || SBLK == 2, "a stage holds one or two key blocks");
     static_assert(CPT * KN_THREADS * 16 == STAGE, "threads must tile a stage");
     static_assert(KN_THREADS % CPR == 0, "a thread keeps its 16-byte column");
-    const int lstride = BUF ? KN_CAP : knn;                   // list slots per query
-    const int pend = (KN_CAP - knn) / 2;                      // pending slots per lane (BUF)
+    constexpr bool BUF = SEL != KN_SEL_INSERT, REGP = SEL == KN_SEL_REG;
+    const int lstride = REGP ? KN_REG_KNN : BUF ? KN_CAP : knn;           // list slots per query
+    const int pend = REGP ? KN_REG_PEND : (KN_CAP - knn) / 2;             // pending keys a lane can hold (BUF)
     u64* lists = reinterpret_cast<u64*>(lds_raw);           // [QPB][lstride]
     unsigned char* stage_buf = lds_raw + (size_t)QPB * lstride * sizeof(u64);   // 16-byte aligned: QPB is even
     const int tid = threadIdx.x, wv = tid / RA_WAVE, lane = tid % RA_WAVE;
@@ -257,8 +306,14 @@ __global__ __launch_bounds__(WAVES * RA_WAVE) void knn_kernel(
 
     float tau[NQ];
     int fill[NQ];                                  // BUF: keys in this lane's pending run
+    u64 pr[NQ][KN_REG_PEND];                       // REGP: the run itself
 #pragma unroll
-    for (int sidx = 0; sidx < NQ; ++sidx) { tau[sidx] = -INFINITY; fill[sidx] = 0; }
+    for (int sidx = 0; sidx < NQ; ++sidx) {
+        tau[sidx] = -INFINITY;
+        fill[sidx] = 0;
+#pragma unroll
+        for (int k = 0; k < KN_REG_PEND; ++k) pr[sidx][k] = 0ull;
+    }
 
     static_assert(CPT == 2 || CPT == 4, "two or four chunks per thread and stage");
     const int64_t nstage = (N + SROWS - 1) / SROWS;
@@ -318,8 +373,8 @@ __global__ __launch_bounds__(WAVES * RA_WAVE) void knn_kernel(
                     gm[g] = fmaxf(fmaxf(cs[4 * g], cs[4 * g + 1]), fmaxf(cs[4 * g + 2], cs[4 * g + 3]));
                 const float mx = fmaxf(fmaxf(gm[0], gm[1]), fmaxf(gm[2], gm[3]));
                 if (__ballot(mx >= tau[sidx]) == 0ull) continue;
-                u64* set_lists = my_lists + (size_t)sidx * 32 * KN_CAP;
-                u64* mine = set_lists + (size_t)col * KN_CAP + knn + half * pend;
+                u64* set_lists = my_lists + (size_t)sidx * 32 * lstride;
+                u64* mine = set_lists + (size_t)col * KN_CAP + knn + half * pend;    // KN_SEL_LDS
 #pragma unroll
                 for (int g = 0; g < 4; ++g) {
                     if (__ballot(gm[g] >= tau[sidx]) == 0ull) continue;
@@ -331,7 +386,12 @@ __global__ __launch_bounds__(WAVES * RA_WAVE) void knn_kernel(
                     u64 need = __ballot(fill[sidx] + n4 > pend);
                     while (need) {
                         const int jq = (__ffsll((long long)need) - 1) & 31;
-                        const float nt = knn_fold(set_lists + (size_t)jq * KN_CAP, knn, lane);
+                        float nt;
+                        if constexpr (REGP)
+                            nt = knn_fold_reg(set_lists + (size_t)jq * KN_REG_KNN, knn, lane, jq, pr[sidx][0],
+                                              pr[sidx][1], pr[sidx][2], pr[sidx][3], fill[sidx]);
+                        else
+                            nt = knn_fold(set_lists + (size_t)jq * KN_CAP, knn, lane);
                         if (col == jq) { tau[sidx] = nt; fill[sidx] = 0; }
                         need &= need - 1;
                         need &= ~(1ull << (jq + 32)) & ~(1ull << jq);
@@ -344,7 +404,15 @@ __global__ __launch_bounds__(WAVES * RA_WAVE) void knn_kernel(
                             const int row = first + (r / 4) * 8 + (r % 4);
                             const int lo = __builtin_amdgcn_readlane(ids, row);
                             const int hi = __builtin_amdgcn_readlane(ids, row + 4);
-                            mine[fill[sidx]++] = knn_key(cs[r], lo ^ ((lo ^ hi) & -half));
+                            const u64 nk = knn_key(cs[r], lo ^ ((lo ^ hi) & -half));
+                            if constexpr (REGP) {
+#pragma unroll
+                                for (int k = 0; k < KN_REG_PEND; ++k)
+                                    pr[sidx][k] = fill[sidx] == k ? nk : pr[sidx][k];
+                                fill[sidx]++;
+                            } else {
+                                mine[fill[sidx]++] = nk;
+                            }
                         }
                     }
                 }
@@ -438,32 +506,42 @@ __global__ __launch_bounds__(WAVES * RA_WAVE) void knn_kernel(
         load_rows(rb, st + 6);
     }
     // write the ids, best first
-    for (int jq = 0; jq < QPW; ++jq) {
-        const int64_t qr = q0 + jq;
-        if (qr >= M) break;
-        if constexpr (BUF) knn_fold(my_lists + (size_t)jq * KN_CAP, knn, lane);
-        if (lane < knn)
-            L_out[((size_t)graph * M + qr) * knn + lane] = knn_key_id(my_lists[(size_t)jq * lstride + lane]);
+#pragma unroll
+    for (int sidx = 0; sidx < NQ; ++sidx) {
+        for (int j = 0; j < 32; ++j) {
+            const int jq = sidx * 32 + j;
+            const int64_t qr = q0 + jq;
+            if (qr >= M) break;
+            u64* lst = my_lists + (size_t)jq * lstride;
+            if constexpr (REGP)
+                knn_fold_reg(lst, knn, lane, j, pr[sidx][0], pr[sidx][1], pr[sidx][2], pr[sidx][3], fill[sidx]);
+            else if constexpr (BUF)
+                knn_fold(lst, knn, lane);
+            if (lane < knn) L_out[((size_t)graph * M + qr) * knn + lane] = knn_key_id(lst[lane]);
+        }
     }
 }
 
-template <int DT, int NQ, int WAVES, bool BUF, int STAGE>
+template <int DT, int NQ, int WAVES, int SEL, int STAGE>
 static ra_status knn_launch_as(const void* K, const void* Q, const void* order, int n_seq, int n_q, int n_kv,
                                int64_t N, int64_t M, int knn, hipStream_t st, int32_t* L) {
     constexpr int QPB = 32 * NQ * WAVES;
-    const size_t lds = (size_t)QPB * (BUF ? KN_CAP : knn) * sizeof(u64) + 2 * STAGE;
+    const int slots = SEL == KN_SEL_REG ? KN_REG_KNN : SEL == KN_SEL_LDS ? KN_CAP : knn;
+    const size_t lds = (size_t)QPB * slots * sizeof(u64) + 2 * STAGE;
     if (lds > RA_LDS_LIMIT)
         RA_FAIL(RA_EUNSUP, "knn %d needs %zu bytes of LDS (limit %d)", knn, lds, RA_LDS_LIMIT);
-    RA_LDS_OPT_IN((knn_kernel<DT, NQ, WAVES, BUF, STAGE>), lds);
+    RA_LDS_OPT_IN((knn_kernel<DT, NQ, WAVES, SEL, STAGE>), lds);
     const dim3 grid((unsigned)((M + QPB - 1) / QPB), (unsigned)(n_seq * n_q));
-    hipLaunchKernelGGL((knn_kernel<DT, NQ, WAVES, BUF, STAGE>), grid, dim3(WAVES * RA_WAVE), lds, st, K, Q,
+    hipLaunchKernelGGL((knn_kernel<DT, NQ, WAVES, SEL, STAGE>), grid, dim3(WAVES * RA_WAVE), lds, st, K, Q,
                        reinterpret_cast<const u64*>(order), ra_knn_order_stride(N), n_q, n_kv, N, M, knn, L);
     RA_HIP(hipGetLastError());
     return RA_OK;
 }
 
-// 8 wavefronts per workgroup (one workgroup per compute unit, two wavefronts per SIMD) and one
-// set of 32 queries per wavefront: 256 queries x 64 slots x 8 bytes of lists beside the stage buffers.
+// bf16: 8 wavefronts per workgroup (one workgroup per compute unit, two wavefronts per SIMD). Lists of
+// up to 32 keys: two sets of 32 queries per wavefront, 512 queries x 32 slots x 8 bytes of lists
+// beside the stage buffers, pending keys in registers. Up to 48 keys: one set per wavefront, 256
+// queries x 64 slots. fp32 operands take twice the registers: 4 wavefronts, one set each.
 ra_status ra_launch_knn(const void* K, const void* Q, ra_dtype dt, int n_seq, int n_q, int n_kv,
                         int64_t N, int64_t M, int knn, void* workspace, hipStream_t st, int32_t* L) {
     // the order the keys are streamed in (knn_order.hip), at the start of the workspace
@@ -471,10 +549,13 @@ ra_status ra_launch_knn(const void* K, const void* Q, ra_dtype dt, int n_seq, in
     if (rc != RA_OK) return rc;
     const bool buf = knn <= KN_BUFFERED_KNN;
     if (dt == RA_BF16) {
+        if (knn <= KN_REG_KNN)
+            return knn_launch_as<RA_BF16, 2, 8, KN_SEL_REG, 16384>(K, Q, workspace, n_seq, n_q, n_kv, N, M, knn, st, L);
         if (buf)
-            return knn_launch_as<RA_BF16, 1, 8, true, 16384>(K, Q, workspace, n_seq, n_q, n_kv, N, M, knn, st, L);
-        return knn_launch_as<RA_BF16, 1, 8, false, 16384>(K, Q, workspace, n_seq, n_q, n_kv, N, M, knn, st, L);
+            return knn_launch_as<RA_BF16, 1, 8, KN_SEL_LDS, 16384>(K, Q, workspace, n_seq, n_q, n_kv, N, M, knn, st, L);
+        return knn_launch_as<RA_BF16, 1, 8, KN_SEL_INSERT, 16384>(K, Q, workspace, n_seq, n_q, n_kv, N, M, knn, st, L);
     }
-    if (buf) return knn_launch_as<RA_F32, 1, 4, true, 16384>(K, Q, workspace, n_seq, n_q, n_kv, N, M, knn, st, L);
-    return knn_launch_as<RA_F32, 1, 4, false, 16384>(K, Q, workspace, n_seq, n_q, n_kv, N, M, knn, st, L);
+    if (buf)
+        return knn_launch_as<RA_F32, 1, 4, KN_SEL_LDS, 16384>(K, Q, workspace, n_seq, n_q, n_kv, N, M, knn, st, L);
+    return knn_launch_as<RA_F32, 1, 4, KN_SEL_INSERT, 16384>(K, Q, workspace, n_seq, n_q, n_kv, N, M, knn, st, L);
 }
