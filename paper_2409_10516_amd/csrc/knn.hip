@@ -37,7 +37,9 @@
 #define KN_CAP 64                 // list slots of a query in the buffered selection (one per lane)
 #define KN_BUFFERED_KNN 48        // longest list that leaves room for pending slots
 #define KN_REG_KNN 32             // longest list of the selection that keeps pending keys in registers
-#define KN_REG_PEND 4             // pending keys a lane holds there
+#ifndef KN_REG_PEND
+#define KN_REG_PEND 4             // pending keys a lane holds there (at least 4: a group of scores)
+#endif
 // how the top-knn selection keeps keys that reached a threshold until they are merged into a list
 #define KN_SEL_INSERT 0           // not at all: sorted insertion, one key at a time
 #define KN_SEL_LDS 1              // in pending runs behind the list in LDS (KN_CAP slots per query)
@@ -104,34 +106,37 @@ __device__ __forceinline__ u64 readlane64(u64 x, int l) {
            (u64)(uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)x, l);
 }
 
-// The same for a query (number jq of its set) whose pending keys sit in registers: p0..p3 and fill
-// are every lane's own, the query's are those of lanes jq and jq + 32. With at most 8 keys to merge
+// The same for a query (number jq of its set) whose pending keys sit in registers: p[] and fill
+// are every lane's own, the query's are those of lanes jq and jq + 32. With a few keys to merge
 // into a sorted list of 32 a sort is not needed: the list goes to the lower half-wave, the pending
-// keys (zero where a lane holds fewer than four) to lanes 32..39 and, one by one as scalars, to
+// keys (zero where a lane holds fewer than it could) to lanes 32.. and, one by one as scalars, to
 // everyone; a list entry moves down by the number of pending keys above it, a pending key lands at
 // the number of keys above it, and every slot below 32 is written exactly once (keys are distinct
 // or zero; a zero pending key writes nothing). The caller resets the fill counts of the query's lanes.
-__device__ __forceinline__ float knn_fold_reg(u64* lst, int knn, int lane, int jq, u64 p0, u64 p1, u64 p2,
-                                              u64 p3, int fill) {
+__device__ __forceinline__ float knn_fold_reg(u64* lst, int knn, int lane, int jq,
+                                              const u64 (&p)[KN_REG_PEND], int fill) {
+    constexpr int P = KN_REG_PEND;
     u64 v = lane < 32 ? lst[lane & 31] : 0ull;
     const int f_lo = __builtin_amdgcn_readlane(fill, jq), f_hi = __builtin_amdgcn_readlane(fill, jq + 32);
-    u64 x[8];
-    x[0] = readlane64(p0, jq); x[1] = readlane64(p1, jq); x[2] = readlane64(p2, jq); x[3] = readlane64(p3, jq);
-    x[4] = readlane64(p0, jq + 32); x[5] = readlane64(p1, jq + 32);
-    x[6] = readlane64(p2, jq + 32); x[7] = readlane64(p3, jq + 32);
+    u64 x[2 * P];
 #pragma unroll
-    for (int k = 0; k < 8; ++k) {
-        if (!(k < 4 ? k < f_lo : k - 4 < f_hi)) x[k] = 0ull;
+    for (int k = 0; k < P; ++k) {
+        x[k] = readlane64(p[k], jq);
+        x[P + k] = readlane64(p[k], jq + 32);
+    }
+#pragma unroll
+    for (int k = 0; k < 2 * P; ++k) {
+        if (!(k < P ? k < f_lo : k - P < f_hi)) x[k] = 0ull;
         if (lane == 32 + k) v = x[k];
     }
     int pos = lane;
 #pragma unroll
-    for (int k = 0; k < 8; ++k) {
+    for (int k = 0; k < 2 * P; ++k) {
         const int above = __popcll(__ballot(v > x[k]));      // keys that beat pending key k
         if (lane < 32) pos += v < x[k] ? 1 : 0;
         if (lane == 32 + k) pos = above;
     }
-    const bool writes = lane < 32 || (lane < 40 && v != 0ull);
+    const bool writes = lane < 32 || (lane < 32 + 2 * P && v != 0ull);
     if (writes && pos < 32) lst[pos] = pos < knn ? v : 0ull;
     const u64 at_end = __ballot(writes && pos == knn - 1);
     const int src = at_end ? __ffsll((long long)at_end) - 1 : 0;
@@ -388,8 +393,7 @@ __global__ __launch_bounds__(WAVES * RA_WAVE) void knn_kernel(
                         const int jq = (__ffsll((long long)need) - 1) & 31;
                         float nt;
                         if constexpr (REGP)
-                            nt = knn_fold_reg(set_lists + (size_t)jq * KN_REG_KNN, knn, lane, jq, pr[sidx][0],
-                                              pr[sidx][1], pr[sidx][2], pr[sidx][3], fill[sidx]);
+                            nt = knn_fold_reg(set_lists + (size_t)jq * KN_REG_KNN, knn, lane, jq, pr[sidx], fill[sidx]);
                         else
                             nt = knn_fold(set_lists + (size_t)jq * KN_CAP, knn, lane);
                         if (col == jq) { tau[sidx] = nt; fill[sidx] = 0; }
@@ -514,7 +518,7 @@ __global__ __launch_bounds__(WAVES * RA_WAVE) void knn_kernel(
             if (qr >= M) break;
             u64* lst = my_lists + (size_t)jq * lstride;
             if constexpr (REGP)
-                knn_fold_reg(lst, knn, lane, j, pr[sidx][0], pr[sidx][1], pr[sidx][2], pr[sidx][3], fill[sidx]);
+                knn_fold_reg(lst, knn, lane, j, pr[sidx], fill[sidx]);
             else if constexpr (BUF)
                 knn_fold(lst, knn, lane);
             if (lane < knn) L_out[((size_t)graph * M + qr) * knn + lane] = knn_key_id(lst[lane]);
