@@ -7,16 +7,23 @@
 // with v_mfma_f32_32x32x16_bf16 (bf16 inputs) or v_mfma_f32_32x32x2_f32 (fp32 inputs). In the
 // 32x32 accumulator layout a lane holds ONE query column (lane % 32) and 16 key rows, so the
 // selection threshold of a query is a single per-lane register: the common case is a
-// max-tree over the lane's 16 scores and one compare. Only scores that reach the threshold
-// (about knn * ln(N / knn) per query over the whole stream) go further. For knn <= KN_BUFFERED_KNN a
-// query owns KN_CAP list slots in LDS: its best knn keys so far, then two runs of pending slots,
-// one per lane that scores for it. A lane appends a qualifying key to its own run with a single
-// LDS write (its fill count is a register); when a run cannot take what a lane is about to append
-// (keys come four at a time) the wavefront sorts the 64
-// slots of that query across its lanes (bitonic network), keeps the best knn and raises the
-// threshold. Between two such merges the threshold is stale but valid (never above the true one),
-// so nothing is lost and a query is merged only ~ln(N/knn) / ln(1 + pending/knn) times. Longer
-// lists use sorted insertion, one key at a time, by the whole wavefront.
+// max-tree over the lane's 16 scores and one compare. Only scores that reach the threshold go
+// further (about knn * ln(N / knn) per query over a stream in storage order, a third of that in
+// the order the keys are streamed in here: see knn_order.hip). Three ways to keep them:
+//   KN_SEL_LDS (knn <= KN_BUFFERED_KNN): a query owns KN_CAP list slots in LDS, its best knn keys
+//     so far, then two runs of pending slots, one per lane that scores for it. A lane appends a
+//     key to its own run with a single LDS write (its fill count is a register); when a run cannot
+//     take what a lane is about to append (keys come four at a time) the wavefront sorts the 64
+//     slots of that query across its lanes (bitonic network), keeps the best knn and raises the
+//     threshold.
+//   KN_SEL_REG (knn <= KN_REG_KNN, bf16): a lane keeps its pending keys (KN_REG_PEND per query
+//     set) in registers and a query's list takes 32 slots, so LDS holds the lists of twice as many
+//     queries and a wavefront owns two sets of 32: every key operand read from LDS feeds two
+//     independent MFMA chains. Merging a query's few pending keys into its sorted list takes no
+//     sort (knn_fold_reg).
+//   KN_SEL_INSERT (longer lists): sorted insertion, one key at a time, by the whole wavefront.
+// Between two merges a threshold is stale but valid (never above the true one), so nothing is
+// lost.
 //
 // A wavefront owns NQ x 32 queries for the whole key stream (their B operands stay in registers,
 // and every key operand fetched feeds NQ MFMA chains); a workgroup is WAVES wavefronts. Lists hold
