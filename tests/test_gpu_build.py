@@ -34,6 +34,9 @@ def _cases():
         "integer_bf16_knn48": lambda: synth.make_integer_case(7, N=777, M=130, T=2, d=128, n_q=2,
                                                               n_kv=1, dtype=torch.bfloat16, deg=48,
                                                               knn=48, topk=9, ef=20),
+        "integer_bf16_knn20": lambda: synth.make_integer_case(9, N=900, M=600, T=2, d=128, n_q=2,
+                                                              n_kv=1, dtype=torch.bfloat16, deg=16,
+                                                              knn=20, topk=9, ef=20),
         "integer_f32_knn40": lambda: synth.make_integer_case(8, N=450, M=70, T=2, d=128, n_q=1,
                                                              n_kv=1, dtype=torch.float32, deg=16,
                                                              knn=40, topk=9, ef=20),
