@@ -133,6 +133,18 @@ ra_status ra_decode_step_grown(const void* q, const ra_index* idx, const void* K
                                int topk, int ef, int expand, void* stream, float* out, float* lse,
                                int32_t* ids, ra_stats* stats);
 
+/* ra_decode_step with a retrieval budget per (sequence, query head) instead of one for all: the
+ * paper's appendix on dynamic retrieval budget allocation varies the number of retrieved tokens
+ * over the layers (a different topk per call does that); this call varies it over the heads of
+ * one layer as well. topk_per_head: device int32 [n_seq][n_q_heads]; head h keeps the best
+ * min(max(topk_per_head[h], 1), topk) ids of its beam outside W and attends to those. The walk
+ * itself (ef, expand) is the same for every head. A row of ids still has topk cells (the rest
+ * are -1) and stats.n_returned counts the ids kept. */
+ra_status ra_decode_step_budgets(const void* q, const ra_index* idx, const void* K, const void* V,
+                                 ra_dtype dt, int64_t N, int sink, int window, int topk,
+                                 const int32_t* topk_per_head, int ef, int expand, void* stream,
+                                 float* out, float* lse, int32_t* ids, ra_stats* stats);
+
 /* ---- exact baselines on the same harness ------------------------------------------- */
 
 /* The paper's "Flat" retrieval (exact KNN by linear scan, Sec. 4.1 and Table 5): the topk keys of

@@ -65,6 +65,9 @@ def lib() -> C.CDLL:
     L.ra_decode_step_grown.argtypes = [vp, vp, vp, vp, i32, i64, i64, i32, i32, i32, i32, i32, vp, vp,
                                        vp, vp, vp]
     L.ra_decode_step_grown.restype = i32
+    L.ra_decode_step_budgets.argtypes = [vp, vp, vp, vp, i32, i64, i32, i32, i32, vp, i32, i32, vp, vp,
+                                         vp, vp, vp]
+    L.ra_decode_step_budgets.restype = i32
     L.ra_index_import.argtypes = [vp, vp, i32, i32, i32, i64, i32, C.POINTER(vp)]
     L.ra_index_export.argtypes = [vp, i32, i32, vp, vp]
     L.ra_index_info.argtypes = [vp, i32]
@@ -284,12 +287,16 @@ def ra_attend(q, idx: Index, K, V, sink: int, window: int, ids: torch.Tensor, st
 
 def ra_decode_step(q, idx: Index, K, V, sink: int, window: int, topk: int, ef: int,
                    expand: int = 1, stream=None, out=None, lse=None, ids=None, stats=None,
-                   n_tokens: Optional[int] = None, k8=None):
+                   n_tokens: Optional[int] = None, k8=None, topk_per_head=None):
     """One layer's decode-step attention. Output tensors may be passed in to avoid
     allocation; -> (out, lse, ids, stats). With n_tokens given, K/V are caches of capacity
     K.shape[2] rows per head holding n_tokens >= idx.N valid tokens (ra_decode_step_grown). With
-    k8 = (K8, scale) from ra_quantize_keys the walk reads the 8-bit keys (ra_decode_step_q8)."""
-    _dev(q, K, V, out, lse, ids, stats)
+    k8 = (K8, scale) from ra_quantize_keys the walk reads the 8-bit keys (ra_decode_step_q8). With
+    topk_per_head (device int32 [n_seq][n_q]) every head keeps its own number of ids, at most topk
+    (ra_decode_step_budgets)."""
+    _dev(q, K, V, out, lse, ids, stats, topk_per_head)
+    if topk_per_head is not None and (k8 is not None or n_tokens is not None):
+        raise ValueError("topk_per_head goes with neither k8 nor n_tokens")
     n_seq, n_q, d = q.shape
     f = dict(dtype=torch.float32, device=q.device)
     if out is None:
@@ -300,7 +307,14 @@ def ra_decode_step(q, idx: Index, K, V, sink: int, window: int, topk: int, ef: i
         ids = torch.empty((n_seq, n_q, topk), dtype=torch.int32, device=q.device)
     if stats is None:
         stats = _stats_tensor(n_seq * n_q, q.device).view(n_seq, n_q, 4)
-    if k8 is not None:
+    if topk_per_head is not None:
+        if topk_per_head.dtype != torch.int32 or tuple(topk_per_head.shape) != (n_seq, n_q) \
+                or not topk_per_head.is_contiguous():
+            raise ValueError("topk_per_head must be a contiguous int32 tensor [n_seq][n_q]")
+        _check(lib().ra_decode_step_budgets(_ptr(q), idx.handle, _ptr(K), _ptr(V), _dt(K), K.shape[2], sink,
+                                            window, topk, _ptr(topk_per_head), ef, expand, _stream(stream),
+                                            _ptr(out), _ptr(lse), _ptr(ids), _ptr(stats)))
+    elif k8 is not None:
         K8, scale = k8
         _dev(K8, scale)
         _check(lib().ra_decode_step_q8(_ptr(q), idx.handle, _ptr(K), _ptr(V), _dt(K), _ptr(K8), _ptr(scale),

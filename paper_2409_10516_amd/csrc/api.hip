@@ -375,9 +375,10 @@ extern "C" ra_status ra_attend(const void* q, const ra_index* idx, const void* K
 
 // K8 / kscale: the 8-bit copy of the keys the walk scores, or NULL for the keys themselves
 static ra_status decode_common(const void* q, const ra_index* idx, const void* K, const void* V,
-                               ra_dtype dt, const int8_t* K8, const float* kscale, int64_t N,
-                               int64_t kv_stride, int sink, int window, int topk, int ef, int expand,
-                               void* stream, float* out, float* lse, int32_t* ids, ra_stats* stats) {
+                               ra_dtype dt, const int8_t* K8, const float* kscale, const int32_t* budgets,
+                               int64_t N, int64_t kv_stride, int sink, int window, int topk, int ef,
+                               int expand, void* stream, float* out, float* lse, int32_t* ids,
+                               ra_stats* stats) {
     if (!q || !K || !V || !out || !lse) RA_FAIL(RA_EINVAL, "NULL argument");
     RA_TRY(check_dtype(dt));
     if (!idx) RA_FAIL(RA_EINVAL, "index handle is NULL");
@@ -399,7 +400,7 @@ static ra_status decode_common(const void* q, const ra_index* idx, const void* K
         RA_TRY(grow((void**)&ix->bitset, &ix->bitset_bytes, heads * ((ix->N + 31) >> 5) * 4));
     return ra_launch_decode(q, ix->adj, ix->entry, K, V, dt, ix->n_seq, ix->n_q, ix->n_kv, ix->N, N,
                             kv_stride, ix->deg, sink, window, topk, ef, expand, ix->bitset, ix->coop,
-                            ix->coop_mode, ix->coop_spin, ix->roots, ix->root_cap, K8, kscale,
+                            ix->coop_mode, ix->coop_spin, ix->roots, ix->root_cap, K8, kscale, budgets,
                             (hipStream_t)stream, out, lse, ids, stats);
 }
 
@@ -408,8 +409,8 @@ extern "C" ra_status ra_decode_step_grown(const void* q, const ra_index* idx, co
                                           int sink, int window, int topk, int ef, int expand,
                                           void* stream, float* out, float* lse, int32_t* ids,
                                           ra_stats* stats) {
-    return decode_common(q, idx, K, V, dt, nullptr, nullptr, N, kv_stride, sink, window, topk, ef, expand,
-                         stream, out, lse, ids, stats);
+    return decode_common(q, idx, K, V, dt, nullptr, nullptr, nullptr, N, kv_stride, sink, window, topk, ef,
+                         expand, stream, out, lse, ids, stats);
 }
 
 extern "C" ra_status ra_decode_step_q8(const void* q, const ra_index* idx, const void* K, const void* V,
@@ -420,8 +421,20 @@ extern "C" ra_status ra_decode_step_q8(const void* q, const ra_index* idx, const
     if (idx && N != idx->N)
         RA_FAIL(RA_ESHAPE, "N = %lld but the index was built over %lld keys", (long long)N,
                 (long long)idx->N);
-    return decode_common(q, idx, K, V, dt, K8, scale, N, N, sink, window, topk, ef, expand, stream, out,
-                         lse, ids, stats);
+    return decode_common(q, idx, K, V, dt, K8, scale, nullptr, N, N, sink, window, topk, ef, expand, stream,
+                         out, lse, ids, stats);
+}
+
+extern "C" ra_status ra_decode_step_budgets(const void* q, const ra_index* idx, const void* K, const void* V,
+                                            ra_dtype dt, int64_t N, int sink, int window, int topk,
+                                            const int32_t* topk_per_head, int ef, int expand, void* stream,
+                                            float* out, float* lse, int32_t* ids, ra_stats* stats) {
+    if (!topk_per_head) RA_FAIL(RA_EINVAL, "NULL argument");
+    if (idx && N != idx->N)
+        RA_FAIL(RA_ESHAPE, "N = %lld but the index was built over %lld keys", (long long)N,
+                (long long)idx->N);
+    return decode_common(q, idx, K, V, dt, nullptr, nullptr, topk_per_head, N, N, sink, window, topk, ef, expand,
+                         stream, out, lse, ids, stats);
 }
 
 extern "C" ra_status ra_decode_step(const void* q, const ra_index* idx, const void* K, const void* V,

@@ -101,7 +101,7 @@ ra_status ra_launch_decode(const void* q, const int32_t* adj, const int32_t* ent
                            int64_t kv_stride, int deg, int sink, int window, int topk, int ef, int expand,
                            uint32_t* bitset, float* coop, int coop_mode, int coop_spin,
                            const int32_t* roots, int root_cap, const void* K8, const float* kscale,
-                           hipStream_t st, float* out, float* lse, int32_t* ids,
+                           const int32_t* budgets, hipStream_t st, float* out, float* lse, int32_t* ids,
                            ra_stats* stats);
 
 ra_status ra_launch_rerank(const void* q, const void* K, ra_dtype dt, int n_seq, int n_q, int n_kv, int64_t N,

@@ -268,7 +268,7 @@ __global__ __launch_bounds__(T) void decode_kernel(
     int32_t* __restrict__ ids, ra_stats* __restrict__ stats, int ids_off, float scale,
     float* __restrict__ out, float* __restrict__ lse, float* coop, int n_helpers, int coop_mode,
     int coop_spin, const int32_t* __restrict__ roots, int root_cap, const void* __restrict__ Ksearch,
-    const float* __restrict__ kscale) {
+    const float* __restrict__ kscale, const int32_t* __restrict__ budgets) {
     extern __shared__ __align__(16) unsigned char lds_raw[];
     const int tid = threadIdx.x, grp = tid >> 4, lane16 = tid & 15;
     const size_t esz = DT == RA_BF16 ? 2 : 4;
@@ -302,8 +302,14 @@ __global__ __launch_bounds__(T) void decode_kernel(
     // The graph covers the first Ng of the N tokens now in the cache; W = [0, s) u [wstart, N) with
     // wstart <= Ng, so every token appended after the build is attended densely.
     // the walk scores Ksearch: K itself, or its 8-bit copy (with kscale)
+    // ids kept for this head: topk, or its own budget clamped into [1, topk]
+    int take = topk;
+    if (budgets) {
+        const int b = budgets[head];
+        take = b < 1 ? 1 : b > topk ? topk : b;
+    }
     const int cnt = run_search<DT, KT, GBITS, T>(lds_raw, head, q, adj, entry, Ksearch, n_q, n_kv, Ng, kv_stride, deg,
-                                          s, (int)(Ng - wstart), topk, ef, expand, gbits, ids, stats,
+                                          s, (int)(Ng - wstart), topk, take, ef, expand, gbits, ids, stats,
                                           lds_ids, roots, root_cap, kscale,
                                           AwaitHelper{ready + head, ready + n_heads, lds_word,
                                                                coop_spin, helpers});
@@ -419,7 +425,8 @@ ra_status ra_launch_decode(const void* q, const int32_t* adj, const int32_t* ent
                            int64_t kv_stride, int deg, int sink, int window, int topk, int ef, int expand,
                            uint32_t* bitset, float* coop, int coop_mode, int coop_spin,
                            const int32_t* roots, int root_cap, const void* K8, const float* kscale,
-                           hipStream_t st, float* out, float* lse, int32_t* ids, ra_stats* stats) {
+                           const int32_t* budgets, hipStream_t st, float* out, float* lse, int32_t* ids,
+                           ra_stats* stats) {
     // W = [0, s) u [wstart, N): the sink, the sliding window, and every token appended after the
     // index was built (wstart <= Ng); overlapping ranges make everything static
     int64_t s = sink < 0 ? 0 : sink, ww = window < 0 ? 0 : window;
@@ -456,7 +463,7 @@ ra_status ra_launch_decode(const void* q, const int32_t* adj, const int32_t* ent
                            lds, st, q, adj, entry, K, V, n_q, n_kv, Ng, N, kv_stride, wstart, deg, \
                            (int)s, topk, ef, expand, bitset, ids, stats, ids_off, scale, out, lse, \
                            coop, n_helpers, coop_mode, coop_spin, roots, root_cap, Ksearch,        \
-                           kscale);                                                                \
+                           kscale, budgets);                                                       \
     } while (0)
 #define RA_DC_GO(DTV, KTV, GB)                                                                     \
     do {                                                                                           \

@@ -9,7 +9,7 @@ __global__ __launch_bounds__(T) void search_kernel(
     ra_stats* __restrict__ stats, const int32_t* __restrict__ roots, int root_cap,
     const float* __restrict__ kscale) {
     extern __shared__ __align__(16) unsigned char lds_raw[];
-    run_search<DT, KT, GBITS, T>(lds_raw, xcd_aware_head(blockIdx.x, gridDim.x, n_q / n_kv), q, adj, entry, K, n_q, n_kv, N, N, deg, s, w, topk, ef,
+    run_search<DT, KT, GBITS, T>(lds_raw, xcd_aware_head(blockIdx.x, gridDim.x, n_q / n_kv), q, adj, entry, K, n_q, n_kv, N, N, deg, s, w, topk, topk, ef,
                           expand, gbits, ids, stats, nullptr, roots, root_cap, kscale, NoHook());
 }
 

@@ -243,8 +243,8 @@ template <int DT, int KT, bool GBITS, int T, typename Hook>
 __device__ __forceinline__ int run_search(
     unsigned char* lds_raw, int head, const void* __restrict__ q, const int32_t* __restrict__ adj,
     const int32_t* __restrict__ entry, const void* __restrict__ K, int n_q, int n_kv, int64_t N,
-    int64_t kv_stride, int deg, int s, int w, int topk, int ef, int expand, uint32_t* __restrict__ gbits,
-    int32_t* __restrict__ ids, ra_stats* __restrict__ stats, int32_t* lds_ids,
+    int64_t kv_stride, int deg, int s, int w, int topk, int take, int ef, int expand,
+    uint32_t* __restrict__ gbits, int32_t* __restrict__ ids, ra_stats* __restrict__ stats, int32_t* lds_ids,
     const int32_t* __restrict__ roots, int root_cap, const float* __restrict__ kscale, const Hook& hook) {
     const int tid = threadIdx.x, grp = tid >> 4, lane16 = tid & 15;
     const int lane = tid & (RA_WAVE - 1), wv = tid / RA_WAVE;
@@ -593,19 +593,20 @@ __device__ __forceinline__ int run_search(
     if (tid < RA_WAVE) {
         int32_t* out = ids + (size_t)head * topk;
         int cnt = 0;
-        for (int base = 0; base < bn && cnt < topk; base += RA_WAVE) {
+        // (a row of ids has topk cells; this head returns at most `take` <= topk of them)
+        for (int base = 0; base < bn && cnt < take; base += RA_WAVE) {
             const int i = base + tid;
             const int id = i < bn ? key_id(cur[i]) : -1;
             const bool ok = i < bn && id >= s && id < N - w;
             const u64 mask = __ballot(ok);
             const int pos = cnt + __popcll(mask & ((1ull << tid) - 1ull));
-            if (ok && pos < topk) {
+            if (ok && pos < take) {
                 out[pos] = id;
                 if (lds_ids) lds_ids[pos] = id;
             }
             cnt += __popcll(mask);
         }
-        if (cnt > topk) cnt = topk;
+        if (cnt > take) cnt = take;
         for (int i = cnt + tid; i < topk; i += RA_WAVE) {
             out[i] = -1;
             if (lds_ids) lds_ids[i] = -1;

@@ -71,6 +71,13 @@ def test_decode_validation_without_index():
                           _fake(), None, None)
     assert rc == 1 and "handle" in L.ra_last_error().decode()
     assert L.ra_search(_fake(), None, _fake(), 1, 100, 4, 8, 10, 20, 1, None, _fake(), None) == 1
+    # per-head budgets: the array is required, then the same checks as ra_decode_step
+    rc = L.ra_decode_step_budgets(_fake(), None, _fake(), _fake(), 1, 100, 4, 8, 10, None, 20, 1, None,
+                                  _fake(), _fake(), None, None)
+    assert rc == 1 and "NULL" in L.ra_last_error().decode()
+    rc = L.ra_decode_step_budgets(_fake(), None, _fake(), _fake(), 1, 100, 4, 8, 10, _fake(), 20, 1, None,
+                                  _fake(), _fake(), None, None)
+    assert rc == 1 and "handle" in L.ra_last_error().decode()
     assert L.ra_index_info(None, 0) == -1
     L.ra_index_free(None)            # must be a no-op
 

@@ -117,6 +117,36 @@ def test_decode_step_end_to_end(name, expand):
 
 
 @pytest.mark.parametrize("name", list(_cases()))
+def test_decode_step_with_a_budget_per_head(name):
+    """ra_decode_step_budgets: every head keeps its own number of ids (values outside [1, topk] are
+    clamped); each head must equal the oracle's decode step run with that head's budget, the rest
+    of its ids row is -1 and n_returned counts what was kept."""
+    w, adj, ent, idx, Kd, Vd = _prepared(name)
+    n_seq, n_kv, N, d = w.K.shape
+    n_q = w.Q_prefill.shape[1]
+    tol = tol_for(w.K.dtype)
+    rng = np.random.default_rng(3)
+    budgets = rng.integers(1, w.topk + 1, size=(n_seq, n_q)).astype(np.int32)
+    budgets.flat[0] = 0                   # clamped to 1
+    budgets.flat[-1] = w.topk + 7         # clamped to topk
+    want = np.clip(budgets, 1, w.topk)
+    out, lse, ids, st = ra.ra_decode_step(w.q_decode[0].to(DEV), idx, Kd, Vd, w.sink, w.window, w.topk,
+                                          w.ef, 8, topk_per_head=torch.from_numpy(budgets).to(DEV))
+    out, lse, ids, st = out.cpu().numpy(), lse.cpu().numpy(), ids.cpu().numpy(), st.cpu().numpy()
+    for s in range(n_seq):
+        for h in range(n_q):
+            g = s * n_q + h
+            K = to_np(w.K[s, h // (n_q // n_kv)]); V = to_np(w.V[s, h // (n_q // n_kv)])
+            b = int(want[s, h])
+            r_out, r_lse, r_ids, _ = OD.decode_step(to_np(w.q_decode[0, s, h]), K, V, adj[g], ent[g],
+                                                    w.sink, w.window, b, w.ef, 8)
+            assert ids[s, h, :b].tolist() == r_ids.tolist()
+            assert (ids[s, h, b:] == -1).all()
+            assert st[s, h, 3] == int((r_ids >= 0).sum())
+            assert out_close(out[s, h], r_out, tol) and lse_close(lse[s, h], r_lse, tol)
+
+
+@pytest.mark.parametrize("name", list(_cases()))
 def test_decode_step_helper_modes_agree_with_oracle(name):
     """ra_index_configure: the attention over W by helper workgroups (default), by the heads
     themselves (RA_HELPERS_OFF), and after a bounded wait that runs out (RA_HELPERS_SILENT with a
