@@ -114,6 +114,35 @@ def test_knn_tiny_key_sets(N, knn):
     assert np.array_equal(L, np.broadcast_to(np.arange(knn), (M, knn)))
 
 
+def _sweep_cases():
+    rng = np.random.default_rng(1234)
+    cases = []
+    for it in range(14):
+        dtype = torch.bfloat16 if it % 3 else torch.float32
+        n_kv = int(rng.choice([1, 2])); G = int(rng.choice([1, 2, 4]))
+        N = int(rng.choice([31, 33, 63, 65, 100, 511, 513, 1000, 2047, 4097]))
+        M = int(rng.choice([1, 5, 33, 255, 257, 511, 513, 1025]))
+        knn = min(int(rng.choice([1, 2, 5, 16, 31, 32, 33, 40, 48, 49, 64])), N)
+        cases.append((it, dtype, n_kv, G, N, M, knn))
+    return cases
+
+
+@pytest.mark.parametrize("it,dtype,n_kv,G,N,M,knn", _sweep_cases())
+def test_knn_shape_sweep(it, dtype, n_kv, G, N, M, knn):
+    """Key and query counts around the kernel's block, stage and workgroup sizes, list lengths on both
+    sides of every selection's limit. Small integer inputs with a shared component: every score is
+    exact, ties abound, the stream order is not the storage order."""
+    g = torch.Generator(); g.manual_seed(1000 + it)
+    K = torch.randint(-3, 4, (1, n_kv, N, 128), generator=g).float()
+    Q = torch.randint(-3, 4, (1, n_kv * G, M, 128), generator=g).float()
+    K[..., 0] += torch.randint(0, 6, (1, n_kv, N), generator=g).float()
+    Q[..., 0] += 2
+    L = ra.ra_knn(K.to(dtype).to(DEV), Q.to(dtype).to(DEV), knn).cpu().numpy()
+    for h in range(n_kv * G):
+        ref, _ = OM.knn_lists(Q[0, h].numpy().astype(np.float64), K[0, h // G].numpy().astype(np.float64), knn)
+        assert np.array_equal(L[0, h], ref), h
+
+
 def test_projection_hand_worked_example():
     g = json.load(open(os.path.join(GOLD, "projection_hand.json")))
     L = torch.tensor([g["L"]], dtype=torch.int32, device=DEV)
