@@ -28,14 +28,35 @@ __global__ __launch_bounds__(AT_THREADS) void attend_partial_kernel(
     }
 }
 
-// grid: x = query head, y = seq; block = 128 threads (one per output dimension).
-__global__ __launch_bounds__(RA_D) void attend_merge_kernel(
+// grid: x = query head, y = seq; block = n_slices x 128 threads (one per slice of the records and
+// output dimension). A head with more than sixteen records (a long static range: full attention)
+// has its batches of sixteen dealt to up to AT_MERGE_SLICES slices that run side by side and are
+// folded through LDS, in slice order, by the first.
+#define AT_MERGE_SLICES 8
+__global__ __launch_bounds__(AT_MERGE_SLICES * RA_D) void attend_merge_kernel(
     const float* __restrict__ partials, int n_q, int nS, int nG, float* __restrict__ out,
     float* __restrict__ lse, float* __restrict__ o_om, float* __restrict__ lse_om,
     float* __restrict__ o_w, float* __restrict__ lse_w) {
+    __shared__ float part[AT_MERGE_SLICES][2][3][RA_D];          // [slice][set][M, L, A][dimension]
     const size_t head = (size_t)blockIdx.y * n_q + blockIdx.x;
-    merge_head<false>(partials + head * (nS + nG) * AT_RS, nS, nG, threadIdx.x, head, out, lse, o_om,
-                      lse_om, o_w, lse_w);
+    const int t = threadIdx.x % RA_D, slice = threadIdx.x / RA_D, n_slices = blockDim.x / RA_D;
+    float M[2] = {-INFINITY, -INFINITY}, L[2] = {0.f, 0.f}, A[2] = {0.f, 0.f};
+    merge_accumulate<false>(partials + head * (nS + nG) * AT_RS, nS, nG, t, slice, n_slices, M, L, A);
+    if (n_slices > 1) {
+#pragma unroll
+        for (int set = 0; set < 2; ++set) {
+            part[slice][set][0][t] = M[set];
+            part[slice][set][1][t] = L[set];
+            part[slice][set][2][t] = A[set];
+        }
+        __syncthreads();
+        if (slice != 0) return;
+        for (int b = 1; b < n_slices; ++b)
+#pragma unroll
+            for (int set = 0; set < 2; ++set)
+                merge_fold(M[set], L[set], A[set], part[b][set][0][t], part[b][set][1][t], part[b][set][2][t]);
+    }
+    merge_finish(M, L, A, t, head, out, lse, o_om, lse_om, o_w, lse_w);
 }
 
 // 64-row sub-chunks per static workgroup: 1 for the decode step's few hundred static rows, more
@@ -98,7 +119,9 @@ ra_status ra_launch_attend(const void* q, const void* K, const void* V, ra_dtype
                                  topk, nS, nG, sub, scale);
     if (rc != RA_OK) return rc;
     RA_HIP(hipGetLastError());
-    hipLaunchKernelGGL(attend_merge_kernel, dim3(n_q, n_seq), dim3(RA_D), 0, st, partials, n_q, nS,
+    int slices = (nS + nG + 15) / 16;                     // one per batch of sixteen records, at most 8
+    if (slices > AT_MERGE_SLICES) slices = AT_MERGE_SLICES;
+    hipLaunchKernelGGL(attend_merge_kernel, dim3(n_q, n_seq), dim3(slices * RA_D), 0, st, partials, n_q, nS,
                        nG, out, lse, o_omega, lse_omega, o_w, lse_w);
     RA_HIP(hipGetLastError());
     return RA_OK;

@@ -243,16 +243,16 @@ __device__ __forceinline__ float rec_load(const float* p) {
     return *p;
 }
 
+// Online (max, sum, weighted sum) of the records of one head, per set (0: the static chunks,
+// 1: the gathered chunks), over the batches of sixteen records slice, slice + n_slices, ...
+// Sixteen at a time so that their loads are in flight together (one round trip for the usual
+// P <= 16).
 template <bool COHERENT>
-__device__ __forceinline__ void merge_head(const float* rec, int nS, int nG, int t, size_t head,
-                                           float* __restrict__ out, float* __restrict__ lse,
-                                           float* __restrict__ o_om, float* __restrict__ lse_om,
-                                           float* __restrict__ o_w, float* __restrict__ lse_w) {
+__device__ __forceinline__ void merge_accumulate(const float* rec, int nS, int nG, int t, int slice,
+                                                 int n_slices, float (&M)[2], float (&L)[2],
+                                                 float (&A)[2]) {
     const int P = nS + nG;
-    float M[2] = {-INFINITY, -INFINITY}, L[2] = {0.f, 0.f}, A[2] = {0.f, 0.f};
-    // records are taken sixteen at a time so that their loads are in flight together (one round
-    // trip for the usual P <= 16); each set keeps an online (max, sum, weighted sum)
-    for (int i0 = 0; i0 < P; i0 += 16) {
+    for (int i0 = slice * 16; i0 < P; i0 += n_slices * 16) {
         float rm[16], rl[16], ra[16];
 #pragma unroll
         for (int u = 0; u < 16; ++u) {
@@ -283,6 +283,25 @@ __device__ __forceinline__ void merge_head(const float* rec, int nS, int nG, int
             }
         }
     }
+}
+
+// One more (max, sum, weighted sum) folded into a set's running one.
+__device__ __forceinline__ void merge_fold(float& M, float& L, float& A, float m, float l, float a) {
+    const float cm = fmaxf(M, m);
+    if (cm > -INFINITY) {
+        const float c0 = expf(M - cm), c1 = expf(m - cm);
+        A = A * c0 + a * c1;
+        L = L * c0 + l * c1;
+        M = cm;
+    }
+}
+
+// Eq. 4 per set and Eq. 5 across the two sets, from their (max, sum, weighted sum); t = output dimension.
+__device__ __forceinline__ void merge_finish(const float (&M)[2], const float (&L)[2], const float (&A)[2],
+                                             int t, size_t head, float* __restrict__ out,
+                                             float* __restrict__ lse, float* __restrict__ o_om,
+                                             float* __restrict__ lse_om, float* __restrict__ o_w,
+                                             float* __restrict__ lse_w) {
     // set-level results of Eq. 4: o_W (set 0) and o_Omega (set 1)
     float* o_set[2] = {o_w, o_om};
     float* l_set[2] = {lse_w, lse_om};
