@@ -97,20 +97,19 @@ __device__ __forceinline__ u64 wave_sort_desc(u64 v, int lane) {
     return v;
 }
 
+__device__ __forceinline__ u64 readlane64(u64 x, int l) {
+    return ((u64)(uint32_t)__builtin_amdgcn_readlane((int)(x >> 32), l) << 32) |
+           (u64)(uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)x, l);
+}
+
 // Fold the pending keys of one query into its list: afterwards slots [0, knn) hold its best knn
 // keys in descending order and the pending slots are empty (all 64 lanes cooperate).
 // Returns the new threshold: the score of slot knn - 1, or -inf while the list is not full.
 __device__ __forceinline__ float knn_fold(u64* lst, int knn, int lane) {
     const u64 v = wave_sort_desc(lst[lane], lane);
     lst[lane] = lane < knn ? v : 0ull;
-    const u64 last = ((u64)(uint32_t)__builtin_amdgcn_readlane((int)(v >> 32), knn - 1) << 32) |
-                     (u64)(uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)v, knn - 1);
+    const u64 last = readlane64(v, knn - 1);
     return last == 0ull ? -INFINITY : f32_from_ordered((uint32_t)(last >> 32));
-}
-
-__device__ __forceinline__ u64 readlane64(u64 x, int l) {
-    return ((u64)(uint32_t)__builtin_amdgcn_readlane((int)(x >> 32), l) << 32) |
-           (u64)(uint32_t)__builtin_amdgcn_readlane((int)(uint32_t)x, l);
 }
 
 // The same for a query (number jq of its set) whose pending keys sit in registers: p[] and fill
