@@ -420,7 +420,7 @@ __global__ __launch_bounds__(WAVES * RA_WAVE) void knn_kernel(
                                 for (int k = 0; k < KN_REG_PEND; ++k)
                                     pr[sidx][k] = fill[sidx] == k ? nk : pr[sidx][k];
                                 fill[sidx]++;
-                            } else {
+                            } else if (fill[sidx] < pend) {      // always, for scores that are numbers
                                 mine[fill[sidx]++] = nk;
                             }
                         }
