@@ -39,11 +39,15 @@
 // them with the 16-byte chunks of a row XOR-swizzled by the row number, and every wavefront
 // reads its operands from there with conflict-free 16-byte LDS reads. Two stage buffers
 // alternate; one barrier per stage.
+#include <stdlib.h>
+#include <string.h>
+
 #include "common.h"
 
 #define KN_CAP 64                 // list slots of a query in the buffered selection (one per lane)
 #define KN_BUFFERED_KNN 48        // longest list that leaves room for pending slots
 #define KN_REG_KNN 32             // longest list of the selection that keeps pending keys in registers
+#define KN_REG_MIN_KEYS 49152     // fewest keys for which that selection is the faster one (see ra_launch_knn)
 #ifndef KN_REG_PEND
 #define KN_REG_PEND 4             // pending keys a lane holds there (at least 4: a group of scores)
 #endif
@@ -558,8 +562,18 @@ ra_status ra_launch_knn(const void* K, const void* Q, ra_dtype dt, int n_seq, in
     ra_status rc = ra_launch_knn_order(K, Q, dt, n_seq, n_q, n_kv, N, M, workspace, st);
     if (rc != RA_OK) return rc;
     const bool buf = knn <= KN_BUFFERED_KNN;
+    // Pending keys in registers: a fold takes 8 keys at most instead of 32, so the start of the stream,
+    // where nearly every key reaches the thresholds, costs more (about 14 ms instead of 6 ms for
+    // 32 heads x 131072 queries), and every later key less (0.80 us instead of 0.95 us): it pays
+    // from about 50 K keys on. RA_KNN_SELECTION=reg|lds in the environment overrides the choice
+    // (the tests run both on small inputs).
+    bool reg = knn <= KN_REG_KNN && N >= KN_REG_MIN_KEYS;
+    if (const char* e = getenv("RA_KNN_SELECTION")) {
+        if (!strcmp(e, "reg")) reg = knn <= KN_REG_KNN;
+        else if (!strcmp(e, "lds")) reg = false;
+    }
     if (dt == RA_BF16) {
-        if (knn <= KN_REG_KNN)
+        if (reg)
             return knn_launch_as<RA_BF16, 2, 8, KN_SEL_REG, 16384>(K, Q, workspace, n_seq, n_q, n_kv, N, M, knn, st, L);
         if (buf)
             return knn_launch_as<RA_BF16, 1, 8, KN_SEL_LDS, 16384>(K, Q, workspace, n_seq, n_q, n_kv, N, M, knn, st, L);

@@ -17,6 +17,14 @@ DEV = "cuda:0"
 GOLD = os.path.join(os.path.dirname(__file__), "golden")
 
 
+@pytest.fixture(params=["reg", "lds"])
+def knn_selection(request, monkeypatch):
+    """Lists of up to 32 bf16 keys have two selections (pending keys in registers, two query sets per
+    wavefront / pending runs in LDS); the library picks by the number of keys, the tests force each."""
+    monkeypatch.setenv("RA_KNN_SELECTION", request.param)
+    return request.param
+
+
 def _cases():
     return {
         "config0_small": lambda: synth.make_config0(N=1024, M=256, T=2, window=32),
@@ -52,7 +60,7 @@ def _heads(w):
 
 
 @pytest.mark.parametrize("name", list(_cases()))
-def test_knn_lists(name):
+def test_knn_lists(name, knn_selection):
     w = _cases()[name]()
     L = ra.ra_knn(w.K.to(DEV), w.Q_prefill.to(DEV), w.knn).cpu().numpy()
     for s, h, g, K, Q in _heads(w):
@@ -65,7 +73,7 @@ def test_knn_lists(name):
 @pytest.mark.parametrize("dtype", [torch.bfloat16, torch.float32])
 @pytest.mark.parametrize("knn", [5, 32, 48, 64])
 @pytest.mark.parametrize("rising", [True, False])
-def test_knn_monotone_stream(dtype, knn, rising):
+def test_knn_monotone_stream(dtype, knn, rising, knn_selection):
     """Scores that rise with the key id make every key of the stream qualify (the selection folds or
     inserts all the time); falling scores make none qualify after the first knn. Key i scores exactly
     +-i for every query (i = 256 * K[i,1] + K[i,0], both exact in bf16), so the lists are known."""
@@ -84,7 +92,7 @@ def test_knn_monotone_stream(dtype, knn, rising):
 
 @pytest.mark.parametrize("dtype", [torch.bfloat16, torch.float32])
 @pytest.mark.parametrize("knn", [7, 32, 64])
-def test_knn_stream_order_against_a_minority_of_queries(dtype, knn):
+def test_knn_stream_order_against_a_minority_of_queries(dtype, knn, knn_selection):
     """The keys are streamed by descending inner product with the head's mean query. Here 60 % of
     the queries are -u and 40 % are +u, so the stream is in the best order for the majority and in
     the worst (every key beats the threshold) for the minority; the lists must not depend on it."""
@@ -104,7 +112,7 @@ def test_knn_stream_order_against_a_minority_of_queries(dtype, knn):
 
 
 @pytest.mark.parametrize("N,knn", [(1, 1), (3, 3), (5, 2), (33, 33), (64, 48), (65, 64)])
-def test_knn_tiny_key_sets(N, knn):
+def test_knn_tiny_key_sets(N, knn, knn_selection):
     """Fewer keys than a stage, than a block, than the sort's smallest chunk: all equal scores, so
     the lists are the lowest ids in order."""
     M = 9
@@ -128,7 +136,7 @@ def _sweep_cases():
 
 
 @pytest.mark.parametrize("it,dtype,n_kv,G,N,M,knn", _sweep_cases())
-def test_knn_shape_sweep(it, dtype, n_kv, G, N, M, knn):
+def test_knn_shape_sweep(it, dtype, n_kv, G, N, M, knn, knn_selection):
     """Key and query counts around the kernel's block, stage and workgroup sizes, list lengths on both
     sides of every selection's limit. Small integer inputs with a shared component: every score is
     exact, ties abound, the stream order is not the storage order."""
