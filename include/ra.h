@@ -139,7 +139,8 @@ ra_status ra_decode_step_grown(const void* q, const ra_index* idx, const void* K
  * one layer as well. topk_per_head: device int32 [n_seq][n_q_heads]; head h keeps the best
  * min(max(topk_per_head[h], 1), topk) ids of its beam outside W and attends to those. The walk
  * itself (ef, expand) is the same for every head. A row of ids still has topk cells (the rest
- * are -1) and stats.n_returned counts the ids kept. */
+ * are -1) and stats.n_returned counts the ids kept. RA_EUNSUP where the visited bitsets do not
+ * fit LDS (a context too long for this ef and expand). */
 ra_status ra_decode_step_budgets(const void* q, const ra_index* idx, const void* K, const void* V,
                                  ra_dtype dt, int64_t N, int sink, int window, int topk,
                                  const int32_t* topk_per_head, int ef, int expand, void* stream,

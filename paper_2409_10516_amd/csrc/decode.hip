@@ -259,7 +259,10 @@ struct AwaitHelper {
     }
 };
 
-template <int DT, int KT, bool GBITS, int T>
+// BUDGETS: every head keeps its own number of ids (budgets[head]) instead of topk. A variant of
+// its own because the value lives through the whole walk: read in the common kernel, even behind a
+// test for a null pointer, it cost 1.5 % of the step.
+template <int DT, int KT, bool GBITS, int T, bool BUDGETS>
 __global__ __launch_bounds__(T) void decode_kernel(
     const void* __restrict__ q, const int32_t* __restrict__ adj, const int32_t* __restrict__ entry,
     const void* __restrict__ K, const void* __restrict__ V, int n_q, int n_kv, int64_t Ng, int64_t N,
@@ -304,7 +307,7 @@ __global__ __launch_bounds__(T) void decode_kernel(
     // the walk scores Ksearch: K itself, or its 8-bit copy (with kscale)
     // ids kept for this head: topk, or its own budget clamped into [1, topk]
     int take = topk;
-    if (budgets) {
+    if constexpr (BUDGETS) {
         const int b = budgets[head];
         take = b < 1 ? 1 : b > topk ? topk : b;
     }
@@ -456,10 +459,11 @@ ra_status ra_launch_decode(const void* q, const int32_t* adj, const int32_t* ent
     const int threads = search_threads(heads, ef);
     const void* Ksearch = kscale ? K8 : K;
     if (kscale && !K8) RA_FAIL(RA_EINVAL, "8-bit keys missing");
-#define RA_DC_GO_T(DTV, KTV, GB, TV)                                                               \
+#define RA_DC_GO_T(DTV, KTV, GB, TV) RA_DC_GO_TB(DTV, KTV, GB, TV, false)
+#define RA_DC_GO_TB(DTV, KTV, GB, TV, BU)                                                          \
     do {                                                                                           \
-        RA_LDS_OPT_IN((decode_kernel<DTV, KTV, GB, TV>), lds);                                     \
-        hipLaunchKernelGGL((decode_kernel<DTV, KTV, GB, TV>), dim3(heads + n_helpers), dim3(TV),   \
+        RA_LDS_OPT_IN((decode_kernel<DTV, KTV, GB, TV, BU>), lds);                                 \
+        hipLaunchKernelGGL((decode_kernel<DTV, KTV, GB, TV, BU>), dim3(heads + n_helpers), dim3(TV), \
                            lds, st, q, adj, entry, K, V, n_q, n_kv, Ng, N, kv_stride, wstart, deg, \
                            (int)s, topk, ef, expand, bitset, ids, stats, ids_off, scale, out, lse, \
                            coop, n_helpers, coop_mode, coop_spin, roots, root_cap, Ksearch,        \
@@ -471,7 +475,20 @@ ra_status ra_launch_decode(const void* q, const int32_t* adj, const int32_t* ent
         else if (threads == 512) RA_DC_GO_T(DTV, KTV, GB, 512);                                    \
         else RA_DC_GO_T(DTV, KTV, GB, 256);                                                        \
     } while (0)
-    if (dt == RA_BF16) {
+    if (budgets) {
+        // per-head budgets: the walk over the keys as stored, visited bitsets in LDS
+        if (kscale || gb)
+            RA_FAIL(RA_EUNSUP, "per-head budgets go with neither 8-bit keys nor visited bitsets in device "
+                               "memory (context too long for LDS at this ef and expand)");
+#define RA_DC_GO_B(DTV)                                                                            \
+    do {                                                                                           \
+        if (threads == 1024) RA_DC_GO_TB(DTV, DTV, false, 1024, true);                             \
+        else if (threads == 512) RA_DC_GO_TB(DTV, DTV, false, 512, true);                          \
+        else RA_DC_GO_TB(DTV, DTV, false, 256, true);                                              \
+    } while (0)
+        if (dt == RA_BF16) RA_DC_GO_B(RA_BF16); else RA_DC_GO_B(RA_F32);
+#undef RA_DC_GO_B
+    } else if (dt == RA_BF16) {
         if (kscale) { if (gb) RA_DC_GO(RA_BF16, RA_KEYS_I8, true); else RA_DC_GO(RA_BF16, RA_KEYS_I8, false); }
         else if (gb) RA_DC_GO(RA_BF16, RA_BF16, true); else RA_DC_GO(RA_BF16, RA_BF16, false);
     } else {
@@ -479,6 +496,7 @@ ra_status ra_launch_decode(const void* q, const int32_t* adj, const int32_t* ent
         else if (gb) RA_DC_GO(RA_F32, RA_F32, true); else RA_DC_GO(RA_F32, RA_F32, false);
     }
 #undef RA_DC_GO_T
+#undef RA_DC_GO_TB
 #undef RA_DC_GO
     RA_HIP(hipGetLastError());
     return RA_OK;
