@@ -68,7 +68,9 @@ typedef struct {
  * largest inner product over ALL N keys of its KV head (non-causal, unscaled), ordered
  * best first; ties go to the lower id.  L_out: device int32 [n_seq][n_q_heads][M][knn].
  * Allocates scratch memory (8 bytes per key and query head, rounded up to a power of two of
- * keys) and synchronises `stream` before returning to free it. */
+ * keys) and synchronises `stream` before returning to free it. bf16 lists of up to 32 keys
+ * have two implementations of the top-knn selection, chosen by N; RA_KNN_SELECTION=reg or =lds
+ * in the environment forces one (same lists either way; for tests and tuning). */
 ra_status ra_knn(const void* K, const void* Q_prefill, ra_dtype dt,
                  int n_seq, int n_q_heads, int n_kv_heads, int64_t N, int64_t M, int d,
                  int knn, void* stream, int32_t* L_out);
