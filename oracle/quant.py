@@ -9,8 +9,8 @@ and per dimension d, symmetric and linear,
 
 in float32 arithmetic (each division rounded once), so that a device kernel can produce
 the same bytes. Only the graph search reads the quantised keys: it scores
-<q * scale, k8> with the products and sums of search.score32, i.e. the walk is
-search.greedy_search run on (scaled_query(q, scale), k8 as float32). Attention (Eq. 1-2)
+<q * scale, k8>, i.e. the walk is search.greedy_search run on
+(scaled_query(q, scale), k8 as float32). Attention (Eq. 1-2)
 always uses the original keys and values.
 """
 import numpy as np
@@ -33,7 +33,3 @@ def quantize_keys(K):
 def scaled_query(q, scale):
     """q * scale in float32: what the search multiplies the 8-bit keys with."""
     return (np.asarray(q, F32) * np.asarray(scale, F32)).astype(F32)
-
-
-def dequantize(k8, scale):
-    return (k8.astype(F32) * np.asarray(scale, F32)[None, :]).astype(F32)

@@ -18,12 +18,21 @@ With expand = 1 this is the textbook loop; a larger width trades a few extra
 expansions for fewer dependent steps. The beam content after a step does not depend
 on the order candidates are inserted in (top-ef of a union), so it is well defined.
 
-Scores that decide ids are float32 and are summed in one fixed order so that the
-decision is taken in the same precision and order as the device kernel: the d
-products are split into 16 contiguous chunks, each chunk is summed left to right
-(product rounded to float32, then added), and the 16 chunk sums are added pairwise
-in a balanced tree over adjacent chunks. `score32` is pinned against the float64
-inner product in the tests.
+Scores are the plain inner product of Sec. 2.4 in float64 (`scores_f64`) unless the
+caller passes another `score_fn`. A device kernel scores in float32, so where two float64
+scores nearly coincide it may order them the other way; to let a test tell such a case from
+a real difference, the walk reports `min_gap`: the smallest relative gap
+|a - b| / max(|a|, |b|) between two scores whose order decided something (which entries a
+step expands, which entries fall off the beam, the order and the cut of the result). A walk
+whose min_gap is above a kernel's score error takes the same decisions in that kernel.
+Bit-identical key rows score identically in any arithmetic, so a gap of exactly zero between
+two such rows is decided by the ids and is not counted.
+
+`score32` is an opt-in `score_fn`: the same inner product in float32, summed in one fixed
+order (16 contiguous chunks summed left to right, product rounded then added, the 16 chunk
+sums added pairwise in a balanced tree over adjacent chunks). With it the walk's decisions
+are taken in float32 and can be compared bit for bit with a float32 implementation that
+adds in that order. It is pinned against the float64 inner product in the tests.
 """
 import numpy as np
 
@@ -55,22 +64,45 @@ def _sort_beam(beam):
     beam.sort(key=lambda e: (-e[0], e[1]))
 
 
-def greedy_search(q, K, adj, entry, ef, topk, expand=1, exclude=None):
+def scores_f64(q, Krows):
+    """<q, k> for each row of Krows, float64: the plain definition (Sec. 2.4)."""
+    return np.asarray(Krows, np.float64) @ np.asarray(q, np.float64)
+
+
+def _rel_gap(a, b):
+    m = max(abs(a), abs(b))
+    return abs(a - b) / m if m > 0 else 0.0
+
+
+def greedy_search(q, K, adj, entry, ef, topk, expand=1, exclude=None, score_fn=None):
     """Returns (ids int32 [topk] padded with -1, stats dict) with stats =
-    {n_visited, n_expanded, n_iters, n_returned, beam: [(score, id)] best-first}."""
+    {n_visited, n_expanded, n_iters, n_returned, beam: [(score, id)] best-first, min_gap}.
+    score_fn(q, rows) -> scores; default float64 inner products."""
     if ef < topk or ef < 1 or topk < 1 or expand < 1:
         raise ValueError("need ef >= topk >= 1 and expand >= 1")
+    score_fn = scores_f64 if score_fn is None else score_fn
     K = np.asarray(K)
     adj = np.asarray(adj)
     excl = set(int(i) for i in exclude) if exclude is not None else set()
+    gaps = [np.inf]
+
+    def decided(x, y):
+        # the order of beam entries x, y decided something: note how close their scores are
+        if x[0] == y[0] and np.array_equal(K[x[1]], K[y[1]]):
+            return
+        gaps.append(_rel_gap(x[0], y[0]))
+
     visited = {int(entry)}
-    s0 = float(score32(q, K[[entry]])[0])
+    s0 = float(score_fn(q, K[[entry]])[0])
     beam = [[s0, int(entry), False]]
     n_expanded = n_iters = 0
     while True:
-        pick = [e for e in beam if not e[2]][:expand]      # beam is kept best-first
+        unexpanded = [e for e in beam if not e[2]]         # beam is kept best-first
+        pick = unexpanded[:expand]
         if not pick:
             break
+        if len(unexpanded) > expand:
+            decided(unexpanded[expand - 1], unexpanded[expand])
         n_iters += 1
         new = []
         for e in pick:
@@ -82,12 +114,17 @@ def greedy_search(q, K, adj, entry, ef, topk, expand=1, exclude=None):
                     visited.add(n)
                     new.append(n)
         if new:
-            sc = score32(q, K[new])
+            sc = score_fn(q, K[new])
             beam.extend([float(s), n, False] for s, n in zip(sc, new))
         _sort_beam(beam)
+        if len(beam) > ef:
+            decided(beam[ef - 1], beam[ef])
         del beam[ef:]
-    res = [e[1] for e in beam if e[1] not in excl][:topk]
+    eligible = [e for e in beam if e[1] not in excl]
+    for x, y in zip(eligible[:topk], eligible[1:topk + 1]):
+        decided(x, y)
+    res = [e[1] for e in eligible][:topk]
     ids = np.full(topk, -1, np.int32)
     ids[:len(res)] = res
     return ids, dict(n_visited=len(visited), n_expanded=n_expanded, n_iters=n_iters,
-                     n_returned=len(res), beam=[(e[0], e[1]) for e in beam])
+                     n_returned=len(res), beam=[(e[0], e[1]) for e in beam], min_gap=float(min(gaps)))

@@ -10,7 +10,7 @@ import torch
 import paper_2409_10516_amd as ra
 from oracle import attention as OA, decode as OD, mips as OM, projection as OP
 from paper_2409_10516_amd import synth
-from tests.util import knn_equivalent, lse_close, out_close, to_np, tol_for
+from tests.util import decode_matches, integer_valued, knn_equivalent, lse_close, out_close, to_np, tol_for
 
 pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
@@ -231,16 +231,15 @@ def test_build_index_then_decode(name):
     tol = tol_for(w.K.dtype)
     q = w.q_decode[0]
     out, lse, ids, st = ra.ra_decode_step(q.to(DEV), idx, Kd, Vd, w.sink, w.window, w.topk, w.ef, 4)
-    out, lse, ids = out.cpu().numpy(), lse.cpu().numpy(), ids.cpu().numpy()
+    out, lse, ids, st = out.cpu().numpy(), lse.cpu().numpy(), ids.cpu().numpy(), st.cpu().numpy()
+    exact = integer_valued(to_np(w.K), to_np(w.q_decode))
     for s, h, g, K, Q in _heads(w):
         radj, rent = OP.project(L[s, h], N, w.deg)
         adj, ent = ra.ra_index_export(idx, s, h)
         assert ent == rent and np.array_equal(adj.numpy(), radj)
         V = to_np(w.V[s, h // (n_q // n_kv)])
-        r_out, r_lse, r_ids, _ = OD.decode_step(to_np(q[s, h]), K, V, radj, rent, w.sink, w.window,
-                                                w.topk, w.ef, 4)
-        assert ids[s, h].tolist() == r_ids.tolist()
-        assert out_close(out[s, h], r_out, tol) and lse_close(lse[s, h], r_lse, tol)
+        decode_matches(out[s, h], lse[s, h], ids[s, h], st[s, h].tolist(), to_np(q[s, h]), K, V, radj, rent,
+                       w.sink, w.window, w.topk, w.ef, 4, tol, exact=exact)
     idx.free()
 
 

@@ -8,13 +8,13 @@ import torch
 import paper_2409_10516_amd as ra
 from oracle import attention as OA, decode as OD, mips as OM, projection as OP, search as OS
 from paper_2409_10516_amd import synth
-from tests.util import knn_equivalent, lse_close, out_close, to_np, tol_for
+from tests.util import decode_matches, knn_equivalent, lse_close, out_close, to_np, tol_for
 
 pytestmark = pytest.mark.gpu
 DEV = "cuda:0"
 
 
-def _check_sampled(w, samples, expand, knn_rows=24, adj_rows=40, seed=0, also_expand=()):
+def _check_sampled(w, samples, expand, knn_rows=24, adj_rows=40, seed=0, also_expand=(), all_queries=False):
     """samples: list of (seq, q_head). Checks, for each: sampled KNN rows against the exact
     float64 lists; sampled adjacency rows (hubs, mid-popularity and cold keys) against the
     oracle's projection of the device's own lists; ids, counters and attention of a decode
@@ -59,32 +59,30 @@ def _check_sampled(w, samples, expand, knn_rows=24, adj_rows=40, seed=0, also_ex
         # structural checks on the whole graph
         assert adj.min() >= -1 and adj.max() < N
         assert not (adj == np.arange(N)[:, None]).any()
-        # search + attention on the exported graph
-        r_out, r_lse, r_ids, rst = OD.decode_step(to_np(q[s, h]), K, V, adj, ent, w.sink, w.window,
-                                                  w.topk, w.ef, expand)
-        assert ids[s, h].tolist() == r_ids.tolist()
-        assert st[s, h].tolist() == [rst["n_visited"], rst["n_expanded"], rst["n_iters"],
-                                     rst["n_returned"]]
-        assert out_close(out[s, h], r_out, tol) and lse_close(lse[s, h], r_lse, tol)
-        truth = OM.topk_bruteforce(to_np(q[s, h]), K, w.topk, exclude=W)
-        recalls.append(OM.recall(ids[s, h], truth))
+        # search + attention on the exported graph (every decode query when all_queries is set)
+        for t in (range(w.q_decode.shape[0]) if all_queries else [0]):
+            if t:
+                o_t, l_t, i_t, s_t = [x.cpu().numpy() for x in ra.ra_decode_step(
+                    w.q_decode[t], idx, w.K, w.V, w.sink, w.window, w.topk, w.ef, expand)]
+            else:
+                o_t, l_t, i_t, s_t = out, lse, ids, st
+            decode_matches(o_t[s, h], l_t[s, h], i_t[s, h], s_t[s, h].tolist(), to_np(w.q_decode[t, s, h]), K, V,
+                           adj, ent, w.sink, w.window, w.topk, w.ef, expand, tol)
+            truth = OM.topk_bruteforce(to_np(w.q_decode[t, s, h]), K, w.topk, exclude=W)
+            recalls.append(OM.recall(i_t[s, h], truth))
         # the same step at other expansion widths (another placement of the visited bitset, say)
         for e2 in (also_expand if (s, h) == tuple(samples[0]) else ()):
             o2, l2, i2, s2 = [x.cpu().numpy() for x in ra.ra_decode_step(
                 q, idx, w.K, w.V, w.sink, w.window, w.topk, w.ef, e2)]
-            r_out, r_lse, r_ids, rst = OD.decode_step(to_np(q[s, h]), K, V, adj, ent, w.sink, w.window,
-                                                      w.topk, w.ef, e2)
-            assert i2[s, h].tolist() == r_ids.tolist(), e2
-            assert s2[s, h].tolist() == [rst["n_visited"], rst["n_expanded"], rst["n_iters"],
-                                         rst["n_returned"]], e2
-            assert out_close(o2[s, h], r_out, tol) and lse_close(l2[s, h], r_lse, tol), e2
+            decode_matches(o2[s, h], l2[s, h], i2[s, h], s2[s, h].tolist(), to_np(q[s, h]), K, V, adj, ent,
+                           w.sink, w.window, w.topk, w.ef, e2, tol)
     idx.free()
     return float(np.mean(recalls))
 
 
 def test_config2_layer_128k():
     w = synth.make_config2_layer(0, device=DEV, T=1)
-    r = _check_sampled(w, [(0, 0), (0, 13), (0, 31)], expand=32)
+    r = _check_sampled(w, [(0, 0), (0, 13), (0, 31)], expand=32, also_expand=(64,))
     assert r >= 0.95, r          # the task's recall target at 128K context
 
 
@@ -105,10 +103,61 @@ def test_config4_stress_1m_global_bitset():
     arrays and lives in device memory; at expand 16 it does. Degree 48, knn 48, topk 200, ef 512."""
     w = synth.make_config4(device=DEV, T=1)
     r = _check_sampled(w, [(0, 0), (0, 3)], expand=32, knn_rows=6, adj_rows=16, also_expand=(16,))
-    assert r > 0.0
+    # two thirds of the 2^20 keys are in no list of the 65536 prefill queries and hang off the heap
+    # backbone alone; the walk (the oracle's too) finds under half of the exact top-200 on this input
+    assert r > 0.3, r
 
 
 def test_config0_full():
     w = synth.make_config0(device=DEV)
-    r = _check_sampled(w, [(0, 0)], expand=4, knn_rows=64, adj_rows=64)
+    r = _check_sampled(w, [(0, 0)], expand=4, knn_rows=64, adj_rows=64, all_queries=True)
     assert r > 0.3
+
+
+def test_config2_hip_graph_replay_at_the_bench_launch_configuration():
+    """What bench.py times: one 128K layer at expand 64, captured into a HIP graph and replayed.
+    Replays (with eager work and synchronisations between them) must reproduce the eager step bit
+    for bit, and sampled heads must match the oracle."""
+    w = synth.make_config2_layer(1, device=DEV, T=3)
+    idx = ra.ra_build_index(w.K, w.Q_prefill, w.deg, w.knn)
+    n_q = w.Q_prefill.shape[1]
+    w.Q_prefill = None
+    f32 = dict(dtype=torch.float32, device=DEV)
+    bufs = lambda: (torch.empty((1, n_q, 128), **f32), torch.empty((1, n_q), **f32),
+                    torch.empty((1, n_q, w.topk), dtype=torch.int32, device=DEV),
+                    torch.zeros((1, n_q, 4), dtype=torch.int32, device=DEV))
+    eager = []
+    for t in range(3):
+        o, l, i, s = bufs()
+        ra.ra_decode_step(w.q_decode[t], idx, w.K, w.V, w.sink, w.window, w.topk, w.ef, 64,
+                          out=o, lse=l, ids=i, stats=s)
+        eager.append((o, l, i, s))
+    torch.cuda.synchronize()
+    go, gl, gi, gs = bufs()
+    qbuf = w.q_decode[0].clone()
+    cs = torch.cuda.Stream()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(cs):
+        with torch.cuda.graph(g, stream=cs):
+            ra.ra_decode_step(qbuf, idx, w.K, w.V, w.sink, w.window, w.topk, w.ef, 64,
+                              out=go, lse=gl, ids=gi, stats=gs)
+    torch.cuda.synchronize()
+    for rep in range(2):
+        for t in (0, 1, 2, 1):
+            qbuf.copy_(w.q_decode[t])
+            g.replay()
+            torch.cuda.synchronize()
+            o, l, i, s = eager[t]
+            assert torch.equal(gi, i) and torch.equal(gs, s), (rep, t)
+            assert out_close(go.cpu().numpy(), o.cpu().numpy(), 1e-6), (rep, t)
+            assert torch.allclose(gl, l, rtol=1e-6, atol=1e-6), (rep, t)
+            (go.sum() + gl.sum()).item()           # eager work between replays
+    assert idx.helpers_active                      # no bounded wait ran out
+    tol = tol_for(w.K.dtype)
+    for h in (3, 18):
+        adj, ent = ra.ra_index_export(idx, 0, h)
+        K, V = to_np(w.K[0, h // 4]), to_np(w.V[0, h // 4])
+        o, l, i, s = [x.cpu().numpy() for x in eager[2]]
+        decode_matches(o[0, h], l[0, h], i[0, h], s[0, h].tolist(), to_np(w.q_decode[2, 0, h]), K, V,
+                       adj.numpy(), ent, w.sink, w.window, w.topk, w.ef, 64, tol)
+    idx.free()

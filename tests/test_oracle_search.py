@@ -1,5 +1,6 @@
 """Pins for oracle/search.py and oracle/decode.py: hand traces, the exhaustive-beam
-invariant, structural checks, and the float32 score against float64. No GPU."""
+invariant, structural checks, the decision-gap report, and the opt-in float32 score against
+float64. No GPU."""
 import json
 import os
 
@@ -95,7 +96,7 @@ def test_structural_invariants(expand):
         keys = [(-s, i) for s, i in beam]
         assert keys == sorted(keys)
         for s, i in beam:
-            assert np.float32(s) == S.score32(q, K[[i]])[0]
+            assert abs(s - float(K[i].astype(np.float64) @ q.astype(np.float64))) <= 1e-12 * abs(s)
         valid = ids[ids >= 0]
         assert not set(valid.tolist()) & set(W.tolist())
         assert valid.tolist() == [i for _, i in beam if i not in set(W.tolist())][:10]
@@ -150,3 +151,42 @@ def test_config0_planted_duplicates_tie_break_and_recall_band():
         assert found == sorted(found)
         rec.append(mips.recall(ids, truth))
     assert 0.3 < np.mean(rec) <= 1.0
+
+
+def test_default_scores_are_float64_and_the_float32_order_is_opt_in():
+    """On integer-valued inputs every arithmetic is exact, so the two score functions give the
+    same walk; on real-valued inputs the default beam carries float64 inner products and the
+    opt-in one float32 values."""
+    w, K, V, adj, entry = _graph(2)
+    q = w.q_decode[0, 0, 0].numpy()
+    a = S.greedy_search(q, K, adj, entry, ef=12, topk=5, expand=2)
+    b = S.greedy_search(q, K, adj, entry, ef=12, topk=5, expand=2, score_fn=S.score32)
+    assert a[0].tolist() == b[0].tolist() and a[1]["beam"] == b[1]["beam"]
+    w2 = synth.make_config0(N=256, M=64, T=1, window=8)
+    K2 = w2.K[0, 0].numpy(); q2 = w2.q_decode[0, 0, 0].numpy()
+    adj2, e2, _ = D.build_index(K2, w2.Q_prefill[0, 0].numpy(), 8, 8)
+    _, st64 = S.greedy_search(q2, K2, adj2, e2, ef=16, topk=4)
+    _, st32 = S.greedy_search(q2, K2, adj2, e2, ef=16, topk=4, score_fn=S.score32)
+    ref = K2.astype(np.float64) @ q2.astype(np.float64)
+    assert all(abs(s - ref[i]) <= 1e-12 * abs(s) for s, i in st64["beam"])
+    assert all(np.float32(s) == s for s, i in st32["beam"])
+    assert any(abs(s - ref[i]) > 1e-9 * abs(s) for s, i in st32["beam"])
+
+
+def test_min_gap_reports_the_closest_decision():
+    """A path graph 0-1-2-3-4-5 walked from node 0 with scores chosen by hand. The decisions:
+    ef = 2 drops the worse of three entries after each step, the result orders its two ids."""
+    adj = np.array([[1, -1], [0, 2], [1, 3], [2, 4], [3, 5], [4, -1]])
+    q = np.zeros(16); q[0] = 1.0
+    K = np.zeros((6, 16)); K[:, 0] = [1.0, 2.0, 4.0, 4.0 + 4e-6, 3.0, 0.5]
+    ids, st = S.greedy_search(q, K, adj, 0, ef=2, topk=2)
+    assert ids.tolist() == [3, 2]
+    assert abs(st["min_gap"] - 4e-6 / (4.0 + 4e-6)) < 1e-12        # the order of 3 and 2 in the result
+    K[3, 0] = 8.0
+    ids, st = S.greedy_search(q, K, adj, 0, ef=2, topk=2)
+    # closest decision now: beam {3: 8, 2: 4} against the newcomer 4 (score 3) at the cut: |4 - 3| / 4
+    assert ids.tolist() == [3, 2] and abs(st["min_gap"] - 0.25) < 1e-12
+    # bit-identical rows tie exactly in any arithmetic: decided by id, not reported as a gap
+    K[:, 0] = [1.0, 2.0, 4.0, 4.0, 0.25, 0.125]
+    ids, st = S.greedy_search(q, K, adj, 0, ef=3, topk=2)
+    assert ids.tolist() == [2, 3] and st["min_gap"] > 0.4
