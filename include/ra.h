@@ -21,7 +21,9 @@
  *         ids         [n_seq][n_q_heads][topk] int32, best first, padded with -1
  * Query head h reads KV head h / (n_q_heads / n_kv_heads): one index per query head,
  * one KV copy per group (Appendix C, "Implementation").
- * Supported: d = 128; dtype float32 or bfloat16 (q, K, V, Q_prefill share the dtype).
+ * Supported: d = 128; dtype float32 or bfloat16 (q, K, V, Q_prefill share the dtype); any number
+ * of query heads per KV head (groups of 1, 2, 4 and 8 share each key row among the group's heads
+ * in the attention and scan kernels; other group sizes read it once per query head).
  */
 #ifndef RA_H
 #define RA_H
@@ -68,9 +70,7 @@ typedef struct {
  * largest inner product over ALL N keys of its KV head (non-causal, unscaled), ordered
  * best first; ties go to the lower id.  L_out: device int32 [n_seq][n_q_heads][M][knn].
  * Allocates scratch memory (8 bytes per key and query head, rounded up to a power of two of
- * keys) and synchronises `stream` before returning to free it. bf16 lists of up to 32 keys
- * have two implementations of the top-knn selection, chosen by N; RA_KNN_SELECTION=reg or =lds
- * in the environment forces one (same lists either way; for tests and tuning). */
+ * keys) and synchronises `stream` before returning to free it. */
 ra_status ra_knn(const void* K, const void* Q_prefill, ra_dtype dt,
                  int n_seq, int n_q_heads, int n_kv_heads, int64_t N, int64_t M, int d,
                  int knn, void* stream, int32_t* L_out);
@@ -222,21 +222,44 @@ int64_t ra_index_info(const ra_index* idx, int what);
  * a head that does not get it within RA_CFG_HELPER_SPIN polls computes o_W itself, and the
  * handle stops using helpers until RA_CFG_HELPERS is set again. Results do not depend on the
  * setting beyond the summation order of Eq. 2/4 (same tolerance).
- *   RA_CFG_HELPERS      RA_HELPERS_ON (default), RA_HELPERS_OFF (each head attends to W itself),
- *                       RA_HELPERS_SILENT (for tests of the bounded wait: helper workgroups are
- *                       launched but do nothing). Setting it also clears a wait that ran out.
+ *   RA_CFG_HELPERS      RA_HELPERS_ON (default), RA_HELPERS_OFF (each head attends to W itself).
+ *                       Setting it also clears a wait that ran out.
  *   RA_CFG_HELPER_SPIN  polls before a head gives up, 1 .. 2^24 (default RA_HELPER_SPIN_DEFAULT,
  *                       tens of milliseconds).
- * Helpers are used only for GQA groups of 1, 2, 4 or 8 query heads per KV head.
+ * Helpers are used only for GQA groups of 1, 2, 4 or 8 query heads per KV head; with any other
+ * group size every head attends to W itself.
+ * The hand-over is ordered without fences: the words that cross workgroups are relaxed
+ * agent-scope atomic accesses (on gfx950 these bypass the per-XCD L2), the helper waits for its
+ * record stores to complete (s_waitcnt vmcnt(0), workgroup barrier) before it stores the ready
+ * word, and the head reads the record only after it has seen the ready word. That ordering is a
+ * property of this part's memory system, not of the HIP memory model; the bounded wait and the
+ * fall-back keep a launch correct if a ready word never arrives.
  * Two ra_decode_step calls on one handle must not overlap in time (they share this memory,
  * like the handle's other workspaces). Returns RA_EINVAL for an unknown setting or value. */
 #define RA_CFG_HELPERS 0
 #define RA_CFG_HELPER_SPIN 1
 #define RA_HELPERS_OFF 0
 #define RA_HELPERS_ON 1
-#define RA_HELPERS_SILENT 2
 #define RA_HELPER_SPIN_DEFAULT 20000
 ra_status ra_index_configure(ra_index* idx, int what, int64_t value);
+
+/* ---- TEST-ONLY settings -------------------------------------------------------------
+ * Not for callers of the library: they exist so that the test-suite can reach code paths that
+ * inputs alone cannot select. Results never depend on them beyond what is stated.
+ *   RA_TEST_KNN_SELECTION   (idx = NULL; process-wide) which of the two top-knn selections
+ *                           ra_knn uses for bf16 lists of up to 32 keys: RA_TEST_KNN_AUTO
+ *                           (default: chosen by N), RA_TEST_KNN_REG, RA_TEST_KNN_LDS. Same lists
+ *                           either way.
+ *   RA_TEST_HELPERS_SILENT  (per handle) 1: the helper workgroups of ra_decode_step are launched
+ *                           but write nothing, so every head's bounded wait runs out and the
+ *                           fall-back is taken; 0: normal. Synchronises the device and clears the
+ *                           hand-over area like RA_CFG_HELPERS. */
+#define RA_TEST_KNN_SELECTION 100
+#define RA_TEST_HELPERS_SILENT 101
+#define RA_TEST_KNN_AUTO 0
+#define RA_TEST_KNN_REG 1
+#define RA_TEST_KNN_LDS 2
+ra_status ra_test_configure(ra_index* idx, int what, int64_t value);
 
 /* Device pointers to the handle's graphs (adj [n_graphs][N][deg], entry [n_graphs]). */
 const int32_t* ra_index_adj(const ra_index* idx);

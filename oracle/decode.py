@@ -13,16 +13,20 @@ def build_index(K, Q_prefill, deg, knn):
     return adj, entry, L
 
 
-def decode_step(q, K, V, adj, entry, sink, window, topk, ef, expand=1, n_index=None, score_fn=None):
+def decode_step(q, K, V, adj, entry, sink, window, topk, ef, expand=1, n_index=None, score_fn=None,
+                n_seeds=0):
     """Algorithm 1 with PredictActiveTokens fixed to sink + window (Sec. 3.3):
     Omega = VectorSearch(q) minus the static set; o_Omega by Eq. 2 over Omega;
     o_W by Eq. 2 over W; combined by Eq. 4-5.
     Returns (out[d], lse, ids[topk], stats). `n_index` (default: all N keys) is the
     number of keys the graph was built over; later tokens are part of W. `score_fn` is
-    passed to the walk (default: float64 inner products)."""
+    passed to the walk (default: float64 inner products). n_seeds > 0 starts the walk from
+    search.backbone_seeds(adj, entry, n_seeds) instead of the entry point alone."""
     N = np.asarray(K).shape[0]
     W = attention.static_ids(N, sink, window, n_index)
-    ids, stats = search.greedy_search(q, K, adj, entry, ef, topk, expand, exclude=W, score_fn=score_fn)
+    seeds = search.backbone_seeds(adj, entry, n_seeds) if n_seeds else None
+    ids, stats = search.greedy_search(q, K, adj, entry, ef, topk, expand, exclude=W, score_fn=score_fn,
+                                      seeds=seeds)
     omega = ids[ids >= 0]
     o_o, l_o = attention.partial_attention(q, K, V, omega)
     o_w, l_w = attention.partial_attention(q, K, V, W)

@@ -7,12 +7,22 @@ this build's determinism choices:
 
   state   visited set; beam of at most `ef` (score, id, expanded?) entries kept under
           the total order of mips.py (score descending, id ascending).
-  start   visited = {entry}; beam = {entry}.
+  start   visited = {entry}; beam = {entry}. With a seed set (below) instead:
+          visited = the seeds, beam = the best `ef` of them, none expanded.
   step    take the `expand` best not-yet-expanded beam entries (all of them if fewer);
           stop if there are none. Mark them expanded. Gather their adjacency rows; the
           new candidates are the distinct valid neighbours not yet visited. Mark them
           visited, score them, add them to the beam, and keep the best `ef`.
   result  walk the final beam best-first, skip ids in the static set, take `topk`.
+
+Seed set. The paper does not say where a walk starts. A single entry point makes the
+first hops of every walk the same climb from the graph's root towards the query; the walk
+may instead start from the `n_seeds` keys nearest the root, all scored at once:
+`backbone_seeds` lists them from the graph alone, breadth first over the binary tree that
+the first two slots of every adjacency row span from the entry point. For a graph made by
+projection.py those slots hold the popularity heap, so the seeds are the n_seeds keys that
+appear in the most KNN lists of the prefill queries, in that order, the entry point first.
+seeds = [entry] is the single-entry start.
 
 With expand = 1 this is the textbook loop; a larger width trades a few extra
 expansions for fewer dependent steps. The beam content after a step does not depend
@@ -74,10 +84,36 @@ def _rel_gap(a, b):
     return abs(a - b) / m if m > 0 else 0.0
 
 
-def greedy_search(q, K, adj, entry, ef, topk, expand=1, exclude=None, score_fn=None):
+def backbone_seeds(adj, entry, n_seeds):
+    """The first `n_seeds` positions, breadth first, of the binary tree spanned from `entry`
+    by slots 0 and 1 of every adjacency row (position p has its children at positions 2p + 1
+    and 2p + 2). Positions without a node (a -1 slot, or below one) and nodes already listed
+    are left out; the order of first occurrence is kept. Returns int64 ids, entry first."""
+    adj = np.asarray(adj)
+    if n_seeds < 1:
+        raise ValueError("n_seeds must be positive")
+    pos = [-1] * n_seeds
+    pos[0] = int(entry)
+    for p in range(n_seeds):
+        if pos[p] < 0:
+            continue
+        for slot in (0, 1):
+            c = 2 * p + 1 + slot
+            if c < n_seeds and slot < adj.shape[1]:
+                pos[c] = int(adj[pos[p], slot])
+    seen, out = set(), []
+    for i in pos:
+        if i >= 0 and i not in seen:
+            seen.add(i)
+            out.append(i)
+    return np.array(out, np.int64)
+
+
+def greedy_search(q, K, adj, entry, ef, topk, expand=1, exclude=None, score_fn=None, seeds=None):
     """Returns (ids int32 [topk] padded with -1, stats dict) with stats =
     {n_visited, n_expanded, n_iters, n_returned, beam: [(score, id)] best-first, min_gap}.
-    score_fn(q, rows) -> scores; default float64 inner products."""
+    score_fn(q, rows) -> scores; default float64 inner products. seeds: distinct ids the walk
+    starts from (default: the entry point alone)."""
     if ef < topk or ef < 1 or topk < 1 or expand < 1:
         raise ValueError("need ef >= topk >= 1 and expand >= 1")
     score_fn = scores_f64 if score_fn is None else score_fn
@@ -92,9 +128,15 @@ def greedy_search(q, K, adj, entry, ef, topk, expand=1, exclude=None, score_fn=N
             return
         gaps.append(_rel_gap(x[0], y[0]))
 
-    visited = {int(entry)}
-    s0 = float(score_fn(q, K[[entry]])[0])
-    beam = [[s0, int(entry), False]]
+    start = [int(entry)] if seeds is None else [int(i) for i in seeds]
+    if not start or len(set(start)) != len(start):
+        raise ValueError("seeds must be distinct and not empty")
+    visited = set(start)
+    beam = [[float(s), i, False] for s, i in zip(score_fn(q, K[start]), start)]
+    _sort_beam(beam)
+    if len(beam) > ef:
+        decided(beam[ef - 1], beam[ef])
+    del beam[ef:]
     n_expanded = n_iters = 0
     while True:
         unexpanded = [e for e in beam if not e[2]]         # beam is kept best-first

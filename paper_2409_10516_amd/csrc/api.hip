@@ -31,9 +31,6 @@ static ra_status check_heads(int n_seq, int n_q, int n_kv) {
         RA_FAIL(RA_EINVAL, "n_seq, n_q_heads, n_kv_heads must be positive (%d, %d, %d)", n_seq, n_q,
                 n_kv);
     if (n_q % n_kv) RA_FAIL(RA_EINVAL, "n_q_heads %d is not a multiple of n_kv_heads %d", n_q, n_kv);
-    const int G = n_q / n_kv;
-    if (G != 1 && G != 2 && G != 4 && G != 8)
-        RA_FAIL(RA_EUNSUP, "query heads per KV head must be 1, 2, 4 or 8 (got %d)", G);
     return RA_OK;
 }
 
@@ -143,12 +140,13 @@ extern "C" ra_status ra_index_configure(ra_index* ix, int what, int64_t value) {
     if (!ix) RA_FAIL(RA_EINVAL, "index handle is NULL");
     switch (what) {
         case RA_CFG_HELPERS: {
-            if (value != RA_HELPERS_OFF && value != RA_HELPERS_ON && value != RA_HELPERS_SILENT)
+            if (value != RA_HELPERS_OFF && value != RA_HELPERS_ON)
                 RA_FAIL(RA_EINVAL, "helpers mode %lld", (long long)value);
             // also forgets a wait that ran out: ready words and the off word start from zero
             RA_HIP(hipDeviceSynchronize());
             RA_HIP(hipMemset(ix->coop, 0, coop_bytes(ix)));
             ix->coop_mode = (int)value;
+            ix->coop_silent = 0;
             return RA_OK;
         }
         case RA_CFG_HELPER_SPIN:
@@ -157,6 +155,25 @@ extern "C" ra_status ra_index_configure(ra_index* ix, int what, int64_t value) {
             return RA_OK;
         default:
             RA_FAIL(RA_EINVAL, "unknown setting %d", what);
+    }
+}
+
+extern "C" ra_status ra_test_configure(ra_index* ix, int what, int64_t value) {
+    switch (what) {
+        case RA_TEST_KNN_SELECTION:
+            if (value != RA_TEST_KNN_AUTO && value != RA_TEST_KNN_REG && value != RA_TEST_KNN_LDS)
+                RA_FAIL(RA_EINVAL, "knn selection %lld", (long long)value);
+            ra_knn_set_selection_override((int)value);
+            return RA_OK;
+        case RA_TEST_HELPERS_SILENT:
+            if (!ix) RA_FAIL(RA_EINVAL, "index handle is NULL");
+            if (value != 0 && value != 1) RA_FAIL(RA_EINVAL, "silent helpers %lld", (long long)value);
+            RA_HIP(hipDeviceSynchronize());
+            RA_HIP(hipMemset(ix->coop, 0, coop_bytes(ix)));
+            ix->coop_silent = (int)value;
+            return RA_OK;
+        default:
+            RA_FAIL(RA_EINVAL, "unknown test setting %d", what);
     }
 }
 
@@ -172,7 +189,7 @@ extern "C" int64_t ra_index_info(const ra_index* ix, int what) {
                                  ix->partials_bytes + ix->ids_bytes + ix->bitset_bytes + coop_bytes(ix) +
                                  (size_t)ix->n_seq * ix->n_q * ix->root_cap * sizeof(int32_t));
         case 6: {
-            if (ix->coop_mode != RA_HELPERS_ON) return 0;
+            if (ix->coop_mode != RA_HELPERS_ON || ix->coop_silent) return 0;
             const size_t heads = (size_t)ix->n_seq * ix->n_q;
             uint32_t off = 1u;
             if (hipDeviceSynchronize() != hipSuccess ||
@@ -400,7 +417,7 @@ static ra_status decode_common(const void* q, const ra_index* idx, const void* K
         RA_TRY(grow((void**)&ix->bitset, &ix->bitset_bytes, heads * ((ix->N + 31) >> 5) * 4));
     return ra_launch_decode(q, ix->adj, ix->entry, K, V, dt, ix->n_seq, ix->n_q, ix->n_kv, ix->N, N,
                             kv_stride, ix->deg, sink, window, topk, ef, expand, ix->bitset, ix->coop,
-                            ix->coop_mode, ix->coop_spin, ix->roots, ix->root_cap, K8, kscale, budgets,
+                            ix->coop_silent ? RA_HELPERS_SILENT_ : ix->coop_mode, ix->coop_spin, ix->roots, ix->root_cap, K8, kscale, budgets,
                             (hipStream_t)stream, out, lse, ids, stats);
 }
 

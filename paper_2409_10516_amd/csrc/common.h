@@ -114,6 +114,7 @@ ra_status ra_launch_flat_topk(const void* q, const void* K, ra_dtype dt, int n_s
 // stream has run the launch
 ra_status ra_launch_knn(const void* K, const void* Q, ra_dtype dt, int n_seq, int n_q, int n_kv,
                         int64_t N, int64_t M, int knn, void* workspace, hipStream_t st, int32_t* L);
+void ra_knn_set_selection_override(int v);      // RA_TEST_KNN_AUTO / _REG / _LDS
 size_t ra_knn_order_bytes(int n_graphs, int64_t N);
 int64_t ra_knn_order_stride(int64_t N);
 ra_status ra_launch_knn_order(const void* K, const void* Q, ra_dtype dt, int n_seq, int n_q, int n_kv,

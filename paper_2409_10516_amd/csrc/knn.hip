@@ -39,8 +39,6 @@
 // them with the 16-byte chunks of a row XOR-swizzled by the row number, and every wavefront
 // reads its operands from there with conflict-free 16-byte LDS reads. Two stage buffers
 // alternate; one barrier per stage.
-#include <stdlib.h>
-#include <string.h>
 
 #include "common.h"
 
@@ -552,6 +550,10 @@ static ra_status knn_launch_as(const void* K, const void* Q, const void* order, 
     return RA_OK;
 }
 
+// RA_TEST_KNN_SELECTION (ra_test_configure): which top-knn selection bf16 lists of up to 32 keys use
+static int g_knn_selection_override = RA_TEST_KNN_AUTO;
+void ra_knn_set_selection_override(int v) { g_knn_selection_override = v; }
+
 // bf16: 8 wavefronts per workgroup (one workgroup per compute unit, two wavefronts per SIMD). Lists of
 // up to 32 keys: two sets of 32 queries per wavefront, 512 queries x 32 slots x 8 bytes of lists
 // beside the stage buffers, pending keys in registers. Up to 48 keys: one set per wavefront, 256
@@ -565,13 +567,11 @@ ra_status ra_launch_knn(const void* K, const void* Q, ra_dtype dt, int n_seq, in
     // Pending keys in registers: a fold takes 8 keys at most instead of 32, so the start of the stream,
     // where nearly every key reaches the thresholds, costs more (about 14 ms instead of 6 ms for
     // 32 heads x 131072 queries), and every later key less (0.80 us instead of 0.95 us): it pays
-    // from about 50 K keys on. RA_KNN_SELECTION=reg|lds in the environment overrides the choice
-    // (the tests run both on small inputs).
+    // from about 50 K keys on. The test-only setting RA_TEST_KNN_SELECTION overrides the choice (the
+    // tests run both on small inputs).
     bool reg = knn <= KN_REG_KNN && N >= KN_REG_MIN_KEYS;
-    if (const char* e = getenv("RA_KNN_SELECTION")) {
-        if (!strcmp(e, "reg")) reg = knn <= KN_REG_KNN;
-        else if (!strcmp(e, "lds")) reg = false;
-    }
+    if (g_knn_selection_override == RA_TEST_KNN_REG) reg = knn <= KN_REG_KNN;
+    else if (g_knn_selection_override == RA_TEST_KNN_LDS) reg = false;
     if (dt == RA_BF16) {
         if (reg)
             return knn_launch_as<RA_BF16, 2, 8, KN_SEL_REG, 16384>(K, Q, workspace, n_seq, n_q, n_kv, N, M, knn, st, L);

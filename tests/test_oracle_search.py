@@ -190,3 +190,59 @@ def test_min_gap_reports_the_closest_decision():
     K[:, 0] = [1.0, 2.0, 4.0, 4.0, 0.25, 0.125]
     ids, st = S.greedy_search(q, K, adj, 0, ef=3, topk=2)
     assert ids.tolist() == [2, 3] and st["min_gap"] > 0.4
+
+
+def test_hand_traced_walks_from_a_seed_set():
+    g = json.load(open(os.path.join(GOLD, "search_hand.json")))
+    adj = np.array(g["adj"])
+    q = np.zeros(16); q[0] = 1.0
+    for case in g["seed_cases"]:
+        K = np.zeros((6, 16)); K[:, 0] = case["scores"]
+        ids, st = S.greedy_search(q, K, adj, case["seeds"][0], case["ef"], case["topk"], case["expand"],
+                                  seeds=case["seeds"])
+        assert ids.tolist() == case["ids"], case
+        for key in ("n_visited", "n_expanded", "n_iters"):
+            assert st[key] == case[key], (key, case)
+
+
+def test_backbone_seeds_are_the_most_popular_keys_of_a_projected_graph():
+    """For a graph made by projection.py the first two slots of a row are the key's children in the
+    heap over (popularity descending, id ascending), so the seeds must be that order's head,
+    recomputed here from the KNN lists alone."""
+    w = synth.make_config0(N=300, M=200, T=1, window=8)
+    K = w.K[0, 0].numpy()
+    adj, entry, L = D.build_index(K, w.Q_prefill[0, 0].numpy(), 8, 6)
+    pop = np.bincount(L.ravel(), minlength=300)
+    order = np.lexsort((np.arange(300), -pop))
+    for R in (1, 2, 3, 10, 64, 149, 300):
+        assert S.backbone_seeds(adj, entry, R).tolist() == order[:R].tolist(), R
+    # a hand-made tree with a missing child and a repeated node: positions 0..6 hold
+    # 4, 2, 5, -, 4(again), 1, 0
+    adj2 = np.array([[-1, -1], [-1, -1], [-1, 4], [-1, -1], [2, 5], [1, 0]])
+    assert S.backbone_seeds(adj2, 4, 7).tolist() == [4, 2, 5, 1, 0]
+    assert S.backbone_seeds(adj2, 4, 2).tolist() == [4, 2]
+    with pytest.raises(ValueError):
+        S.backbone_seeds(adj2, 4, 0)
+
+
+@pytest.mark.parametrize("seed", range(3))
+def test_seeded_walk_invariants(seed):
+    """seeds = [entry] is the single-entry walk; with ef >= N any seed set returns the exact
+    top-k (every key stays reachable); seeds are counted as visited, not as expanded."""
+    w, K, V, adj, entry = _graph(seed)
+    W = A.static_ids(64, 2, 4)
+    for q in w.q_decode[:, 0, 0].numpy():
+        a = S.greedy_search(q, K, adj, entry, ef=12, topk=5, expand=2, exclude=W)
+        b = S.greedy_search(q, K, adj, entry, ef=12, topk=5, expand=2, exclude=W, seeds=[entry])
+        assert a[0].tolist() == b[0].tolist() and a[1] == b[1]
+        sd = S.backbone_seeds(adj, entry, 9)
+        ids, st = S.greedy_search(q, K, adj, entry, ef=64, topk=7, expand=3, exclude=W, seeds=sd)
+        assert ids.tolist() == mips.topk_bruteforce(q, K, 7, exclude=W).tolist()
+        assert st["n_visited"] == 64
+        ids, st = S.greedy_search(q, K, adj, entry, ef=4, topk=2, expand=1, seeds=sd)
+        assert st["n_visited"] >= 9 and st["n_expanded"] == st["n_iters"] >= 1
+        out, lse, ids2, st2 = D.decode_step(q, K, V, adj, entry, 2, 4, topk=5, ef=12, expand=2, n_seeds=9)
+        ids3, _ = S.greedy_search(q, K, adj, entry, 12, 5, 2, exclude=W, seeds=sd)
+        assert ids2.tolist() == ids3.tolist()
+    with pytest.raises(ValueError):
+        S.greedy_search(q, K, adj, entry, ef=4, topk=2, seeds=[1, 1])
