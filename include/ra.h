@@ -61,7 +61,8 @@ typedef struct {
 #define RA_MAX_DEG 64
 #define RA_MAX_KNN 64
 #define RA_MAX_EF 2048
-#define RA_MAX_EXPAND 64
+#define RA_MAX_EXPAND 256
+#define RA_MAX_SEEDS 2048
 #define RA_MAX_TOPK 2048
 
 /* ---- index build (Sec. 3.2) -------------------------------------------------------- */
@@ -210,7 +211,8 @@ ra_status ra_decode_step_q8(const void* q, const ra_index* idx, const void* K, c
                             int32_t* ids, ra_stats* stats);
 
 /* what: 0 n_seq, 1 n_q_heads, 2 n_kv_heads, 3 N, 4 deg, 5 bytes of device memory owned,
- * 6 whether ra_decode_step will use helper workgroups (1 / 0; synchronises the device). */
+ * 6 whether ra_decode_step will use helper workgroups (1 / 0; synchronises the device),
+ * 7 the seed-set size in use (RA_CFG_SEEDS; 0: single entry point). */
 int64_t ra_index_info(const ra_index* idx, int what);
 
 /* Settings of the handle's decode path (host side; synchronises the device).
@@ -235,9 +237,23 @@ int64_t ra_index_info(const ra_index* idx, int what);
  * property of this part's memory system, not of the HIP memory model; the bounded wait and the
  * fall-back keep a launch correct if a ready word never arrives.
  * Two ra_decode_step calls on one handle must not overlap in time (they share this memory,
- * like the handle's other workspaces). Returns RA_EINVAL for an unknown setting or value. */
+ * like the handle's other workspaces). Returns RA_EINVAL for an unknown setting or value.
+ *
+ *   RA_CFG_SEEDS        0 (default): every walk of the handle starts from its head's entry point.
+ *                       n in 1 .. RA_MAX_SEEDS: it starts from a seed set instead - the paper does
+ *                       not say where a walk starts (Sec. 2.4) - namely the first n positions,
+ *                       breadth first, of the binary tree that slots 0 and 1 of the adjacency rows
+ *                       span from the entry point (position p has its children at 2p + 1, 2p + 2;
+ *                       positions without a node and repeated nodes are dropped). For a graph from
+ *                       ra_project these are the n keys that appear in the most KNN lists of the
+ *                       prefill queries. All seeds are scored at once, the best ef of them form the
+ *                       beam, none is expanded yet; they count as visited, no step is counted for
+ *                       them. n = 1 is the single-entry walk. Applies to ra_search, ra_decode_step
+ *                       and their variants, which then need n <= expand x deg (RA_EINVAL
+ *                       otherwise). Lists the sets on the device and synchronises it. */
 #define RA_CFG_HELPERS 0
 #define RA_CFG_HELPER_SPIN 1
+#define RA_CFG_SEEDS 2
 #define RA_HELPERS_OFF 0
 #define RA_HELPERS_ON 1
 #define RA_HELPER_SPIN_DEFAULT 20000

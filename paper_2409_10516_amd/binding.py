@@ -18,8 +18,11 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.environ.get("RA_LIBRARY") or os.path.join(_HERE, "libra.so")
 
 RA_F32, RA_BF16 = 0, 1
-RA_CFG_HELPERS, RA_CFG_HELPER_SPIN = 0, 1
-RA_HELPERS_OFF, RA_HELPERS_ON, RA_HELPERS_SILENT = 0, 1, 2
+RA_CFG_HELPERS, RA_CFG_HELPER_SPIN, RA_CFG_SEEDS = 0, 1, 2
+RA_HELPERS_OFF, RA_HELPERS_ON = 0, 1
+# test-only settings (ra_test_configure)
+RA_TEST_KNN_SELECTION, RA_TEST_HELPERS_SILENT = 100, 101
+RA_TEST_KNN_AUTO, RA_TEST_KNN_REG, RA_TEST_KNN_LDS = 0, 1, 2
 STATUS = {0: "RA_OK", 1: "RA_EINVAL", 2: "RA_ESHAPE", 3: "RA_EDTYPE", 4: "RA_ENOMEM",
           5: "RA_EHIP", 6: "RA_EUNSUP"}
 
@@ -74,6 +77,8 @@ def lib() -> C.CDLL:
     L.ra_index_info.restype = i64
     L.ra_index_configure.argtypes = [vp, i32, i64]
     L.ra_index_configure.restype = i32
+    L.ra_test_configure.argtypes = [vp, i32, i64]
+    L.ra_test_configure.restype = i32
     L.ra_index_adj.argtypes = [vp]
     L.ra_index_adj.restype = vp
     L.ra_index_entry.argtypes = [vp]
@@ -150,9 +155,15 @@ class Index:
     device_bytes = property(lambda s: s.info(5))
     helpers_active = property(lambda s: s.info(6) == 1)
 
+    n_seeds = property(lambda s: s.info(7))
+
     def configure(self, what: int, value: int) -> None:
-        """ra_index_configure: RA_CFG_HELPERS / RA_CFG_HELPER_SPIN."""
+        """ra_index_configure: RA_CFG_HELPERS / RA_CFG_HELPER_SPIN / RA_CFG_SEEDS."""
         _check(lib().ra_index_configure(self.handle, what, value))
+
+    def test_configure(self, what: int, value: int) -> None:
+        """ra_test_configure on this handle (test-only settings)."""
+        _check(lib().ra_test_configure(self.handle, what, value))
 
     def free(self):
         if self._h is not None:
@@ -164,6 +175,11 @@ class Index:
             self.free()
         except Exception:
             pass
+
+
+def ra_test_configure(what: int, value: int) -> None:
+    """ra_test_configure without a handle (process-wide test-only settings)."""
+    _check(lib().ra_test_configure(None, what, value))
 
 
 def ra_knn(K, Q_prefill, knn: int, stream=None) -> torch.Tensor:

@@ -50,6 +50,19 @@ static ra_status check_decode_args(const ra_index* idx, int64_t N, int sink, int
     return RA_OK;
 }
 
+// the start set the walks of this handle use: its seed sets when configured, else its root sets
+static const int32_t* start_sets(const ra_index* ix, int* cap) {
+    *cap = ix->n_seeds ? ix->seed_cap : ix->root_cap;
+    return ix->n_seeds ? ix->seeds : ix->roots;
+}
+
+static ra_status check_seeds_fit(const ra_index* ix, int expand) {
+    if (ix->n_seeds > expand * ix->deg)
+        RA_FAIL(RA_EINVAL, "n_seeds %d exceeds expand x deg = %d (the seeds are scored like one step's "
+                "candidates): raise expand or lower RA_CFG_SEEDS", ix->n_seeds, expand * ix->deg);
+    return RA_OK;
+}
+
 static ra_status check_search_args(int topk, int ef, int expand) {
     if (ef < 1 || expand < 1) RA_FAIL(RA_EINVAL, "ef and expand must be positive");
     if (ef < topk) RA_FAIL(RA_EINVAL, "ef (%d) must be at least topk (%d)", ef, topk);
@@ -133,6 +146,7 @@ extern "C" void ra_index_free(ra_index* ix) {
     if (ix->bitset) (void)hipFree(ix->bitset);
     if (ix->coop) (void)hipFree(ix->coop);
     if (ix->roots) (void)hipFree(ix->roots);
+    if (ix->seeds) (void)hipFree(ix->seeds);
     delete ix;
 }
 
@@ -153,6 +167,30 @@ extern "C" ra_status ra_index_configure(ra_index* ix, int what, int64_t value) {
             if (value < 1 || value > (1 << 24)) RA_FAIL(RA_EINVAL, "spin limit %lld", (long long)value);
             ix->coop_spin = (int)value;
             return RA_OK;
+        case RA_CFG_SEEDS: {
+            if (value < 0 || value > RA_MAX_SEEDS)
+                RA_FAIL(RA_EINVAL, "n_seeds %lld outside [0, %d]", (long long)value, RA_MAX_SEEDS);
+            RA_HIP(hipDeviceSynchronize());
+            const int n = (int)(value > ix->N ? ix->N : value);
+            if (n == 0) {
+                ix->n_seeds = 0;
+                return RA_OK;
+            }
+            const size_t graphs = (size_t)ix->n_seq * ix->n_q;
+            if (n + 2 > ix->seed_cap) {
+                if (ix->seeds) RA_HIP(hipFree(ix->seeds));
+                ix->seeds = nullptr;
+                ix->seed_cap = 0;
+                ix->n_seeds = 0;
+                RA_HIP(hipMalloc((void**)&ix->seeds, graphs * (size_t)(n + 2) * sizeof(int32_t)));
+                ix->seed_cap = n + 2;
+            }
+            RA_TRY(ra_launch_seeds(ix->adj, ix->entry, (int)graphs, ix->N, ix->deg, n, ix->seeds, ix->seed_cap,
+                                   nullptr));
+            RA_HIP(hipStreamSynchronize(nullptr));
+            ix->n_seeds = n;
+            return RA_OK;
+        }
         default:
             RA_FAIL(RA_EINVAL, "unknown setting %d", what);
     }
@@ -187,9 +225,11 @@ extern "C" int64_t ra_index_info(const ra_index* ix, int what) {
         case 4: return ix->deg;
         case 5: return (int64_t)(ix->graph_bytes + (size_t)ix->n_seq * ix->n_q * 4 +
                                  ix->partials_bytes + ix->ids_bytes + ix->bitset_bytes + coop_bytes(ix) +
-                                 (size_t)ix->n_seq * ix->n_q * ix->root_cap * sizeof(int32_t));
+                                 (size_t)ix->n_seq * ix->n_q * (ix->root_cap + ix->seed_cap) * sizeof(int32_t));
         case 6: {
             if (ix->coop_mode != RA_HELPERS_ON || ix->coop_silent) return 0;
+            const int G = ix->n_q / ix->n_kv;
+            if (G != 1 && G != 2 && G != 4 && G != 8) return 0;      // see ra_launch_decode
             const size_t heads = (size_t)ix->n_seq * ix->n_q;
             uint32_t off = 1u;
             if (hipDeviceSynchronize() != hipSuccess ||
@@ -199,6 +239,7 @@ extern "C" int64_t ra_index_info(const ra_index* ix, int what) {
                 return -1;
             return off == 0u;
         }
+        case 7: return ix->n_seeds;
         default: return -1;
     }
 }
@@ -342,12 +383,15 @@ static ra_status search_common(const void* q, const ra_index* idx, const void* K
     RA_TRY(check_decode_args(idx, N, sink, window, topk));
     RA_TRY(check_search_args(topk, ef, expand));
     ra_index* ix = const_cast<ra_index*>(idx);
+    RA_TRY(check_seeds_fit(ix, expand));
     if (ra_search_needs_global_bitset(N, ix->deg, ef, expand)) {
         const size_t need = (size_t)ix->n_seq * ix->n_q * ((N + 31) >> 5) * 4;
         RA_TRY(grow((void**)&ix->bitset, &ix->bitset_bytes, need));
     }
+    int start_cap;
+    const int32_t* start = start_sets(ix, &start_cap);
     return ra_launch_search(q, ix->adj, ix->entry, K, dt, ix->n_seq, ix->n_q, ix->n_kv, N, ix->deg,
-                            sink, window, topk, ef, expand, ix->bitset, ix->roots, ix->root_cap, kscale,
+                            sink, window, topk, ef, expand, ix->bitset, start, start_cap, kscale,
                             (hipStream_t)stream, ids, stats);
 }
 
@@ -407,6 +451,7 @@ static ra_status decode_common(const void* q, const ra_index* idx, const void* K
     RA_TRY(check_decode_args(idx, idx->N, sink, window, topk));
     RA_TRY(check_search_args(topk, ef, expand));
     ra_index* ix = const_cast<ra_index*>(idx);
+    RA_TRY(check_seeds_fit(ix, expand));
     if (!ids) {
         RA_TRY(grow((void**)&ix->ids_ws, &ix->ids_bytes,
                     (size_t)ix->n_seq * ix->n_q * topk * sizeof(int32_t)));
@@ -415,9 +460,12 @@ static ra_status decode_common(const void* q, const ra_index* idx, const void* K
     const size_t heads = (size_t)ix->n_seq * ix->n_q;
     if (ra_decode_needs_global_bitset(ix->N, ix->deg, ef, expand, topk))
         RA_TRY(grow((void**)&ix->bitset, &ix->bitset_bytes, heads * ((ix->N + 31) >> 5) * 4));
+    int start_cap;
+    const int32_t* start = start_sets(ix, &start_cap);
     return ra_launch_decode(q, ix->adj, ix->entry, K, V, dt, ix->n_seq, ix->n_q, ix->n_kv, ix->N, N,
                             kv_stride, ix->deg, sink, window, topk, ef, expand, ix->bitset, ix->coop,
-                            ix->coop_silent ? RA_HELPERS_SILENT_ : ix->coop_mode, ix->coop_spin, ix->roots, ix->root_cap, K8, kscale, budgets,
+                            ix->coop_silent ? RA_HELPERS_SILENT_ : ix->coop_mode, ix->coop_spin, start, start_cap, K8, kscale,
+                            budgets,
                             (hipStream_t)stream, out, lse, ids, stats);
 }
 

@@ -1,19 +1,21 @@
 // Stand-alone attention launches (ra_attend); the device code is in attend_dev.h.
 #include "attend_dev.h"
 
-// grid: x = record slot (nS static chunks, then G x nG gathered chunks), y = KV head, z = seq
+// grid: x = record slot (nS static chunks, then G x nG gathered chunks), y = KV head, z = seq.
+// GQA groups of another size than the kernel is built for run as G = 1 with one grid row per query
+// head, kv_div of which share a KV head (kv_div = 1 otherwise).
 template <int DT, int G>
 __global__ __launch_bounds__(AT_THREADS) void attend_partial_kernel(
     const void* __restrict__ q, const void* __restrict__ K, const void* __restrict__ V,
     const int32_t* __restrict__ ids, float* __restrict__ partials, int n_q, int n_kv, int64_t N,
-    int s, int w, int topk, int nS, int nG, int sub, float scale) {
+    int s, int w, int topk, int nS, int nG, int sub, float scale, int kv_div) {
     extern __shared__ float smem[];
-    const int kvh = blockIdx.y, seq = blockIdx.z, x = blockIdx.x;
+    const int kvh = blockIdx.y / kv_div, seq = blockIdx.z, x = blockIdx.x;
     const int P = nS + nG;
     const size_t esz = DT == RA_BF16 ? 2 : 4;
     const char* Kh = reinterpret_cast<const char*>(K) + ((size_t)seq * n_kv + kvh) * N * RA_D * esz;
     const char* Vh = reinterpret_cast<const char*>(V) + ((size_t)seq * n_kv + kvh) * N * RA_D * esz;
-    const int h0 = kvh * G;
+    const int h0 = blockIdx.y * G;
     const char* qg = reinterpret_cast<const char*>(q) + ((size_t)seq * n_q + h0) * RA_D * esz;
     float* rec_g = partials + ((size_t)seq * n_q + h0) * P * AT_RS;
     if (x < nS) {
@@ -89,15 +91,18 @@ static ra_status launch_partial(int G, dim3 grid, size_t lds, hipStream_t st, co
 #define RA_AT_CASE(GG)                                                                          \
     case GG:                                                                                    \
         hipLaunchKernelGGL((attend_partial_kernel<DT, GG>), grid, dim3(AT_THREADS), lds, st, q, K, \
-                           V, ids, partials, n_q, n_kv, N, s, w, topk, nS, nG, sub, scale);     \
+                           V, ids, partials, n_q, n_kv, N, s, w, topk, nS, nG, sub, scale, 1);  \
         break;
     switch (G) {
         RA_AT_CASE(1)
         RA_AT_CASE(2)
         RA_AT_CASE(4)
         RA_AT_CASE(8)
-        default:
-            RA_FAIL(RA_EUNSUP, "query heads per KV head must be 1, 2, 4 or 8 (got %d)", G);
+        default:                 // any other group size: every query head reads its rows itself
+            grid.x = nS + nG;
+            grid.y = n_q;
+            hipLaunchKernelGGL((attend_partial_kernel<DT, 1>), grid, dim3(AT_THREADS), lds, st, q, K, V,
+                               ids, partials, n_q, n_kv, N, s, w, topk, nS, nG, sub, scale, G);
     }
 #undef RA_AT_CASE
     return RA_OK;

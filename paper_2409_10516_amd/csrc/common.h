@@ -65,6 +65,10 @@ struct ra_index {
     float* coop;
     int coop_mode;      // RA_HELPERS_*
     int coop_spin;      // polls of the ready word before a head gives up on its helper
+    int coop_silent;    // test-only (RA_TEST_HELPERS_SILENT): helpers are launched but write nothing
+    // seed sets (RA_CFG_SEEDS): [n_seq*n_q][seed_cap] in the layout of the root sets, or null
+    int32_t* seeds;
+    int n_seeds, seed_cap;
     // root sets: what the first two steps of every walk of a head visit ([n_seq*n_q][root_cap])
     int32_t* roots;
     int root_cap;
@@ -72,6 +76,7 @@ struct ra_index {
 };
 
 #define RA_COOP_REC 132
+#define RA_HELPERS_SILENT_ 2   /* launch-time helper mode behind RA_TEST_HELPERS_SILENT */
 #define RA_KEYS_I8 2          /* key type of a search over 8-bit keys (beside RA_F32, RA_BF16) */
 
 // ---- launchers implemented in the .hip files (all enqueue on `st`, no sync) ----------
@@ -84,6 +89,9 @@ ra_status ra_launch_quantize(const void* K, ra_dtype dt, int n_groups, int64_t N
                              int8_t* K8, float* scale);
 ra_status ra_launch_roots(const int32_t* adj, const int32_t* entry, int heads, int64_t N, int deg,
                           int32_t* roots, int cap, hipStream_t st);
+// seed sets: per head [0] the number of ids, [1] 0, then the ids (cap >= 2 + n_seeds ints per head)
+ra_status ra_launch_seeds(const int32_t* adj, const int32_t* entry, int heads, int64_t N, int deg,
+                          int n_seeds, int32_t* seeds, int cap, hipStream_t st);
 size_t ra_search_lds_bytes(int64_t N, int deg, int ef, int expand, bool global_bitset);
 bool ra_search_needs_global_bitset(int64_t N, int deg, int ef, int expand);
 

@@ -282,7 +282,7 @@ __global__ __launch_bounds__(T) void decode_kernel(
     const bool helpers = n_helpers > 0 && xwg_load(ready + n_heads) == 0u;
     if ((int)blockIdx.x < n_helpers) {
         // ---- helper workgroup of (sequence, KV head) blockIdx.x: attention over W for its G heads
-        if (!helpers || coop_mode == RA_HELPERS_SILENT) return;
+        if (!helpers || coop_mode == RA_HELPERS_SILENT_) return;
         const int g = blockIdx.x;
         const char* Kg = reinterpret_cast<const char*>(K) + (size_t)g * kv_stride * RA_D * esz;
         const char* Vg = reinterpret_cast<const char*>(V) + (size_t)g * kv_stride * RA_D * esz;

@@ -29,13 +29,14 @@
 #define FL_TILE (FL_CHUNK / 16)     // keys per tile maximum: chunk base + group + 16 j, j < FL_TILE
 #define FL_TILES_MAX 8192          // tiles per head the select kernel can list (256K keys)
 
-// grid: x = chunk of FL_CHUNK keys, y = KV head, z = seq
+// grid: x = chunk of FL_CHUNK keys, y = KV head, z = seq. GQA groups of another size than the
+// kernel is built for run as G = 1 with one grid row per query head, kv_div of which share a KV head.
 template <int DT, int G>
 __global__ __launch_bounds__(FL_THREADS) void flat_scores_kernel(
     const void* __restrict__ q, const void* __restrict__ K, int n_q, int n_kv, int64_t N, int s, int w,
-    uint32_t* __restrict__ keys, uint32_t* __restrict__ tile_max, int64_t n_tiles) {
+    uint32_t* __restrict__ keys, uint32_t* __restrict__ tile_max, int64_t n_tiles, int kv_div) {
     const int tid = threadIdx.x, grp = tid >> 4, lane16 = tid & 15;
-    const int kvh = blockIdx.y, seq = blockIdx.z, h0 = seq * n_q + kvh * G;
+    const int kvh = blockIdx.y / kv_div, seq = blockIdx.z, h0 = seq * n_q + blockIdx.y * G;
     const size_t esz = DT == RA_BF16 ? 2 : 4;
     const char* Kh = reinterpret_cast<const char*>(K) + ((size_t)seq * n_kv + kvh) * N * RA_D * esz;
     float qv[G][8];
@@ -381,15 +382,22 @@ ra_status ra_launch_flat_topk(const void* q, const void* K, ra_dtype dt, int n_s
 #define RA_FL_CASE(DTV, GG)                                                                     \
     case GG:                                                                                    \
         hipLaunchKernelGGL((flat_scores_kernel<DTV, GG>), grid, dim3(FL_THREADS), 0, st, q, K, n_q, \
-                           n_kv, N, (int)ss, (int)ww, keys_ws, tile_max, n_tiles);              \
+                           n_kv, N, (int)ss, (int)ww, keys_ws, tile_max, n_tiles, 1);           \
         break;
+    // any other group size: one grid row per query head, every head scans its keys itself
+    const dim3 grid1(grid.x, n_q, n_seq);
+#define RA_FL_OTHER(DTV)                                                                        \
+    default:                                                                                    \
+        hipLaunchKernelGGL((flat_scores_kernel<DTV, 1>), grid1, dim3(FL_THREADS), 0, st, q, K, n_q, \
+                           n_kv, N, (int)ss, (int)ww, keys_ws, tile_max, n_tiles, G);
     if (dt == RA_BF16) {
         switch (G) { RA_FL_CASE(RA_BF16, 1) RA_FL_CASE(RA_BF16, 2) RA_FL_CASE(RA_BF16, 4) RA_FL_CASE(RA_BF16, 8)
-            default: RA_FAIL(RA_EUNSUP, "query heads per KV head must be 1, 2, 4 or 8 (got %d)", G); }
+            RA_FL_OTHER(RA_BF16) }
     } else {
         switch (G) { RA_FL_CASE(RA_F32, 1) RA_FL_CASE(RA_F32, 2) RA_FL_CASE(RA_F32, 4) RA_FL_CASE(RA_F32, 8)
-            default: RA_FAIL(RA_EUNSUP, "query heads per KV head must be 1, 2, 4 or 8 (got %d)", G); }
+            RA_FL_OTHER(RA_F32) }
     }
+#undef RA_FL_OTHER
 #undef RA_FL_CASE
     RA_HIP(hipGetLastError());
     hipLaunchKernelGGL(flat_select_kernel, dim3(n_seq * n_q), dim3(FL_SEL_T), 0, st, keys_ws, tile_max,

@@ -82,6 +82,73 @@ ra_status ra_launch_roots(const int32_t* adj, const int32_t* entry, int heads, i
     return RA_OK;
 }
 
+// Seed sets: the first n_seeds positions, breadth first, of the binary tree that slots 0 and 1 of
+// every adjacency row span from the entry point (position p has its children at 2p + 1 and 2p + 2;
+// for a projected graph this is the head of the popularity order). Positions without a node and
+// nodes already listed at an earlier position are dropped, the order kept. Layout of a root set
+// with [1] = 0: no id enters the beam as expanded. One workgroup per head; a set-up step.
+#define SD_THREADS 1024
+__global__ __launch_bounds__(SD_THREADS) void seeds_kernel(const int32_t* __restrict__ adj,
+                                                           const int32_t* __restrict__ entry, int64_t N,
+                                                           int deg, int n_seeds, int32_t* __restrict__ seeds,
+                                                           int cap) {
+    __shared__ int pos[RA_MAX_SEEDS];
+    __shared__ int keep[RA_MAX_SEEDS];
+    __shared__ int wsum[SD_THREADS / RA_WAVE];
+    const int tid = threadIdx.x, head = blockIdx.x;
+    const int32_t* adj_h = adj + (size_t)head * N * deg;
+    int32_t* out = seeds + (size_t)head * cap;
+    for (int p = tid; p < n_seeds; p += SD_THREADS) {
+        // the path from the root to position p: the bits of p + 1 below its leading one, high to low
+        int cur = entry[head];
+        const unsigned path = (unsigned)p + 1u;
+        for (int b = 30 - __clz(path); b >= 0 && cur >= 0; --b) {
+            const int slot = (path >> b) & 1u;
+            cur = slot < deg ? adj_h[(size_t)cur * deg + slot] : -1;
+            if (cur < 0 || cur >= N) cur = -1;
+        }
+        pos[p] = cur;
+    }
+    __syncthreads();
+    for (int p = tid; p < n_seeds; p += SD_THREADS) {
+        const int id = pos[p];
+        bool k = id >= 0;
+        for (int y = 0; k && y < p; ++y) k = pos[y] != id;
+        keep[p] = k;
+    }
+    __syncthreads();
+    // ordered compaction: RA_MAX_SEEDS <= 2 * SD_THREADS, two rounds of a workgroup-wide prefix sum
+    int base = 0;
+    for (int p0 = 0; p0 < n_seeds; p0 += SD_THREADS) {
+        const int p = p0 + tid;
+        const bool k = p < n_seeds && keep[p];
+        const unsigned long long m = __ballot(k);
+        const int lane = tid & (RA_WAVE - 1), wv = tid / RA_WAVE;
+        if (lane == 0) wsum[wv] = __popcll(m);
+        __syncthreads();
+        int before = base, total = base;
+        for (int x = 0; x < SD_THREADS / RA_WAVE; ++x) {
+            if (x < wv) before += wsum[x];
+            total += wsum[x];
+        }
+        if (k) out[2 + before + __popcll(m & ((1ull << lane) - 1ull))] = pos[p];
+        base = total;
+        __syncthreads();
+    }
+    if (tid == 0) {
+        out[0] = base;
+        out[1] = 0;
+    }
+}
+
+ra_status ra_launch_seeds(const int32_t* adj, const int32_t* entry, int heads, int64_t N, int deg,
+                          int n_seeds, int32_t* seeds, int cap, hipStream_t st) {
+    if (n_seeds < 1 || n_seeds > RA_MAX_SEEDS || cap < 2 + n_seeds) RA_FAIL(RA_EINVAL, "seed set buffer too small");
+    hipLaunchKernelGGL(seeds_kernel, dim3(heads), dim3(SD_THREADS), 0, st, adj, entry, N, deg, n_seeds, seeds, cap);
+    RA_HIP(hipGetLastError());
+    return RA_OK;
+}
+
 size_t ra_search_lds_bytes(int64_t N, int deg, int ef, int expand, bool global_bitset) {
     return search_lds_bytes(N, deg, ef, expand, global_bitset);
 }

@@ -301,7 +301,13 @@ __device__ __forceinline__ int run_search(
     if (!GBITS)
         for (int i = tid; i < nwords; i += T) bits[i] = 0u;
     for (int i = tid; i < maxc + 2 * ef + 2; i += T) cnt[i] = 0;      // cnt, hist, hist_nxt
-    const bool fill = root && n_first > 1 && expand >= n_first - 1 && ef >= n_first && n_root <= maxc;
+    // A seed set (ra_launch_seeds) has the same layout with [1] = 0: the walk starts from all of its
+    // keys at once, scored in one gather, the best ef of them in the beam and none of them expanded.
+    // That is a start of its own, not a shortcut for steps of the single-entry walk: no step is
+    // counted for it. (The host checks that a seed set fits the candidate arrays.)
+    const bool seeded = root && n_first == 0;
+    const bool fill = root && n_root <= maxc &&
+                      (seeded ? n_root >= 1 : n_first > 1 && expand >= n_first - 1 && ef >= n_first);
     __syncthreads();                                             // the LDS state is cleared
     int bn, n_visited, n_expanded, n_iters;
     bool first = fill;               // the coming step is that doubled first step
@@ -395,8 +401,10 @@ __device__ __forceinline__ int run_search(
         }
         SR_TICK(0);
         if (first) {
-            n_iters = 2;             // the entry point's step and its neighbours' step
-            n_expanded = n_first;
+            if (!seeded) {
+                n_iters = 2;         // the entry point's step and its neighbours' step
+                n_expanded = n_first;
+            }
         } else {
             ++n_iters;
             n_expanded += np;
@@ -504,7 +512,7 @@ __device__ __forceinline__ int run_search(
                 const int above = ch + 1 < nch ? count_above16_full(ckey + ch * 16, ckey[c])
                                                : count_above16(ckey + ch * 16, nk - ch * 16, ckey[c]);
                 if (above) atomicAdd(&cnt[c], above);
-                if (first) {
+                if (first && n_first > 0) {
                     // the doubled first step has expanded candidates too: how many of those beat
                     // this one goes into the counter's high half (the beam is empty, so it is free)
                     const int exp_above = count_above16_expanded(ckey + ch * 16, nk - ch * 16, ckey[c]);

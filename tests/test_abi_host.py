@@ -41,7 +41,6 @@ def _fake():
     ((None, _fake(), 1, 1, 4, 2, 100, 10, 128, 8), 1, "NULL"),
     ((_fake(), _fake(), 7, 1, 4, 2, 100, 10, 128, 8), 3, "dtype"),
     ((_fake(), _fake(), 1, 1, 4, 3, 100, 10, 128, 8), 1, "multiple"),
-    ((_fake(), _fake(), 1, 1, 12, 4, 100, 10, 128, 8), 6, "per KV head"),
     ((_fake(), _fake(), 1, 1, 4, 2, 100, 10, 64, 8), 6, "d = 128"),
     ((_fake(), _fake(), 1, 1, 4, 2, 100, 10, 128, 101), 1, "exceeds N"),
     ((_fake(), _fake(), 1, 1, 4, 2, 100, 0, 128, 8), 1, "positive"),
@@ -80,6 +79,20 @@ def test_decode_validation_without_index():
     assert rc == 1 and "handle" in L.ra_last_error().decode()
     assert L.ra_index_info(None, 0) == -1
     L.ra_index_free(None)            # must be a no-op
+
+
+def test_settings_validation():
+    """ra_index_configure / ra_test_configure reject a missing handle and unknown settings or values
+    before anything touches a device; the process-wide test setting needs no handle."""
+    L = ra.lib()
+    L.ra_index_configure.restype = C.c_int
+    L.ra_test_configure.restype = C.c_int
+    assert L.ra_index_configure(None, 2, C.c_int64(64)) == 1 and "handle" in L.ra_last_error().decode()
+    assert L.ra_test_configure(None, 101, C.c_int64(1)) == 1 and "handle" in L.ra_last_error().decode()
+    assert L.ra_test_configure(None, 7, C.c_int64(0)) == 1 and "unknown" in L.ra_last_error().decode()
+    assert L.ra_test_configure(None, 100, C.c_int64(9)) == 1
+    assert L.ra_test_configure(None, 100, C.c_int64(2)) == 0
+    assert L.ra_test_configure(None, 100, C.c_int64(0)) == 0
 
 
 def test_import_validation():

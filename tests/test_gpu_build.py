@@ -18,11 +18,15 @@ GOLD = os.path.join(os.path.dirname(__file__), "golden")
 
 
 @pytest.fixture(params=["reg", "lds"])
-def knn_selection(request, monkeypatch):
+def knn_selection(request):
     """Lists of up to 32 bf16 keys have two selections (pending keys in registers, two query sets per
-    wavefront / pending runs in LDS); the library picks by the number of keys, the tests force each."""
-    monkeypatch.setenv("RA_KNN_SELECTION", request.param)
-    return request.param
+    wavefront / pending runs in LDS); the library picks by the number of keys, the tests force each
+    through the test-only setting."""
+    from paper_2409_10516_amd import binding as B
+    ra.ra_test_configure(B.RA_TEST_KNN_SELECTION,
+                         B.RA_TEST_KNN_REG if request.param == "reg" else B.RA_TEST_KNN_LDS)
+    yield request.param
+    ra.ra_test_configure(B.RA_TEST_KNN_SELECTION, B.RA_TEST_KNN_AUTO)
 
 
 def _cases():

@@ -179,7 +179,7 @@ def test_decode_step_with_a_budget_per_head(name):
 @pytest.mark.parametrize("name", list(_cases()))
 def test_decode_step_helper_modes_agree_with_oracle(name):
     """ra_index_configure: the attention over W by helper workgroups (default), by the heads
-    themselves (RA_HELPERS_OFF), and after a bounded wait that runs out (RA_HELPERS_SILENT with a
+    themselves (RA_HELPERS_OFF), and after a bounded wait that runs out (RA_TEST_HELPERS_SILENT with a
     tiny spin limit: no helper ever reports, every head falls back and the handle stops using
     helpers) all give the oracle's result; ids and counters stay bit-exact."""
     from paper_2409_10516_amd import binding as B
@@ -212,7 +212,8 @@ def test_decode_step_helper_modes_agree_with_oracle(name):
         idx.configure(B.RA_CFG_HELPERS, B.RA_HELPERS_OFF)
         assert not idx.helpers_active
         check()
-        idx.configure(B.RA_CFG_HELPERS, B.RA_HELPERS_SILENT)
+        idx.configure(B.RA_CFG_HELPERS, B.RA_HELPERS_ON)
+        idx.test_configure(B.RA_TEST_HELPERS_SILENT, 1)
         idx.configure(B.RA_CFG_HELPER_SPIN, 3)
         check()                               # every head's wait runs out
         idx.configure(B.RA_CFG_HELPERS, B.RA_HELPERS_ON)   # also forgets the wait that ran out
@@ -233,7 +234,7 @@ def test_helpers_switch_off_after_a_wait_that_ran_out():
         # look at the outputs instead: after the timed-out call the results must still be right
         # with helpers nominally on, which they can only be if the heads no longer wait on them
         a = ra.ra_decode_step(q, idx, Kd, Vd, w.sink, w.window, w.topk, w.ef, 8)
-        idx.configure(B.RA_CFG_HELPERS, B.RA_HELPERS_SILENT)
+        idx.test_configure(B.RA_TEST_HELPERS_SILENT, 1)
         idx.configure(B.RA_CFG_HELPER_SPIN, 2)
         b = ra.ra_decode_step(q, idx, Kd, Vd, w.sink, w.window, w.topk, w.ef, 8)
         c = ra.ra_decode_step(q, idx, Kd, Vd, w.sink, w.window, w.topk, w.ef, 8)   # off word set: no waiting
@@ -427,3 +428,112 @@ def test_grown_cache_with_everything_retrieved_is_full_attention():
         ref_o, ref_l = OA.full_attention(to_np(q[0, 0]), to_np(w.K[0, 0]), to_np(w.V[0, 0]))
         assert sorted(ids[0, 0].tolist()) == list(range(4, 300))
         assert out_close(out[0, 0].cpu().numpy(), ref_o, 1e-5) and lse_close(float(lse[0, 0]), ref_l, 1e-5)
+
+
+@pytest.mark.parametrize("name", list(_cases()))
+@pytest.mark.parametrize("n_seeds,expand", [(1, 4), (7, 8), (100, 32), (300, 64), (2048, 256)])
+def test_walks_from_a_seed_set(name, n_seeds, expand):
+    """RA_CFG_SEEDS: the device lists the seed sets from the graph alone (the oracle's
+    backbone_seeds), starts every walk from them, and counts no step for them. ra_search and
+    ra_decode_step against the oracle's seeded walk; a seed set that does not fit one step's
+    candidate arrays is refused; 0 restores the single-entry walk."""
+    from paper_2409_10516_amd import binding as B
+    w, adj, ent, idx, Kd, Vd = _prepared(name)
+    n_seq, n_kv, N, d = w.K.shape
+    n_q = w.Q_prefill.shape[1]
+    tol = tol_for(w.K.dtype)
+    exact = integer_valued(to_np(w.K), to_np(w.q_decode))
+    W = OA.static_ids(N, w.sink, w.window)
+    ef = max(w.ef, 24)
+    try:
+        idx.configure(B.RA_CFG_SEEDS, n_seeds)
+        assert idx.n_seeds == min(n_seeds, N)
+        if idx.n_seeds > expand * idx.deg:
+            with pytest.raises(ra.RaError) as e:
+                ra.ra_search(w.q_decode[0].to(DEV), idx, Kd, w.sink, w.window, w.topk, ef, expand)
+            assert e.value.status == 1 and "n_seeds" in str(e.value)
+            return
+        tally = Tally()
+        for t in range(min(3, w.q_decode.shape[0])):
+            q = w.q_decode[t].to(DEV)
+            ids_s, st_s = ra.ra_search(q, idx, Kd, w.sink, w.window, w.topk, ef, expand)
+            out, lse, ids, st = ra.ra_decode_step(q, idx, Kd, Vd, w.sink, w.window, w.topk, ef, expand)
+            assert torch.equal(ids_s, ids) and torch.equal(st_s, st)
+            out, lse, ids, st = out.cpu().numpy(), lse.cpu().numpy(), ids.cpu().numpy(), st.cpu().numpy()
+            for s in range(n_seq):
+                for h in range(n_q):
+                    g = s * n_q + h
+                    K = to_np(w.K[s, h // (n_q // n_kv)]); V = to_np(w.V[s, h // (n_q // n_kv)])
+                    tally.add(decode_matches(out[s, h], lse[s, h], ids[s, h], st[s, h].tolist(),
+                                             to_np(w.q_decode[t, s, h]), K, V, adj[g], ent[g], w.sink, w.window,
+                                             w.topk, ef, expand, tol, exact=exact, n_seeds=n_seeds))
+        tally.check()
+        if n_seeds == 100:
+            with pytest.raises(ra.RaError) as e:      # 100 seeds do not fit one expansion's candidates
+                ra.ra_search(w.q_decode[0].to(DEV), idx, Kd, w.sink, w.window, w.topk, ef, 1)
+            assert e.value.status == 1 and "n_seeds" in str(e.value)
+    finally:
+        idx.configure(B.RA_CFG_SEEDS, 0)
+    assert idx.n_seeds == 0
+
+
+def test_seed_sets_of_a_graph_with_missing_and_repeated_nodes():
+    """An imported graph need not be a projection: slots 0 and 1 may hold -1 or lead back to a node
+    already listed. The device's seed list must be the oracle's (checked through the walk: with ef
+    and expand covering everything, n_visited after zero steps is the number of distinct seeds)."""
+    from paper_2409_10516_amd import binding as B
+    rng = np.random.default_rng(5)
+    N, deg = 200, 4
+    adj = rng.integers(-1, N, size=(1, N, deg)).astype(np.int32)
+    adj[0, np.arange(N), 0] = np.where(adj[0, :, 0] == np.arange(N), -1, adj[0, :, 0])
+    for j in range(deg):
+        adj[0, adj[0, :, j] == np.arange(N), j] = -1
+    adj[0, 7, 0] = -1
+    adj[0, 7, 1] = 7 + 1
+    ent = np.array([7], np.int32)
+    K = torch.from_numpy(rng.integers(-3, 4, size=(1, 1, N, 128)).astype(np.float32))
+    q = torch.from_numpy(rng.integers(-3, 4, size=(1, 1, 128)).astype(np.float32))
+    idx = ra.ra_index_import(torch.from_numpy(adj), torch.from_numpy(ent), 1, 1, 1)
+    for R in (1, 2, 5, 33, 64):
+        idx.configure(B.RA_CFG_SEEDS, R)
+        seeds = OS.backbone_seeds(adj[0], 7, R)
+        ids, st = ra.ra_search(q.to(DEV), idx, K.to(DEV), 0, 0, 10, 200, 64)
+        ref, rst = OS.greedy_search(to_np(q[0, 0]), to_np(K[0, 0]), adj[0], 7, 200, 10, 64, seeds=seeds)
+        assert ids[0, 0].tolist() == ref.tolist(), R
+        assert st[0, 0].tolist() == [rst["n_visited"], rst["n_expanded"], rst["n_iters"], rst["n_returned"]], R
+    idx.free()
+
+
+@pytest.mark.parametrize("n_q,n_kv,dtype", [(6, 2, torch.bfloat16), (5, 1, torch.float32), (12, 4, torch.bfloat16)])
+def test_group_sizes_the_kernels_are_not_specialised_for(n_q, n_kv, dtype):
+    """GQA groups of 3 and 5 query heads per KV head: ra_decode_step runs without helper workgroups,
+    ra_attend and ra_flat_topk read the rows once per query head. All against the oracle."""
+    w = synth.make_llama_layer(33, N=800, M=200, T=2, n_q=n_q, n_kv=n_kv, dtype=dtype, ef=48, topk=20,
+                               window=60, deg=12, knn=10)
+    adj, ent, _ = oracle_graphs(w)
+    idx = ra.ra_index_import(torch.from_numpy(adj), torch.from_numpy(ent), 1, n_q, n_kv)
+    Kd, Vd = w.K.to(DEV), w.V.to(DEV)
+    tol = tol_for(dtype)
+    G = n_q // n_kv
+    N = 800
+    W = OA.static_ids(N, w.sink, w.window)
+    for t in range(2):
+        q = w.q_decode[t].to(DEV)
+        out, lse, ids, st = ra.ra_decode_step(q, idx, Kd, Vd, w.sink, w.window, w.topk, w.ef, 8)
+        ids_s, _ = ra.ra_search(q, idx, Kd, w.sink, w.window, w.topk, w.ef, 8)
+        o2, l2 = ra.ra_attend(q, idx, Kd, Vd, w.sink, w.window, ids_s)
+        flat = ra.ra_flat_topk(q, Kd, w.sink, w.window, w.topk).cpu().numpy()
+        assert torch.equal(ids, ids_s)
+        out, lse, ids, st = out.cpu().numpy(), lse.cpu().numpy(), ids.cpu().numpy(), st.cpu().numpy()
+        o2, l2 = o2.cpu().numpy(), l2.cpu().numpy()
+        for h in range(n_q):
+            K = to_np(w.K[0, h // G]); V = to_np(w.V[0, h // G])
+            qq = to_np(w.q_decode[t, 0, h])
+            decode_matches(out[0, h], lse[0, h], ids[0, h], st[0, h].tolist(), qq, K, V, adj[h], ent[h], w.sink,
+                           w.window, w.topk, w.ef, 8, tol)
+            decode_matches(o2[0, h], l2[0, h], ids[0, h], None, qq, K, V, adj[h], ent[h], w.sink,
+                           w.window, w.topk, w.ef, 8, tol)
+            ref = OM.topk_bruteforce(qq, K, w.topk, exclude=W)
+            topk_equivalent(flat[0, h], ref, qq, K)
+    assert not idx.helpers_active
+    idx.free()

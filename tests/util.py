@@ -122,7 +122,7 @@ def walk_equivalent(ids, stats4, r_ids, rst, q, K, W, rel=NEAR_TIE, exact=False)
 
 
 def decode_matches(out, lse, ids, stats4, q, K, V, adj, entry, sink, window, topk, ef, expand, tol,
-                   n_index=None, exact=False, score_fn=None):
+                   n_index=None, exact=False, score_fn=None, n_seeds=0):
     """One head of a device decode step against the oracle's (float64 scores unless `score_fn`):
     the walk by walk_equivalent, then out / lse against Eq. 2 and Eq. 4-5 over the ids the device
     returned (the oracle's own when they are identical). Returns True when ids and counters were
@@ -130,7 +130,7 @@ def decode_matches(out, lse, ids, stats4, q, K, V, adj, entry, sink, window, top
     N = np.asarray(K).shape[0]
     W = OA.static_ids(N, sink, window, n_index)
     r_out, r_lse, r_ids, rst = OD.decode_step(q, K, V, adj, entry, sink, window, topk, ef, expand,
-                                              n_index=n_index, score_fn=score_fn)
+                                              n_index=n_index, score_fn=score_fn, n_seeds=n_seeds)
     ids = np.asarray(ids)
     same = walk_equivalent(ids, stats4, r_ids, rst, q, K, W, exact=exact or score_fn is not None)
     if not same:
