@@ -347,6 +347,7 @@ __global__ __launch_bounds__(T) void decode_kernel(
         RowBits<DT> kb[DC_ROWS], vb[DC_ROWS];
 #pragma unroll
         for (int u = 0; u < DC_ROWS; ++u) {
+            if (r0 + u * (T / 16) >= R) break;          // uniform: no group has a row in this slot
             const int r = r0 + u * (T / 16) + grp;
             int64_t id = -1;
             if (r < cnt) id = lds_ids[r];
@@ -358,6 +359,7 @@ __global__ __launch_bounds__(T) void decode_kernel(
         }
 #pragma unroll
         for (int u = 0; u < DC_ROWS; ++u) {
+            if (r0 + u * (T / 16) >= R) break;
             if (rid[u] < 0) continue;
             float dot = ql.dot(kb[u]);
             dot += at_dpp<0xB1>(dot);

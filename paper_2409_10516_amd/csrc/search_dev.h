@@ -34,14 +34,17 @@
 #endif
 
 
-enum { C_NCAND = 1, C_NKEEP = 2, C_NUNEXP = 3, C_WTOT = 8, C_COUNT = 8 + SR_THREADS / RA_WAVE };
+enum { C_NCAND = 1, C_NKEEP = 2, C_NUNEXP = 3, C_LO = 4, C_HI = 5, C_NSURV = 6, C_BIN = 7, C_WTOT = 8,
+       C_COUNT = 8 + SR_THREADS / RA_WAVE };
+#define SR_PREFILTER_SLACK 64     // a step that keeps more than ef + this many candidates drops the hopeless ones first
+#define SR_PREFILTER_REGS 8       // ... when a thread can hold its share of them (nk <= 8 T)
 
 typedef unsigned long long u64;
 
 // Phase clocks for tuning builds (-DSR_PHASE_CLOCKS): thread 0 of the first 64 workgroups adds the
 // ticks spent in each phase to a device array that ra_dbg_phase_ticks copies out. Off otherwise.
 #ifdef SR_PHASE_CLOCKS
-#define SR_NPHASE 12
+#define SR_NPHASE 13
 #define SR_NITER 16
 static __device__ long long sr_phase_ticks[64 * SR_NITER * SR_NPHASE];
 #define SR_TICK_INIT long long tick_ = clock64(); int tick_it_ = 0
@@ -350,6 +353,33 @@ __device__ __forceinline__ int run_search(
     // feed a test that never holds; they are consumed one phase later, when they have long arrived.
     uint32_t early_a = 0u, early_b = 0u, early_acc = 0u;
     __syncthreads();
+    if (fill) {
+        // ---- the start set is scored here, ahead of the loop, where few registers are live: twice
+        //      the rows in flight of a step's gather (a seed set of a thousand keys is one trip to
+        //      memory for 1024 threads). The beam is empty, so every key is kept; the first
+        //      n_first of a root set enter as expanded.
+        constexpr int SEED_ROWS = KT == RA_F32 ? SR_UNROLL : 2 * SR_UNROLL;
+        for (int c0 = 0; c0 < n_root; c0 += (T / 16) * SEED_ROWS) {
+            RowBits<KT> rows[SEED_ROWS];
+#pragma unroll
+            for (int u = 0; u < SEED_ROWS; ++u) {
+                if (c0 + u * (T / 16) >= n_root) break;      // uniform over the workgroup
+                const int c = c0 + u * (T / 16) + grp;
+                rows[u] = load_key<KT>(Kh, c < n_root ? cid[c] : e0, lane16);
+            }
+#pragma unroll
+            for (int u = 0; u < SEED_ROWS; ++u) {
+                if (c0 + u * (T / 16) >= n_root) break;
+                const float sc = score_fixed<KT>(rows[u], qv);
+                const int c = c0 + u * (T / 16) + grp;
+                if (lane16 == 0 && c < n_root) {
+                    u64 key = make_key(sc, cid[c]);
+                    if (c < n_first) key &= ~1ull;
+                    ckey[atomicAdd(&ctr[C_NKEEP], 1)] = key;
+                }
+            }
+        }
+    }
     SR_TICK(5);
 
     for (;;) {
@@ -440,13 +470,18 @@ __device__ __forceinline__ int run_search(
         const int nc = ctr[C_NCAND];
         n_visited += nc;
         SR_TICK(1);
-        if (tid == 0) ctr[C_NUNEXP] = 0;     // everyone read it before the barrier above
+        if (tid == 0) {
+            ctr[C_NUNEXP] = 0;               // everyone read it before the barrier above
+            ctr[C_LO] = -1;                  // (as unsigned: the largest value) see the pre-filter below
+            ctr[C_HI] = 0;
+            ctr[C_NSURV] = 0;
+        }
         early_acc ^= early_a ^ early_b;      // issued a phase or more ago
         early_a = early_b = 0u;
 
         // ---- gather and score the new candidates; keep those that can enter the beam
         const u64 worst = bn == ef ? (cur[bn - 1] >> 1) : 0ull;
-        for (int c0 = 0; c0 < nc; c0 += (T / 16) * SR_UNROLL) {
+        for (int c0 = 0; c0 < (first ? 0 : nc); c0 += (T / 16) * SR_UNROLL) {   // (a start set is scored already)
             RowBits<KT> rows[SR_UNROLL];
             int cidv[SR_UNROLL];
 #pragma unroll
@@ -462,21 +497,85 @@ __device__ __forceinline__ int run_search(
                 if (c0 + u * (T / 16) >= nc) break;
                 const float sc = score_fixed<KT>(rows[u], qv);
                 if (lane16 == 0 && cidv[u] >= 0) {
-                    u64 key = make_key(sc, cidv[u]);
-                    // in the doubled first step the entry point and its neighbours, the first
-                    // n_first candidates, enter the beam as expanded
-                    if (first && c0 + u * (T / 16) + grp < n_first) key &= ~1ull;
+                    const u64 key = make_key(sc, cidv[u]);
                     if ((key >> 1) > worst) ckey[atomicAdd(&ctr[C_NKEEP], 1)] = key;
                 }
             }
         }
         __syncthreads();
-        const int nk = ctr[C_NKEEP];
+        int nk = ctr[C_NKEEP];
         SR_TICK(2);
         if (nk == 0) {               // uniform: nothing enters the beam
             picked = false;
             continue;
         }
+        // ---- pre-filter. At most ef of the kept candidates can enter the beam, and the merge below
+        //      ranks them against each other at a cost quadratic in their number. A step that keeps
+        //      many more than ef (a seed set scored at once) first drops those that cannot be among
+        //      its best ef: the scores are cut into 256 equal-width bins between the smallest and
+        //      the largest, a histogram finds the highest bin b such that the bins
+        //      from b up hold at least ef candidates, and only those survive, compacted in place.
+        //      Everything dropped is below at least ef survivors; which survive does not depend on
+        //      the order of the candidates. The claimed ids (cid) are dead by now: their first 256
+        //      words are the histogram.
+        if (nk > ef + SR_PREFILTER_SLACK && nk <= SR_PREFILTER_REGS * T && maxc >= 256) {
+            u64 mine[SR_PREFILTER_REGS];
+            uint32_t lo = 0xffffffffu, hi = 0u;
+#pragma unroll
+            for (int r = 0; r < SR_PREFILTER_REGS; ++r) {
+                const int c = r * T + tid;
+                mine[r] = c < nk ? ckey[c] : 0ull;
+                if (c < nk) {
+                    const uint32_t sc = (uint32_t)(mine[r] >> 32);
+                    lo = sc < lo ? sc : lo;
+                    hi = sc > hi ? sc : hi;
+                }
+            }
+#pragma unroll
+            for (int d = 1; d < RA_WAVE; d <<= 1) {
+                const uint32_t ol = __shfl_xor(lo, d), oh = __shfl_xor(hi, d);
+                lo = ol < lo ? ol : lo;
+                hi = oh > hi ? oh : hi;
+            }
+            if (lane == 0) {
+                atomicMin(reinterpret_cast<unsigned int*>(&ctr[C_LO]), lo);
+                atomicMax(reinterpret_cast<unsigned int*>(&ctr[C_HI]), hi);
+            }
+            if (tid < 256) cid[tid] = 0;
+            __syncthreads();
+            // bin = (score - lowest) * 255 / (highest - lowest), truncated: every operation is
+            // monotone in the score, so a larger score never lands in a lower bin. Non-finite
+            // scores (from non-finite inputs) leave the factor at zero: one bin, everything survives.
+            const float lo_f = f32_from_ordered((uint32_t)ctr[C_LO]);
+            const float width = f32_from_ordered((uint32_t)ctr[C_HI]) - lo_f;
+            const float to_bin = width > 0.f && width < INFINITY ? 255.0f / width : 0.f;
+            int bin[SR_PREFILTER_REGS];
+#pragma unroll
+            for (int r = 0; r < SR_PREFILTER_REGS; ++r) {
+                const float b = (f32_from_ordered((uint32_t)(mine[r] >> 32)) - lo_f) * to_bin;
+                bin[r] = b >= 255.f ? 255 : b > 0.f ? (int)b : 0;
+                if (r * T + tid < nk) atomicAdd(&cid[bin[r]], 1);
+            }
+            __syncthreads();
+            if (wv == 0) {
+                // lane l owns bins 4l .. 4l + 3; candidates in the bins from b up = total - (those below b)
+                const int b0 = cid[4 * lane], b1 = cid[4 * lane + 1], b2 = cid[4 * lane + 2], b3 = cid[4 * lane + 3];
+                const int incl = wave_incl_scan(b0 + b1 + b2 + b3);
+                const int total = __builtin_amdgcn_readlane(incl, RA_WAVE - 1);
+                const int from3 = total - incl + b3, from2 = from3 + b2, from1 = from2 + b1, from0 = from1 + b0;
+                const int best = from3 >= ef ? 3 : from2 >= ef ? 2 : from1 >= ef ? 1 : from0 >= ef ? 0 : -1;
+                const u64 has = __ballot(best >= 0);          // never empty: bin 0 and up hold all nk > ef
+                if (lane == 63 - __clzll(has)) ctr[C_BIN] = 4 * lane + best;
+            }
+            __syncthreads();
+            const int bstar = ctr[C_BIN];
+#pragma unroll
+            for (int r = 0; r < SR_PREFILTER_REGS; ++r)
+                if (r * T + tid < nk && bin[r] >= bstar) ckey[atomicAdd(&ctr[C_NSURV], 1)] = mine[r];
+            __syncthreads();
+            nk = ctr[C_NSURV];
+        }
+        SR_TICK(11);
 
         // ---- merge by rank into the other beam buffer, truncating at ef. The final position of
         //      an element of (beam u kept candidates) is the number of elements that beat it.
