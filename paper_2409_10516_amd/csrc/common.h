@@ -29,7 +29,9 @@ void ra_set_error(const char* fmt, ...);
     } while (0)
 
 // ---- LDS above 64 KB ------------------------------------------------------------------
+#ifndef RA_LDS_LIMIT
 #define RA_LDS_LIMIT (160 * 1024)     // LDS a workgroup can have on this part (above 64 KB: opt-in)
+#endif
 #define RA_MAX_DEVICES 64
 // A kernel that wants more than 64 KB of dynamic LDS has to say so once per device (host side).
 #define RA_LDS_OPT_IN(KERNEL, BYTES)                                                               \

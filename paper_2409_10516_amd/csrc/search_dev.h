@@ -47,20 +47,32 @@ typedef unsigned long long u64;
 #define SR_NPHASE 13
 #define SR_NITER 16
 static __device__ long long sr_phase_ticks[64 * SR_NITER * SR_NPHASE];
-#define SR_TICK_INIT long long tick_ = clock64(); int tick_it_ = 0
+// ticks are added up in LDS (a fire-and-forget add) and copied out when the search has ended
+#define SR_TICK_INIT                                                                           \
+    __shared__ long long tick_lds_[SR_NITER * SR_NPHASE];                                      \
+    for (int i_ = threadIdx.x; i_ < SR_NITER * SR_NPHASE; i_ += blockDim.x) tick_lds_[i_] = 0; \
+    __syncthreads();                                                                           \
+    long long tick_ = clock64(); int tick_it_ = 0
 #define SR_TICK_ITER(i) tick_it_ = (i) < SR_NITER ? (i) : SR_NITER - 1
 #define SR_TICK(p)                                                                             \
     do {                                                                                       \
-        if (threadIdx.x == 0 && blockIdx.x < 64) {                                             \
+        if (threadIdx.x == 0) {                                                                \
             const long long now_ = clock64();                                                  \
-            sr_phase_ticks[(blockIdx.x * SR_NITER + tick_it_) * SR_NPHASE + (p)] += now_ - tick_; \
+            tick_lds_[tick_it_ * SR_NPHASE + (p)] += now_ - tick_;                             \
             tick_ = now_;                                                                      \
         }                                                                                      \
+    } while (0)
+#define SR_TICK_FLUSH                                                                          \
+    do {                                                                                       \
+        if (blockIdx.x < 64)                                                                   \
+            for (int i_ = threadIdx.x; i_ < SR_NITER * SR_NPHASE; i_ += blockDim.x)            \
+                sr_phase_ticks[blockIdx.x * SR_NITER * SR_NPHASE + i_] += tick_lds_[i_];       \
     } while (0)
 #else
 #define SR_TICK_INIT
 #define SR_TICK_ITER(i)
 #define SR_TICK(p)
+#define SR_TICK_FLUSH
 #endif
 
 __device__ __forceinline__ u64 make_key(float score, int id) {
@@ -323,8 +335,11 @@ __device__ __forceinline__ int run_search(
         if (tid == 0) {
             urank[0] = 0;
             ctr[C_NCAND] = n_root;
-            ctr[C_NKEEP] = 0;
+            ctr[C_NKEEP] = n_root;           // every key of a start set is kept (scored below)
             ctr[C_NUNEXP] = 0;
+            ctr[C_LO] = -1;
+            ctr[C_HI] = 0;
+            ctr[C_NSURV] = 0;
         }
         bn = 0; n_visited = 0; n_expanded = 0; n_iters = 0;
     } else {
@@ -359,6 +374,7 @@ __device__ __forceinline__ int run_search(
         //      memory for 1024 threads). The beam is empty, so every key is kept; the first
         //      n_first of a root set enter as expanded.
         constexpr int SEED_ROWS = KT == RA_F32 ? SR_UNROLL : 2 * SR_UNROLL;
+        uint32_t lo = 0xffffffffu, hi = 0u;                  // of the ordered score bits (see the pre-filter)
         for (int c0 = 0; c0 < n_root; c0 += (T / 16) * SEED_ROWS) {
             RowBits<KT> rows[SEED_ROWS];
 #pragma unroll
@@ -375,9 +391,19 @@ __device__ __forceinline__ int run_search(
                 if (lane16 == 0 && c < n_root) {
                     u64 key = make_key(sc, cid[c]);
                     if (c < n_first) key &= ~1ull;
-                    ckey[atomicAdd(&ctr[C_NKEEP], 1)] = key;
+                    ckey[c] = key;                           // all are kept: no counter needed
+                    const uint32_t so = (uint32_t)(key >> 32);
+                    lo = so < lo ? so : lo;
+                    hi = so > hi ? so : hi;
                 }
             }
+        }
+        // lanes 0, 16, 32, 48 of a wavefront hold the extremes of its keys
+        lo = min(lo, (uint32_t)__shfl_xor((int)lo, 16)); lo = min(lo, (uint32_t)__shfl_xor((int)lo, 32));
+        hi = max(hi, (uint32_t)__shfl_xor((int)hi, 16)); hi = max(hi, (uint32_t)__shfl_xor((int)hi, 32));
+        if (lane == 0) {
+            atomicMin(reinterpret_cast<unsigned int*>(&ctr[C_LO]), lo);
+            atomicMax(reinterpret_cast<unsigned int*>(&ctr[C_HI]), hi);
         }
     }
     SR_TICK(5);
@@ -472,9 +498,11 @@ __device__ __forceinline__ int run_search(
         SR_TICK(1);
         if (tid == 0) {
             ctr[C_NUNEXP] = 0;               // everyone read it before the barrier above
-            ctr[C_LO] = -1;                  // (as unsigned: the largest value) see the pre-filter below
-            ctr[C_HI] = 0;
-            ctr[C_NSURV] = 0;
+            if (!first) {                    // (a start set's extremes were collected while it was scored)
+                ctr[C_LO] = -1;              // as unsigned: the largest value; see the pre-filter below
+                ctr[C_HI] = 0;
+                ctr[C_NSURV] = 0;
+            }
         }
         early_acc ^= early_a ^ early_b;      // issued a phase or more ago
         early_a = early_b = 0u;
@@ -531,15 +559,17 @@ __device__ __forceinline__ int run_search(
                     hi = sc > hi ? sc : hi;
                 }
             }
+            if (!first) {                    // (a start set's extremes are known already)
 #pragma unroll
-            for (int d = 1; d < RA_WAVE; d <<= 1) {
-                const uint32_t ol = __shfl_xor(lo, d), oh = __shfl_xor(hi, d);
-                lo = ol < lo ? ol : lo;
-                hi = oh > hi ? oh : hi;
-            }
-            if (lane == 0) {
-                atomicMin(reinterpret_cast<unsigned int*>(&ctr[C_LO]), lo);
-                atomicMax(reinterpret_cast<unsigned int*>(&ctr[C_HI]), hi);
+                for (int d = 1; d < RA_WAVE; d <<= 1) {
+                    const uint32_t ol = __shfl_xor(lo, d), oh = __shfl_xor(hi, d);
+                    lo = ol < lo ? ol : lo;
+                    hi = oh > hi ? oh : hi;
+                }
+                if (lane == 0) {
+                    atomicMin(reinterpret_cast<unsigned int*>(&ctr[C_LO]), lo);
+                    atomicMax(reinterpret_cast<unsigned int*>(&ctr[C_HI]), hi);
+                }
             }
             if (tid < 256) cid[tid] = 0;
             __syncthreads();
@@ -730,6 +760,7 @@ __device__ __forceinline__ int run_search(
     }
     __syncthreads();
     SR_TICK(6);
+    SR_TICK_FLUSH;
     return ctr[C_NKEEP];
 }
 
