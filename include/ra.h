@@ -168,6 +168,12 @@ ra_status ra_full_attention(const void* q, const void* K, const void* V, ra_dtyp
                             int n_q_heads, int n_kv_heads, int64_t N, int d, void* workspace,
                             size_t workspace_bytes, void* stream, float* out, float* lse);
 
+/* Measurement aid: reads the `bytes` bytes at `buf` (device, 16-byte aligned, a multiple of 16)
+ * once with a plain streaming kernel and xors a 64-bit fold of them into *out (device). Timed by
+ * the benchmark, it gives the read bandwidth a streaming kernel sustains on the device, which the
+ * scan kernels above (Sec. 4.1's exact baselines) are compared with. */
+ra_status ra_hbm_read_probe(const void* buf, size_t bytes, void* stream, uint64_t* out);
+
 /* ---- handle management ------------------------------------------------------------- */
 
 /* Build a handle from HOST arrays adj [n_seq*n_q_heads][N][deg], entries [n_seq*n_q_heads]

@@ -91,6 +91,7 @@ def lib() -> C.CDLL:
     L.ra_flat_topk.restype = i32
     L.ra_full_attention_workspace_bytes.argtypes = [i32, i32, i32, i64]
     L.ra_full_attention_workspace_bytes.restype = C.c_size_t
+    L.ra_hbm_read_probe.argtypes = [vp, C.c_size_t, vp, vp]
     L.ra_full_attention.argtypes = [vp, vp, vp, i32, i32, i32, i32, i64, i32, vp, C.c_size_t, vp, vp, vp]
     L.ra_full_attention.restype = i32
     for name in ("ra_knn", "ra_project", "ra_build_index", "ra_search", "ra_attend",
@@ -345,6 +346,12 @@ def ra_decode_step(q, idx: Index, K, V, sink: int, window: int, topk: int, ef: i
                                           K.shape[2], sink, window, topk, ef, expand, _stream(stream),
                                           _ptr(out), _ptr(lse), _ptr(ids), _ptr(stats)))
     return out, lse, ids, stats
+
+
+def ra_hbm_read_probe(buf: torch.Tensor, out: torch.Tensor, stream=None) -> None:
+    """Stream `buf` (contiguous device tensor) once; xors a fold of it into out (device int64 [1])."""
+    _dev(buf, out)
+    _check(lib().ra_hbm_read_probe(_ptr(buf), buf.numel() * buf.element_size(), _stream(stream), _ptr(out)))
 
 
 def ra_flat_topk(q, K, sink: int, window: int, topk: int, stream=None, workspace=None, ids=None):

@@ -551,6 +551,13 @@ extern "C" ra_status ra_flat_topk(const void* q, const void* K, ra_dtype dt, int
                                (uint32_t*)workspace, (hipStream_t)stream, ids);
 }
 
+extern "C" ra_status ra_hbm_read_probe(const void* buf, size_t bytes, void* stream, uint64_t* out) {
+    if (!buf || !out) RA_FAIL(RA_EINVAL, "NULL argument");
+    if (bytes < 16 || (bytes & 15) || ((uintptr_t)buf & 15))
+        RA_FAIL(RA_EINVAL, "the buffer must be 16-byte aligned and a multiple of 16 bytes long");
+    return ra_launch_read_probe(buf, bytes, (hipStream_t)stream, reinterpret_cast<unsigned long long*>(out));
+}
+
 extern "C" size_t ra_full_attention_workspace_bytes(int n_seq, int n_q_heads, int n_kv_heads,
                                                      int64_t N) {
     if (n_seq < 1 || n_q_heads < 1 || n_kv_heads < 1 || N < 1) return 0;

@@ -405,3 +405,43 @@ ra_status ra_launch_flat_topk(const void* q, const void* K, ra_dtype dt, int n_s
     RA_HIP(hipGetLastError());
     return RA_OK;
 }
+
+
+// ---- streaming-read probe ---------------------------------------------------------------------
+// Reads a buffer once, start to end, and folds it into one word: what a read-only streaming kernel
+// sustains on the device, the yardstick the scan kernels above are compared with. 256 threads per
+// workgroup, 16 bytes per lane and load, 8 loads in flight, consecutive wavefronts on consecutive
+// kilobytes; the grid walks the buffer in strides.
+#define PR_THREADS 256
+#define PR_LOADS 8
+__global__ __launch_bounds__(PR_THREADS) void read_probe_kernel(const uint4* __restrict__ p, size_t n16,
+                                                                unsigned long long* __restrict__ out) {
+    const size_t stride = (size_t)gridDim.x * PR_THREADS;
+    uint4 acc = make_uint4(0u, 0u, 0u, 0u);
+    for (size_t i = (size_t)blockIdx.x * PR_THREADS + threadIdx.x; i < n16; i += stride * PR_LOADS) {
+        uint4 v[PR_LOADS];
+#pragma unroll
+        for (int u = 0; u < PR_LOADS; ++u) {
+            const size_t j = i + u * stride;
+            v[u] = p[j < n16 ? j : i];                       // loads stay unconditional
+        }
+#pragma unroll
+        for (int u = 0; u < PR_LOADS; ++u)
+            if (i + u * stride < n16) { acc.x ^= v[u].x; acc.y ^= v[u].y; acc.z ^= v[u].z; acc.w ^= v[u].w; }
+    }
+    unsigned long long w = ((unsigned long long)(acc.x ^ acc.z) << 32) | (acc.y ^ acc.w);
+#pragma unroll
+    for (int d = 1; d < RA_WAVE; d <<= 1) w ^= __shfl_xor(w, d);
+    if ((threadIdx.x & (RA_WAVE - 1)) == 0) atomicXor(out, w);
+}
+
+ra_status ra_launch_read_probe(const void* buf, size_t bytes, hipStream_t st, unsigned long long* out) {
+    const size_t n16 = bytes / 16;
+    size_t blocks = (n16 + (size_t)PR_THREADS * PR_LOADS - 1) / ((size_t)PR_THREADS * PR_LOADS);
+    if (blocks > 256 * 16) blocks = 256 * 16;                // 16 workgroups per compute unit
+    if (blocks < 1) blocks = 1;
+    hipLaunchKernelGGL(read_probe_kernel, dim3((unsigned)blocks), dim3(PR_THREADS), 0, st,
+                       reinterpret_cast<const uint4*>(buf), n16, out);
+    RA_HIP(hipGetLastError());
+    return RA_OK;
+}
