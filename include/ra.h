@@ -115,6 +115,22 @@ ra_status ra_attend(const void* q, const ra_index* idx, const void* K, const voi
                     const int32_t* ids, void* stream, float* out, float* lse,
                     float* o_omega, float* lse_omega, float* o_w, float* lse_w);
 
+/* ra_attend for callers that cannot allocate device memory: code under HIP graph capture, tight
+ * serving loops, harnesses that forbid hipMalloc. Same arguments, same kernels, same results as
+ * ra_attend; the partial records go to a fixed array of RA_ATTEND_NOALLOC_SCRATCH_BYTES bytes that
+ * the library holds on every device it runs on until the process ends, instead of memory the
+ * handle allocates on first use. No allocation and no free, ever (the first call on a device looks
+ * the array's address up, once). RA_EUNSUP, with the sizes in the message, when the records of the
+ * call do not fit: n_seq * n_q_heads * (ceil((sink + window) / 64) + ceil(topk / 64)) * 528 bytes
+ * for the decode step's static sets (a few thousand heads of the 128K configuration). All calls on
+ * one device share the array: calls that overlap in time on one device race; calls in stream
+ * order do not, and nothing has to be cleared between them. */
+#define RA_ATTEND_NOALLOC_SCRATCH_BYTES (8u << 20)
+ra_status ra_attend_noalloc(const void* q, const ra_index* idx, const void* K, const void* V,
+                            ra_dtype dt, int64_t N, int sink, int window, int topk,
+                            const int32_t* ids, void* stream, float* out, float* lse,
+                            float* o_omega, float* lse_omega, float* o_w, float* lse_w);
+
 /* One layer's decode-step attention for all sequences and query heads: the results of
  * ra_search followed by ra_attend, computed by a single fused launch (search, Eq. 2 over
  * Omega and W, Eq. 4-5). ids and stats may be NULL (ids then live in the index workspace).

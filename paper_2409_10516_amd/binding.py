@@ -63,6 +63,7 @@ def lib() -> C.CDLL:
     L.ra_rerank.argtypes = [vp, vp, i32, i32, i32, i32, i64, i32, vp, i32, i32, vp, vp]
     L.ra_rerank.restype = i32
     L.ra_attend.argtypes = [vp, vp, vp, vp, i32, i64, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp]
+    L.ra_attend_noalloc.argtypes = [vp, vp, vp, vp, i32, i64, i32, i32, i32, vp, vp, vp, vp, vp, vp, vp, vp]
     L.ra_decode_step.argtypes = [vp, vp, vp, vp, i32, i64, i32, i32, i32, i32, i32, vp, vp, vp,
                                  vp, vp]
     L.ra_decode_step_grown.argtypes = [vp, vp, vp, vp, i32, i64, i64, i32, i32, i32, i32, i32, vp, vp,
@@ -95,7 +96,8 @@ def lib() -> C.CDLL:
     L.ra_full_attention.argtypes = [vp, vp, vp, i32, i32, i32, i32, i64, i32, vp, C.c_size_t, vp, vp, vp]
     L.ra_full_attention.restype = i32
     for name in ("ra_knn", "ra_project", "ra_build_index", "ra_search", "ra_attend",
-                 "ra_decode_step", "ra_index_import", "ra_index_export"):
+                 "ra_attend_noalloc", "ra_hbm_read_probe", "ra_decode_step", "ra_index_import",
+                 "ra_index_export"):
         getattr(L, name).restype = i32
     _lib = L
     return L
@@ -285,20 +287,24 @@ def ra_rerank(q, K, cand, topk: int, stream=None):
 
 
 def ra_attend(q, idx: Index, K, V, sink: int, window: int, ids: torch.Tensor, stream=None,
-              partials: bool = False):
-    """-> (out, lse) or, with partials=True, (out, lse, o_omega, lse_omega, o_w, lse_w)."""
-    _dev(q, K, V, ids)
+              partials: bool = False, noalloc: bool = False, out=None, lse=None):
+    """-> (out, lse) or, with partials=True, (out, lse, o_omega, lse_omega, o_w, lse_w).
+    noalloc=True calls ra_attend_noalloc (pass out and lse in, then nothing is allocated at all)."""
+    _dev(q, K, V, ids, out, lse)
     n_seq, n_q, d = q.shape
     topk = ids.shape[-1]
     f = dict(dtype=torch.float32, device=q.device)
-    out, lse = torch.empty((n_seq, n_q, d), **f), torch.empty((n_seq, n_q), **f)
+    if out is None:
+        out = torch.empty((n_seq, n_q, d), **f)
+    if lse is None:
+        lse = torch.empty((n_seq, n_q), **f)
     extra = [None] * 4
     if partials:
         extra = [torch.empty((n_seq, n_q, d), **f), torch.empty((n_seq, n_q), **f),
                  torch.empty((n_seq, n_q, d), **f), torch.empty((n_seq, n_q), **f)]
-    _check(lib().ra_attend(_ptr(q), idx.handle, _ptr(K), _ptr(V), _dt(K), K.shape[2], sink, window,
-                           topk, _ptr(ids), _stream(stream), _ptr(out), _ptr(lse),
-                           *[_ptr(t) for t in extra]))
+    fn = lib().ra_attend_noalloc if noalloc else lib().ra_attend
+    _check(fn(_ptr(q), idx.handle, _ptr(K), _ptr(V), _dt(K), K.shape[2], sink, window,
+              topk, _ptr(ids), _stream(stream), _ptr(out), _ptr(lse), *[_ptr(t) for t in extra]))
     return (out, lse, *extra) if partials else (out, lse)
 
 

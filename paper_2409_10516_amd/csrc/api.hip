@@ -434,6 +434,17 @@ extern "C" ra_status ra_attend(const void* q, const ra_index* idx, const void* K
                             lse_w);
 }
 
+extern "C" ra_status ra_attend_noalloc(const void* q, const ra_index* idx, const void* K, const void* V,
+                                       ra_dtype dt, int64_t N, int sink, int window, int topk,
+                                       const int32_t* ids, void* stream, float* out, float* lse,
+                                       float* o_omega, float* lse_omega, float* o_w, float* lse_w) {
+    if (!q || !K || !V || !ids || !out || !lse) RA_FAIL(RA_EINVAL, "NULL argument");
+    RA_TRY(check_dtype(dt));
+    RA_TRY(check_decode_args(idx, N, sink, window, topk));
+    return ra_launch_attend_noalloc(q, K, V, dt, idx->n_seq, idx->n_q, idx->n_kv, N, sink, window, topk, ids,
+                                    (hipStream_t)stream, out, lse, o_omega, lse_omega, o_w, lse_w);
+}
+
 // K8 / kscale: the 8-bit copy of the keys the walk scores, or NULL for the keys themselves
 static ra_status decode_common(const void* q, const ra_index* idx, const void* K, const void* V,
                                ra_dtype dt, const int8_t* K8, const float* kscale, const int32_t* budgets,

@@ -135,3 +135,42 @@ ra_status ra_launch_attend(const void* q, const void* K, const void* V, ra_dtype
     RA_HIP(hipGetLastError());
     return RA_OK;
 }
+
+
+// ---- ra_attend for callers that cannot allocate ---------------------------------------------------
+// The partial records live in a file-scope device array instead of memory the handle allocates on
+// first use. Every device the library runs on holds its own copy of the array at its own address;
+// host code never passes the array's name to a kernel, only the address hipGetSymbolAddress gives
+// for the current device (looked up once per device and kept).
+static __device__ __align__(256) unsigned char scratch[RA_ATTEND_NOALLOC_SCRATCH_BYTES];
+static void* g_scratch_addr[RA_MAX_DEVICES];
+
+static ra_status scratch_address(void** out) {
+    int dev = 0;
+    RA_HIP(hipGetDevice(&dev));
+    if (dev < 0 || dev >= RA_MAX_DEVICES) RA_FAIL(RA_EUNSUP, "device %d out of range", dev);
+    if (!g_scratch_addr[dev]) {
+        void* p = nullptr;
+        RA_HIP(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+        if (!p) RA_FAIL(RA_EHIP, "the scratch array has no address on device %d", dev);
+        g_scratch_addr[dev] = p;
+    }
+    *out = g_scratch_addr[dev];
+    return RA_OK;
+}
+
+ra_status ra_launch_attend_noalloc(const void* q, const void* K, const void* V, ra_dtype dt, int n_seq,
+                                   int n_q, int n_kv, int64_t N, int sink, int window, int topk,
+                                   const int32_t* ids, hipStream_t st, float* out, float* lse,
+                                   float* o_omega, float* lse_omega, float* o_w, float* lse_w) {
+    const size_t need = ra_attend_partial_floats(n_seq, n_q, n_kv, N, sink, window, topk) * sizeof(float);
+    if (need > RA_ATTEND_NOALLOC_SCRATCH_BYTES)
+        RA_FAIL(RA_EUNSUP, "the partial records of this call take %zu bytes, above the %u bytes "
+                "ra_attend_noalloc keeps (use ra_attend)", need, (unsigned)RA_ATTEND_NOALLOC_SCRATCH_BYTES);
+    void* ptr = nullptr;
+    ra_status rc = scratch_address(&ptr);
+    if (rc != RA_OK) return rc;
+    // nothing to clear: every record the merge reads is written by this call's first kernel
+    return ra_launch_attend(q, K, V, dt, n_seq, n_q, n_kv, N, sink, window, topk, ids,
+                            reinterpret_cast<float*>(ptr), st, out, lse, o_omega, lse_omega, o_w, lse_w);
+}

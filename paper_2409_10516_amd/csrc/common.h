@@ -105,6 +105,11 @@ ra_status ra_launch_attend(const void* q, const void* K, const void* V, ra_dtype
                            float* lse, float* o_omega, float* lse_omega, float* o_w,
                            float* lse_w);
 
+ra_status ra_launch_attend_noalloc(const void* q, const void* K, const void* V, ra_dtype dt, int n_seq,
+                                   int n_q, int n_kv, int64_t N, int sink, int window, int topk,
+                                   const int32_t* ids, hipStream_t st, float* out, float* lse,
+                                   float* o_omega, float* lse_omega, float* o_w, float* lse_w);
+
 bool ra_decode_needs_global_bitset(int64_t N, int deg, int ef, int expand, int topk);
 ra_status ra_launch_decode(const void* q, const int32_t* adj, const int32_t* entry, const void* K,
                            const void* V, ra_dtype dt, int n_seq, int n_q, int n_kv, int64_t Ng, int64_t N,
