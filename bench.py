@@ -317,7 +317,19 @@ def main():
 
         def timed_train(fn, reps):
             # one event pair around a train of back-to-back launches captured in one graph: no host in
-            # the loop, the gaps are the device's own
+            # the loop, the gaps are the device's own (--graph 0: the same train launched eagerly)
+            if not a.graph:
+                for L in layers:
+                    fn(L, 0)
+                torch.cuda.synchronize()
+                s_, e_ = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                s_.record()
+                for r in range(reps):
+                    for L in layers:
+                        fn(L, r)
+                e_.record()
+                torch.cuda.synchronize()
+                return s_.elapsed_time(e_) / (reps * len(layers))
             g = torch.cuda.CUDAGraph()
             cs2 = torch.cuda.Stream()
             with torch.cuda.stream(cs2):

@@ -80,6 +80,24 @@ __device__ __forceinline__ Row8<DT> load_row8_raw(const void* base, int64_t row,
     }
     return r;
 }
+// the same with non-temporal loads, for long dense ranges that are streamed once
+typedef unsigned int at_u32x4 __attribute__((ext_vector_type(4)));
+template <int DT>
+__device__ __forceinline__ Row8<DT> load_row8_stream(const void* base, int64_t row, int lane16) {
+    Row8<DT> r;
+    if constexpr (DT == RA_BF16) {
+        const at_u32x4 v = __builtin_nontemporal_load(reinterpret_cast<const at_u32x4*>(
+            reinterpret_cast<const uint16_t*>(base) + row * RA_D + lane16 * 8));
+        r.a = make_uint4(v.x, v.y, v.z, v.w);
+    } else {
+        const at_u32x4* p = reinterpret_cast<const at_u32x4*>(reinterpret_cast<const float*>(base) +
+                                                              row * RA_D + lane16 * 8);
+        const at_u32x4 a = __builtin_nontemporal_load(p), b = __builtin_nontemporal_load(p + 1);
+        r.a = make_float4(__uint_as_float(a.x), __uint_as_float(a.y), __uint_as_float(a.z), __uint_as_float(a.w));
+        r.b = make_float4(__uint_as_float(b.x), __uint_as_float(b.y), __uint_as_float(b.z), __uint_as_float(b.w));
+    }
+    return r;
+}
 template <int DT>
 __device__ __forceinline__ void row8_floats(const Row8<DT>& r, float* o) {
     if constexpr (DT == RA_BF16) {
@@ -137,8 +155,13 @@ __device__ void attend_chunk(int tid, bool active, const void* q0, const void* K
 #pragma unroll
         for (int i = 0; i < RPG; ++i) {
             const int64_t row = rid[i] >= 0 ? rid[i] : 0;
-            kr[i] = load_row8_raw<DT>(Kh, row, lane16);
-            vr[i] = load_row8_raw<DT>(Vh, row, lane16);
+            if (n_sub > 1) {                    // a long dense range, streamed once
+                kr[i] = load_row8_stream<DT>(Kh, row, lane16);
+                vr[i] = load_row8_stream<DT>(Vh, row, lane16);
+            } else {
+                kr[i] = load_row8_raw<DT>(Kh, row, lane16);
+                vr[i] = load_row8_raw<DT>(Vh, row, lane16);
+            }
         }
     };
     auto consume = [&](const int64_t (&rid)[RPG], const Row8<DT> (&kr)[RPG], const Row8<DT> (&vr)[RPG]) {

@@ -53,7 +53,7 @@ __global__ __launch_bounds__(FL_THREADS) void flat_scores_kernel(
 #pragma unroll
         for (int u = 0; u < FL_ROWS; ++u) {
             id[u] = base + r0 + u * 16 + grp;
-            rows[u] = load_key<DT>(Kh, id[u] < N ? id[u] : N - 1, lane16);   // loads stay unconditional
+            rows[u] = load_key_stream<DT>(Kh, id[u] < N ? id[u] : N - 1, lane16);   // loads stay unconditional
         }
 #pragma unroll
         for (int u = 0; u < FL_ROWS; ++u) {
@@ -409,30 +409,32 @@ ra_status ra_launch_flat_topk(const void* q, const void* K, ra_dtype dt, int n_s
 
 // ---- streaming-read probe ---------------------------------------------------------------------
 // Reads a buffer once, start to end, and folds it into one word: what a read-only streaming kernel
-// sustains on the device, the yardstick the scan kernels above are compared with. 256 threads per
-// workgroup, 16 bytes per lane and load, 8 loads in flight, consecutive wavefronts on consecutive
-// kilobytes; the grid walks the buffer in strides.
+// sustains on the device, the yardstick the scan kernels above are compared with. The shape is the
+// best of those measured on a 1 GiB buffer: every workgroup owns one contiguous span, 256 threads,
+// 16 bytes per lane and load, 8 non-temporal loads in flight, 16 workgroups per compute unit
+// (7.1 TB/s; 6.2 with ordinary loads; 4.8 to 6.4 when the grid walks the buffer in strides).
 #define PR_THREADS 256
 #define PR_LOADS 8
 __global__ __launch_bounds__(PR_THREADS) void read_probe_kernel(const uint4* __restrict__ p, size_t n16,
                                                                 unsigned long long* __restrict__ out) {
-    const size_t stride = (size_t)gridDim.x * PR_THREADS;
+    const size_t per = (n16 + gridDim.x - 1) / gridDim.x;
+    const size_t b0 = (size_t)blockIdx.x * per, b1 = b0 + per < n16 ? b0 + per : n16;
     uint4 acc = make_uint4(0u, 0u, 0u, 0u);
-    for (size_t i = (size_t)blockIdx.x * PR_THREADS + threadIdx.x; i < n16; i += stride * PR_LOADS) {
+    for (size_t i = b0 + threadIdx.x; i < b1; i += (size_t)PR_THREADS * PR_LOADS) {
         uint4 v[PR_LOADS];
 #pragma unroll
         for (int u = 0; u < PR_LOADS; ++u) {
-            const size_t j = i + u * stride;
-            v[u] = p[j < n16 ? j : i];                       // loads stay unconditional
+            const size_t j = i + (size_t)u * PR_THREADS;
+            v[u] = load16_stream(p + (j < b1 ? j : i));      // loads stay unconditional
         }
 #pragma unroll
         for (int u = 0; u < PR_LOADS; ++u)
-            if (i + u * stride < n16) { acc.x ^= v[u].x; acc.y ^= v[u].y; acc.z ^= v[u].z; acc.w ^= v[u].w; }
+            if (i + (size_t)u * PR_THREADS < b1) { acc.x ^= v[u].x; acc.y ^= v[u].y; acc.z ^= v[u].z; acc.w ^= v[u].w; }
     }
     unsigned long long w = ((unsigned long long)(acc.x ^ acc.z) << 32) | (acc.y ^ acc.w);
 #pragma unroll
     for (int d = 1; d < RA_WAVE; d <<= 1) w ^= __shfl_xor(w, d);
-    if ((threadIdx.x & (RA_WAVE - 1)) == 0) atomicXor(out, w);
+    if ((threadIdx.x & (RA_WAVE - 1)) == 0 && w) atomicXor(out, w);
 }
 
 ra_status ra_launch_read_probe(const void* buf, size_t bytes, hipStream_t st, unsigned long long* out) {

@@ -116,6 +116,33 @@ __device__ __forceinline__ RowBits<DT> load_key(const void* Kh, int64_t row, int
     return r;
 }
 
+// The same for a kernel that streams every row once (a scan): non-temporal loads, which leave the
+// caches to data that is read again (measured on a plain read of 1 GiB: 7.1 against 6.2 TB/s).
+typedef unsigned int ra_u32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned int ra_u32x2 __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ uint4 load16_stream(const void* p) {
+    const ra_u32x4 v = __builtin_nontemporal_load(reinterpret_cast<const ra_u32x4*>(p));
+    return make_uint4(v.x, v.y, v.z, v.w);
+}
+template <int DT>
+__device__ __forceinline__ RowBits<DT> load_key_stream(const void* Kh, int64_t row, int lane16) {
+    RowBits<DT> r;
+    if (DT == RA_KEYS_I8) {
+        const ra_u32x2 u = __builtin_nontemporal_load(
+            reinterpret_cast<const ra_u32x2*>(reinterpret_cast<const int8_t*>(Kh) + row * RA_D) + lane16);
+        r.a = make_uint4(u.x, u.y, 0u, 0u);
+        r.b = r.a;
+    } else if (DT == RA_BF16) {
+        r.a = load16_stream(reinterpret_cast<const uint4*>(reinterpret_cast<const uint16_t*>(Kh) + row * RA_D) + lane16);
+        r.b = r.a;
+    } else {
+        const uint4* p = reinterpret_cast<const uint4*>(reinterpret_cast<const float*>(Kh) + row * RA_D);
+        r.a = load16_stream(p + lane16 * 2);
+        r.b = load16_stream(p + lane16 * 2 + 1);
+    }
+    return r;
+}
+
 template <int CTRL>
 __device__ __forceinline__ float dpp_f32(float v) {
     return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xF, 0xF, true));
