@@ -39,10 +39,10 @@ __global__ __launch_bounds__(FL_THREADS) void flat_scores_kernel(
     const int kvh = blockIdx.y / kv_div, seq = blockIdx.z, h0 = seq * n_q + blockIdx.y * G;
     const size_t esz = DT == RA_BF16 ? 2 : 4;
     const char* Kh = reinterpret_cast<const char*>(K) + ((size_t)seq * n_kv + kvh) * N * RA_D * esz;
-    float qv[G][8];
+    ScoreQuery<DT> qv[G];
 #pragma unroll
     for (int g = 0; g < G; ++g)
-        load_q8<DT>(reinterpret_cast<const char*>(q) + (size_t)(h0 + g) * RA_D * esz, lane16, qv[g]);
+        load_score_query<DT, DT>(reinterpret_cast<const char*>(q) + (size_t)(h0 + g) * RA_D * esz, lane16, qv[g]);
     const int64_t base = (int64_t)blockIdx.x * FL_CHUNK;
     uint32_t best[G];
 #pragma unroll
@@ -318,8 +318,8 @@ __global__ __launch_bounds__(RR_THREADS) void rerank_kernel(const void* __restri
     const char* Kh = reinterpret_cast<const char*>(K) + ((size_t)seq * n_kv + kvh) * N * RA_D * esz;
     const int32_t* ch = cand + (size_t)head * n_cand;
     int32_t* out = ids + (size_t)head * topk;
-    float qv[8];
-    load_q8<DT>(reinterpret_cast<const char*>(q) + (size_t)head * RA_D * esz, lane16, qv);
+    ScoreQuery<DT> qv;
+    load_score_query<DT, DT>(reinterpret_cast<const char*>(q) + (size_t)head * RA_D * esz, lane16, qv);
     if (tid == 0) n_valid = 0;
     __syncthreads();
     for (int c0 = 0; c0 < n_cand; c0 += 16 * RR_ROWS) {

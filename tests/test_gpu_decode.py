@@ -71,9 +71,13 @@ def test_search_against_the_float64_oracle(name, expand):
 @pytest.mark.parametrize("name", list(_cases()))
 @pytest.mark.parametrize("expand", [1, 32])
 def test_search_bit_exact_against_the_fixed_order_float32_scores(name, expand):
-    """The kernel adds its 128 products in a documented order; the oracle's opt-in float32 score
-    adds in that order, and then every id and counter must agree with no allowance at all."""
+    """For float32 inputs the kernel adds its 128 products in a documented order; the oracle's opt-in
+    float32 score adds in that order, and then every id and counter must agree with no allowance at
+    all. (bf16 inputs go through the two-element dot instruction, whose internal rounding has no
+    float32 formula: they are covered by the float64 rule alone, unless integer-valued.)"""
     w, adj, ent, idx, Kd, Vd = _prepared(name)
+    if w.K.dtype != torch.float32 and not integer_valued(to_np(w.K), to_np(w.q_decode)):
+        pytest.skip("bf16 scores use the hardware's dot instruction; see the float64 test")
     n_seq, n_kv, N, d = w.K.shape
     n_q = w.Q_prefill.shape[1]
     W = OA.static_ids(N, w.sink, w.window)
