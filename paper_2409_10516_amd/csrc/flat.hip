@@ -9,8 +9,8 @@
 //      as the graph search, so both rank keys identically); writes one order-preserving uint32
 //      per (head, key), 0 for keys of the static set W, which retrieval must not return, and
 //      the largest of them per tile: the FL_TILE keys that one 16-lane group scores in a chunk
-//      (ids congruent modulo 16 within the chunk of FL_CHUNK), so a tile maximum is one
-//      register that never leaves its lane until it is written.
+//      of FL_CHUNK (FL_ROWS consecutive keys out of every 16 x FL_ROWS), so a tile maximum
+//      stays in registers until it is written.
 //   2. flat_select_kernel: one workgroup per head. The topk-th largest tile maximum is a
 //      threshold that at least topk keys reach, so every key of the answer (and every tie of
 //      its last one) lies at or above it, in a tile whose maximum does: only those tiles (about
@@ -26,7 +26,7 @@
 #define FL_CHUNK 512               // keys per workgroup of the scoring kernel
 #define FL_SEL_T 1024
 #define FL_ROWS 8                  // key rows in flight per 16-lane group
-#define FL_TILE (FL_CHUNK / 16)     // keys per tile maximum: chunk base + group + 16 j, j < FL_TILE
+#define FL_TILE (FL_CHUNK / 16)     // keys per tile maximum: chunk base + 128 (j / 8) + 8 group + j % 8, j < FL_TILE
 #define FL_TILES_MAX 8192          // tiles per head the select kernel can list (256K keys)
 
 // grid: x = chunk of FL_CHUNK keys, y = KV head, z = seq. GQA groups of another size than the
@@ -47,27 +47,58 @@ __global__ __launch_bounds__(FL_THREADS) void flat_scores_kernel(
     uint32_t best[G];
 #pragma unroll
     for (int g = 0; g < G; ++g) best[g] = 0u;
+    // A 16-lane group takes FL_ROWS consecutive rows per round (a wavefront 4 x FL_ROWS rows, whole
+    // cache lines either way). Every lane of a group ends up with the same score, so lane u simply
+    // keeps the key of row u: the FL_ROWS keys of a group and head then leave in one store, 32
+    // consecutive keys (128 bytes) per wavefront, with no branch around the scoring.
+    // (the rows of the next round are requested before the current round is scored)
+    RowBits<DT> nxt[FL_ROWS];
+    auto request = [&](int r0) {
+        const int64_t id0 = base + r0 + grp * FL_ROWS;
+#pragma unroll
+        for (int u = 0; u < FL_ROWS; ++u)
+            nxt[u] = load_key_stream<DT>(Kh, id0 + u < N ? id0 + u : N - 1, lane16);   // loads stay unconditional
+    };
+    request(0);
+#pragma unroll
     for (int r0 = 0; r0 < FL_CHUNK; r0 += 16 * FL_ROWS) {
         RowBits<DT> rows[FL_ROWS];
-        int64_t id[FL_ROWS];
+#pragma unroll
+        for (int u = 0; u < FL_ROWS; ++u) rows[u] = nxt[u];
+        if (r0 + 16 * FL_ROWS < FL_CHUNK) request(r0 + 16 * FL_ROWS);
+        const int64_t id0 = base + r0 + grp * FL_ROWS;
+        uint32_t mine[G];
+#pragma unroll
+        for (int g = 0; g < G; ++g) mine[g] = 0u;
 #pragma unroll
         for (int u = 0; u < FL_ROWS; ++u) {
-            id[u] = base + r0 + u * 16 + grp;
-            rows[u] = load_key_stream<DT>(Kh, id[u] < N ? id[u] : N - 1, lane16);   // loads stay unconditional
-        }
-#pragma unroll
-        for (int u = 0; u < FL_ROWS; ++u) {
+            const int64_t id = id0 + u;
+            const bool counts = id < N && id >= s && id < N - w;      // keys of W (and past the end) read as 0
 #pragma unroll
             for (int g = 0; g < G; ++g) {
                 const float sc = score_fixed<DT>(rows[u], qv[g]);
-                if (lane16 == 0 && id[u] < N) {
-                    const bool is_static = id[u] < s || id[u] >= N - w;
-                    const uint32_t key = is_static ? 0u : f32_ordered(sc);
-                    keys[(size_t)(h0 + g) * N + id[u]] = key;
-                    best[g] = key > best[g] ? key : best[g];
-                }
+                const uint32_t key = counts ? f32_ordered(sc) : 0u;
+                mine[g] = lane16 == u ? key : mine[g];
             }
         }
+        const int64_t my_id = id0 + lane16;
+        if (lane16 < FL_ROWS && my_id < N) {
+#pragma unroll
+            for (int g = 0; g < G; ++g) {
+                keys[(size_t)(h0 + g) * N + my_id] = mine[g];
+                best[g] = mine[g] > best[g] ? mine[g] : best[g];
+            }
+        }
+    }
+    // the tile maximum: over the lanes of the group that kept keys
+#pragma unroll
+    for (int g = 0; g < G; ++g) {
+        uint32_t m = best[g], o;
+        o = lane_xor32<1>(m, tid); m = o > m ? o : m;
+        o = lane_xor32<2>(m, tid); m = o > m ? o : m;
+        o = lane_xor32<4>(m, tid); m = o > m ? o : m;
+        o = lane_xor32<8>(m, tid); m = o > m ? o : m;
+        best[g] = m;
     }
     if (lane16 == 0) {
         const int64_t tile = (int64_t)blockIdx.x * 16 + grp;
@@ -180,7 +211,7 @@ __global__ __launch_bounds__(FL_SEL_T) void flat_select_kernel(const uint32_t* _
                 for (int u = 0; u < 4; ++u) {                 // loads first, all in flight
                     const int l = l0 + u * TPI + sub;
                     const int64_t tl = s_tl[l < ntl ? l : ntl - 1];
-                    ki[u] = (tl / 16) * FL_CHUNK + (tl % 16) + 16 * kk;
+                    ki[u] = (tl / 16) * FL_CHUNK + (kk / FL_ROWS) * (16 * FL_ROWS) + (tl % 16) * FL_ROWS + kk % FL_ROWS;
                     kv[u] = kh[ki[u] < N ? ki[u] : N - 1];
                 }
 #pragma unroll
