@@ -541,3 +541,32 @@ def test_group_sizes_the_kernels_are_not_specialised_for(n_q, n_kv, dtype):
             topk_equivalent(flat[0, h], ref, qq, K)
     assert not idx.helpers_active
     idx.free()
+
+
+@pytest.mark.parametrize("dtype", [torch.bfloat16, torch.float32])
+def test_root_set_much_larger_than_the_beam(dtype):
+    """A wide graph (deg 64) walked with a narrow beam: the root set (the entry point, its neighbours
+    and theirs, the first 65 entering as expanded) is far larger than ef, so
+    the step that scores it goes through the pre-filter that drops hopeless candidates ahead of the
+    merge. Ids and counters against the oracle's two ordinary steps; real-valued and tie-laden inputs."""
+    for w in (synth.make_llama_layer(61, N=6000, M=1500, T=3, n_q=2, n_kv=1, dtype=dtype, ef=66, topk=30,
+                                     window=50, deg=64, knn=40),
+              synth.make_integer_case(62, N=3000, M=800, T=3, d=128, n_q=1, n_kv=1, dtype=dtype, lo=-2, hi=2,
+                                      deg=64, knn=40, topk=30, ef=66, sink=3, window=10)):
+        adj, ent, _ = oracle_graphs(w)
+        n_q = w.Q_prefill.shape[1]
+        idx = ra.ra_index_import(torch.from_numpy(adj), torch.from_numpy(ent), 1, n_q, 1)
+        Kd, Vd = w.K.to(DEV), w.V.to(DEV)
+        tol = tol_for(dtype)
+        exact = integer_valued(to_np(w.K), to_np(w.q_decode))
+        for t in range(3):
+            out, lse, ids, st = [x.cpu().numpy() for x in ra.ra_decode_step(
+                w.q_decode[t].to(DEV), idx, Kd, Vd, w.sink, w.window, w.topk, w.ef, 64)]
+            for h in range(n_q):
+                first = [int(x) for x in adj[h][ent[h]] if x >= 0]
+                root = {int(ent[h]), *first, *(int(x) for a in first for x in adj[h][a] if x >= 0)}
+                assert len(first) + 1 <= w.ef and len(root) > w.ef + 64      # the pre-filter's condition
+                decode_matches(out[0, h], lse[0, h], ids[0, h], st[0, h].tolist(), to_np(w.q_decode[t, 0, h]),
+                               to_np(w.K[0, 0]), to_np(w.V[0, 0]), adj[h], ent[h], w.sink, w.window, w.topk,
+                               w.ef, 64, tol, exact=exact)
+        idx.free()
