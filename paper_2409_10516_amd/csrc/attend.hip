@@ -64,7 +64,9 @@ __global__ __launch_bounds__(AT_MERGE_SLICES * RA_D) void attend_merge_kernel(
 // 64-row sub-chunks per static workgroup: 1 for the decode step's few hundred static rows, more
 // when the static range is long (full attention), so that a head has at most AT_MAX_STATIC_RECORDS
 // static records to combine. Measured for full attention over 131072 tokens, 8 KV heads (us per
-// layer): 16 or 32 records 166, 64 records 115, 128 records 124, 256 records 137, 512 records 158.
+// layer): 32 records 178, 64 records 115, 128 records 123, 256 records 136 (the kernel's 178 vector
+// registers allow two workgroups per compute unit: 512 workgroups run side by side from start to end;
+// builds held to fewer registers spill and take 150 us and more).
 #ifndef AT_MAX_STATIC_RECORDS
 #define AT_MAX_STATIC_RECORDS 64
 #endif

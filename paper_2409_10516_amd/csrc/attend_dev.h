@@ -164,12 +164,16 @@ __device__ void attend_chunk(int tid, bool active, const void* q0, const void* K
             }
         }
     };
+    // One sub-chunk: the RPG logits of every head first (independent chains the compiler can
+    // interleave), then one move of the running maximum per head and sub-chunk, then the weighted
+    // sums. No branch separates the rows: the dependent latencies of one (row, head) hide behind
+    // the others' work.
     auto consume = [&](const int64_t (&rid)[RPG], const Row8<DT> (&kr)[RPG], const Row8<DT> (&vr)[RPG]) {
+        float z[NH][RPG];
 #pragma unroll
         for (int i = 0; i < RPG; ++i) {
-            float kv[8], vv[8];
+            float kv[8];
             row8_floats<DT>(kr[i], kv);
-            row8_floats<DT>(vr[i], vv);
             const bool have = rid[i] >= 0;
 #pragma unroll
             for (int g = 0; g < NH; ++g) {
@@ -180,22 +184,37 @@ __device__ void attend_chunk(int tid, bool active, const void* q0, const void* K
                 dot += at_dpp<0x4E>(dot);      // xor 2
                 dot += at_dpp<0x141>(dot);     // half-mirror: the other quad pair of the row of 8
                 dot += at_dpp<0x140>(dot);     // mirror: the other half of the row of 16
-                const float z = have ? dot * scale : -INFINITY;
-                // the running maximum settles after a few rows: the sums are rescaled only when
-                // some lane of the wavefront sees a larger logit
-                if (__builtin_amdgcn_ballot_w64(z > m[g]) != 0ull) {
-                    const bool up = z > m[g];                     // other lanes keep their sums
-                    const float corr = up ? at_exp<DT>(m[g] - z) : 1.f;   // exp(-inf) = 0 on the first row
-                    l[g] *= corr;
-#pragma unroll
-                    for (int e = 0; e < 8; ++e) acc[g][e] *= corr;
-                    m[g] = up ? z : m[g];
-                }
-                const float p = have ? at_exp<DT>(z - m[g]) : 0.f;
-                l[g] += p;
-#pragma unroll
-                for (int e = 0; e < 8; ++e) acc[g][e] = fmaf(p, vv[e], acc[g][e]);
+                z[g][i] = have ? dot * scale : -INFINITY;
             }
+        }
+        float p[NH][RPG];
+#pragma unroll
+        for (int g = 0; g < NH; ++g) {
+            float mn = m[g];
+#pragma unroll
+            for (int i = 0; i < RPG; ++i) mn = fmaxf(mn, z[g][i]);
+            // exp(-inf - finite) = 0 rescales the empty sums of the first rows; nothing to do while
+            // every row so far was missing
+            const float corr = mn > -INFINITY ? at_exp<DT>(m[g] - mn) : 1.f;
+            m[g] = mn;
+            float lsum = 0.f;
+#pragma unroll
+            for (int i = 0; i < RPG; ++i) {
+                p[g][i] = z[g][i] > -INFINITY ? at_exp<DT>(z[g][i] - mn) : 0.f;
+                lsum += p[g][i];
+            }
+            l[g] = fmaf(l[g], corr, lsum);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) acc[g][e] *= corr;
+        }
+#pragma unroll
+        for (int i = 0; i < RPG; ++i) {
+            float vv[8];
+            row8_floats<DT>(vr[i], vv);
+#pragma unroll
+            for (int g = 0; g < NH; ++g)
+#pragma unroll
+                for (int e = 0; e < 8; ++e) acc[g][e] = fmaf(p[g][i], vv[e], acc[g][e]);
         }
     };
     {
