@@ -396,6 +396,11 @@ __global__ __launch_bounds__(T) void decode_kernel(
 #ifdef SR_PHASE_CLOCKS
 // Tuning builds only: copy the phase clocks of the fused kernel to `host` (64 x 16 x 8 values: workgroup,
 // search step, phase) and clear them.
+#ifdef SR_WAVE_CLOCKS
+extern "C" int ra_dbg_wave_ticks(long long* host) {
+    return hipMemcpyFromSymbol(host, HIP_SYMBOL(sr_wave_ticks), sizeof(long long) * 64) != hipSuccess;
+}
+#endif
 extern "C" int ra_dbg_phase_ticks(long long* host) {
     if (hipMemcpyFromSymbol(host, HIP_SYMBOL(sr_phase_ticks), sizeof(long long) * 64 * SR_NITER * SR_NPHASE) != hipSuccess)
         return 1;
@@ -423,6 +428,14 @@ __global__ void dc_fill_u32_kernel(uint32_t* p, size_t n, uint32_t v) {
     for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n;
          i += (size_t)gridDim.x * blockDim.x)
         p[i] = v;
+}
+
+// helper workgroups in front of the heads' in a decode launch: one per (sequence, KV head), for
+// GQA groups of 1, 2, 4 or 8 while the handle has them switched on
+static int decode_helper_slots(const float* coop, int coop_mode, int n_seq, int n_q, int n_kv) {
+    const int G = n_q / n_kv;
+    const bool coop_on = coop && coop_mode != RA_HELPERS_OFF && (G == 1 || G == 2 || G == 4 || G == 8);
+    return coop_on ? n_seq * n_kv : 0;
 }
 
 ra_status ra_launch_decode(const void* q, const int32_t* adj, const int32_t* entry, const void* K,
@@ -454,10 +467,8 @@ ra_status ra_launch_decode(const void* q, const int32_t* adj, const int32_t* ent
     }
     const float scale = 1.0f / sqrtf((float)RA_D);
     // one helper workgroup per (sequence, KV head) in front of the heads' (GQA groups of 1, 2, 4 or 8)
-    const int G = n_q / n_kv;
-    const bool coop_on = coop && coop_mode != RA_HELPERS_OFF && (G == 1 || G == 2 || G == 4 || G == 8);
-    const int n_helpers = coop_on ? n_seq * n_kv : 0;
     if (!coop) RA_FAIL(RA_EINVAL, "hand-over area missing");
+    const int n_helpers = decode_helper_slots(coop, coop_mode, n_seq, n_q, n_kv);
     const int threads = search_threads(heads, ef);
     const void* Ksearch = kscale ? K8 : K;
     if (kscale && !K8) RA_FAIL(RA_EINVAL, "8-bit keys missing");

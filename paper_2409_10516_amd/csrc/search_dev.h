@@ -46,9 +46,14 @@ typedef unsigned long long u64;
 // Phase clocks for tuning builds (-DSR_PHASE_CLOCKS): thread 0 of the first 64 workgroups adds the
 // ticks spent in each phase to a device array that ra_dbg_phase_ticks copies out. Off otherwise.
 #ifdef SR_PHASE_CLOCKS
-#define SR_NPHASE 13
+#define SR_NPHASE 16
 #define SR_NITER 16
 static __device__ long long sr_phase_ticks[64 * SR_NITER * SR_NPHASE];
+#ifdef SR_WAVE_CLOCKS
+// (with -DSR_WAVE_CLOCKS: when each wavefront of workgroup 8, the first head behind eight helpers,
+// entered and left the scoring of its start set; ra_dbg_wave_ticks copies them out)
+static __device__ long long sr_wave_ticks[64];
+#endif
 // ticks are added up in LDS (a fire-and-forget add) and copied out when the search has ended
 #define SR_TICK_INIT                                                                           \
     __shared__ long long tick_lds_[SR_NITER * SR_NPHASE];                                      \
@@ -76,6 +81,8 @@ static __device__ long long sr_phase_ticks[64 * SR_NITER * SR_NPHASE];
 #define SR_TICK(p)
 #define SR_TICK_FLUSH
 #endif
+
+template <int V> struct sr_int { static constexpr int value = V; };      // a compile-time row count as an argument
 
 __device__ __forceinline__ u64 make_key(float score, int id) {
     return ((u64)f32_ordered(score) << 32) | ((u64)(uint32_t)(0x7fffffff - id) << 1) | 1ull;
@@ -160,11 +167,11 @@ __device__ __forceinline__ float dpp_f32(float v) {
     return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xF, 0xF, true));
 }
 
-// The fixed-order inner product described in the file header. All 16 lanes of the group
-// return the same value.
+// The fixed-order inner product described in the file header, in two parts: a lane's share (its 8
+// dimensions, summed left to right), then the pairwise tree over the 16 lanes of the group.
 typedef __bf16 sr_bf16x2 __attribute__((ext_vector_type(2)));
 template <int DT>
-__device__ __forceinline__ float score_fixed(const RowBits<DT>& r, const ScoreQuery<DT>& sq) {
+__device__ __forceinline__ float score_share(const RowBits<DT>& r, const ScoreQuery<DT>& sq) {
     float acc;
     if constexpr (DT == RA_KEYS_I8) {
         const float* qv = sq.v;
@@ -197,6 +204,12 @@ __device__ __forceinline__ float score_fixed(const RowBits<DT>& r, const ScoreQu
         acc = __fadd_rn(acc, __fmul_rn(qv[6], __uint_as_float(r.b.z)));
         acc = __fadd_rn(acc, __fmul_rn(qv[7], __uint_as_float(r.b.w)));
     }
+    return acc;
+}
+// All 16 lanes of the group return the same value.
+template <int DT>
+__device__ __forceinline__ float score_fixed(const RowBits<DT>& r, const ScoreQuery<DT>& sq) {
+    float acc = score_share<DT>(r, sq);
     // pairwise tree over adjacent lanes with DPP lane permutations inside a row of 16:
     // quad_perm [1,0,3,2] and [2,3,0,1] are xor 1 and xor 2; after them the four lanes of a
     // quad hold the same sum, so half-mirror (i -> 7-i) and mirror (i -> 15-i) deliver exactly
@@ -206,6 +219,49 @@ __device__ __forceinline__ float score_fixed(const RowBits<DT>& r, const ScoreQu
     acc = __fadd_rn(acc, dpp_f32<0x141>(acc));
     acc = __fadd_rn(acc, dpp_f32<0x140>(acc));
     return acc;
+}
+
+// The same tree for R rows at once (R = 1, 2, 4, 8 or 16 shares per lane): at level k a lane and its
+// partner (lane ^ 2^k) split the rows they both still hold, each adding the partner's share of the
+// rows it keeps, so the work halves per level instead of every lane adding up every row; once one
+// row is left the remaining levels add as in score_fixed. Lane l of the group ends with the sum of
+// row l & (R - 1): the same operands added in the same pairs as in score_fixed, hence the same bits.
+// Partner values: quad_perm for xor 1 and 2, a row rotation by 8 for xor 8, and for xor 4 two
+// row shifts by 4, each written to the banks of four lanes it is right for.
+template <int K>
+__device__ __forceinline__ float lane16_xor(float x) {
+    if constexpr (K == 0) return dpp_f32<0xB1>(x);
+    else if constexpr (K == 1) return dpp_f32<0x4E>(x);
+    else if constexpr (K == 3) return dpp_f32<0x128>(x);
+    else {
+        const int v = __float_as_int(x);
+        int t = __builtin_amdgcn_update_dpp(v, v, 0x104, 0xF, 0x5, false);      // lanes 0-3, 8-11 <- lane + 4
+        t = __builtin_amdgcn_update_dpp(t, v, 0x114, 0xF, 0xA, false);          // lanes 4-7, 12-15 <- lane - 4
+        return __int_as_float(t);
+    }
+}
+template <int K, int N>
+__device__ __forceinline__ void rows_tree_level(float* a, int lane16) {
+    if constexpr (N > 1) {
+        const bool hi = (lane16 >> K) & 1;
+#pragma unroll
+        for (int j = 0; j < N / 2; ++j) {
+            const float keep = hi ? a[2 * j + 1] : a[2 * j];
+            const float send = hi ? a[2 * j] : a[2 * j + 1];
+            a[j] = __fadd_rn(keep, lane16_xor<K>(send));
+        }
+    } else {
+        a[0] = __fadd_rn(a[0], lane16_xor<K>(a[0]));
+    }
+}
+template <int R>
+__device__ __forceinline__ float rows_tree(float (&a)[R], int lane16) {
+    static_assert(R == 1 || R == 2 || R == 4 || R == 8 || R == 16, "a power of two up to the lanes of a group");
+    rows_tree_level<0, R>(a, lane16);
+    rows_tree_level<1, (R > 1 ? R / 2 : 1)>(a, lane16);
+    rows_tree_level<2, (R > 2 ? R / 4 : 1)>(a, lane16);
+    rows_tree_level<3, (R > 4 ? R / 8 : 1)>(a, lane16);
+    return a[0];
 }
 
 // number of entries of the descending array arr[0..n) that beat k (flag bit ignored)
@@ -364,6 +420,7 @@ __device__ __forceinline__ int run_search(
     const bool fill = root && n_root <= maxc &&
                       (seeded ? n_root >= 1 : n_first > 1 && expand >= n_first - 1 && ef >= n_first);
     __syncthreads();                                             // the LDS state is cleared
+    SR_TICK(12);
     int bn, n_visited, n_expanded, n_iters;
     bool first = fill;               // the coming step is that doubled first step
     if (fill) {
@@ -408,6 +465,10 @@ __device__ __forceinline__ int run_search(
     // feed a test that never holds; they are consumed one phase later, when they have long arrived.
     uint32_t early_a = 0u, early_b = 0u, early_acc = 0u;
     __syncthreads();
+    SR_TICK(13);
+#ifdef SR_WAVE_CLOCKS
+    const long long wave_t0_ = clock64();
+#endif
     if (fill) {
         // ---- the start set is scored here, ahead of the loop, where few registers are live: twice
         //      the rows in flight of a step's gather (a seed set of a thousand keys is one trip to
@@ -415,37 +476,58 @@ __device__ __forceinline__ int run_search(
         //      n_first of a root set enter as expanded.
         constexpr int SEED_ROWS = KT == RA_F32 ? SR_UNROLL : 2 * SR_UNROLL;
         uint32_t lo = 0xffffffffu, hi = 0u;                  // of the ordered score bits (see the pre-filter)
-        for (int c0 = 0; c0 < n_root; c0 += (T / 16) * SEED_ROWS) {
-            RowBits<KT> rows[SEED_ROWS];
+        // R rows per 16-lane group with no branch between them: the ids leave LDS in one batch, the
+        // rows are all requested before the first is scored, and each is scored as it arrives
+        auto score_rows = [&](auto rows_c, int c0) __attribute__((always_inline)) {
+            constexpr int R = decltype(rows_c)::value;
+            RowBits<KT> rows[R];
+            int idv[R];
 #pragma unroll
-            for (int u = 0; u < SEED_ROWS; ++u) {
-                if (c0 + u * (T / 16) >= n_root) break;      // uniform over the workgroup
+            for (int u = 0; u < R; ++u) {
                 const int c = c0 + u * (T / 16) + grp;
-                rows[u] = load_key<KT>(Kh, c < n_root ? cid[c] : e0, lane16);
+                idv[u] = c < n_root ? cid[c] : -1;           // (only the last call of a set is ragged)
             }
 #pragma unroll
-            for (int u = 0; u < SEED_ROWS; ++u) {
-                if (c0 + u * (T / 16) >= n_root) break;
-                const float sc = score_fixed<KT>(rows[u], qv);
-                const int c = c0 + u * (T / 16) + grp;
-                if (lane16 == 0 && c < n_root) {
-                    u64 key = make_key(sc, cid[c]);
-                    if (c < n_first) key &= ~1ull;
-                    ckey[c] = key;                           // all are kept: no counter needed
-                    const uint32_t so = (uint32_t)(key >> 32);
-                    lo = so < lo ? so : lo;
-                    hi = so > hi ? so : hi;
-                }
+            for (int u = 0; u < R; ++u) rows[u] = load_key<KT>(Kh, idv[u] >= 0 ? idv[u] : e0, lane16);
+            float part[R];
+#pragma unroll
+            for (int u = 0; u < R; ++u) part[u] = score_share<KT>(rows[u], qv);
+            const float sc = rows_tree<R>(part, lane16);     // of row lane16 (R = 16), lane16 & (R - 1) in general
+            const int c = c0 + (lane16 & (R - 1)) * (T / 16) + grp;
+            if (lane16 < R && c < n_root) {
+                u64 key = make_key(sc, cid[c]);
+                if (c < n_first) key &= ~1ull;
+                ckey[c] = key;                               // all are kept: no counter needed
+                const uint32_t so = (uint32_t)(key >> 32);
+                lo = so < lo ? so : lo;
+                hi = so > hi ? so : hi;
             }
+        };
+        {
+            constexpr int PER = T / 16;                      // rows one call takes per row in flight
+            int c0 = 0;
+            for (; n_root - c0 >= SEED_ROWS * PER; c0 += SEED_ROWS * PER) score_rows(sr_int<SEED_ROWS>{}, c0);
+            if constexpr (SEED_ROWS > 8)
+                if (n_root - c0 >= 8 * PER) { score_rows(sr_int<8>{}, c0); c0 += 8 * PER; }
+            if (n_root - c0 >= 4 * PER) { score_rows(sr_int<4>{}, c0); c0 += 4 * PER; }
+            if (n_root - c0 >= 2 * PER) { score_rows(sr_int<2>{}, c0); c0 += 2 * PER; }
+            if (n_root - c0 >= PER) { score_rows(sr_int<1>{}, c0); c0 += PER; }
+            if (n_root - c0 > 0) score_rows(sr_int<1>{}, c0);
         }
-        // lanes 0, 16, 32, 48 of a wavefront hold the extremes of its keys
-        lo = min(lo, (uint32_t)__shfl_xor((int)lo, 16)); lo = min(lo, (uint32_t)__shfl_xor((int)lo, 32));
-        hi = max(hi, (uint32_t)__shfl_xor((int)hi, 16)); hi = max(hi, (uint32_t)__shfl_xor((int)hi, 32));
+        // every lane may hold extremes of its keys: fold the wavefront
+#pragma unroll
+        for (int d = 1; d < RA_WAVE; d <<= 1) {
+            lo = min(lo, (uint32_t)__shfl_xor((int)lo, d));
+            hi = max(hi, (uint32_t)__shfl_xor((int)hi, d));
+        }
         if (lane == 0) {
             atomicMin(reinterpret_cast<unsigned int*>(&ctr[C_LO]), lo);
             atomicMax(reinterpret_cast<unsigned int*>(&ctr[C_HI]), hi);
         }
     }
+#ifdef SR_WAVE_CLOCKS
+    if (lane == 0 && blockIdx.x == 8) { sr_wave_ticks[wv * 2] = wave_t0_; sr_wave_ticks[wv * 2 + 1] = clock64(); }
+#endif
     SR_TICK(5);
 
     for (;;) {
@@ -549,26 +631,38 @@ __device__ __forceinline__ int run_search(
 
         // ---- gather and score the new candidates; keep those that can enter the beam
         const u64 worst = bn == ef ? (cur[bn - 1] >> 1) : 0ull;
-        for (int c0 = 0; c0 < (first ? 0 : nc); c0 += (T / 16) * SR_UNROLL) {   // (a start set is scored already)
-            RowBits<KT> rows[SR_UNROLL];
-            int cidv[SR_UNROLL];
+        // (R rows per 16-lane group with no branch between them, as for a start set)
+        auto gather_rows = [&](auto rows_c, int c0) __attribute__((always_inline)) {
+            constexpr int R = decltype(rows_c)::value;
+            RowBits<KT> rows[R];
+            int cidv[R];
 #pragma unroll
-            for (int u = 0; u < SR_UNROLL; ++u) {
-                if (c0 + u * (T / 16) >= nc) break;          // uniform over the workgroup
+            for (int u = 0; u < R; ++u) {
                 const int c = c0 + u * (T / 16) + grp;
                 cidv[u] = c < nc ? cid[c] : -1;
-                // groups without a candidate re-read the entry row instead of branching
-                rows[u] = load_key<KT>(Kh, cidv[u] >= 0 ? cidv[u] : e0, lane16);
             }
+            // groups without a candidate re-read the entry row instead of branching
 #pragma unroll
-            for (int u = 0; u < SR_UNROLL; ++u) {
-                if (c0 + u * (T / 16) >= nc) break;
-                const float sc = score_fixed<KT>(rows[u], qv);
-                if (lane16 == 0 && cidv[u] >= 0) {
-                    const u64 key = make_key(sc, cidv[u]);
-                    if ((key >> 1) > worst) ckey[atomicAdd(&ctr[C_NKEEP], 1)] = key;
-                }
+            for (int u = 0; u < R; ++u) rows[u] = load_key<KT>(Kh, cidv[u] >= 0 ? cidv[u] : e0, lane16);
+            float part[R];
+#pragma unroll
+            for (int u = 0; u < R; ++u) part[u] = score_share<KT>(rows[u], qv);
+            const float sc = rows_tree<R>(part, lane16);     // of row lane16 & (R - 1)
+            const int c = c0 + (lane16 & (R - 1)) * (T / 16) + grp;
+            if (lane16 < R && c < nc) {
+                const u64 key = make_key(sc, cid[c]);
+                if ((key >> 1) > worst) ckey[atomicAdd(&ctr[C_NKEEP], 1)] = key;
             }
+        };
+        if (!first) {                                        // (a start set is scored already)
+            constexpr int PER = T / 16;
+            int c0 = 0;
+            for (; nc - c0 >= SR_UNROLL * PER; c0 += SR_UNROLL * PER) gather_rows(sr_int<SR_UNROLL>{}, c0);
+            if constexpr (SR_UNROLL > 4)
+                if (nc - c0 >= 4 * PER) { gather_rows(sr_int<4>{}, c0); c0 += 4 * PER; }
+            if (nc - c0 >= 2 * PER) { gather_rows(sr_int<2>{}, c0); c0 += 2 * PER; }
+            if (nc - c0 >= PER) { gather_rows(sr_int<1>{}, c0); c0 += PER; }
+            if (nc - c0 > 0) gather_rows(sr_int<1>{}, c0);
         }
         __syncthreads();
         int nk = ctr[C_NKEEP];
