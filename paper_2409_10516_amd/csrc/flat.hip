@@ -48,9 +48,9 @@ __global__ __launch_bounds__(FL_THREADS) void flat_scores_kernel(
 #pragma unroll
     for (int g = 0; g < G; ++g) best[g] = 0u;
     // A 16-lane group takes FL_ROWS consecutive rows per round (a wavefront 4 x FL_ROWS rows, whole
-    // cache lines either way). Every lane of a group ends up with the same score, so lane u simply
-    // keeps the key of row u: the FL_ROWS keys of a group and head then leave in one store, 32
-    // consecutive keys (128 bytes) per wavefront, with no branch around the scoring.
+    // cache lines either way). Lane u ends with the score of row u, so the FL_ROWS keys of a group
+    // and head leave in one store, 32 consecutive keys (128 bytes) per wavefront, with no branch
+    // around the scoring.
     // (the rows of the next round are requested before the current round is scored)
     RowBits<DT> nxt[FL_ROWS];
     auto request = [&](int r0) {
@@ -67,18 +67,18 @@ __global__ __launch_bounds__(FL_THREADS) void flat_scores_kernel(
         for (int u = 0; u < FL_ROWS; ++u) rows[u] = nxt[u];
         if (r0 + 16 * FL_ROWS < FL_CHUNK) request(r0 + 16 * FL_ROWS);
         const int64_t id0 = base + r0 + grp * FL_ROWS;
+        // the 16-lane sums of the FL_ROWS rows as one halving tree (rows_tree): lane u ends with row u's
         uint32_t mine[G];
-#pragma unroll
-        for (int g = 0; g < G; ++g) mine[g] = 0u;
-#pragma unroll
-        for (int u = 0; u < FL_ROWS; ++u) {
-            const int64_t id = id0 + u;
+        {
+            const int64_t id = id0 + (lane16 & (FL_ROWS - 1));
             const bool counts = id < N && id >= s && id < N - w;      // keys of W (and past the end) read as 0
 #pragma unroll
             for (int g = 0; g < G; ++g) {
-                const float sc = score_fixed<DT>(rows[u], qv[g]);
-                const uint32_t key = counts ? f32_ordered(sc) : 0u;
-                mine[g] = lane16 == u ? key : mine[g];
+                float part[FL_ROWS];
+#pragma unroll
+                for (int u = 0; u < FL_ROWS; ++u) part[u] = score_share<DT>(rows[u], qv[g]);
+                const float sc = rows_tree<FL_ROWS>(part, lane16);
+                mine[g] = counts ? f32_ordered(sc) : 0u;
             }
         }
         const int64_t my_id = id0 + lane16;
