@@ -31,7 +31,9 @@
 
 // grid: x = chunk of FL_CHUNK keys, y = KV head, z = seq. GQA groups of another size than the
 // kernel is built for run as G = 1 with one grid row per query head, kv_div of which share a KV head.
-template <int DT, int G>
+// STORE = false: only the tile maxima are written (the keys of the few tiles that matter are scored
+// again by flat_rescore_kernel).
+template <int DT, int G, bool STORE>
 __global__ __launch_bounds__(FL_THREADS) void flat_scores_kernel(
     const void* __restrict__ q, const void* __restrict__ K, int n_q, int n_kv, int64_t N, int s, int w,
     uint32_t* __restrict__ keys, uint32_t* __restrict__ tile_max, int64_t n_tiles, int kv_div) {
@@ -85,7 +87,7 @@ __global__ __launch_bounds__(FL_THREADS) void flat_scores_kernel(
         if (lane16 < FL_ROWS && my_id < N) {
 #pragma unroll
             for (int g = 0; g < G; ++g) {
-                keys[(size_t)(h0 + g) * N + my_id] = mine[g];
+                if (STORE) keys[(size_t)(h0 + g) * N + my_id] = mine[g];
                 best[g] = mine[g] > best[g] ? mine[g] : best[g];
             }
         }
@@ -164,6 +166,163 @@ __device__ __forceinline__ void radix_select(const uint32_t* __restrict__ kh, in
 }
 
 #define FL_CAND 4096               // candidate capacity of the fast path
+#define FL_SLICES 8                // workgroups per head that score the listed tiles again
+#define FL_SLICE_CAND 1024         // candidates one of them can hold
+
+// Second pass of the scan that stores no keys. Every workgroup of a head finds T0, a tile maximum
+// that at least topk tile maxima reach (so at least topk keys reach it, and the answer and all ties
+// of its last key lie in tiles whose maximum does), lists those tiles, and scores its share of them
+// again - the same rows through the same instructions as the first pass, hence the same bits -
+// appending every key at or above T0 to its own list: pairs (key, id) in the slice's eighth of the
+// head's key area, their number in cand_count[head][slice]. A head with T0 = 0 (fewer than topk
+// tiles hold an eligible key) or a slice with more candidates than it can hold (a crowd of ties)
+// sets the top bit of the count instead: the select kernel then scores the whole head itself.
+// grid: x = slice, y = head; a wavefront takes one tile at a time (a 16-lane group one run of 8 rows).
+template <int DT>
+__global__ __launch_bounds__(FL_SEL_T) void flat_rescore_kernel(
+    const void* __restrict__ q, const void* __restrict__ K, int n_q, int n_kv, int64_t N, int s, int w,
+    const uint32_t* __restrict__ tile_max, int64_t n_tiles, int topk, uint32_t* __restrict__ keys,
+    uint32_t* __restrict__ cand_count, int cand_cap) {
+    __shared__ unsigned hist[256];
+    __shared__ unsigned s_ntl, s_prefix, s_cnt, s_lo, s_hi, s_t0;
+    __shared__ uint32_t tm[FL_TILES_MAX];
+    __shared__ unsigned short s_tl[FL_TILES_MAX];
+    __shared__ unsigned long long mine[FL_SLICE_CAND];        // this workgroup's candidates: (key, id)
+    const int tid = threadIdx.x, lane = tid & (RA_WAVE - 1), wv = tid / RA_WAVE, g4 = lane >> 4, lane16 = tid & 15;
+    const int head = blockIdx.y, slice = blockIdx.x;
+    const int seq = head / n_q, kvh = (head % n_q) / (n_q / n_kv);
+    const size_t esz = DT == RA_BF16 ? 2 : 4;
+    const char* Kh = reinterpret_cast<const char*>(K) + ((size_t)seq * n_kv + kvh) * N * RA_D * esz;
+    ScoreQuery<DT> qv;
+    load_score_query<DT, DT>(reinterpret_cast<const char*>(q) + (size_t)head * RA_D * esz, lane16, qv);
+    for (int64_t t = tid; t < n_tiles; t += FL_SEL_T) tm[t] = tile_max[(size_t)head * n_tiles + t];
+    if (tid == 0) { s_ntl = 0u; s_cnt = 0u; s_lo = 0xffffffffu; s_hi = 0u; s_t0 = 0xffffffffu; }
+    if (tid < 256) hist[tid] = 0u;
+    __syncthreads();
+    // A threshold that at least topk tile maxima reach, without an exact selection: the maxima are
+    // cut into 255 equal-width bins between the smallest and the largest (bin 0 is for tiles with no
+    // eligible key, whose maximum is 0), b is the highest bin such that the bins from b up hold at
+    // least topk maxima, and T0 is the smallest maximum in those bins. It is at or below the
+    // topk-th largest maximum, so nothing of the answer is lost, and a tile whose maximum reaches
+    // T0 lies in those bins (the binning is monotone), so "maximum >= T0" lists exactly them.
+    {
+        uint32_t lo = 0xffffffffu, hi = 0u;
+        for (int64_t t = tid; t < n_tiles; t += FL_SEL_T) {
+            const uint32_t v = tm[t];
+            if (v) { lo = v < lo ? v : lo; hi = v > hi ? v : hi; }
+        }
+#pragma unroll
+        for (int d = 1; d < RA_WAVE; d <<= 1) {
+            const uint32_t ol = __shfl_xor(lo, d), oh = __shfl_xor(hi, d);
+            lo = ol < lo ? ol : lo;
+            hi = oh > hi ? oh : hi;
+        }
+        if (lane == 0) { atomicMin(&s_lo, lo); atomicMax(&s_hi, hi); }
+    }
+    __syncthreads();
+    const float lo_f = f32_from_ordered(s_lo);
+    const float width = s_hi ? f32_from_ordered(s_hi) - lo_f : 0.f;
+    const float to_bin = width > 0.f && width < INFINITY ? 254.0f / width : 0.f;
+    auto bin_of = [&](uint32_t v) {
+        if (!v) return 0;
+        const float b = (f32_from_ordered(v) - lo_f) * to_bin;
+        return 1 + (b >= 254.f ? 254 : b > 0.f ? (int)b : 0);
+    };
+    for (int64_t t = tid; t < n_tiles; t += FL_SEL_T) atomicAdd(&hist[bin_of(tm[t])], 1u);
+    __syncthreads();
+    if (wv == 0) {
+        // lane l owns bins 4l .. 4l + 3; maxima in the bins from b up = total - (those below b)
+        const int b0 = (int)hist[4 * lane], b1 = (int)hist[4 * lane + 1], b2 = (int)hist[4 * lane + 2],
+                  b3 = (int)hist[4 * lane + 3];
+        const int incl = wave_incl_scan(b0 + b1 + b2 + b3);
+        const int total = __builtin_amdgcn_readlane(incl, RA_WAVE - 1);
+        const int from3 = total - incl + b3, from2 = from3 + b2, from1 = from2 + b1, from0 = from1 + b0;
+        const int best = from3 >= topk ? 3 : from2 >= topk ? 2 : from1 >= topk ? 1 : from0 >= topk ? 0 : -1;
+        const unsigned long long has = __ballot(best >= 0);     // never empty: n_tiles >= 2 topk
+        if (lane == 63 - __clzll(has)) s_prefix = (unsigned)(4 * lane + best);
+    }
+    __syncthreads();
+    const int bstar = (int)s_prefix;
+    if (bstar > 0) {
+        uint32_t m = 0xffffffffu;
+        for (int64_t t = tid; t < n_tiles; t += FL_SEL_T) {
+            const uint32_t v = tm[t];
+            if (bin_of(v) >= bstar) m = v < m ? v : m;
+        }
+#pragma unroll
+        for (int d = 1; d < RA_WAVE; d <<= 1) {
+            const uint32_t o = __shfl_xor(m, d);
+            m = o < m ? o : m;
+        }
+        if (lane == 0) atomicMin(&s_t0, m);
+    }
+    __syncthreads();
+    const uint32_t T0 = bstar > 0 ? s_t0 : 0u;
+    if (T0 == 0u) {
+        if (tid == 0) cand_count[head * FL_SLICES + slice] = 0x80000000u;
+        return;
+    }
+    // this workgroup's share: the listed tiles whose number is congruent to its slice (the order of
+    // a list differs from workgroup to workgroup, the tile numbers do not)
+    for (int64_t t = tid; t < n_tiles; t += FL_SEL_T)
+        if (tm[t] >= T0 && (int)(t % FL_SLICES) == slice) s_tl[atomicAdd(&s_ntl, 1u)] = (unsigned short)t;
+    __syncthreads();
+    const int ntl = (int)s_ntl;
+    for (int l = wv; l < ntl; l += FL_SEL_T / RA_WAVE) {
+        const int64_t tl = s_tl[l];
+        const int64_t id0 = (tl / 16) * FL_CHUNK + g4 * (16 * FL_ROWS) + (tl % 16) * FL_ROWS;
+        RowBits<DT> rows[FL_ROWS];
+#pragma unroll
+        for (int u = 0; u < FL_ROWS; ++u) rows[u] = load_key<DT>(Kh, id0 + u < N ? id0 + u : N - 1, lane16);
+        float part[FL_ROWS];
+#pragma unroll
+        for (int u = 0; u < FL_ROWS; ++u) part[u] = score_share<DT>(rows[u], qv);
+        const float sc = rows_tree<FL_ROWS>(part, lane16);
+        const int64_t id = id0 + (lane16 & (FL_ROWS - 1));
+        const bool counts = id < N && id >= s && id < N - w;
+        const uint32_t key = counts ? f32_ordered(sc) : 0u;
+        if (lane16 < FL_ROWS && key >= T0) {
+            const unsigned at = atomicAdd(&s_cnt, 1u);
+            if (at < FL_SLICE_CAND) mine[at] = ((unsigned long long)key << 32) | (uint32_t)id;
+        }
+    }
+    __syncthreads();
+    const unsigned cnt = s_cnt;
+    const bool fits = cnt <= (unsigned)cand_cap;
+    if (tid == 0) cand_count[head * FL_SLICES + slice] = fits ? cnt : 0x80000000u;
+    if (!fits) return;
+    uint32_t* region = keys + (size_t)head * N + (size_t)slice * (N / FL_SLICES);
+    for (unsigned i = tid; i < cnt; i += FL_SEL_T) {
+        region[2 * (size_t)i] = (uint32_t)(mine[i] >> 32);
+        region[2 * (size_t)i + 1] = (uint32_t)mine[i];
+    }
+}
+
+// Every key of one head scored by one workgroup into kh[0..N) (0 for the static set W): what the
+// select kernel falls back on when the second pass could not place a threshold.
+template <int DT>
+__device__ __forceinline__ void flat_score_head(const void* q, const void* K, int head, int n_q, int n_kv,
+                                                int64_t N, int s, int w, uint32_t* kh) {
+    const int tid = threadIdx.x, grp = tid >> 4, lane16 = tid & 15;
+    const int seq = head / n_q, kvh = (head % n_q) / (n_q / n_kv);
+    const size_t esz = DT == RA_BF16 ? 2 : 4;
+    const char* Kh = reinterpret_cast<const char*>(K) + ((size_t)seq * n_kv + kvh) * N * RA_D * esz;
+    ScoreQuery<DT> qv;
+    load_score_query<DT, DT>(reinterpret_cast<const char*>(q) + (size_t)head * RA_D * esz, lane16, qv);
+    for (int64_t b = 0; b < N; b += (FL_SEL_T / 16) * FL_ROWS) {
+        const int64_t id0 = b + grp * FL_ROWS;
+        RowBits<DT> rows[FL_ROWS];
+#pragma unroll
+        for (int u = 0; u < FL_ROWS; ++u) rows[u] = load_key<DT>(Kh, id0 + u < N ? id0 + u : N - 1, lane16);
+        float part[FL_ROWS];
+#pragma unroll
+        for (int u = 0; u < FL_ROWS; ++u) part[u] = score_share<DT>(rows[u], qv);
+        const float sc = rows_tree<FL_ROWS>(part, lane16);
+        const int64_t id = id0 + (lane16 & (FL_ROWS - 1));
+        if (lane16 < FL_ROWS && id < N) kh[id] = id >= s && id < N - w ? f32_ordered(sc) : 0u;
+    }
+}
+
 #define FL_SAMPLE 4096             // keys sampled to place the threshold
 
 // grid: x = head; block = FL_SEL_T threads. ids_out [heads][topk], padded with -1.
@@ -172,10 +331,17 @@ __device__ __forceinline__ void radix_select(const uint32_t* __restrict__ kh, in
 // whole); one pass collects every key at or above it; if at least topk and at most FL_CAND were
 // collected, sorting them gives the exact answer (all ties of the k-th key are in the set).
 // Otherwise (tiny or adversarial inputs) the exact radix select over all keys decides.
-__global__ __launch_bounds__(FL_SEL_T) void flat_select_kernel(const uint32_t* __restrict__ keys,
+// two_pass: the keys were not stored; the candidates come from flat_rescore_kernel (q, K, n_q, n_kv,
+// s, w are for the head that has to score itself after all, see there).
+template <int DT>
+__global__ __launch_bounds__(FL_SEL_T) void flat_select_kernel(uint32_t* __restrict__ keys,
                                                                const uint32_t* __restrict__ tile_max,
                                                                int64_t n_tiles, int64_t N, int topk,
-                                                               int32_t* __restrict__ ids_out) {
+                                                               int32_t* __restrict__ ids_out, bool two_pass,
+                                                               const uint32_t* __restrict__ cand_count,
+                                                               const void* __restrict__ q,
+                                                               const void* __restrict__ K, int n_q, int n_kv,
+                                                               int s, int w) {
     __shared__ unsigned hist[256], wsum4[4];
     __shared__ unsigned s_ntl;
     __shared__ unsigned short s_tl[FL_TILES_MAX];
@@ -183,10 +349,39 @@ __global__ __launch_bounds__(FL_SEL_T) void flat_select_kernel(const uint32_t* _
     __shared__ unsigned long long sel[FL_CAND];
     __shared__ int wtot[FL_SEL_T / RA_WAVE];
     const int tid = threadIdx.x, lane = tid & (RA_WAVE - 1), wv = tid / RA_WAVE;
-    const uint32_t* kh = keys + (size_t)blockIdx.x * N;
+    uint32_t* kh = keys + (size_t)blockIdx.x * N;
     int32_t* out = ids_out + (size_t)blockIdx.x * topk;
     int n = -1;                                  // number of selected entries once known
-    if (n_tiles >= 2 * (int64_t)topk && n_tiles <= FL_TILES_MAX) {
+    if (two_pass) {
+        unsigned c = 0u, bad = 0u, start[FL_SLICES + 1];
+#pragma unroll
+        for (int j = 0; j < FL_SLICES; ++j) {
+            const unsigned cj = cand_count[blockIdx.x * FL_SLICES + j];
+            bad |= cj & 0x80000000u;
+            start[j] = c;
+            c += cj & 0x7fffffffu;
+        }
+        start[FL_SLICES] = c;
+        if (!bad && c >= (unsigned)topk && c <= FL_CAND) {
+            // entry i of the eight lists laid end to end (all loads in one trip)
+            for (unsigned i = tid; i < c; i += FL_SEL_T) {
+                int j = 0;
+#pragma unroll
+                for (int x = 1; x < FL_SLICES; ++x) j += i >= start[x] ? 1 : 0;
+                unsigned first = 0u;
+#pragma unroll
+                for (int x = 1; x < FL_SLICES; ++x) first = j == x ? start[x] : first;
+                const uint32_t* e = kh + (size_t)j * (N / FL_SLICES) + 2 * (size_t)(i - first);
+                sel[i] = ((unsigned long long)e[0] << 32) | (0xffffffffu - e[1]);
+            }
+            n = (int)c;
+        } else {
+            __syncthreads();                     // (every thread has read the counts)
+            flat_score_head<DT>(q, K, (int)blockIdx.x, n_q, n_kv, N, s, w, kh);
+        }
+        __syncthreads();
+    }
+    if (!two_pass && n_tiles >= 2 * (int64_t)topk && n_tiles <= FL_TILES_MAX) {
         // ---- tile path: T0 = the topk-th largest tile maximum (exact), then only the tiles at or above it
         // the head's tile maxima, copied into LDS (the candidate array is not in use yet)
         uint32_t* tm = reinterpret_cast<uint32_t*>(sel);
@@ -409,30 +604,48 @@ ra_status ra_launch_flat_topk(const void* q, const void* K, ra_dtype dt, int n_s
     if (ww > N) ww = N;
     if (ss + ww >= N) { ss = N; ww = 0; }
     const int G = n_q / n_kv;
+    const int heads = n_seq * n_q;
+    uint32_t* cand_count = tile_max + (size_t)heads * n_tiles;   // [heads][FL_SLICES], after the tile maxima
+    // Two passes without stored keys whenever the tile maxima can place the threshold: writing the
+    // 16.8 MB of keys of a 128K layer costs the scan a fifth of its time, and all but a few thousand
+    // of them are never read again. Candidate pairs (key, id) live in the head's key area.
+    // (pairs a slice can hold: its eighth of the key area, and what its workgroup keeps in LDS)
+    const int cand_cap = (int)(N / FL_SLICES / 2 < FL_SLICE_CAND ? N / FL_SLICES / 2 : FL_SLICE_CAND);
+    const bool two_pass = n_tiles >= 2 * (int64_t)topk && n_tiles <= FL_TILES_MAX && cand_cap >= 64;
     const dim3 grid((unsigned)((N + FL_CHUNK - 1) / FL_CHUNK), n_kv, n_seq);
-#define RA_FL_CASE(DTV, GG)                                                                     \
-    case GG:                                                                                    \
-        hipLaunchKernelGGL((flat_scores_kernel<DTV, GG>), grid, dim3(FL_THREADS), 0, st, q, K, n_q, \
-                           n_kv, N, (int)ss, (int)ww, keys_ws, tile_max, n_tiles, 1);           \
-        break;
-    // any other group size: one grid row per query head, every head scans its keys itself
+    // any other group size than 1, 2, 4, 8: one grid row per query head, every head scans its keys itself
     const dim3 grid1(grid.x, n_q, n_seq);
-#define RA_FL_OTHER(DTV)                                                                        \
-    default:                                                                                    \
-        hipLaunchKernelGGL((flat_scores_kernel<DTV, 1>), grid1, dim3(FL_THREADS), 0, st, q, K, n_q, \
-                           n_kv, N, (int)ss, (int)ww, keys_ws, tile_max, n_tiles, G);
-    if (dt == RA_BF16) {
-        switch (G) { RA_FL_CASE(RA_BF16, 1) RA_FL_CASE(RA_BF16, 2) RA_FL_CASE(RA_BF16, 4) RA_FL_CASE(RA_BF16, 8)
-            RA_FL_OTHER(RA_BF16) }
-    } else {
-        switch (G) { RA_FL_CASE(RA_F32, 1) RA_FL_CASE(RA_F32, 2) RA_FL_CASE(RA_F32, 4) RA_FL_CASE(RA_F32, 8)
-            RA_FL_OTHER(RA_F32) }
-    }
-#undef RA_FL_OTHER
-#undef RA_FL_CASE
-    RA_HIP(hipGetLastError());
-    hipLaunchKernelGGL(flat_select_kernel, dim3(n_seq * n_q), dim3(FL_SEL_T), 0, st, keys_ws, tile_max,
-                       n_tiles, N, topk, ids);
+#define RA_FL_GO(DTV, GG, GRID, DIV)                                                                          \
+    do {                                                                                                      \
+        if (two_pass)                                                                                         \
+            hipLaunchKernelGGL((flat_scores_kernel<DTV, GG, false>), GRID, dim3(FL_THREADS), 0, st, q, K, n_q,  \
+                               n_kv, N, (int)ss, (int)ww, keys_ws, tile_max, n_tiles, DIV);                   \
+        else                                                                                                  \
+            hipLaunchKernelGGL((flat_scores_kernel<DTV, GG, true>), GRID, dim3(FL_THREADS), 0, st, q, K, n_q,   \
+                               n_kv, N, (int)ss, (int)ww, keys_ws, tile_max, n_tiles, DIV);                   \
+    } while (0)
+#define RA_FL_DT(DTV)                                                                                         \
+    do {                                                                                                      \
+        switch (G) {                                                                                          \
+            case 1: RA_FL_GO(DTV, 1, grid, 1); break;                                                         \
+            case 2: RA_FL_GO(DTV, 2, grid, 1); break;                                                         \
+            case 4: RA_FL_GO(DTV, 4, grid, 1); break;                                                         \
+            case 8: RA_FL_GO(DTV, 8, grid, 1); break;                                                         \
+            default: RA_FL_GO(DTV, 1, grid1, G);                                                              \
+        }                                                                                                     \
+        RA_HIP(hipGetLastError());                                                                            \
+        if (two_pass) {                                                                                       \
+            hipLaunchKernelGGL((flat_rescore_kernel<DTV>), dim3(FL_SLICES, heads), dim3(FL_SEL_T), 0, st, q, K, \
+                               n_q, n_kv, N, (int)ss, (int)ww, tile_max, n_tiles, topk, keys_ws, cand_count,  \
+                               cand_cap);                                                                     \
+            RA_HIP(hipGetLastError());                                                                        \
+        }                                                                                                     \
+        hipLaunchKernelGGL((flat_select_kernel<DTV>), dim3(heads), dim3(FL_SEL_T), 0, st, keys_ws, tile_max,    \
+                           n_tiles, N, topk, ids, two_pass, cand_count, q, K, n_q, n_kv, (int)ss, (int)ww);   \
+    } while (0)
+    if (dt == RA_BF16) RA_FL_DT(RA_BF16); else RA_FL_DT(RA_F32);
+#undef RA_FL_DT
+#undef RA_FL_GO
     RA_HIP(hipGetLastError());
     return RA_OK;
 }

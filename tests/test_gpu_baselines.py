@@ -70,6 +70,22 @@ def test_flat_topk_all_scores_equal_takes_lowest_ids(N):
     assert ids.tolist() == list(range(2, 52))
 
 
+def test_flat_topk_long_context_with_few_eligible_keys():
+    """40000 keys of which the static set leaves 300: fewer tiles hold an eligible key than topk asks
+    for, so no tile maximum can serve as a threshold and the head is scored as a whole."""
+    w = synth.make_llama_layer(43, N=40000, M=8, T=1, n_q=4, n_kv=2)
+    sink, window = 100, 40000 - 400
+    W = OA.static_ids(40000, sink, window)
+    for topk in (50, 400):
+        ids = ra.ra_flat_topk(w.q_decode[0].to(DEV), w.K.to(DEV), sink, window, topk).cpu().numpy()
+        for h in range(4):
+            qq, Kh = to_np(w.q_decode[0, 0, h]), to_np(w.K[0, h // 2])
+            ref = OM.topk_bruteforce(qq, Kh, topk, exclude=W)
+            assert len(ref) == min(topk, 300)
+            topk_equivalent(ids[0, h], np.pad(ref, (0, topk - len(ref)), constant_values=-1), qq, Kh,
+                            eligible=set(range(40000)) - set(W.tolist()))
+
+
 @pytest.mark.parametrize("topk", [1, 100, 1024, 2048])
 def test_flat_topk_sampled_threshold_path(topk):
     """40000 keys are 1264 tiles: topk 1 and 100 take their threshold from the tile maxima, 1024 and
