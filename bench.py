@@ -451,13 +451,29 @@ def main():
     base_layers = layers[:min(len(layers), 4)]
 
     def timed_layers(fn, reps=5):
+        """ms per layer of an exact baseline, replayed from a HIP graph like the decode step (eager
+        launches with --graph 0), so that the comparison is between kernels, not launch paths."""
         fn(base_layers[0])
         torch.cuda.synchronize()
+        graph = None
+        if a.graph:
+            cs = torch.cuda.Stream()
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.stream(cs):
+                with torch.cuda.graph(graph, stream=cs):
+                    for L in base_layers:
+                        fn(L)
+            torch.cuda.synchronize()
+            graph.replay()
+            torch.cuda.synchronize()
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         e0.record()
         for _ in range(reps):
-            for L in base_layers:
-                fn(L)
+            if graph is not None:
+                graph.replay()
+            else:
+                for L in base_layers:
+                    fn(L)
         e1.record()
         torch.cuda.synchronize()
         return e0.elapsed_time(e1) / (reps * len(base_layers))
