@@ -20,6 +20,13 @@ __global__ __launch_bounds__(AT_THREADS) void attend_partial_kernel(
     float* rec_g = partials + ((size_t)seq * n_q + h0) * P * AT_RS;
     if (x < nS) {
         RowSrc src{nullptr, N, s, w, s + w, 0};
+        if constexpr (DT == RA_BF16 && G <= 4) {
+            if (sub > 1) {                      // a long dense range (full attention): logits on the matrix cores
+                attend_chunk_mfma<G>(threadIdx.x, qg, Kh, Vh, src, x, sub, scale, rec_g + (size_t)x * AT_RS,
+                                     (int64_t)P * AT_RS, smem);
+                return;
+            }
+        }
         attend_chunk<DT, G>(threadIdx.x, true, qg, Kh, Vh, src, x, sub, scale, rec_g + (size_t)x * AT_RS,
                             (int64_t)P * AT_RS, smem);
     } else {

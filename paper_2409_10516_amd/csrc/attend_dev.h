@@ -113,6 +113,49 @@ __device__ __forceinline__ void row8_floats(const Row8<DT>& r, float* o) {
 template <int DT>
 __device__ __forceinline__ float at_exp(float x) { return DT == RA_BF16 ? __expf(x) : expf(x); }
 
+// The closing step of a chunk: the (max, sum, weighted sum) states of the 16 lane groups of a team,
+// each lane holding 8 of the 128 outputs of its group, become one partial record per head.
+template <int NH>
+__device__ __forceinline__ void chunk_records(int tid, bool active, const float (&m)[NH], const float (&l)[NH],
+                                              const float (&acc)[NH][8], float* rec0, int64_t rec_stride,
+                                              float* smem) {
+    const int grp = tid >> 4, lane16 = tid & 15;
+    float* sm = smem;                       // [16]
+    float* sl = sm + 16;                    // [16]
+    float* sa = sl + 16;                    // [16][128]
+#pragma unroll
+    for (int g = 0; g < NH; ++g) {
+        if (g) __syncthreads();
+        if (lane16 == 0) {
+            sm[grp] = m[g];
+            sl[grp] = l[g];
+        }
+#pragma unroll
+        for (int e = 0; e < 8; ++e) sa[grp * RA_D + lane16 * 8 + e] = acc[g][e];
+        __syncthreads();
+        if (tid < RA_D && active) {
+            float mx = -INFINITY;
+#pragma unroll
+            for (int j = 0; j < 16; ++j) mx = fmaxf(mx, sm[j]);
+            float a = 0.f, ll = 0.f;
+            if (mx > -INFINITY) {
+#pragma unroll
+                for (int j = 0; j < 16; ++j) {
+                    const float wgt = expf(sm[j] - mx);
+                    a = fmaf(sa[j * RA_D + tid], wgt, a);
+                    ll = fmaf(sl[j], wgt, ll);
+                }
+            }
+            float* rec = rec0 + g * rec_stride;
+            rec[tid] = a;
+            if (tid == 0) {
+                rec[RA_D] = mx;
+                rec[RA_D + 1] = ll;
+            }
+        }
+    }
+}
+
 // One chunk for NH query heads that share the same K/V rows.
 // A call covers `n_sub` consecutive sub-chunks of 64 rows (1 for the decode step; more when a
 // long dense range is streamed, so that the number of partial records stays small).
@@ -237,41 +280,131 @@ __device__ void attend_chunk(int tid, bool active, const void* q0, const void* K
             consume(rid_b, k_b, v_b);
         }
     }
-    // combine the 16 row-groups of the workgroup, one head at a time
-    float* sm = smem;                       // [16]
-    float* sl = sm + 16;                    // [16]
-    float* sa = sl + 16;                    // [16][128]
+    chunk_records<NH>(tid, active, m, l, acc, rec0, rec_stride, smem);
+}
+
+// The same chunk for a long dense range of bf16 rows and up to four heads, with the logits on the
+// matrix cores: S = Q K^T is a dense contraction, and on the vector units its 16-lane sums and the
+// redundant softmax of every lane cost about as much issue time as the K / V streams leave. A
+// wavefront owns 16 consecutive rows of each sub-chunk of 64. v_mfma_f32_16x16x32_bf16 takes them
+// as its 32 x 16 operand (lane l: row l % 16, the 16 bytes at 64 j + 16 (l / 16) of the row for
+// instruction j = 0..3: four lanes read 64 consecutive bytes, four instructions the whole row) and
+// the queries as its 16 x 32 operand (row h = head h, the same bytes of the query; rows past the
+// last head are zero), so lane n < 16 ends with the logits of row n for every head. Those lanes do
+// the softmax bookkeeping once per row (running maximum shared by the wavefront, weights, their
+// sum); the weighted sum of V stays on the vector units with 16 lanes per V row as elsewhere, each
+// lane fetching the weight of its row from the lane that computed it. The sum over the 128
+// dimensions is rounded in the hardware's order (tolerance of Eq. 1 as for the other path).
+__device__ __forceinline__ float first_lane_f32(float v) {        // the builtin moves 32 bits, typed as an integer
+    return __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(v)));
+}
+typedef __bf16 at_bf16x8 __attribute__((ext_vector_type(8)));
+typedef float at_f32x4 __attribute__((ext_vector_type(4)));
+template <int NH>
+__device__ void attend_chunk_mfma(int tid, const void* q0, const void* Kh, const void* Vh, const RowSrc& src,
+                                  int chunk, int n_sub, float scale, float* rec0, int64_t rec_stride,
+                                  float* smem) {
+    static_assert(NH >= 1 && NH <= 4, "the heads sit in the first four rows of the query operand");
+    const int wv = tid >> 6, lane = tid & 63, n = lane & 15, c = lane >> 4, lane16 = n;
+    uint4 qa[4];
+    {
+        const uint4* qrow = reinterpret_cast<const uint4*>(reinterpret_cast<const uint16_t*>(q0) +
+                                                           (size_t)(n < NH ? n : 0) * RA_D);
 #pragma unroll
-    for (int g = 0; g < NH; ++g) {
-        if (g) __syncthreads();
-        if (lane16 == 0) {
-            sm[grp] = m[g];
-            sl[grp] = l[g];
-        }
-#pragma unroll
-        for (int e = 0; e < 8; ++e) sa[grp * RA_D + lane16 * 8 + e] = acc[g][e];
-        __syncthreads();
-        if (tid < RA_D && active) {
-            float mx = -INFINITY;
-#pragma unroll
-            for (int j = 0; j < 16; ++j) mx = fmaxf(mx, sm[j]);
-            float a = 0.f, ll = 0.f;
-            if (mx > -INFINITY) {
-#pragma unroll
-                for (int j = 0; j < 16; ++j) {
-                    const float wgt = expf(sm[j] - mx);
-                    a = fmaf(sa[j * RA_D + tid], wgt, a);
-                    ll = fmaf(sl[j], wgt, ll);
-                }
-            }
-            float* rec = rec0 + g * rec_stride;
-            rec[tid] = a;
-            if (tid == 0) {
-                rec[RA_D] = mx;
-                rec[RA_D + 1] = ll;
-            }
+        for (int j = 0; j < 4; ++j) {
+            const uint4 v = qrow[4 * j + c];
+            qa[j] = n < NH ? v : make_uint4(0u, 0u, 0u, 0u);
         }
     }
+    float acc[NH][8], m[NH], lpart[NH];
+#pragma unroll
+    for (int h = 0; h < NH; ++h) {
+        m[h] = -INFINITY;
+        lpart[h] = 0.f;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) acc[h][e] = 0.f;
+    }
+    struct Tile { int64_t rk; uint4 kb[4]; Row8<RA_BF16> vb[4]; };
+    const int sub_end = (chunk + 1) * n_sub;
+    auto fetch = [&](int sub, Tile& t) {
+        if (sub >= sub_end) sub = sub_end - 1;       // past the end: the last one again, unused
+        const int rb = sub * AT_CH + 16 * wv;
+        t.rk = chunk_row(src, rb + n);
+        const char* kp = reinterpret_cast<const char*>(Kh) + (size_t)(t.rk >= 0 ? t.rk : 0) * (RA_D * 2) + 16 * c;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const at_u32x4 v = __builtin_nontemporal_load(reinterpret_cast<const at_u32x4*>(kp + 64 * j));
+            t.kb[j] = make_uint4(v.x, v.y, v.z, v.w);
+        }
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int64_t rv = chunk_row(src, rb + 4 * i + c);
+            t.vb[i] = load_row8_stream<RA_BF16>(Vh, rv >= 0 ? rv : 0, lane16);    // a missing row's weight is 0
+        }
+    };
+    auto consume = [&](const Tile& t) {
+        at_f32x4 d = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+            d = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(at_bf16x8, qa[j]),
+                                                        __builtin_bit_cast(at_bf16x8, t.kb[j]), d, 0, 0, 0);
+        float p[NH];
+#pragma unroll
+        for (int h = 0; h < NH; ++h) {
+            // lanes 0..15 hold row n's logit for head h (the other lanes hold the operand's zero rows)
+            const float z = t.rk >= 0 ? d[h] * scale : -INFINITY;
+            float mx = z;
+            mx = fmaxf(mx, at_dpp<0xB1>(mx));
+            mx = fmaxf(mx, at_dpp<0x4E>(mx));
+            mx = fmaxf(mx, at_dpp<0x141>(mx));
+            mx = fmaxf(mx, at_dpp<0x140>(mx));
+            const float mrow = first_lane_f32(mx);                       // of lanes 0..15
+            const float mn = fmaxf(m[h], mrow);
+            const float corr = mn > -INFINITY ? __expf(m[h] - mn) : 1.f;
+            m[h] = mn;
+            p[h] = z > -INFINITY ? __expf(z - mn) : 0.f;
+            lpart[h] = fmaf(lpart[h], corr, p[h]);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) acc[h][e] *= corr;
+        }
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            float vv[8];
+            row8_floats<RA_BF16>(t.vb[i], vv);
+#pragma unroll
+            for (int h = 0; h < NH; ++h) {
+                const float pv = __shfl(p[h], 4 * i + c);                // the weight of row 4 i + c
+#pragma unroll
+                for (int e = 0; e < 8; ++e) acc[h][e] = fmaf(pv, vv[e], acc[h][e]);
+            }
+        }
+    };
+    {
+        Tile a, b;
+        int sub = chunk * n_sub;
+        fetch(sub, a);
+        for (; sub < sub_end; sub += 2) {
+            fetch(sub + 1, b);
+            consume(a);
+            if (sub + 1 >= sub_end) break;
+            fetch(sub + 2, a);
+            consume(b);
+        }
+    }
+    // the wavefront's sums of weights sit in lanes 0..15: add them up, hand them to its first lane
+    // group (the four groups of a wavefront share its maximum), and close like any chunk
+    float l[NH];
+#pragma unroll
+    for (int h = 0; h < NH; ++h) {
+        float v = lpart[h];
+        v += at_dpp<0xB1>(v);
+        v += at_dpp<0x4E>(v);
+        v += at_dpp<0x141>(v);
+        v += at_dpp<0x140>(v);
+        const float tot = first_lane_f32(v);
+        l[h] = c == 0 ? tot : 0.f;
+    }
+    chunk_records<NH>(tid, true, m, l, acc, rec0, rec_stride, smem);
 }
 
 // Combination of one head's P = nS + nG partial records: Eq. 4-5 with the re-scaling factors
