@@ -359,13 +359,17 @@ __device__ void attend_chunk_mfma(int tid, const void* q0, const void* Kh, const
             mx = fmaxf(mx, at_dpp<0x141>(mx));
             mx = fmaxf(mx, at_dpp<0x140>(mx));
             const float mrow = first_lane_f32(mx);                       // of lanes 0..15
-            const float mn = fmaxf(m[h], mrow);
-            const float corr = mn > -INFINITY ? __expf(m[h] - mn) : 1.f;
-            m[h] = mn;
-            p[h] = z > -INFINITY ? __expf(z - mn) : 0.f;
-            lpart[h] = fmaf(lpart[h], corr, p[h]);
+            // the running maximum (one value for the whole wavefront) settles after a few tiles: the
+            // sums are rescaled only when it moves
+            if (mrow > m[h]) {
+                const float corr = __expf(m[h] - mrow);                  // exp(-inf) = 0 on the first rows
+                m[h] = mrow;
+                lpart[h] *= corr;
 #pragma unroll
-            for (int e = 0; e < 8; ++e) acc[h][e] *= corr;
+                for (int e = 0; e < 8; ++e) acc[h][e] *= corr;
+            }
+            p[h] = z > -INFINITY ? __expf(z - m[h]) : 0.f;
+            lpart[h] += p[h];
         }
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
