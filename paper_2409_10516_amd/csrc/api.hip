@@ -541,8 +541,8 @@ extern "C" ra_status ra_rerank(const void* q, const void* K, ra_dtype dt, int n_
 extern "C" size_t ra_flat_workspace_bytes(int n_seq, int n_q_heads, int64_t N) {
     if (n_seq < 1 || n_q_heads < 1 || N < 1) return 0;
     // one order-preserving key per (head, key), then 16 tile maxima per (head, chunk of 512 keys),
-    // then eight candidate counters per head
-    return (size_t)n_seq * n_q_heads * (N + 16 * ((N + 511) / 512) + 8) * sizeof(uint32_t);
+    // then the candidate counters of the second pass
+    return (size_t)n_seq * n_q_heads * (N + 16 * ((N + 511) / 512) + RA_FLAT_SLICES) * sizeof(uint32_t);
 }
 
 extern "C" ra_status ra_flat_topk(const void* q, const void* K, ra_dtype dt, int n_seq, int n_q,

@@ -78,6 +78,7 @@ struct ra_index {
 };
 
 #define RA_COOP_REC 132
+#define RA_FLAT_SLICES 8       /* workgroups per head in the second pass of ra_flat_topk (one counter each) */
 #define RA_HELPERS_SILENT_ 2   /* launch-time helper mode behind RA_TEST_HELPERS_SILENT */
 #define RA_KEYS_I8 2          /* key type of a search over 8-bit keys (beside RA_F32, RA_BF16) */
 

@@ -166,7 +166,7 @@ __device__ __forceinline__ void radix_select(const uint32_t* __restrict__ kh, in
 }
 
 #define FL_CAND 4096               // candidate capacity of the fast path
-#define FL_SLICES 8                // workgroups per head that score the listed tiles again
+#define FL_SLICES RA_FLAT_SLICES    // workgroups per head that score the listed tiles again
 #define FL_SLICE_CAND 1024         // candidates one of them can hold
 
 // Second pass of the scan that stores no keys. Every workgroup of a head finds T0, a tile maximum

@@ -119,6 +119,19 @@ def test_full_attention_matches_eq1(name):
             assert out_close(out[s, h], ro, tol) and lse_close(lse[s, h], rl, tol)
 
 
+@pytest.mark.parametrize("n_q,n_kv", [(2, 2), (4, 2), (4, 1), (8, 1), (3, 1)])
+def test_full_attention_group_sizes_on_a_long_ragged_context(n_q, n_kv):
+    """4321 bf16 tokens: several sub-chunks per workgroup and a ragged last chunk. Groups of up to four
+    query heads take their logits from the matrix cores, larger and odd ones from the vector units."""
+    w = synth.make_llama_layer(23, N=4321, M=8, T=1, n_q=n_q, n_kv=n_kv)
+    out, lse = ra.ra_full_attention(w.q_decode[0].to(DEV), w.K.to(DEV), w.V.to(DEV))
+    out, lse = out.cpu().numpy(), lse.cpu().numpy()
+    for h in range(n_q):
+        g = h // (n_q // n_kv)
+        ro, rl = OA.full_attention(to_np(w.q_decode[0, 0, h]), to_np(w.K[0, g]), to_np(w.V[0, g]))
+        assert out_close(out[0, h], ro, 2e-3) and lse_close(lse[0, h], rl, 2e-3), (n_q, n_kv, h)
+
+
 def test_full_attention_long_context_uses_few_records():
     """A 40000-token context takes the multi-sub-chunk path of the attention kernel."""
     w = synth.make_llama_layer(21, N=40000, M=8, T=1, n_q=4, n_kv=2)
