@@ -171,6 +171,9 @@ ra_status ra_decode_step_budgets(const void* q, const ra_index* idx, const void*
  * largest inner product outside W for every (sequence, query head), best first, ties to the lower
  * id, padded with -1. Scores are the same fixed-order float32 inner products ra_search uses, so
  * the two rank keys identically and recall of the graph search can be measured on the device.
+ * The scan stores no per-key scores when the context is long enough for it (at least 64 x topk keys,
+ * at most 256K): it keeps the largest score of every 32 keys, derives a threshold that at least topk
+ * of those maxima reach, and scores the few tiles at or above it a second time.
  * workspace: device memory of at least ra_flat_workspace_bytes(n_seq, n_q_heads, N) bytes. */
 size_t ra_flat_workspace_bytes(int n_seq, int n_q_heads, int64_t N);
 ra_status ra_flat_topk(const void* q, const void* K, ra_dtype dt, int n_seq, int n_q_heads,
@@ -178,6 +181,9 @@ ra_status ra_flat_topk(const void* q, const void* K, ra_dtype dt, int n_seq, int
                        void* workspace, size_t workspace_bytes, void* stream, int32_t* ids);
 
 /* Eq. 1: softmax attention over all N tokens (what the method approximates), as (out, lse).
+ * float32 accumulation throughout; for bf16 inputs and GQA groups of up to four query heads the
+ * logits of a long context come from the matrix cores (sums of exact bf16 products in the
+ * hardware's order), otherwise from the vector units. Same tolerance either way.
  * workspace: device memory of at least ra_full_attention_workspace_bytes(...) bytes. */
 size_t ra_full_attention_workspace_bytes(int n_seq, int n_q_heads, int n_kv_heads, int64_t N);
 ra_status ra_full_attention(const void* q, const void* K, const void* V, ra_dtype dt, int n_seq,
