@@ -19,6 +19,8 @@ def _cases():
                                                       window=100), 64),
         "llama_f32_2seq": (lambda: synth.make_llama_layer(12, N=701, M=8, T=2, n_seq=2, n_q=4, n_kv=4,
                                                           dtype=torch.float32, window=37), 16),
+        "llama_f32_long": (lambda: synth.make_llama_layer(13, N=6000, M=8, T=1, n_q=4, n_kv=2,
+                                                          dtype=torch.float32, window=100), 40),
         "integer_ties": (lambda: synth.make_integer_case(5, N=2500, M=8, T=3, d=128, n_q=2, n_kv=1,
                                                          sink=3, window=10), 200),
         "integer_bf16_g8": (lambda: synth.make_integer_case(6, N=300, M=8, T=2, d=128, n_q=8, n_kv=1,
