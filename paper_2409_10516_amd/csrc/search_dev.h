@@ -680,7 +680,18 @@ __device__ __forceinline__ int run_search(
         //      Everything dropped is below at least ef survivors; which survive does not depend on
         //      the order of the candidates. The claimed ids (cid) are dead by now: their first 256
         //      words are the histogram.
+        // A seed set (empty beam, nothing expanded, every key kept) goes one step further: the same
+        // bins also order the survivors. A survivor's place among the kept keys is the number of
+        // keys in higher bins (a suffix sum over the histogram) plus its rank inside its own bin,
+        // found by comparing it with the few keys that share the bin: the survivors are dealt into
+        // buckets by bin (ckey is free: every thread holds its keys in registers), and each one
+        // then counts the larger keys of its bucket. That replaces the merge below, whose counting
+        // is quadratic in the survivors (about ef of them), for the one step where it is large;
+        // beam, picks and counters come out as the merge would leave them (all entries unexpanded:
+        // the unexpanded entries above a key are its position).
+        bool bucketed = false;
         if (nk > ef + SR_PREFILTER_SLACK && nk <= SR_PREFILTER_REGS * T && maxc >= 256) {
+            const bool buckets = first && seeded && maxc >= 768;
             u64 mine[SR_PREFILTER_REGS];
             uint32_t lo = 0xffffffffu, hi = 0u;
 #pragma unroll
@@ -705,7 +716,7 @@ __device__ __forceinline__ int run_search(
                     atomicMax(reinterpret_cast<unsigned int*>(&ctr[C_HI]), hi);
                 }
             }
-            if (tid < 256) cid[tid] = 0;
+            if (tid < 256) { cid[tid] = 0; if (buckets) cid[512 + tid] = 0; }    // counts; bucket fill
             __syncthreads();
             // bin = (score - lowest) * 255 / (highest - lowest), truncated: every operation is
             // monotone in the score, so a larger score never lands in a lower bin. Non-finite
@@ -729,15 +740,60 @@ __device__ __forceinline__ int run_search(
                 const int from3 = total - incl + b3, from2 = from3 + b2, from1 = from2 + b1, from0 = from1 + b0;
                 const int best = from3 >= ef ? 3 : from2 >= ef ? 2 : from1 >= ef ? 1 : from0 >= ef ? 0 : -1;
                 const u64 has = __ballot(best >= 0);          // never empty: bin 0 and up hold all nk > ef
-                if (lane == 63 - __clzll(has)) ctr[C_BIN] = 4 * lane + best;
+                if (lane == 63 - __clzll(has)) {
+                    ctr[C_BIN] = 4 * lane + best;
+                    if (buckets) ctr[C_NSURV] = best == 3 ? from3 : best == 2 ? from2 : best == 1 ? from1 : from0;
+                }
+                if (buckets) {                               // keys in the bins above each bin
+                    cid[256 + 4 * lane + 3] = from3 - b3;
+                    cid[256 + 4 * lane + 2] = from2 - b2;
+                    cid[256 + 4 * lane + 1] = from1 - b1;
+                    cid[256 + 4 * lane] = from0 - b0;
+                }
             }
             __syncthreads();
             const int bstar = ctr[C_BIN];
+            if (buckets) {
+                const int nsurv = ctr[C_NSURV];              // >= ef
+#pragma unroll
+                for (int r = 0; r < SR_PREFILTER_REGS; ++r)
+                    if (r * T + tid < nk && bin[r] >= bstar)
+                        ckey[cid[256 + bin[r]] + atomicAdd(&cid[512 + bin[r]], 1)] = mine[r];
+                __syncthreads();
+                for (int p = tid; p < nsurv; p += T) {
+                    u64 k = ckey[p];
+                    const float b = (f32_from_ordered((uint32_t)(k >> 32)) - lo_f) * to_bin;
+                    const int kb = b >= 255.f ? 255 : b > 0.f ? (int)b : 0;
+                    const int bs = cid[256 + kb], be = bs + cid[kb];
+                    int pos = bs;
+                    for (int j = bs; j < be; ++j) pos += ckey[j] > k ? 1 : 0;
+                    if (pos < ef) {
+                        if (pos < expand) {                  // this step's picks: the first `expand` entries
+                            picks[pos] = key_id(k);
+#ifndef SR_NO_EARLY_TOUCH
+                            early_a = *reinterpret_cast<const uint32_t*>(adj_h + (size_t)key_id(k) * deg);
+#endif
+                            k &= ~1ull;
+                        }
+                        nxt[pos] = k;
+                        urank_nxt[pos] = (uint16_t)pos;
+                    }
+                }
+                if (tid == 0) {
+                    ctr[C_NUNEXP] = ef;                      // every entry of the new beam (nsurv >= ef)
+                    ctr[C_NCAND] = 0;
+                    ctr[C_NKEEP] = 0;
+                }
+                nk = nsurv;
+                bucketed = true;
+            }
+            if (!bucketed) {
 #pragma unroll
             for (int r = 0; r < SR_PREFILTER_REGS; ++r)
                 if (r * T + tid < nk && bin[r] >= bstar) ckey[atomicAdd(&ctr[C_NSURV], 1)] = mine[r];
             __syncthreads();
             nk = ctr[C_NSURV];
+            }
         }
         SR_TICK(11);
 
@@ -750,7 +806,7 @@ __device__ __forceinline__ int run_search(
         //      count of *unexpanded* elements above each element (every candidate is unexpanded;
         //      for the beam's part urank has it), so the next step's picks, the elements with
         //      fewer than `expand` unexpanded ones above them, fall out of the merge.
-        {
+        if (!bucketed) {
             const int E = bn + nk;
             const int nch = (nk + 15) >> 4;
             const int items = nk * nch;
