@@ -70,6 +70,9 @@ def parse():
     p.add_argument("--graph", type=int, default=1, help="replay the step from a captured HIP graph")
     p.add_argument("--q8", type=int, default=0,
                    help="1: the graph walk reads an 8-bit copy of the keys (ra_decode_step_q8)")
+    p.add_argument("--seed-shares", type=int, default=None,
+                   help="workgroups a head's start set is scored by beside its own (RA_CFG_SEED_SHARES: 0, 2..8; "
+                        "default: the library's)")
     p.add_argument("--helpers", type=int, default=1,
                    help="0: every head attends to the static set itself (no helper workgroups)")
     p.add_argument("--copy-calibration", action="store_true",
@@ -237,6 +240,8 @@ def main():
             if not a.helpers:
                 idx.configure(B.RA_CFG_HELPERS, B.RA_HELPERS_OFF)
             idx.configure(B.RA_CFG_SEEDS, seeds)
+            if a.seed_shares is not None:
+                idx.configure(B.RA_CFG_SEED_SHARES, a.seed_shares)
             k8 = ra.ra_quantize_keys(w.K) if a.q8 else None
             torch.cuda.synchronize()
             t2 = time.time()
@@ -303,6 +308,7 @@ def main():
         ms_per_step = 1e3 * wall / steps
         decode_ms_region = ev0.elapsed_time(ev1) / (steps * len(layers))
         helpers_still_on = all(L["idx"].helpers_active for L in layers) if a.helpers else False
+        seed_shares_on = all(L["idx"].seed_shares_active for L in layers) if a.helpers else False
 
         # spread of the step latency (a separate pass: one event pair per step, each step waited for)
         lat = []
@@ -403,7 +409,8 @@ def main():
                          "algorithmic_bytes_per_launch": decode_bytes,
                          "visited_per_search": visited / heads, "expanded_per_search": expanded / heads,
                          "iters_per_search": iters / heads,
-                         "helper_workgroups_active_after_timed_region": helpers_still_on},
+                         "helper_workgroups_active_after_timed_region": helpers_still_on,
+                         "seed_workgroups_active_after_timed_region": seed_shares_on},
             "build": {"seconds": t_build, "generate_seconds": t_gen,
                       "knn_TFLOPs_incl_projection": build_flop / max(t_build, 1e-9) / 1e12, "knn_kernel": knn_rec},
         }

@@ -240,7 +240,10 @@ ra_status ra_decode_step_q8(const void* q, const ra_index* idx, const void* K, c
 
 /* what: 0 n_seq, 1 n_q_heads, 2 n_kv_heads, 3 N, 4 deg, 5 bytes of device memory owned,
  * 6 whether ra_decode_step will use helper workgroups (1 / 0; synchronises the device),
- * 7 the seed-set size in use (RA_CFG_SEEDS; 0: single entry point). */
+ * 7 the seed-set size in use (RA_CFG_SEEDS; 0: single entry point),
+ * 8 whether ra_decode_step may score the seed sets in workgroups of their own (RA_CFG_SEED_SHARES;
+ *   1 / 0: off, no seed sets, helpers off, or a head's wait for its keys ran out; synchronises the
+ *   device). */
 int64_t ra_index_info(const ra_index* idx, int what);
 
 /* Settings of the handle's decode path (host side; synchronises the device).
@@ -278,10 +281,27 @@ int64_t ra_index_info(const ra_index* idx, int what);
  *                       beam, none is expanded yet; they count as visited, no step is counted for
  *                       them. n = 1 is the single-entry walk. Applies to ra_search, ra_decode_step
  *                       and their variants, which then need n <= expand x deg (RA_EINVAL
- *                       otherwise). Lists the sets on the device and synchronises it. */
+ *                       otherwise). Lists the sets on the device and synchronises it.
+ *   RA_CFG_SEED_SHARES  into how many shares ra_decode_step cuts a head's seed set, each scored by a
+ *                       workgroup of its own in the same launch while the head's workgroup sets up
+ *                       (what bounds the scoring of a start set is the rate at which one compute
+ *                       unit takes in scattered key rows): 0 (the head scores its set itself) or
+ *                       2 .. 8; default 4. Used only where every workgroup of the launch has a compute
+ *                       unit to itself (the searches, their shares and the helpers together number at
+ *                       most the device's compute units; fewer shares are used to make that so, none
+ *                       below two), the walks use 1024-thread workgroups and the visited bitsets fit
+ *                       LDS; RA_HELPERS_OFF switches the shares off as well. The keys are the same
+ *                       bits whoever computes them, so ids, counters and outputs do not depend on the
+ *                       setting. They cross workgroups through device memory the handle owns, one
+ *                       64-bit slot per seed that the head polls and zeroes again, with the same
+ *                       relaxed agent-scope accesses, the same bounded wait (RA_CFG_HELPER_SPIN
+ *                       polls per slot) and the same fall-back as the helpers' records: a head whose
+ *                       keys do not arrive scores its set itself and the handle stops using shares
+ *                       until RA_CFG_HELPERS or RA_CFG_SEED_SHARES is set again. */
 #define RA_CFG_HELPERS 0
 #define RA_CFG_HELPER_SPIN 1
 #define RA_CFG_SEEDS 2
+#define RA_CFG_SEED_SHARES 3
 #define RA_HELPERS_OFF 0
 #define RA_HELPERS_ON 1
 #define RA_HELPER_SPIN_DEFAULT 20000
@@ -294,10 +314,10 @@ ra_status ra_index_configure(ra_index* idx, int what, int64_t value);
  *                           ra_knn uses for bf16 lists of up to 32 keys: RA_TEST_KNN_AUTO
  *                           (default: chosen by N), RA_TEST_KNN_REG, RA_TEST_KNN_LDS. Same lists
  *                           either way.
- *   RA_TEST_HELPERS_SILENT  (per handle) 1: the helper workgroups of ra_decode_step are launched
- *                           but write nothing, so every head's bounded wait runs out and the
- *                           fall-back is taken; 0: normal. Synchronises the device and clears the
- *                           hand-over area like RA_CFG_HELPERS. */
+ *   RA_TEST_HELPERS_SILENT  (per handle) 1: the helper and seed workgroups of ra_decode_step are
+ *                           launched but write nothing, so every head's bounded wait runs out and
+ *                           the fall-back is taken; 0: normal. Synchronises the device and clears
+ *                           the hand-over areas like RA_CFG_HELPERS. */
 #define RA_TEST_KNN_SELECTION 100
 #define RA_TEST_HELPERS_SILENT 101
 #define RA_TEST_KNN_AUTO 0

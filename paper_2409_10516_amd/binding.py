@@ -18,7 +18,7 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.environ.get("RA_LIBRARY") or os.path.join(_HERE, "libra.so")
 
 RA_F32, RA_BF16 = 0, 1
-RA_CFG_HELPERS, RA_CFG_HELPER_SPIN, RA_CFG_SEEDS = 0, 1, 2
+RA_CFG_HELPERS, RA_CFG_HELPER_SPIN, RA_CFG_SEEDS, RA_CFG_SEED_SHARES = 0, 1, 2, 3
 RA_HELPERS_OFF, RA_HELPERS_ON = 0, 1
 # test-only settings (ra_test_configure)
 RA_TEST_KNN_SELECTION, RA_TEST_HELPERS_SILENT = 100, 101
@@ -157,11 +157,12 @@ class Index:
     deg = property(lambda s: s.info(4))
     device_bytes = property(lambda s: s.info(5))
     helpers_active = property(lambda s: s.info(6) == 1)
+    seed_shares_active = property(lambda s: s.info(8) == 1)
 
     n_seeds = property(lambda s: s.info(7))
 
     def configure(self, what: int, value: int) -> None:
-        """ra_index_configure: RA_CFG_HELPERS / RA_CFG_HELPER_SPIN / RA_CFG_SEEDS."""
+        """ra_index_configure: RA_CFG_HELPERS / RA_CFG_HELPER_SPIN / RA_CFG_SEEDS / RA_CFG_SEED_SHARES."""
         _check(lib().ra_index_configure(self.handle, what, value))
 
     def test_configure(self, what: int, value: int) -> None:

@@ -124,6 +124,7 @@ static ra_status new_handle(int n_seq, int n_q, int n_kv, int64_t N, int deg, ra
     if (e == hipSuccess) e = hipMemset(ix->coop, 0, coop_bytes(ix));
     ix->coop_mode = RA_HELPERS_ON;
     ix->coop_spin = RA_HELPER_SPIN_DEFAULT;
+    ix->seed_parts = RA_SEED_PARTS_DEFAULT;
     if (e != hipSuccess) {
         ra_set_error("allocating the graph (%zu B) failed: %s", ix->graph_bytes, hipGetErrorString(e));
         if (ix->adj) (void)hipFree(ix->adj);
@@ -147,6 +148,7 @@ extern "C" void ra_index_free(ra_index* ix) {
     if (ix->coop) (void)hipFree(ix->coop);
     if (ix->roots) (void)hipFree(ix->roots);
     if (ix->seeds) (void)hipFree(ix->seeds);
+    if (ix->seedx) (void)hipFree(ix->seedx);
     delete ix;
 }
 
@@ -159,6 +161,7 @@ extern "C" ra_status ra_index_configure(ra_index* ix, int what, int64_t value) {
             // also forgets a wait that ran out: ready words and the off word start from zero
             RA_HIP(hipDeviceSynchronize());
             RA_HIP(hipMemset(ix->coop, 0, coop_bytes(ix)));
+            if (ix->seedx) RA_HIP(hipMemset(ix->seedx, 0, ix->seedx_bytes));
             ix->coop_mode = (int)value;
             ix->coop_silent = 0;
             return RA_OK;
@@ -166,6 +169,13 @@ extern "C" ra_status ra_index_configure(ra_index* ix, int what, int64_t value) {
         case RA_CFG_HELPER_SPIN:
             if (value < 1 || value > (1 << 24)) RA_FAIL(RA_EINVAL, "spin limit %lld", (long long)value);
             ix->coop_spin = (int)value;
+            return RA_OK;
+        case RA_CFG_SEED_SHARES:
+            if (value != 0 && (value < 2 || value > RA_SEED_PARTS_MAX))
+                RA_FAIL(RA_EINVAL, "seed shares %lld: 0 or 2 .. %d", (long long)value, RA_SEED_PARTS_MAX);
+            RA_HIP(hipDeviceSynchronize());
+            if (ix->seedx) RA_HIP(hipMemset(ix->seedx, 0, ix->seedx_bytes));
+            ix->seed_parts = (int)value;
             return RA_OK;
         case RA_CFG_SEEDS: {
             if (value < 0 || value > RA_MAX_SEEDS)
@@ -184,6 +194,11 @@ extern "C" ra_status ra_index_configure(ra_index* ix, int what, int64_t value) {
                 ix->n_seeds = 0;
                 RA_HIP(hipMalloc((void**)&ix->seeds, graphs * (size_t)(n + 2) * sizeof(int32_t)));
                 ix->seed_cap = n + 2;
+                if (ix->seedx) RA_HIP(hipFree(ix->seedx));
+                ix->seedx = nullptr;
+                ix->seedx_bytes = RA_SEEDX_KEYS_OFF + graphs * (size_t)(n + 2) * sizeof(uint64_t);
+                RA_HIP(hipMalloc((void**)&ix->seedx, ix->seedx_bytes));
+                RA_HIP(hipMemset(ix->seedx, 0, ix->seedx_bytes));
             }
             RA_TRY(ra_launch_seeds(ix->adj, ix->entry, (int)graphs, ix->N, ix->deg, n, ix->seeds, ix->seed_cap,
                                    nullptr));
@@ -208,6 +223,7 @@ extern "C" ra_status ra_test_configure(ra_index* ix, int what, int64_t value) {
             if (value != 0 && value != 1) RA_FAIL(RA_EINVAL, "silent helpers %lld", (long long)value);
             RA_HIP(hipDeviceSynchronize());
             RA_HIP(hipMemset(ix->coop, 0, coop_bytes(ix)));
+            if (ix->seedx) RA_HIP(hipMemset(ix->seedx, 0, ix->seedx_bytes));
             ix->coop_silent = (int)value;
             return RA_OK;
         default:
@@ -225,6 +241,7 @@ extern "C" int64_t ra_index_info(const ra_index* ix, int what) {
         case 4: return ix->deg;
         case 5: return (int64_t)(ix->graph_bytes + (size_t)ix->n_seq * ix->n_q * 4 +
                                  ix->partials_bytes + ix->ids_bytes + ix->bitset_bytes + coop_bytes(ix) +
+                                 ix->seedx_bytes +
                                  (size_t)ix->n_seq * ix->n_q * (ix->root_cap + ix->seed_cap) * sizeof(int32_t));
         case 6: {
             if (ix->coop_mode != RA_HELPERS_ON || ix->coop_silent) return 0;
@@ -240,6 +257,16 @@ extern "C" int64_t ra_index_info(const ra_index* ix, int what) {
             return off == 0u;
         }
         case 7: return ix->n_seeds;
+        case 8: {
+            // 1 while the seed shares are on and no head's wait for them has run out
+            if (!ix->n_seeds || !ix->seedx || ix->seed_parts < 2 || ix->coop_mode != RA_HELPERS_ON || ix->coop_silent)
+                return 0;
+            uint32_t off = 1u;
+            if (hipDeviceSynchronize() != hipSuccess ||
+                hipMemcpy(&off, ix->seedx, sizeof(off), hipMemcpyDeviceToHost) != hipSuccess)
+                return -1;
+            return off == 0u;
+        }
         default: return -1;
     }
 }
@@ -476,7 +503,7 @@ static ra_status decode_common(const void* q, const ra_index* idx, const void* K
     return ra_launch_decode(q, ix->adj, ix->entry, K, V, dt, ix->n_seq, ix->n_q, ix->n_kv, ix->N, N,
                             kv_stride, ix->deg, sink, window, topk, ef, expand, ix->bitset, ix->coop,
                             ix->coop_silent ? RA_HELPERS_SILENT_ : ix->coop_mode, ix->coop_spin, start, start_cap, K8, kscale,
-                            budgets,
+                            budgets, ix->n_seeds ? ix->seedx : nullptr, ix->seed_parts,
                             (hipStream_t)stream, out, lse, ids, stats);
 }
 

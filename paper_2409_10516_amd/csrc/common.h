@@ -71,6 +71,11 @@ struct ra_index {
     // seed sets (RA_CFG_SEEDS): [n_seq*n_q][seed_cap] in the layout of the root sets, or null
     int32_t* seeds;
     int n_seeds, seed_cap;
+    // seed hand-over area of the fused decode kernel (allocated with the seed sets): one "shares
+    // off" word, then from byte RA_SEEDX_KEYS_OFF seed_cap 64-bit keys per head, zero between launches
+    uint32_t* seedx;
+    size_t seedx_bytes;
+    int seed_parts;     // shares a head's start set is scored in by workgroups of their own (0: by the head)
     // root sets: what the first two steps of every walk of a head visit ([n_seq*n_q][root_cap])
     int32_t* roots;
     int root_cap;
@@ -78,6 +83,11 @@ struct ra_index {
 };
 
 #define RA_COOP_REC 132
+#define RA_SEED_PARTS_MAX 8    /* most shares a head's start set is scored in */
+#ifndef RA_SEED_PARTS_DEFAULT
+#define RA_SEED_PARTS_DEFAULT 4
+#endif
+#define RA_SEEDX_KEYS_OFF 256  /* bytes in front of the keys of the seed hand-over area */
 #define RA_FLAT_SLICES 8       /* workgroups per head in the second pass of ra_flat_topk (one counter each) */
 #define RA_HELPERS_SILENT_ 2   /* launch-time helper mode behind RA_TEST_HELPERS_SILENT */
 #define RA_KEYS_I8 2          /* key type of a search over 8-bit keys (beside RA_F32, RA_BF16) */
@@ -117,8 +127,8 @@ ra_status ra_launch_decode(const void* q, const int32_t* adj, const int32_t* ent
                            int64_t kv_stride, int deg, int sink, int window, int topk, int ef, int expand,
                            uint32_t* bitset, float* coop, int coop_mode, int coop_spin,
                            const int32_t* roots, int root_cap, const void* K8, const float* kscale,
-                           const int32_t* budgets, hipStream_t st, float* out, float* lse, int32_t* ids,
-                           ra_stats* stats);
+                           const int32_t* budgets, uint32_t* seedx, int seed_parts, hipStream_t st,
+                           float* out, float* lse, int32_t* ids, ra_stats* stats);
 
 ra_status ra_launch_rerank(const void* q, const void* K, ra_dtype dt, int n_seq, int n_q, int n_kv, int64_t N,
                            const int32_t* cand, int n_cand, int topk, hipStream_t st, int32_t* ids);

@@ -26,6 +26,16 @@
 // the helpers off for later launches, so a ready word that arrives late is never taken for the
 // next launch's. Query heads of a GQA group still run on one XCD (xcd_aware_head) so that the key
 // rows their searches have in common are served by that XCD's L2.
+//
+// A walk that starts from a seed set first scores the whole set, and what bounds that is the rate
+// at which one compute unit takes in scattered key rows. A launch with few searches leaves most
+// compute units idle, so it has "seed" workgroups as well (between the helpers and the heads):
+// each scores one share of one head's set (score_seed_share) and stores the 64-bit keys in a
+// hand-over area of their own, one slot per position of the set. A key is never zero and is one
+// 64-bit store, so the slot itself says whether its key has come: the head's threads poll their
+// slots (bounded), take the keys and zero the slots for the next launch. If a key does not come
+// in time the head scores its set itself and switches the shares off for later launches. Same
+// relaxed agent-scope accesses as above; no ordering between different words is needed at all.
 #include "attend_dev.h"
 #include "search_dev.h"
 
@@ -112,20 +122,6 @@ template <> struct LaneQuery<RA_F32> {
         return d;
     }
 };
-
-// Words that cross workgroups inside one launch: relaxed agent-scope atomics (see the file header).
-__device__ __forceinline__ void xwg_store(float* p, float v) {
-    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-__device__ __forceinline__ void xwg_store(uint32_t* p, uint32_t v) {
-    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-__device__ __forceinline__ float xwg_load(const float* p) {
-    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
-__device__ __forceinline__ uint32_t xwg_load(const uint32_t* p) {
-    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-}
 
 // Combine the online-softmax states of the lane groups of a workgroup of T threads into one (max,
 // sum, weighted sum for output `tid`), valid in threads tid < 128 (T >= 128): first the four
@@ -246,6 +242,35 @@ struct AwaitHelper {
     uint32_t* lds_word;
     int spin;
     bool on;
+    // this head's keys in the seed hand-over area, the area's "shares off" word, whether the launch
+    // has seed workgroups
+    u64* seed_keys;
+    uint32_t* seed_off;
+    bool seed_on;
+    static constexpr bool kSeedShare = true;
+    __device__ __forceinline__ bool seeds_shared() const { return seed_on; }
+    // Keys c0 and c1 of the head's start set (c1 < 0: only c0, and k1 = k0), polled together a bounded
+    // number of times, the slots zeroed for the next launch once the keys are taken; a key that did
+    // not come reads 0. A poll is a trip to memory (agent-scope loads go around the caches); more
+    // than one in flight per slot was measured and is slower.
+    __device__ __forceinline__ void take_seed_keys(int c0, int c1, u64& k0, u64& k1) const {
+        u64* p0 = seed_keys + c0;
+        u64* p1 = seed_keys + (c1 >= 0 ? c1 : c0);
+        k0 = 0ull;
+        k1 = 0ull;
+        for (int i = 0; i < spin; ++i) {
+            const u64 a = xwg_load(p0), b = xwg_load(p1);
+            if (k0 == 0ull) k0 = a;
+            if (k1 == 0ull) k1 = b;
+            if (k0 != 0ull && k1 != 0ull) break;
+            __builtin_amdgcn_s_sleep(6);
+        }
+        if (k0 != 0ull) xwg_store(p0, 0ull);
+        if (c1 >= 0 && k1 != 0ull) xwg_store(p1, 0ull);
+    }
+    // a key did not come: later launches score in the head again, so that keys that arrive late
+    // are never taken for a later launch's
+    __device__ __forceinline__ void seeds_missed() const { xwg_store(seed_off, 1u); }
     __device__ __forceinline__ void before_output() const {
         if (!on || threadIdx.x != RA_WAVE) return;
         uint32_t f = 0u;
@@ -271,12 +296,13 @@ __global__ __launch_bounds__(T) void decode_kernel(
     int32_t* __restrict__ ids, ra_stats* __restrict__ stats, int ids_off, float scale,
     float* __restrict__ out, float* __restrict__ lse, float* coop, int n_helpers, int coop_mode,
     int coop_spin, const int32_t* __restrict__ roots, int root_cap, const void* __restrict__ Ksearch,
-    const float* __restrict__ kscale, const int32_t* __restrict__ budgets) {
+    const float* __restrict__ kscale, const int32_t* __restrict__ budgets, uint32_t* seedx, int seed_parts,
+    int seed_stride) {
     extern __shared__ __align__(16) unsigned char lds_raw[];
     const int tid = threadIdx.x, grp = tid >> 4, lane16 = tid & 15;
     const size_t esz = DT == RA_BF16 ? 2 : 4;
     const int G = n_q / n_kv;
-    const int n_heads = (int)gridDim.x - n_helpers;
+    const int n_heads = ((int)gridDim.x - n_helpers) / (1 + seed_parts);
     // hand-over area: records, ready words, "helpers off" word (set by a head whose wait ran out)
     uint32_t* ready = reinterpret_cast<uint32_t*>(coop + (size_t)n_heads * RA_COOP_REC);
     const bool helpers = n_helpers > 0 && xwg_load(ready + n_heads) == 0u;
@@ -296,7 +322,21 @@ __global__ __launch_bounds__(T) void decode_kernel(
         }
         return;
     }
-    const int head = xcd_aware_head((int)blockIdx.x - n_helpers, n_heads, G);
+    // seed hand-over area: [0] the "shares off" word, then (from byte RA_SEEDX_KEYS_OFF) seed_stride
+    // 64-bit keys per head, zero between launches
+    u64* seed_keys_all = reinterpret_cast<u64*>(reinterpret_cast<char*>(seedx) + RA_SEEDX_KEYS_OFF);
+    const bool shares = seed_parts > 0 && xwg_load(seedx) == 0u;
+    if ((int)blockIdx.x < n_helpers + n_heads * seed_parts) {
+        // ---- seed workgroup: one share of one head's start set (on the XCD of the head's workgroup
+        //      when the number of heads is a multiple of 8)
+        if (!shares || coop_mode == RA_HELPERS_SILENT_) return;
+        const int i = (int)blockIdx.x - n_helpers;
+        const int part = i / n_heads, hd = xcd_aware_head(i % n_heads, n_heads, G);
+        score_seed_share<DT, KT, T>(hd, part, seed_parts, q, Ksearch, n_q, n_kv, kv_stride, roots, root_cap,
+                                    root_cap - 2, expand * deg, kscale, seed_keys_all + (size_t)hd * seed_stride);
+        return;
+    }
+    const int head = xcd_aware_head((int)blockIdx.x - n_helpers - n_heads * seed_parts, n_heads, G);
     const int seq = head / n_q, h = head % n_q, kvh = h / G;
     int32_t* lds_ids = reinterpret_cast<int32_t*>(lds_raw + ids_off);
     uint32_t* lds_word = reinterpret_cast<uint32_t*>(lds_ids + topk);
@@ -315,7 +355,9 @@ __global__ __launch_bounds__(T) void decode_kernel(
                                           s, (int)(Ng - wstart), topk, take, ef, expand, gbits, ids, stats,
                                           lds_ids, roots, root_cap, kscale,
                                           AwaitHelper{ready + head, ready + n_heads, lds_word,
-                                                               coop_spin, helpers});
+                                                      coop_spin, helpers,
+                                                      seed_keys_all + (size_t)head * seed_stride, seedx,
+                                                      shares});
 #ifdef SR_PHASE_CLOCKS
     const long long t_attn = clock64();
 #endif
@@ -389,7 +431,7 @@ __global__ __launch_bounds__(T) void decode_kernel(
         }
     }
 #ifdef SR_PHASE_CLOCKS
-    if (tid == 0 && blockIdx.x < 64) sr_phase_ticks[blockIdx.x * SR_NITER * SR_NPHASE + 7] += clock64() - t_attn;
+    if (tid == 0 && head < 64) sr_phase_ticks[head * SR_NITER * SR_NPHASE + 7] += clock64() - t_attn;
 #endif
 }
 
@@ -438,13 +480,26 @@ static int decode_helper_slots(const float* coop, int coop_mode, int n_seq, int 
     return coop_on ? n_seq * n_kv : 0;
 }
 
+// compute units of the current device (asked once per device)
+static int decode_compute_units() {
+    static int cached[64];
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return 0;
+    if (cached[dev] == 0) {
+        int n = 0;
+        if (hipDeviceGetAttribute(&n, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) n = 0;
+        cached[dev] = n > 0 ? n : -1;
+    }
+    return cached[dev] > 0 ? cached[dev] : 0;
+}
+
 ra_status ra_launch_decode(const void* q, const int32_t* adj, const int32_t* entry, const void* K,
                            const void* V, ra_dtype dt, int n_seq, int n_q, int n_kv, int64_t Ng, int64_t N,
                            int64_t kv_stride, int deg, int sink, int window, int topk, int ef, int expand,
                            uint32_t* bitset, float* coop, int coop_mode, int coop_spin,
                            const int32_t* roots, int root_cap, const void* K8, const float* kscale,
-                           const int32_t* budgets, hipStream_t st, float* out, float* lse, int32_t* ids,
-                           ra_stats* stats) {
+                           const int32_t* budgets, uint32_t* seedx, int seed_parts, hipStream_t st,
+                           float* out, float* lse, int32_t* ids, ra_stats* stats) {
     // W = [0, s) u [wstart, N): the sink, the sliding window, and every token appended after the
     // index was built (wstart <= Ng); overlapping ranges make everything static
     int64_t s = sink < 0 ? 0 : sink, ww = window < 0 ? 0 : window;
@@ -471,16 +526,28 @@ ra_status ra_launch_decode(const void* q, const int32_t* adj, const int32_t* ent
     const int n_helpers = decode_helper_slots(coop, coop_mode, n_seq, n_q, n_kv);
     const int threads = search_threads(heads, ef);
     const void* Ksearch = kscale ? K8 : K;
+    // a start set scored in shares by workgroups of their own: only where every workgroup of the
+    // launch has a compute unit to itself (few searches, 1024 threads each) and the visited bitsets
+    // are in LDS; fewer shares when the part has too few compute units, none below two
+    int parts = 0;
+    if (seedx && seed_parts > 0 && roots && !gb && threads == 1024 && coop_mode != RA_HELPERS_OFF) {
+        const int room = (decode_compute_units() - n_helpers) / heads - 1;
+        parts = seed_parts < room ? seed_parts : room;
+        if (parts > RA_SEED_PARTS_MAX) parts = RA_SEED_PARTS_MAX;
+        if (parts < 2) parts = 0;
+    }
+    const int seed_stride = root_cap;
     if (kscale && !K8) RA_FAIL(RA_EINVAL, "8-bit keys missing");
 #define RA_DC_GO_T(DTV, KTV, GB, TV) RA_DC_GO_TB(DTV, KTV, GB, TV, false)
 #define RA_DC_GO_TB(DTV, KTV, GB, TV, BU)                                                          \
     do {                                                                                           \
         RA_LDS_OPT_IN((decode_kernel<DTV, KTV, GB, TV, BU>), lds);                                 \
-        hipLaunchKernelGGL((decode_kernel<DTV, KTV, GB, TV, BU>), dim3(heads + n_helpers), dim3(TV), \
+        hipLaunchKernelGGL((decode_kernel<DTV, KTV, GB, TV, BU>),                                  \
+                           dim3(heads * (1 + parts) + n_helpers), dim3(TV),                        \
                            lds, st, q, adj, entry, K, V, n_q, n_kv, Ng, N, kv_stride, wstart, deg, \
                            (int)s, topk, ef, expand, bitset, ids, stats, ids_off, scale, out, lse, \
                            coop, n_helpers, coop_mode, coop_spin, roots, root_cap, Ksearch,        \
-                           kscale, budgets);                                                       \
+                           kscale, budgets, seedx, parts, seed_stride);                            \
     } while (0)
 #define RA_DC_GO(DTV, KTV, GB)                                                                     \
     do {                                                                                           \

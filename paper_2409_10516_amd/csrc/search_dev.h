@@ -36,22 +36,24 @@
 #endif
 
 
-enum { C_NCAND = 1, C_NKEEP = 2, C_NUNEXP = 3, C_LO = 4, C_HI = 5, C_NSURV = 6, C_BIN = 7, C_WTOT = 8,
+enum { C_MISSED = 0, C_NCAND = 1, C_NKEEP = 2, C_NUNEXP = 3, C_LO = 4, C_HI = 5, C_NSURV = 6, C_BIN = 7, C_WTOT = 8,
        C_COUNT = 8 + SR_THREADS / RA_WAVE };
 #define SR_PREFILTER_SLACK 64     // a step that keeps more than ef + this many candidates drops the hopeless ones first
 #define SR_PREFILTER_REGS 8       // ... when a thread can hold its share of them (nk <= 8 T)
 
 typedef unsigned long long u64;
 
-// Phase clocks for tuning builds (-DSR_PHASE_CLOCKS): thread 0 of the first 64 workgroups adds the
+// Phase clocks for tuning builds (-DSR_PHASE_CLOCKS): thread 0 of the workgroups of the first 64 searches adds the
 // ticks spent in each phase to a device array that ra_dbg_phase_ticks copies out. Off otherwise.
 #ifdef SR_PHASE_CLOCKS
 #define SR_NPHASE 16
 #define SR_NITER 16
 static __device__ long long sr_phase_ticks[64 * SR_NITER * SR_NPHASE];
 #ifdef SR_WAVE_CLOCKS
-// (with -DSR_WAVE_CLOCKS: when each wavefront of workgroup 8, the first head behind eight helpers,
-// entered and left the scoring of its start set; ra_dbg_wave_ticks copies them out)
+// (with -DSR_WAVE_CLOCKS: wall-clock stamps of the first head's workgroup, [0..3] search entered,
+// state cleared, claims made, start set's keys in LDS, and of the first and last of its seed
+// workgroups, [8..11] and [16..19]: entered, header read, first rows scored, first keys stored;
+// ra_dbg_wave_ticks copies them out)
 static __device__ long long sr_wave_ticks[64];
 #endif
 // ticks are added up in LDS (a fire-and-forget add) and copied out when the search has ended
@@ -71,9 +73,9 @@ static __device__ long long sr_wave_ticks[64];
     } while (0)
 #define SR_TICK_FLUSH                                                                          \
     do {                                                                                       \
-        if (blockIdx.x < 64)                                                                   \
+        if (head < 64)                                                                         \
             for (int i_ = threadIdx.x; i_ < SR_NITER * SR_NPHASE; i_ += blockDim.x)            \
-                sr_phase_ticks[blockIdx.x * SR_NITER * SR_NPHASE + i_] += tick_lds_[i_];       \
+                sr_phase_ticks[head * SR_NITER * SR_NPHASE + i_] += tick_lds_[i_];             \
     } while (0)
 #else
 #define SR_TICK_INIT
@@ -346,9 +348,104 @@ __device__ __forceinline__ int xcd_aware_head(int block, int heads, int G) {
 // A caller's hook into run_search: before_output() is called by every thread when the walk has
 // ended, ahead of the phase in which the first wavefront writes the result (the others idle until
 // the closing barrier, which also publishes whatever the hook left in LDS).
+// Its kSeedShare says whether the start set of a seeded walk may be scored by other workgroups of
+// the launch (score_seed_share below): then seeds_shared() says whether it is in this launch,
+// take_seed_keys(c0, c1, k0, k1) waits (bounded) for keys c0 and c1 of the set (c1 < 0: only c0; k1 is
+// then k0 again) and leaves 0 for one that did not come, and seeds_missed() is called by one thread
+// when some key did not.
 struct NoHook {
+    static constexpr bool kSeedShare = false;
     __device__ __forceinline__ void before_output() const {}
 };
+
+// Words that cross workgroups inside one launch: relaxed agent-scope atomics, which go around the
+// cache levels that are not coherent across the part's XCDs.
+__device__ __forceinline__ void xwg_store(float* p, float v) {
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void xwg_store(uint32_t* p, uint32_t v) {
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void xwg_store(u64* p, u64 v) {
+    __hip_atomic_store(p, v, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ float xwg_load(const float* p) {
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ uint32_t xwg_load(const uint32_t* p) {
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ u64 xwg_load(const u64* p) {
+    return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
+// One of `parts` shares of a head's seed set, scored by a workgroup of its own (T threads) while the
+// head's workgroup clears its state and claims the set's ids: what bounds the scoring of a start set
+// is the rate at which one compute unit takes in scattered rows, and a launch with few searches
+// leaves most compute units idle. The keys (the same bits the head would have made: same share
+// sums, same tree) go to keys[c] for the share's positions c of the set. A key is never zero and
+// is written by one 64-bit store, so the slot itself tells the head that its key has come; the head
+// zeroes it again when it has taken the key. n_cfg is the size the sets were listed for (a head's
+// set may have fewer ids): shares are cut by it, so the ids can be requested together with the set's
+// header. A set that is no seed set, or does not fit the candidate array of the walk (maxc), is
+// left to the head, which applies the same test and does not wait then.
+template <int DT, int KT, int T>
+__device__ __forceinline__ void score_seed_share(int head, int part, int parts, const void* __restrict__ q,
+                                                 const void* __restrict__ K, int n_q, int n_kv, int64_t kv_stride,
+                                                 const int32_t* __restrict__ roots, int root_cap, int n_cfg,
+                                                 int maxc, const float* __restrict__ kscale, u64* keys) {
+    const int tid = threadIdx.x, grp = tid >> 4, lane16 = tid & 15;
+    const int seq = head / n_q, h = head % n_q, kvh = h / (n_q / n_kv);
+    const size_t esz = DT == RA_BF16 ? 2 : 4;
+    const size_t ksz = KT == RA_KEYS_I8 ? 1 : KT == RA_BF16 ? 2 : 4;
+    const int32_t* root = roots + (size_t)head * root_cap;
+    const int per = (n_cfg + parts - 1) / parts;
+    const int c_beg = part * per;
+    constexpr int R = SR_UNROLL, PER = T / 16;
+    const char* Kh = reinterpret_cast<const char*>(K) + ((size_t)seq * n_kv + kvh) * kv_stride * RA_D * ksz;
+    ScoreQuery<KT> qv;
+    load_score_query<DT, KT>(reinterpret_cast<const char*>(q) + (size_t)head * RA_D * esz, lane16, qv);
+    if constexpr (KT == RA_KEYS_I8) {
+        const float* sc = kscale + ((size_t)seq * n_kv + kvh) * RA_D + lane16 * 8;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) qv.v[e] = __fmul_rn(qv.v[e], sc[e]);
+    }
+    const int n_root = root[0], n_first = root[1];
+#ifdef SR_WAVE_CLOCKS
+    const int wslot_ = head == 0 && tid == 0 ? (part == 0 ? 8 : part == parts - 1 ? 16 : -1) : -1;
+    if (wslot_ >= 0) sr_wave_ticks[wslot_] = wall_clock64();
+    if (wslot_ >= 0 && n_root >= 0) sr_wave_ticks[wslot_ + 1] = wall_clock64();
+#endif
+    for (int c0 = c_beg; c0 < c_beg + per; c0 += R * PER) {
+        // ids first, wherever the set ends (slots up to root_cap - 3 exist), then the header decides
+        const int cw = c0 + (lane16 & (R - 1)) * PER + grp;      // the key this lane will write
+        int idw = root[2 + min(cw, root_cap - 3)];
+        int idv[R];
+#pragma unroll
+        for (int u = 0; u < R; ++u) idv[u] = root[2 + min(c0 + u * PER + grp, root_cap - 3)];
+        if (n_first != 0 || n_root < 1 || n_root > maxc) return;
+        const int c_end = min(n_root, c_beg + per);
+        if (c0 >= c_end) return;
+        const int id0 = root[2];
+        RowBits<KT> rows[R];
+#pragma unroll
+        for (int u = 0; u < R; ++u)                           // past the end: the set's first row again
+            rows[u] = load_key<KT>(Kh, c0 + u * PER + grp < c_end ? idv[u] : id0, lane16);
+        float sh[R];
+#pragma unroll
+        for (int u = 0; u < R; ++u) sh[u] = score_share<KT>(rows[u], qv);
+        const float sc = rows_tree<R>(sh, lane16);
+#ifdef SR_WAVE_CLOCKS
+        if (wslot_ >= 0 && sc == sc) sr_wave_ticks[wslot_ + 2] = wall_clock64();
+#endif
+        if (lane16 < R && cw < c_end) xwg_store(keys + cw, make_key(sc, idw));
+#ifdef SR_WAVE_CLOCKS
+        __builtin_amdgcn_s_waitcnt(0x0F70);
+        if (wslot_ >= 0) sr_wave_ticks[wslot_ + 3] = wall_clock64();
+        if (head == 0 && (tid & 63) == 0 && tid < 512) sr_wave_ticks[32 + part * 8 + tid / 64] = wall_clock64();
+#endif
+    }
+}
 
 template <int DT, int KT, bool GBITS, int T, typename Hook>
 __device__ __forceinline__ int run_search(
@@ -368,6 +465,9 @@ __device__ __forceinline__ int run_search(
     const int nwords = (int)((N + 31) >> 5);
 
     SR_TICK_INIT;
+#ifdef SR_WAVE_CLOCKS
+    if (head == 0 && tid == 0) sr_wave_ticks[0] = wall_clock64();      // search entered
+#endif
     u64* cur = reinterpret_cast<u64*>(lds_raw);
     u64* nxt = cur + ef;
     u64* ckey = nxt + ef;            // [maxc + 16] candidates that passed the beam threshold
@@ -421,6 +521,9 @@ __device__ __forceinline__ int run_search(
                       (seeded ? n_root >= 1 : n_first > 1 && expand >= n_first - 1 && ef >= n_first);
     __syncthreads();                                             // the LDS state is cleared
     SR_TICK(12);
+#ifdef SR_WAVE_CLOCKS
+    if (head == 0 && tid == 0) sr_wave_ticks[1] = wall_clock64();
+#endif
     int bn, n_visited, n_expanded, n_iters;
     bool first = fill;               // the coming step is that doubled first step
     if (fill) {
@@ -437,6 +540,7 @@ __device__ __forceinline__ int run_search(
             ctr[C_LO] = -1;
             ctr[C_HI] = 0;
             ctr[C_NSURV] = 0;
+            ctr[C_MISSED] = 0;
         }
         bn = 0; n_visited = 0; n_expanded = 0; n_iters = 0;
     } else {
@@ -467,7 +571,7 @@ __device__ __forceinline__ int run_search(
     __syncthreads();
     SR_TICK(13);
 #ifdef SR_WAVE_CLOCKS
-    const long long wave_t0_ = clock64();
+    if (head == 0 && tid == 0) sr_wave_ticks[2] = wall_clock64();      // claims made
 #endif
     if (fill) {
         // ---- the start set is scored here, ahead of the loop, where few registers are live: twice
@@ -503,7 +607,37 @@ __device__ __forceinline__ int run_search(
                 hi = so > hi ? so : hi;
             }
         };
-        {
+        bool shared = false;
+        if constexpr (Hook::kSeedShare) {
+            if (seeded && hook.seeds_shared()) {
+                // the keys come from other workgroups of the launch: every thread takes those of its
+                // positions as they arrive; if one does not, the set is scored here after all
+                bool came = true;
+                for (int c = tid; c < n_root; c += 2 * T) {
+                    const bool two = c + T < n_root;
+                    u64 k0, k1;
+                    hook.take_seed_keys(c, two ? c + T : -1, k0, k1);
+                    came = came && k0 != 0ull && k1 != 0ull;
+#ifdef SR_WAVE_CLOCKS
+                    if (head == 0 && (c & 127) == 0 && c < 1024) sr_wave_ticks[24 + c / 128] = wall_clock64();
+#endif
+                    ckey[c] = k0;
+                    if (two) ckey[c + T] = k1;
+                    const uint32_t s0 = (uint32_t)(k0 >> 32), s1 = (uint32_t)(k1 >> 32);
+                    lo = min(lo, min(s0, s1));
+                    hi = max(hi, max(s0, s1));
+                }
+                if (!came) ctr[C_MISSED] = 1;
+                __syncthreads();
+                shared = ctr[C_MISSED] == 0;
+                if (!shared) {
+                    if (tid == 0) hook.seeds_missed();
+                    lo = 0xffffffffu;
+                    hi = 0u;
+                }
+            }
+        }
+        if (!shared) {
             constexpr int PER = T / 16;                      // rows one call takes per row in flight
             int c0 = 0;
             for (; n_root - c0 >= SEED_ROWS * PER; c0 += SEED_ROWS * PER) score_rows(sr_int<SEED_ROWS>{}, c0);
@@ -526,7 +660,7 @@ __device__ __forceinline__ int run_search(
         }
     }
 #ifdef SR_WAVE_CLOCKS
-    if (lane == 0 && blockIdx.x == 8) { sr_wave_ticks[wv * 2] = wave_t0_; sr_wave_ticks[wv * 2 + 1] = clock64(); }
+    if (head == 0 && tid == 0) sr_wave_ticks[3] = wall_clock64();      // start set's keys in LDS
 #endif
     SR_TICK(5);
 

@@ -481,6 +481,129 @@ def test_walks_from_a_seed_set(name, n_seeds, expand):
     assert idx.n_seeds == 0
 
 
+@pytest.mark.parametrize("name", ["llama_bf16", "llama_f32_2seq", "integer_ties"])
+def test_seed_shares_give_the_heads_the_same_keys(name):
+    """RA_CFG_SEED_SHARES: the start sets of ra_decode_step scored by workgroups of their own (2 to 8
+    shares per head, sets that do not divide evenly, sets with fewer ids than configured) or by the
+    heads themselves (0) must give the same ids, counters and outputs, bit for bit - the keys are
+    the same bits either way - on different queries back to back (a key left over from the launch
+    before would belong to another query), and equal the oracle's seeded walk. A wait that runs out
+    (silent seed workgroups, tiny spin limit) falls back to scoring in the head and switches the
+    shares off until the helpers are configured again."""
+    from paper_2409_10516_amd import binding as B
+    w, adj, ent, idx, Kd, Vd = _prepared(name)
+    n_seq, n_kv, N, d = w.K.shape
+    n_q = w.Q_prefill.shape[1]
+    tol = tol_for(w.K.dtype)
+    exact = integer_valued(to_np(w.K), to_np(w.q_decode))
+    ef = max(w.ef, 24)
+    T = w.q_decode.shape[0]
+    turn = [0]
+
+    def step(expand):
+        t = turn[0] % T
+        turn[0] += 1
+        return t, ra.ra_decode_step(w.q_decode[t].to(DEV), idx, Kd, Vd, w.sink, w.window, w.topk, ef, expand)
+
+    def same(a, b):
+        return all(torch.equal(x, y) for x, y in zip(a, b))
+
+    try:
+        for n_seeds, expand in ((7, 8), (150, 32), (1000, 64)):
+            idx.configure(B.RA_CFG_SEEDS, n_seeds)
+            idx.configure(B.RA_CFG_SEED_SHARES, 0)
+            assert not idx.seed_shares_active
+            ref = {}
+            for _ in range(T):
+                t, r = step(expand)
+                ref[t] = r
+            # the oracle's walk, once per size
+            out, lse, ids, st = (x.cpu().numpy() for x in ref[0])
+            for s_ in range(n_seq):
+                for h in range(n_q):
+                    g = s_ * n_q + h
+                    K = to_np(w.K[s_, h // (n_q // n_kv)]); V = to_np(w.V[s_, h // (n_q // n_kv)])
+                    decode_matches(out[s_, h], lse[s_, h], ids[s_, h], st[s_, h].tolist(), to_np(w.q_decode[0, s_, h]),
+                                   K, V, adj[g], ent[g], w.sink, w.window, w.topk, ef, expand, tol, exact=exact,
+                                   n_seeds=n_seeds)
+            for shares in (2, 3, 4, 8):
+                idx.configure(B.RA_CFG_SEED_SHARES, shares)
+                assert idx.seed_shares_active
+                for _ in range(T + 1):
+                    t, r = step(expand)
+                    assert same(r, ref[t]), (n_seeds, shares, t)
+                assert idx.seed_shares_active              # no wait ran out
+        # a wait that runs out: nothing arrives, the heads score their sets themselves
+        idx.configure(B.RA_CFG_SEED_SHARES, 4)
+        idx.test_configure(B.RA_TEST_HELPERS_SILENT, 1)
+        idx.configure(B.RA_CFG_HELPER_SPIN, 2)
+        t, r = step(64)
+        assert same(r[2:], ref[t][2:])                      # ids and counters; W is attended by the heads now
+        assert torch.allclose(r[0], ref[t][0], rtol=0, atol=tol * float(ref[t][0].abs().max()))
+        t, r = step(64)                                     # the off word is set: no head waits any more
+        assert same(r[2:], ref[t][2:])
+        idx.test_configure(B.RA_TEST_HELPERS_SILENT, 0)     # also forgets the wait that ran out
+        idx.configure(B.RA_CFG_HELPER_SPIN, 20000)
+        assert idx.seed_shares_active
+        for _ in range(2):
+            t, r = step(64)
+            assert same(r, ref[t])
+        assert idx.seed_shares_active
+        idx.configure(B.RA_CFG_HELPERS, B.RA_HELPERS_OFF)   # no extra workgroups of either kind
+        assert not idx.seed_shares_active
+        t, r = step(64)
+        assert same(r[2:], ref[t][2:])
+    finally:
+        idx.test_configure(B.RA_TEST_HELPERS_SILENT, 0)
+        idx.configure(B.RA_CFG_HELPERS, B.RA_HELPERS_ON)
+        idx.configure(B.RA_CFG_HELPER_SPIN, 20000)
+        idx.configure(B.RA_CFG_SEED_SHARES, 4)
+        idx.configure(B.RA_CFG_SEEDS, 0)
+
+
+def test_seed_shares_replayed_from_a_graph():
+    """The launch with seed workgroups captured in a HIP graph and replayed with eager launches in
+    between: every replay must leave the key slots as it found them (zero), so each gives the
+    eager result."""
+    from paper_2409_10516_amd import binding as B
+    w, adj, ent, idx, Kd, Vd = _prepared("llama_bf16")
+    n_seq, n_kv, N, d = w.K.shape
+    n_q = w.Q_prefill.shape[1]
+    try:
+        idx.configure(B.RA_CFG_SEEDS, 600)
+        idx.configure(B.RA_CFG_SEED_SHARES, 4)
+        q0, q1 = w.q_decode[0].to(DEV), w.q_decode[1].to(DEV)
+        e0 = ra.ra_decode_step(q0, idx, Kd, Vd, w.sink, w.window, w.topk, w.ef, 64)
+        e1 = ra.ra_decode_step(q1, idx, Kd, Vd, w.sink, w.window, w.topk, w.ef, 64)
+        f32 = dict(dtype=torch.float32, device=DEV)
+        out = torch.empty((n_seq, n_q, d), **f32); lse = torch.empty((n_seq, n_q), **f32)
+        ids = torch.empty((n_seq, n_q, w.topk), dtype=torch.int32, device=DEV)
+        st = torch.zeros((n_seq, n_q, 4), dtype=torch.int32, device=DEV)
+        qbuf = q0.clone()
+        torch.cuda.synchronize()
+        g = torch.cuda.CUDAGraph()
+        cs = torch.cuda.Stream()
+        with torch.cuda.stream(cs):
+            ra.ra_decode_step(qbuf, idx, Kd, Vd, w.sink, w.window, w.topk, w.ef, 64, out=out, lse=lse, ids=ids, stats=st)
+            cs.synchronize()
+            with torch.cuda.graph(g, stream=cs):
+                ra.ra_decode_step(qbuf, idx, Kd, Vd, w.sink, w.window, w.topk, w.ef, 64, out=out, lse=lse, ids=ids,
+                                  stats=st)
+        torch.cuda.synchronize()
+        for rep in range(4):
+            src, want = (q0, e0) if rep % 2 == 0 else (q1, e1)
+            qbuf.copy_(src)
+            g.replay()
+            torch.cuda.synchronize()
+            assert torch.equal(ids, want[2]) and torch.equal(st, want[3]), rep
+            assert torch.equal(out, want[0]) and torch.equal(lse, want[1]), rep
+            mid = ra.ra_decode_step(q1 if rep % 2 == 0 else q0, idx, Kd, Vd, w.sink, w.window, w.topk, w.ef, 64)
+            assert torch.equal(mid[2], (e1 if rep % 2 == 0 else e0)[2])
+        assert idx.seed_shares_active
+    finally:
+        idx.configure(B.RA_CFG_SEEDS, 0)
+
+
 def test_seed_sets_of_a_graph_with_missing_and_repeated_nodes():
     """An imported graph need not be a projection: slots 0 and 1 may hold -1 or lead back to a node
     already listed. The device's seed list must be the oracle's (checked through the walk: with ef
