@@ -35,7 +35,7 @@ METRIC = "decode-step retrieval-attention latency (ms) @128K ctx, 1 GPU; recall@
 # start-set size and expansion width per workload (the walk's own parameters; ef, topk, deg and knn
 # are the workload's): the fastest setting of a sweep over (seeds, expand) that keeps recall@k where the
 # single-entry walk had it or above
-DEFAULT_SEEDS = {"config2": 1536, "config1": 1024, "config3": 1024, "config4": 2048, "config0": 0}
+DEFAULT_SEEDS = {"config2": 2048, "config1": 1024, "config3": 1024, "config4": 2048, "config0": 0}
 DEFAULT_EXPAND = {"config2": 256, "config1": 128, "config3": 64, "config4": 64, "config0": 64}
 # sources that make up decode_kernel: a counter summary under profiles/ applies to this build
 # only if it was taken with the same ones

@@ -114,14 +114,22 @@ def test_config0_full():
     assert r > 0.3
 
 
-def test_config2_hip_graph_replay_at_the_bench_launch_configuration():
-    """What bench.py times: one 128K layer at expand 64, captured into a HIP graph and replayed.
-    Replays (with eager work and synchronisations between them) must reproduce the eager step bit
-    for bit, and sampled heads must match the oracle."""
+@pytest.mark.parametrize("walk", ["bench", "single_entry"])
+def test_config2_hip_graph_replay_at_the_bench_launch_configuration(walk):
+    """What bench.py times: one 128K layer with the walk parameters of its default run (start sets
+    and expansion width read from bench.py itself, seed workgroups on), captured into a HIP graph
+    and replayed; and the same with the single-entry walk at expand 64. Replays (with eager work and
+    synchronisations between them) must reproduce the eager step bit for bit, and sampled heads must
+    match the oracle."""
+    import bench
+    from paper_2409_10516_amd import binding as B
     w = synth.make_config2_layer(1, device=DEV, T=3)
     idx = ra.ra_build_index(w.K, w.Q_prefill, w.deg, w.knn)
     n_q = w.Q_prefill.shape[1]
     w.Q_prefill = None
+    n_seeds, expand = (bench.DEFAULT_SEEDS["config2"], bench.DEFAULT_EXPAND["config2"]) if walk == "bench" else (0, 64)
+    idx.configure(B.RA_CFG_SEEDS, n_seeds)
+    assert idx.seed_shares_active == (walk == "bench")
     f32 = dict(dtype=torch.float32, device=DEV)
     bufs = lambda: (torch.empty((1, n_q, 128), **f32), torch.empty((1, n_q), **f32),
                     torch.empty((1, n_q, w.topk), dtype=torch.int32, device=DEV),
@@ -129,7 +137,7 @@ def test_config2_hip_graph_replay_at_the_bench_launch_configuration():
     eager = []
     for t in range(3):
         o, l, i, s = bufs()
-        ra.ra_decode_step(w.q_decode[t], idx, w.K, w.V, w.sink, w.window, w.topk, w.ef, 64,
+        ra.ra_decode_step(w.q_decode[t], idx, w.K, w.V, w.sink, w.window, w.topk, w.ef, expand,
                           out=o, lse=l, ids=i, stats=s)
         eager.append((o, l, i, s))
     torch.cuda.synchronize()
@@ -139,7 +147,7 @@ def test_config2_hip_graph_replay_at_the_bench_launch_configuration():
     g = torch.cuda.CUDAGraph()
     with torch.cuda.stream(cs):
         with torch.cuda.graph(g, stream=cs):
-            ra.ra_decode_step(qbuf, idx, w.K, w.V, w.sink, w.window, w.topk, w.ef, 64,
+            ra.ra_decode_step(qbuf, idx, w.K, w.V, w.sink, w.window, w.topk, w.ef, expand,
                               out=go, lse=gl, ids=gi, stats=gs)
     torch.cuda.synchronize()
     for rep in range(2):
@@ -153,11 +161,12 @@ def test_config2_hip_graph_replay_at_the_bench_launch_configuration():
             assert torch.allclose(gl, l, rtol=1e-6, atol=1e-6), (rep, t)
             (go.sum() + gl.sum()).item()           # eager work between replays
     assert idx.helpers_active                      # no bounded wait ran out
+    assert idx.seed_shares_active == (walk == "bench")
     tol = tol_for(w.K.dtype)
     for h in (3, 18):
         adj, ent = ra.ra_index_export(idx, 0, h)
         K, V = to_np(w.K[0, h // 4]), to_np(w.V[0, h // 4])
         o, l, i, s = [x.cpu().numpy() for x in eager[2]]
         decode_matches(o[0, h], l[0, h], i[0, h], s[0, h].tolist(), to_np(w.q_decode[2, 0, h]), K, V,
-                       adj.numpy(), ent, w.sink, w.window, w.topk, w.ef, 64, tol)
+                       adj.numpy(), ent, w.sink, w.window, w.topk, w.ef, expand, tol, n_seeds=n_seeds)
     idx.free()
