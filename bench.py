@@ -12,7 +12,8 @@ projection) runs before the timed region and is reported separately.
 Prints ONE JSON line: the metric and its value, the workload, `roofline` (the fused decode
 kernel's algorithmic bytes per launch over its measured launch time, against 8 TB/s, with the
 HBM traffic the counters read for this build of the kernel, if a summary under profiles/ has it),
-`hbm_measured` (what a 1 GiB device copy and a read-only streaming kernel sustain on this device),
+`hbm_measured` (what a 1 GiB device copy, a read-only streaming kernel and a gather of scattered 256-byte
+rows sustain on this device),
 `stages`, `exact_baselines`, `build` (with `knn_kernel`: the index-build GEMM's live time for one
 layer against the dense MFMA peak), `other_configs` (the batched and the 1M-key configurations,
 measured the same way after the headline one), `cpu_baseline` (the oracle over the host's cores).
@@ -512,14 +513,18 @@ def main():
 
     copy_gbs = gbs(lambda: dst.copy_(src), 2.0 * (1 << 30))
     read_gbs = gbs(lambda: ra.ra_hbm_read_probe(src, fold), 1.0 * (1 << 30))
+    # scattered rows of 256 B (a bf16 key), as many bytes as the buffer holds, 16 lanes per row
+    gather_gbs = gbs(lambda: ra.ra_hbm_gather_probe(src, (1 << 30) // 256, fold), 1.0 * (1 << 30))
     if a.copy_calibration:
         for _ in range(3):
             dst.copy_(src)
         torch.cuda.synchronize()
     del src, dst
     hbm_measured = {"copy_1GiB_read_plus_write_GBs": copy_gbs, "read_stream_1GiB_GBs": read_gbs,
+                    "gather_256B_rows_of_1GiB_GBs": gather_gbs,
                     "peak_GBs": HBM_PEAK_GBS,
-                    "decode_kernel_frac_of_read_stream": res["roofline"]["achieved"] / read_gbs}
+                    "decode_kernel_frac_of_read_stream": res["roofline"]["achieved"] / read_gbs,
+                    "decode_kernel_frac_of_gather": res["roofline"]["achieved"] / gather_gbs}
 
     # ---- recall@k against brute force (CPU oracle) on a sample of layers ---------------
     from oracle import attention as OA, mips as OM
@@ -547,6 +552,7 @@ def main():
         for wl, st_, tk in (("config3", 20, 4), ("config4", 10, 4)):
             r, s2 = measure(wl, st_, 2, tk)
             r["ms_per_launch"] = r["roofline"]["avg_launch_ms"]
+            r["roofline"]["frac_of_measured_gather"] = r["roofline"]["achieved"] / gather_gbs
             other[wl] = r
             for L in s2["layers"]:
                 L["idx"].free()

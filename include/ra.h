@@ -196,6 +196,16 @@ ra_status ra_full_attention(const void* q, const void* K, const void* V, ra_dtyp
  * scan kernels above (Sec. 4.1's exact baselines) are compared with. */
 ra_status ra_hbm_read_probe(const void* buf, size_t bytes, void* stream, uint64_t* out);
 
+/* Measurement aid for the gathers of the walk (Sec. 2.4: a search touches scattered key vectors):
+ * reads n_rows rows of 256 bytes (a bf16 key of d = 128) of the `bytes` bytes at `buf` (device,
+ * 16-byte aligned, a multiple of 256; at most 2^32 - 1 rows), at row numbers drawn by a counter-based
+ * hash of (position in the sequence, seed), each row by 16 lanes as the search kernels read it, 8
+ * rows in flight per lane group, and xors a 64-bit fold into *out (device). Timed by the benchmark,
+ * it gives the bandwidth the device sustains for scattered rows, the bound of a launch whose bytes
+ * are mostly start sets. RA_EINVAL for a NULL or misaligned buffer or n_rows = 0. */
+ra_status ra_hbm_gather_probe(const void* buf, size_t bytes, size_t n_rows, uint32_t seed, void* stream,
+                              uint64_t* out);
+
 /* ---- handle management ------------------------------------------------------------- */
 
 /* Build a handle from HOST arrays adj [n_seq*n_q_heads][N][deg], entries [n_seq*n_q_heads]

@@ -93,10 +93,11 @@ def lib() -> C.CDLL:
     L.ra_full_attention_workspace_bytes.argtypes = [i32, i32, i32, i64]
     L.ra_full_attention_workspace_bytes.restype = C.c_size_t
     L.ra_hbm_read_probe.argtypes = [vp, C.c_size_t, vp, vp]
+    L.ra_hbm_gather_probe.argtypes = [vp, C.c_size_t, C.c_size_t, C.c_uint32, vp, vp]
     L.ra_full_attention.argtypes = [vp, vp, vp, i32, i32, i32, i32, i64, i32, vp, C.c_size_t, vp, vp, vp]
     L.ra_full_attention.restype = i32
     for name in ("ra_knn", "ra_project", "ra_build_index", "ra_search", "ra_attend",
-                 "ra_attend_noalloc", "ra_hbm_read_probe", "ra_decode_step", "ra_index_import",
+                 "ra_attend_noalloc", "ra_hbm_read_probe", "ra_hbm_gather_probe", "ra_decode_step", "ra_index_import",
                  "ra_index_export"):
         getattr(L, name).restype = i32
     _lib = L
@@ -359,6 +360,13 @@ def ra_hbm_read_probe(buf: torch.Tensor, out: torch.Tensor, stream=None) -> None
     """Stream `buf` (contiguous device tensor) once; xors a fold of it into out (device int64 [1])."""
     _dev(buf, out)
     _check(lib().ra_hbm_read_probe(_ptr(buf), buf.numel() * buf.element_size(), _stream(stream), _ptr(out)))
+
+
+def ra_hbm_gather_probe(buf: torch.Tensor, n_rows: int, out: torch.Tensor, seed: int = 0, stream=None) -> None:
+    """Read n_rows rows of 256 B of `buf` at hashed row numbers; xors a fold into out (device int64 [1])."""
+    _dev(buf, out)
+    _check(lib().ra_hbm_gather_probe(_ptr(buf), buf.numel() * buf.element_size(), n_rows, seed, _stream(stream),
+                                     _ptr(out)))
 
 
 def ra_flat_topk(q, K, sink: int, window: int, topk: int, stream=None, workspace=None, ids=None):

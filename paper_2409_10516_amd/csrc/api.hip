@@ -597,6 +597,16 @@ extern "C" ra_status ra_hbm_read_probe(const void* buf, size_t bytes, void* stre
     return ra_launch_read_probe(buf, bytes, (hipStream_t)stream, reinterpret_cast<unsigned long long*>(out));
 }
 
+extern "C" ra_status ra_hbm_gather_probe(const void* buf, size_t bytes, size_t n_rows, uint32_t seed, void* stream,
+                                         uint64_t* out) {
+    if (!buf || !out) RA_FAIL(RA_EINVAL, "NULL argument");
+    if (bytes < 256 || (bytes & 255) || ((uintptr_t)buf & 15))
+        RA_FAIL(RA_EINVAL, "the buffer must be 16-byte aligned and a multiple of 256 bytes long");
+    if (n_rows < 1) RA_FAIL(RA_EINVAL, "n_rows must be positive");
+    return ra_launch_gather_probe(buf, bytes, n_rows, seed, (hipStream_t)stream,
+                                  reinterpret_cast<unsigned long long*>(out));
+}
+
 extern "C" size_t ra_full_attention_workspace_bytes(int n_seq, int n_q_heads, int n_kv_heads,
                                                      int64_t N) {
     if (n_seq < 1 || n_q_heads < 1 || n_kv_heads < 1 || N < 1) return 0;

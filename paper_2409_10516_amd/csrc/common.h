@@ -133,6 +133,8 @@ ra_status ra_launch_decode(const void* q, const int32_t* adj, const int32_t* ent
 ra_status ra_launch_rerank(const void* q, const void* K, ra_dtype dt, int n_seq, int n_q, int n_kv, int64_t N,
                            const int32_t* cand, int n_cand, int topk, hipStream_t st, int32_t* ids);
 ra_status ra_launch_read_probe(const void* buf, size_t bytes, hipStream_t st, unsigned long long* out);
+ra_status ra_launch_gather_probe(const void* buf, size_t bytes, size_t n_rows, uint32_t seed, hipStream_t st,
+                                 unsigned long long* out);
 ra_status ra_launch_flat_topk(const void* q, const void* K, ra_dtype dt, int n_seq, int n_q, int n_kv,
                               int64_t N, int sink, int window, int topk, uint32_t* keys_ws,
                               hipStream_t st, int32_t* ids);

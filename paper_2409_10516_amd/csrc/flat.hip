@@ -681,6 +681,54 @@ __global__ __launch_bounds__(PR_THREADS) void read_probe_kernel(const uint4* __r
     if ((threadIdx.x & (RA_WAVE - 1)) == 0 && w) atomicXor(out, w);
 }
 
+// The same for rows of 256 bytes at scattered places, the access pattern of the walk's gathers: every
+// group of 16 lanes asks for 8 rows at a time, 16 bytes per lane, at row numbers drawn by a
+// counter-based hash of the row's index in the sequence (so a run is reproducible and rows repeat
+// only by chance); the grid walks the sequence of n_rows indices.
+#define PG_THREADS 1024
+#define PG_ROWS 8
+__device__ __forceinline__ uint32_t pg_hash(uint32_t x) {
+    x ^= x >> 16; x *= 0x7feb352du; x ^= x >> 15; x *= 0x846ca68bu; x ^= x >> 16;
+    return x;
+}
+__global__ __launch_bounds__(PG_THREADS) void gather_probe_kernel(const uint4* __restrict__ p, uint32_t rows_in_buf,
+                                                                  size_t n_rows, uint32_t seed,
+                                                                  unsigned long long* __restrict__ out) {
+    const int lane16 = threadIdx.x & 15;
+    const size_t groups = (size_t)gridDim.x * (PG_THREADS / 16);
+    const size_t g = (size_t)blockIdx.x * (PG_THREADS / 16) + (threadIdx.x >> 4);
+    uint4 acc = make_uint4(0u, 0u, 0u, 0u);
+    for (size_t i = g * PG_ROWS; i < n_rows; i += groups * PG_ROWS) {
+        uint4 v[PG_ROWS];
+#pragma unroll
+        for (int u = 0; u < PG_ROWS; ++u) {
+            const size_t j = i + u < n_rows ? i + u : i;         // loads stay unconditional
+            const uint32_t row = pg_hash((uint32_t)j * 0x9e3779b9u + seed) % rows_in_buf;
+            v[u] = load16_stream(p + (size_t)row * 16 + lane16);
+        }
+#pragma unroll
+        for (int u = 0; u < PG_ROWS; ++u)
+            if (i + u < n_rows) { acc.x ^= v[u].x; acc.y ^= v[u].y; acc.z ^= v[u].z; acc.w ^= v[u].w; }
+    }
+    unsigned long long w = ((unsigned long long)(acc.x ^ acc.z) << 32) | (acc.y ^ acc.w);
+#pragma unroll
+    for (int d = 1; d < RA_WAVE; d <<= 1) w ^= __shfl_xor(w, d);
+    if ((threadIdx.x & (RA_WAVE - 1)) == 0 && w) atomicXor(out, w);
+}
+
+ra_status ra_launch_gather_probe(const void* buf, size_t bytes, size_t n_rows, uint32_t seed, hipStream_t st,
+                                 unsigned long long* out) {
+    const size_t rows_in_buf = bytes / 256;
+    if (rows_in_buf < 1 || rows_in_buf > 0xffffffffull) RA_FAIL(RA_EINVAL, "buffer of %zu B: 1 .. 2^32 - 1 rows of 256 B", bytes);
+    size_t blocks = (n_rows + (size_t)(PG_THREADS / 16) * PG_ROWS - 1) / ((size_t)(PG_THREADS / 16) * PG_ROWS);
+    if (blocks > 512) blocks = 512;                          // two workgroups per compute unit
+    if (blocks < 1) blocks = 1;
+    hipLaunchKernelGGL(gather_probe_kernel, dim3((unsigned)blocks), dim3(PG_THREADS), 0, st,
+                       reinterpret_cast<const uint4*>(buf), (uint32_t)rows_in_buf, n_rows, seed, out);
+    RA_HIP(hipGetLastError());
+    return RA_OK;
+}
+
 ra_status ra_launch_read_probe(const void* buf, size_t bytes, hipStream_t st, unsigned long long* out) {
     const size_t n16 = bytes / 16;
     size_t blocks = (n16 + (size_t)PR_THREADS * PR_LOADS - 1) / ((size_t)PR_THREADS * PR_LOADS);

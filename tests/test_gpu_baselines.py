@@ -159,3 +159,41 @@ def test_graph_recall_can_be_measured_on_device():
         # (a near-tie at the cut of the exact list can move one id)
         assert abs(OM.recall(ids[0, h].cpu().numpy(), flat[0, h].cpu().numpy()) -
                    OM.recall(ids[0, h].cpu().numpy(), truth)) <= 1.0 / w.topk
+
+
+def _fold16(words):
+    """xor over 16-byte pieces (4 uint32 x, y, z, w each) of ((x ^ z) << 32) | (y ^ w)."""
+    w = words.reshape(-1, 4).astype(np.uint64)
+    f = ((w[:, 0] ^ w[:, 2]) << np.uint64(32)) | (w[:, 1] ^ w[:, 3])
+    return int(np.bitwise_xor.reduce(f)) if len(f) else 0
+
+
+@pytest.mark.parametrize("n16", [1, 999, 8 * 256 * 3 + 5, 1 << 16])
+def test_read_probe_reads_every_byte_once(n16):
+    """The streaming probe's fold is the xor over all 16-byte pieces of the buffer: every piece is
+    read exactly once, ragged tails included."""
+    rng = np.random.default_rng(n16)
+    host = rng.integers(0, 2**32, size=n16 * 4, dtype=np.uint64).astype(np.uint32)
+    buf = torch.from_numpy(host.view(np.int32)).to(DEV)
+    out = torch.zeros(1, dtype=torch.int64, device=DEV)
+    ra.ra_hbm_read_probe(buf, out)
+    assert int(out.cpu().numpy().view(np.uint64)[0]) == _fold16(host)
+
+
+@pytest.mark.parametrize("rows_in_buf,n_rows,seed", [(1, 5, 0), (37, 1000, 3), (4096, 8 * 64 * 2 + 3, 7), (50000, 200000, 1)])
+def test_gather_probe_reads_the_hashed_rows(rows_in_buf, n_rows, seed):
+    """The gather probe reads row hash(position, seed) mod rows for every position of the sequence,
+    whole rows of 256 bytes: its fold is the xor over those rows (with their multiplicity)."""
+    rng = np.random.default_rng(rows_in_buf)
+    host = rng.integers(0, 2**32, size=rows_in_buf * 64, dtype=np.uint64).astype(np.uint32)
+    buf = torch.from_numpy(host.view(np.int32)).to(DEV)
+    out = torch.zeros(1, dtype=torch.int64, device=DEV)
+    ra.ra_hbm_gather_probe(buf, n_rows, out, seed=seed)
+    x = (np.arange(n_rows, dtype=np.uint64) * np.uint64(0x9e3779b9) + np.uint64(seed)) & np.uint64(0xffffffff)
+    x ^= x >> np.uint64(16); x = (x * np.uint64(0x7feb352d)) & np.uint64(0xffffffff)
+    x ^= x >> np.uint64(15); x = (x * np.uint64(0x846ca68b)) & np.uint64(0xffffffff)
+    x ^= x >> np.uint64(16)
+    rows = (x % np.uint64(rows_in_buf)).astype(np.int64)
+    assert int(out.cpu().numpy().view(np.uint64)[0]) == _fold16(host.reshape(rows_in_buf, 64)[rows])
+    with pytest.raises(ra.RaError):
+        ra.ra_hbm_gather_probe(buf, 0, out)

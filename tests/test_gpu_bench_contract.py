@@ -32,6 +32,8 @@ def test_bench_line_has_the_contract_fields():
     assert cb["kind"] == "oracle" and cb["cores"] >= 1 and cb["value"] > 0 and cb["sample"]
     hm = d["hbm_measured"]
     assert 100.0 < hm["read_stream_1GiB_GBs"] < 8000.0 and 100.0 < hm["copy_1GiB_read_plus_write_GBs"] < 8000.0
+    assert 100.0 < hm["gather_256B_rows_of_1GiB_GBs"] < 8000.0
     assert "traffic" in rf and "helper_workgroups_active_after_timed_region" in rf
+    assert "seed_workgroups_active_after_timed_region" in rf
     knn = d["build"]["knn_kernel"]
     assert knn["bound"] == "mfma" and knn["achieved"] > 0
