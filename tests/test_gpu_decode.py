@@ -561,6 +561,51 @@ def test_seed_shares_give_the_heads_the_same_keys(name):
         idx.configure(B.RA_CFG_SEEDS, 0)
 
 
+@pytest.mark.parametrize("dtype", [torch.bfloat16, torch.float32])
+def test_seed_shares_in_the_variants_of_the_decode_step(dtype):
+    """The decode step over 8-bit keys, with a budget per head, and on a cache that has grown past the
+    index (spare capacity: the key rows of a KV head start every `capacity` rows), each with the
+    start sets scored by seed workgroups and by the heads: same ids, counters and outputs, bit for
+    bit, on two queries in turn; the 8-bit walk also equals ra_search over the same keys."""
+    from paper_2409_10516_amd import binding as B
+    n_index, grown, pad, n_q, n_kv = 1100, 40, 13, 4, 2
+    N = n_index + grown
+    w = synth.make_llama_layer(71, N=N, M=500, T=2, n_q=n_q, n_kv=n_kv, dtype=dtype, ef=64, topk=20,
+                               window=50, deg=16, knn=12)
+    from types import SimpleNamespace
+    wi = SimpleNamespace(K=w.K[:, :, :n_index].contiguous(), Q_prefill=w.Q_prefill, knn=w.knn, deg=w.deg)
+    adj, ent, _ = oracle_graphs(wi)
+    idx = ra.ra_index_import(torch.from_numpy(adj), torch.from_numpy(ent), 1, n_q, n_kv)
+    Ki, Vi = wi.K.to(DEV), w.V[:, :, :n_index].contiguous().to(DEV)
+    k8 = ra.ra_quantize_keys(Ki)
+    Kc = torch.zeros((1, n_kv, N + pad, 128), dtype=dtype); Kc[:, :, :N] = w.K
+    Vc = torch.zeros((1, n_kv, N + pad, 128), dtype=dtype); Vc[:, :, :N] = w.V
+    Kc, Vc = Kc.to(DEV), Vc.to(DEV)
+    budgets = torch.tensor([[3, 20, 1, 11]], dtype=torch.int32, device=DEV)
+    idx.configure(B.RA_CFG_SEEDS, 333)
+    variants = {
+        "q8": lambda q: ra.ra_decode_step(q, idx, Ki, Vi, w.sink, w.window, w.topk, w.ef, 32, k8=k8),
+        "budgets": lambda q: ra.ra_decode_step(q, idx, Ki, Vi, w.sink, w.window, w.topk, w.ef, 32,
+                                               topk_per_head=budgets),
+        "grown": lambda q: ra.ra_decode_step(q, idx, Kc, Vc, w.sink, w.window, w.topk, w.ef, 32, n_tokens=N),
+    }
+    for name, fn in variants.items():
+        ref = []
+        idx.configure(B.RA_CFG_SEED_SHARES, 0)
+        for t in range(2):
+            ref.append(fn(w.q_decode[t].to(DEV)))
+        idx.configure(B.RA_CFG_SEED_SHARES, 4)
+        assert idx.seed_shares_active
+        for t in (0, 1, 0):
+            got = fn(w.q_decode[t].to(DEV))
+            assert all(torch.equal(x, y) for x, y in zip(got, ref[t])), (name, t)
+        assert idx.seed_shares_active, name
+    ids8, st8 = ra.ra_search(w.q_decode[1].to(DEV), idx, Ki, w.sink, w.window, w.topk, w.ef, 32, k8=k8)
+    got = variants["q8"](w.q_decode[1].to(DEV))
+    assert torch.equal(got[2], ids8) and torch.equal(got[3], st8)
+    idx.free()
+
+
 def test_seed_shares_replayed_from_a_graph():
     """The launch with seed workgroups captured in a HIP graph and replayed with eager launches in
     between: every replay must leave the key slots as it found them (zero), so each gives the
