@@ -527,10 +527,10 @@ ra_status ra_launch_decode(const void* q, const int32_t* adj, const int32_t* ent
     const int threads = search_threads(heads, ef);
     const void* Ksearch = kscale ? K8 : K;
     // a start set scored in shares by workgroups of their own: only where every workgroup of the
-    // launch has a compute unit to itself (few searches, 1024 threads each) and the visited bitsets
-    // are in LDS; fewer shares when the part has too few compute units, none below two
+    // launch has a compute unit to itself (few searches, 1024 threads each); fewer shares when the
+    // part has too few compute units, none below two
     int parts = 0;
-    if (seedx && seed_parts > 0 && roots && !gb && threads == 1024 && coop_mode != RA_HELPERS_OFF) {
+    if (seedx && seed_parts > 0 && roots && threads == 1024 && coop_mode != RA_HELPERS_OFF) {
         const int room = (decode_compute_units() - n_helpers) / heads - 1;
         parts = seed_parts < room ? seed_parts : room;
         if (parts > RA_SEED_PARTS_MAX) parts = RA_SEED_PARTS_MAX;

@@ -108,6 +108,34 @@ def test_config4_stress_1m_global_bitset():
     assert r > 0.3, r
 
 
+def test_config4_at_the_bench_walk_with_seed_workgroups():
+    """The 1M-key configuration as bench.py runs it (its start-set size and expansion width): visited
+    bitsets in device memory, start sets scored by seed workgroups. Same ids, counters and outputs as
+    with the heads scoring their own sets, bit for bit, and one head against the oracle."""
+    import bench
+    from paper_2409_10516_amd import binding as B
+    w = synth.make_config4(device=DEV, T=2)
+    idx = ra.ra_build_index(w.K, w.Q_prefill, w.deg, w.knn)
+    w.Q_prefill = None
+    n_seeds, expand = bench.DEFAULT_SEEDS["config4"], bench.DEFAULT_EXPAND["config4"]
+    idx.configure(B.RA_CFG_SEEDS, n_seeds)
+    step = lambda t: ra.ra_decode_step(w.q_decode[t], idx, w.K, w.V, w.sink, w.window, w.topk, w.ef, expand)
+    idx.configure(B.RA_CFG_SEED_SHARES, 0)
+    ref = [step(0), step(1)]
+    idx.configure(B.RA_CFG_SEED_SHARES, 4)
+    for t in (0, 1, 0):
+        got = step(t)
+        assert all(torch.equal(x, y) for x, y in zip(got, ref[t])), t
+    assert idx.seed_shares_active and idx.helpers_active
+    h = 2
+    adj, ent = ra.ra_index_export(idx, 0, h)
+    o, l, i, s = [x.cpu().numpy() for x in ref[1]]
+    decode_matches(o[0, h], l[0, h], i[0, h], s[0, h].tolist(), to_np(w.q_decode[1, 0, h]), to_np(w.K[0, 0]),
+                   to_np(w.V[0, 0]), adj.numpy(), ent, w.sink, w.window, w.topk, w.ef, expand, tol_for(w.K.dtype),
+                   n_seeds=n_seeds)
+    idx.free()
+
+
 def test_config0_full():
     w = synth.make_config0(device=DEV)
     r = _check_sampled(w, [(0, 0)], expand=4, knn_rows=64, adj_rows=64, all_queries=True)
