@@ -259,9 +259,8 @@ struct AwaitHelper {
         k0 = 0ull;
         k1 = 0ull;
         for (int i = 0; i < spin; ++i) {
-            const u64 a = xwg_load(p0), b = xwg_load(p1);
-            if (k0 == 0ull) k0 = a;
-            if (k1 == 0ull) k1 = b;
+            if (k0 == 0ull) k0 = xwg_load(p0);               // (a slot whose key has come is not read again)
+            if (k1 == 0ull) k1 = xwg_load(p1);
             if (k0 != 0ull && k1 != 0ull) break;
             __builtin_amdgcn_s_sleep(6);
         }
