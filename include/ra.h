@@ -299,8 +299,8 @@ int64_t ra_index_info(const ra_index* idx, int what);
  *                       2 .. 8; default 4. Used only where every workgroup of the launch has a compute
  *                       unit to itself (the searches, their shares and the helpers together number at
  *                       most the device's compute units; fewer shares are used to make that so, none
- *                       below two) and the walks use 1024-thread workgroups; RA_HELPERS_OFF switches
- *                       the shares off as well. The keys are the same
+ *                       below two) and a walk has a workgroup of 512 threads or more; RA_HELPERS_OFF
+ *                       switches the shares off as well. The keys are the same
  *                       bits whoever computes them, so ids, counters and outputs do not depend on the
  *                       setting. They cross workgroups through device memory the handle owns, one
  *                       64-bit slot per seed that the head polls and zeroes again, with the same

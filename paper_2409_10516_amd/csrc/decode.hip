@@ -479,6 +479,18 @@ static int decode_helper_slots(const float* coop, int coop_mode, int n_seq, int 
     return coop_on ? n_seq * n_kv : 0;
 }
 
+// Threads per workgroup of the fused launch. With the start sets scored by seed workgroups and the
+// static set by helpers, what a head's workgroup is left with is mostly merges and barriers, which
+// 512 threads get through sooner than 1024 (128K layer, 32 searches: 28.4 against 29.6 us; 27.3 against
+// 29.6 us for 128 searches of 32K keys, and still 37.5 against 49.1 us when 256 searches and their 64
+// helpers outnumber the compute units); a beam of more than 256 entries keeps 1024 threads (its steps
+// gather thousands of rows: 215 against 200 us on the 1M-key configuration). From 512 searches on,
+// 256 threads as in the stand-alone search (48.3 against 52.8 us).
+static int decode_threads(int heads, int ef) {
+    if (ef > 256) return search_threads(heads, ef);
+    return heads <= 384 ? 512 : 256;
+}
+
 // compute units of the current device (asked once per device)
 static int decode_compute_units() {
     static int cached[64];
@@ -523,13 +535,13 @@ ra_status ra_launch_decode(const void* q, const int32_t* adj, const int32_t* ent
     // one helper workgroup per (sequence, KV head) in front of the heads' (GQA groups of 1, 2, 4 or 8)
     if (!coop) RA_FAIL(RA_EINVAL, "hand-over area missing");
     const int n_helpers = decode_helper_slots(coop, coop_mode, n_seq, n_q, n_kv);
-    const int threads = search_threads(heads, ef);
+    const int threads = decode_threads(heads, ef);
     const void* Ksearch = kscale ? K8 : K;
     // a start set scored in shares by workgroups of their own: only where every workgroup of the
-    // launch has a compute unit to itself (few searches, 1024 threads each); fewer shares when the
-    // part has too few compute units, none below two
+    // launch has a compute unit to itself (few searches, 512 or 1024 threads each); fewer shares when
+    // the part has too few compute units, none below two
     int parts = 0;
-    if (seedx && seed_parts > 0 && roots && threads == 1024 && coop_mode != RA_HELPERS_OFF) {
+    if (seedx && seed_parts > 0 && roots && threads >= 512 && coop_mode != RA_HELPERS_OFF) {
         const int room = (decode_compute_units() - n_helpers) / heads - 1;
         parts = seed_parts < room ? seed_parts : room;
         if (parts > RA_SEED_PARTS_MAX) parts = RA_SEED_PARTS_MAX;
