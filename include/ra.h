@@ -260,7 +260,8 @@ int64_t ra_index_info(const ra_index* idx, int what);
  *
  * ra_decode_step computes the attention over the static set W (Sec. 3.3: o_W of Eq. 4, which
  * does not depend on the retrieval) in extra "helper" workgroups of the same launch, one per
- * (sequence, KV head), while the query heads' workgroups search; each head takes over its
+ * (sequence, KV head) - one per query head where the launch leaves compute units idle - while the
+ * query heads' workgroups search; each head takes over its
  * helper's result through device memory the handle owns. The wait for that result is bounded:
  * a head that does not get it within RA_CFG_HELPER_SPIN polls computes o_W itself, and the
  * handle stops using helpers until RA_CFG_HELPERS is set again. Results do not depend on the
@@ -296,7 +297,7 @@ int64_t ra_index_info(const ra_index* idx, int what);
  *                       workgroup of its own in the same launch while the head's workgroup sets up
  *                       (what bounds the scoring of a start set is the rate at which one compute
  *                       unit takes in scattered key rows): 0 (the head scores its set itself) or
- *                       2 .. 8; default 4. Used only where every workgroup of the launch has a compute
+ *                       2 .. 8; default 6. Used only where every workgroup of the launch has a compute
  *                       unit to itself (the searches, their shares and the helpers together number at
  *                       most the device's compute units; fewer shares are used to make that so, none
  *                       below two) and a walk has a workgroup of 512 threads or more; RA_HELPERS_OFF

@@ -85,7 +85,7 @@ struct ra_index {
 #define RA_COOP_REC 132
 #define RA_SEED_PARTS_MAX 8    /* most shares a head's start set is scored in */
 #ifndef RA_SEED_PARTS_DEFAULT
-#define RA_SEED_PARTS_DEFAULT 4
+#define RA_SEED_PARTS_DEFAULT 6
 #endif
 #define RA_SEEDX_KEYS_OFF 256  /* bytes in front of the keys of the seed hand-over area */
 #define RA_FLAT_SLICES 8       /* workgroups per head in the second pass of ra_flat_topk (one counter each) */

@@ -13,7 +13,8 @@
 // reads the rows of W once for the whole GQA group and leaves (max, sum, weighted sums) per query
 // head in a hand-over area; the head's workgroup picks its record up after the search and only
 // attends to the retrieved rows itself. Helpers have the lowest workgroup ids, never wait for
-// anything, and are finished long before the first search is.
+// anything, and are finished before the first search is. (A launch with few searches has one
+// helper per query head instead: see ra_launch_decode.)
 //
 // The hand-over uses no fence. A variant with agent-scope release/acquire was measured: the part
 // has one L2 per XCD, so those fences write back and invalidate L2, about 18 us per launch, more
@@ -296,7 +297,7 @@ __global__ __launch_bounds__(T) void decode_kernel(
     float* __restrict__ out, float* __restrict__ lse, float* coop, int n_helpers, int coop_mode,
     int coop_spin, const int32_t* __restrict__ roots, int root_cap, const void* __restrict__ Ksearch,
     const float* __restrict__ kscale, const int32_t* __restrict__ budgets, uint32_t* seedx, int seed_parts,
-    int seed_stride) {
+    int seed_stride, int helper_heads) {
     extern __shared__ __align__(16) unsigned char lds_raw[];
     const int tid = threadIdx.x, grp = tid >> 4, lane16 = tid & 15;
     const size_t esz = DT == RA_BF16 ? 2 : 4;
@@ -308,15 +309,20 @@ __global__ __launch_bounds__(T) void decode_kernel(
     if ((int)blockIdx.x < n_helpers) {
         // ---- helper workgroup of (sequence, KV head) blockIdx.x: attention over W for its G heads
         if (!helpers || coop_mode == RA_HELPERS_SILENT_) return;
-        const int g = blockIdx.x;
+        // helper_heads of the group's G query heads per helper workgroup (G: one helper per group, W
+        // read once; fewer where the launch leaves compute units idle: the helpers of a group then
+        // run side by side on one XCD and share the rows in its L2)
+        const int n_groups = n_heads / G;
+        const int g = (int)blockIdx.x % n_groups, part = (int)blockIdx.x / n_groups;
         const char* Kg = reinterpret_cast<const char*>(K) + (size_t)g * kv_stride * RA_D * esz;
         const char* Vg = reinterpret_cast<const char*>(V) + (size_t)g * kv_stride * RA_D * esz;
         // G is 1, 2, 4 or 8 when helpers are on; 4 heads per pass over W (2 for fp32: registers)
         constexpr int PASS = DT == RA_BF16 ? 4 : 2;
-        for (int h0 = 0; h0 < G; h0 += PASS) {
+        const int h_end = (part + 1) * helper_heads;
+        for (int h0 = part * helper_heads; h0 < h_end; h0 += PASS) {
             const int head0 = g * G + h0;
-            if (G - h0 >= PASS) static_helper<DT, PASS, T>(lds_raw, q, head0, Kg, Vg, s, wstart, N, scale, coop, ready);
-            else if (G - h0 == 2) static_helper<DT, 2, T>(lds_raw, q, head0, Kg, Vg, s, wstart, N, scale, coop, ready);
+            if (h_end - h0 >= PASS) static_helper<DT, PASS, T>(lds_raw, q, head0, Kg, Vg, s, wstart, N, scale, coop, ready);
+            else if (h_end - h0 == 2) static_helper<DT, 2, T>(lds_raw, q, head0, Kg, Vg, s, wstart, N, scale, coop, ready);
             else static_helper<DT, 1, T>(lds_raw, q, head0, Kg, Vg, s, wstart, N, scale, coop, ready);
         }
         return;
@@ -534,8 +540,17 @@ ra_status ra_launch_decode(const void* q, const int32_t* adj, const int32_t* ent
     const float scale = 1.0f / sqrtf((float)RA_D);
     // one helper workgroup per (sequence, KV head) in front of the heads' (GQA groups of 1, 2, 4 or 8)
     if (!coop) RA_FAIL(RA_EINVAL, "hand-over area missing");
-    const int n_helpers = decode_helper_slots(coop, coop_mode, n_seq, n_q, n_kv);
+    int n_helpers = decode_helper_slots(coop, coop_mode, n_seq, n_q, n_kv);
     const int threads = decode_threads(heads, ef);
+    // One helper per query head instead of one per KV head where the launch leaves compute units idle
+    // (few searches): with 512 threads a helper's pass over W for a whole group ends later than a
+    // short walk does (128K layer: 26.5 against 27.25 us). The helpers of a group run side by side on
+    // one XCD and find each other's rows in its L2.
+    int helper_heads = n_q / n_kv;
+    if (n_helpers > 0 && threads >= 512 && 2 * heads <= decode_compute_units()) {
+        n_helpers *= helper_heads;
+        helper_heads = 1;
+    }
     const void* Ksearch = kscale ? K8 : K;
     // a start set scored in shares by workgroups of their own: only where every workgroup of the
     // launch has a compute unit to itself (few searches, 512 or 1024 threads each); fewer shares when
@@ -558,7 +573,7 @@ ra_status ra_launch_decode(const void* q, const int32_t* adj, const int32_t* ent
                            lds, st, q, adj, entry, K, V, n_q, n_kv, Ng, N, kv_stride, wstart, deg, \
                            (int)s, topk, ef, expand, bitset, ids, stats, ids_off, scale, out, lse, \
                            coop, n_helpers, coop_mode, coop_spin, roots, root_cap, Ksearch,        \
-                           kscale, budgets, seedx, parts, seed_stride);                            \
+                           kscale, budgets, seedx, parts, seed_stride, helper_heads);              \
     } while (0)
 #define RA_DC_GO(DTV, KTV, GB)                                                                     \
     do {                                                                                           \

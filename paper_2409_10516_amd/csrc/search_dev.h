@@ -401,7 +401,9 @@ __device__ __forceinline__ void score_seed_share(int head, int part, int parts, 
     const int32_t* root = roots + (size_t)head * root_cap;
     const int per = (n_cfg + parts - 1) / parts;
     const int c_beg = part * per;
-    constexpr int R = SR_UNROLL, PER = T / 16;
+    // (twice the rows in flight per lane group where the workgroup is small: the walk's own registers
+    // are not live here, and a share is then one trip to memory again)
+    constexpr int R = (T <= 512 && KT != RA_F32) ? 2 * SR_UNROLL : SR_UNROLL, PER = T / 16;
     const char* Kh = reinterpret_cast<const char*>(K) + ((size_t)seq * n_kv + kvh) * kv_stride * RA_D * ksz;
     ScoreQuery<KT> qv;
     load_score_query<DT, KT>(reinterpret_cast<const char*>(q) + (size_t)head * RA_D * esz, lane16, qv);

@@ -557,7 +557,7 @@ def test_seed_shares_give_the_heads_the_same_keys(name):
         idx.test_configure(B.RA_TEST_HELPERS_SILENT, 0)
         idx.configure(B.RA_CFG_HELPERS, B.RA_HELPERS_ON)
         idx.configure(B.RA_CFG_HELPER_SPIN, 20000)
-        idx.configure(B.RA_CFG_SEED_SHARES, 4)
+        idx.configure(B.RA_CFG_SEED_SHARES, 6)
         idx.configure(B.RA_CFG_SEEDS, 0)
 
 
