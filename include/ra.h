@@ -172,7 +172,7 @@ ra_status ra_decode_step_budgets(const void* q, const ra_index* idx, const void*
  * id, padded with -1. Scores are the same fixed-order float32 inner products ra_search uses, so
  * the two rank keys identically and recall of the graph search can be measured on the device.
  * The scan stores no per-key scores when the context is long enough for it (at least 64 x topk keys,
- * at most 256K): it keeps the largest score of every 32 keys, derives a threshold that at least topk
+ * at most 1M): it keeps the largest score of every 32 keys, derives a threshold that at least topk
  * of those maxima reach, and scores the few tiles at or above it a second time.
  * workspace: device memory of at least ra_flat_workspace_bytes(n_seq, n_q_heads, N) bytes. */
 size_t ra_flat_workspace_bytes(int n_seq, int n_q_heads, int64_t N);

@@ -27,7 +27,7 @@
 #define FL_SEL_T 1024
 #define FL_ROWS 8                  // key rows in flight per 16-lane group
 #define FL_TILE (FL_CHUNK / 16)     // keys per tile maximum: chunk base + 128 (j / 8) + 8 group + j % 8, j < FL_TILE
-#define FL_TILES_MAX 8192          // tiles per head the select kernel can list (256K keys)
+#define FL_TILES_MAX 8192          // tiles per head whose maxima (and list) fit LDS: 256K keys; four times as many from memory
 
 // grid: x = chunk of FL_CHUNK keys, y = KV head, z = seq. GQA groups of another size than the
 // kernel is built for run as G = 1 with one grid row per query head, kv_div of which share a KV head.
@@ -178,14 +178,16 @@ __device__ __forceinline__ void radix_select(const uint32_t* __restrict__ kh, in
 // tiles hold an eligible key) or a slice with more candidates than it can hold (a crowd of ties)
 // sets the top bit of the count instead: the select kernel then scores the whole head itself.
 // grid: x = slice, y = head; a wavefront takes one tile at a time (a 16-lane group one run of 8 rows).
-template <int DT>
+// BIG: more tiles than fit LDS (over 256K keys): the maxima are read where they are, in device memory
+// (a few passes over at most 128 KB that the cache holds), and only the list of tiles is in LDS.
+template <int DT, bool BIG>
 __global__ __launch_bounds__(FL_SEL_T) void flat_rescore_kernel(
     const void* __restrict__ q, const void* __restrict__ K, int n_q, int n_kv, int64_t N, int s, int w,
     const uint32_t* __restrict__ tile_max, int64_t n_tiles, int topk, uint32_t* __restrict__ keys,
     uint32_t* __restrict__ cand_count, int cand_cap) {
     __shared__ unsigned hist[256];
     __shared__ unsigned s_ntl, s_prefix, s_cnt, s_lo, s_hi, s_t0;
-    __shared__ uint32_t tm[FL_TILES_MAX];
+    __shared__ uint32_t tm_lds[BIG ? 1 : FL_TILES_MAX];
     __shared__ unsigned short s_tl[FL_TILES_MAX];
     __shared__ unsigned long long mine[FL_SLICE_CAND];        // this workgroup's candidates: (key, id)
     const int tid = threadIdx.x, lane = tid & (RA_WAVE - 1), wv = tid / RA_WAVE, g4 = lane >> 4, lane16 = tid & 15;
@@ -195,7 +197,10 @@ __global__ __launch_bounds__(FL_SEL_T) void flat_rescore_kernel(
     const char* Kh = reinterpret_cast<const char*>(K) + ((size_t)seq * n_kv + kvh) * N * RA_D * esz;
     ScoreQuery<DT> qv;
     load_score_query<DT, DT>(reinterpret_cast<const char*>(q) + (size_t)head * RA_D * esz, lane16, qv);
-    for (int64_t t = tid; t < n_tiles; t += FL_SEL_T) tm[t] = tile_max[(size_t)head * n_tiles + t];
+    const uint32_t* tm_mem = tile_max + (size_t)head * n_tiles;
+    if constexpr (!BIG)
+        for (int64_t t = tid; t < n_tiles; t += FL_SEL_T) tm_lds[t] = tm_mem[t];
+    auto tm = [&](int64_t t) -> uint32_t { if constexpr (BIG) return tm_mem[t]; else return tm_lds[t]; };
     if (tid == 0) { s_ntl = 0u; s_cnt = 0u; s_lo = 0xffffffffu; s_hi = 0u; s_t0 = 0xffffffffu; }
     if (tid < 256) hist[tid] = 0u;
     __syncthreads();
@@ -208,7 +213,7 @@ __global__ __launch_bounds__(FL_SEL_T) void flat_rescore_kernel(
     {
         uint32_t lo = 0xffffffffu, hi = 0u;
         for (int64_t t = tid; t < n_tiles; t += FL_SEL_T) {
-            const uint32_t v = tm[t];
+            const uint32_t v = tm(t);
             if (v) { lo = v < lo ? v : lo; hi = v > hi ? v : hi; }
         }
 #pragma unroll
@@ -228,7 +233,7 @@ __global__ __launch_bounds__(FL_SEL_T) void flat_rescore_kernel(
         const float b = (f32_from_ordered(v) - lo_f) * to_bin;
         return 1 + (b >= 254.f ? 254 : b > 0.f ? (int)b : 0);
     };
-    for (int64_t t = tid; t < n_tiles; t += FL_SEL_T) atomicAdd(&hist[bin_of(tm[t])], 1u);
+    for (int64_t t = tid; t < n_tiles; t += FL_SEL_T) atomicAdd(&hist[bin_of(tm(t))], 1u);
     __syncthreads();
     if (wv == 0) {
         // lane l owns bins 4l .. 4l + 3; maxima in the bins from b up = total - (those below b)
@@ -246,7 +251,7 @@ __global__ __launch_bounds__(FL_SEL_T) void flat_rescore_kernel(
     if (bstar > 0) {
         uint32_t m = 0xffffffffu;
         for (int64_t t = tid; t < n_tiles; t += FL_SEL_T) {
-            const uint32_t v = tm[t];
+            const uint32_t v = tm(t);
             if (bin_of(v) >= bstar) m = v < m ? v : m;
         }
 #pragma unroll
@@ -265,8 +270,15 @@ __global__ __launch_bounds__(FL_SEL_T) void flat_rescore_kernel(
     // this workgroup's share: the listed tiles whose number is congruent to its slice (the order of
     // a list differs from workgroup to workgroup, the tile numbers do not)
     for (int64_t t = tid; t < n_tiles; t += FL_SEL_T)
-        if (tm[t] >= T0 && (int)(t % FL_SLICES) == slice) s_tl[atomicAdd(&s_ntl, 1u)] = (unsigned short)t;
+        if ((int)(t % FL_SLICES) == slice && tm(t) >= T0) {
+            const unsigned at = atomicAdd(&s_ntl, 1u);
+            if (at < FL_TILES_MAX) s_tl[at] = (unsigned short)t;
+        }
     __syncthreads();
+    if (s_ntl > FL_TILES_MAX) {              // (only with more tiles than the list holds: a crowd of ties)
+        if (tid == 0) cand_count[head * FL_SLICES + slice] = 0x80000000u;
+        return;
+    }
     const int ntl = (int)s_ntl;
     for (int l = wv; l < ntl; l += FL_SEL_T / RA_WAVE) {
         const int64_t tl = s_tl[l];
@@ -611,7 +623,8 @@ ra_status ra_launch_flat_topk(const void* q, const void* K, ra_dtype dt, int n_s
     // of them are never read again. Candidate pairs (key, id) live in the head's key area.
     // (pairs a slice can hold: its eighth of the key area, and what its workgroup keeps in LDS)
     const int cand_cap = (int)(N / FL_SLICES / 2 < FL_SLICE_CAND ? N / FL_SLICES / 2 : FL_SLICE_CAND);
-    const bool two_pass = n_tiles >= 2 * (int64_t)topk && n_tiles <= FL_TILES_MAX && cand_cap >= 64;
+    const bool two_pass = n_tiles >= 2 * (int64_t)topk && n_tiles <= 4 * FL_TILES_MAX && cand_cap >= 64;
+    const bool big = n_tiles > FL_TILES_MAX;                     // (tile numbers stay below 2^16 in the lists)
     const dim3 grid((unsigned)((N + FL_CHUNK - 1) / FL_CHUNK), n_kv, n_seq);
     // any other group size than 1, 2, 4, 8: one grid row per query head, every head scans its keys itself
     const dim3 grid1(grid.x, n_q, n_seq);
@@ -634,10 +647,14 @@ ra_status ra_launch_flat_topk(const void* q, const void* K, ra_dtype dt, int n_s
             default: RA_FL_GO(DTV, 1, grid1, G);                                                              \
         }                                                                                                     \
         RA_HIP(hipGetLastError());                                                                            \
-        if (two_pass) {                                                                                       \
-            hipLaunchKernelGGL((flat_rescore_kernel<DTV>), dim3(FL_SLICES, heads), dim3(FL_SEL_T), 0, st, q, K, \
-                               n_q, n_kv, N, (int)ss, (int)ww, tile_max, n_tiles, topk, keys_ws, cand_count,  \
-                               cand_cap);                                                                     \
+        if (two_pass && big) {                                                                                \
+            hipLaunchKernelGGL((flat_rescore_kernel<DTV, true>), dim3(FL_SLICES, heads), dim3(FL_SEL_T), 0, st, \
+                               q, K, n_q, n_kv, N, (int)ss, (int)ww, tile_max, n_tiles, topk, keys_ws,        \
+                               cand_count, cand_cap);                                                         \
+        } else if (two_pass) {                                                                                \
+            hipLaunchKernelGGL((flat_rescore_kernel<DTV, false>), dim3(FL_SLICES, heads), dim3(FL_SEL_T), 0, st, \
+                               q, K, n_q, n_kv, N, (int)ss, (int)ww, tile_max, n_tiles, topk, keys_ws,        \
+                               cand_count, cand_cap);                                                         \
             RA_HIP(hipGetLastError());                                                                        \
         }                                                                                                     \
         hipLaunchKernelGGL((flat_select_kernel<DTV>), dim3(heads), dim3(FL_SEL_T), 0, st, keys_ws, tile_max,    \

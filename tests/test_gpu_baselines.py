@@ -88,6 +88,24 @@ def test_flat_topk_long_context_with_few_eligible_keys():
                             eligible=set(range(40000)) - set(W.tolist()))
 
 
+@pytest.mark.parametrize("N,dtype", [(300000, torch.bfloat16), (270001, torch.float32)])
+def test_flat_topk_beyond_256k_keys(N, dtype):
+    """More than 8192 tiles per head: the second pass reads the tile maxima from device memory instead
+    of LDS. Real-valued keys against the float64 brute force, and integer-valued keys with thousands
+    of ties around the k-th score (a crowd the candidate lists cannot hold: whole-head fallback)."""
+    w = synth.make_llama_layer(47, N=N, M=8, T=1, n_q=2, n_kv=1, dtype=dtype, window=640)
+    W = OA.static_ids(N, 4, 640)
+    for topk in (100, 700):
+        ids = ra.ra_flat_topk(w.q_decode[0].to(DEV), w.K.to(DEV), 4, 640, topk).cpu().numpy()
+        for h in range(2):
+            qq, Kh = to_np(w.q_decode[0, 0, h]), to_np(w.K[0, 0])
+            topk_equivalent(ids[0, h], OM.topk_bruteforce(qq, Kh, topk, exclude=W), qq, Kh)
+    wi = synth.make_integer_case(9, N=N, M=4, T=1, d=128, lo=-1, hi=1, dtype=dtype)
+    ids = ra.ra_flat_topk(wi.q_decode[0].to(DEV), wi.K.to(DEV), 0, 0, 100).cpu().numpy()[0, 0]
+    ref = OM.topk_bruteforce(to_np(wi.q_decode[0, 0, 0]), to_np(wi.K[0, 0]), 100)
+    assert ids.tolist() == ref.tolist()
+
+
 @pytest.mark.parametrize("topk", [1, 100, 1024, 2048])
 def test_flat_topk_sampled_threshold_path(topk):
     """40000 keys are 1264 tiles: topk 1 and 100 take their threshold from the tile maxima, 1024 and
