@@ -1,7 +1,7 @@
 // VectorSearch(q) of Algorithm 1: bounded best-first walk over one head's key graph
 // (Sec. 2.4 describes proximity-graph search as a greedy walk towards the most similar
-// vectors). One workgroup per (sequence, query head), of 1024 threads, or 512 / 256 when a launch
-// has more searches than the part has compute units; the whole search state lives in LDS:
+// vectors). One workgroup per (sequence, query head), of 1024, 512 or 256 threads (search_threads
+// below; the fused decode launch chooses for itself); the whole search state lives in LDS:
 //   * visited: an exact bitset over the N keys (N/8 bytes; a global-memory bitset is used
 //     instead when the context is too long for LDS),
 //   * beam: at most ef entries, always sorted, as 64-bit keys
