@@ -34,6 +34,9 @@
 #ifndef SR_UNROLL
 #define SR_UNROLL 8               // key rows in flight per 16-lane group
 #endif
+#ifndef SR_ADJ_LOADS
+#define SR_ADJ_LOADS 8            // adjacency cells a thread has in flight while it claims neighbours
+#endif
 
 
 enum { C_MISSED = 0, C_NCAND = 1, C_NKEEP = 2, C_NUNEXP = 3, C_LO = 4, C_HI = 5, C_NSURV = 6, C_BIN = 7, C_WTOT = 8,
@@ -728,27 +731,39 @@ __device__ __forceinline__ int run_search(
         //      claim unvisited neighbours (the doubled first step has its candidates already)
         if (!first) {
             const int cells = np * deg;
-            for (int x0 = 0; x0 < cells; x0 += T * 2) {
-                int nbv[2];
+            // cell x is slot x % deg of pick x / deg; the quotient by a multiplication (exact while
+            // x * deg < 2^32: there are at most RA_MAX_EXPAND * deg cells), because a division per
+            // cell costs more than everything else in this loop
+            const uint32_t deg_m = 0xffffffffu / (uint32_t)deg + 1u;
+            // L cells per thread and pass, all L loads issued before the first claim: 8 for a wide
+            // step (8192 cells), fewer for a narrow one, where the loads past the last cell are waste
+            auto claim_cells = [&](auto loads_c) __attribute__((always_inline)) {
+                constexpr int L = decltype(loads_c)::value;
+                for (int x0 = 0; x0 < cells; x0 += T * L) {
+                    int nbv[L];
 #pragma unroll
-                for (int u = 0; u < 2; ++u) {
-                    // out-of-range slots re-read the last cell: loads without a branch around
-                    // them can all be issued before the first one is consumed
-                    const int x = x0 + u * T + tid;
-                    const int xc = x < cells ? x : cells - 1;
-                    const int v = adj_h[(size_t)picks[xc / deg] * deg + (xc % deg)];
-                    nbv[u] = x < cells ? v : -1;
-                }
+                    for (int u = 0; u < L; ++u) {
+                        // out-of-range slots re-read the last cell: loads without a branch around
+                        // them can all be issued before the first one is consumed
+                        const int x = x0 + u * T + tid;
+                        const int xc = x < cells ? x : cells - 1;
+                        const int xr = (int)__umulhi((uint32_t)xc, deg_m);       // xc / deg
+                        const int v = adj_h[(size_t)picks[xr] * deg + (xc - xr * deg)];
+                        nbv[u] = x < cells ? v : -1;
+                    }
 #pragma unroll
-                for (int u = 0; u < 2; ++u) {
-                    const int nb = nbv[u];
-                    if (nb >= 0 && nb < N) {
-                        const uint32_t bit = 1u << (nb & 31);
-                        const uint32_t old = atomicOr(&bits[nb >> 5], bit);
-                        if (!(old & bit)) cid[atomicAdd(&ctr[C_NCAND], 1)] = nb;
+                    for (int u = 0; u < L; ++u) {
+                        const int nb = nbv[u];
+                        if (nb >= 0 && nb < N) {
+                            const uint32_t bit = 1u << (nb & 31);
+                            const uint32_t old = atomicOr(&bits[nb >> 5], bit);
+                            if (!(old & bit)) cid[atomicAdd(&ctr[C_NCAND], 1)] = nb;
+                        }
                     }
                 }
-            }
+            };
+            if (cells > 4 * T) claim_cells(sr_int<SR_ADJ_LOADS>{});
+            else claim_cells(sr_int<2>{});
         }
         __syncthreads();
         const int nc = ctr[C_NCAND];
